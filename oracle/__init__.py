@@ -1,0 +1,305 @@
+"""TEST INFRASTRUCTURE ONLY: the CPU oracle for REST's draft-and-verify step.
+
+A plain, slow statement of what each stage of the hot path computes, written
+from the paper (arXiv 2311.08252) and independent of the GPU library: it
+imports nothing from the product package and the product imports nothing from
+here.  Only tests, the smoke check and the benchmark's CPU-baseline leg may
+use it.
+
+Integer stages (suffix array, Algorithm 1 retrieval, Algorithm 2 Trie
+selection, breadth-first pseudo sequence + tree mask, acceptance) live in
+rest_oracle.c and are reached through ctypes; tree attention is written here
+with numpy in float64.
+
+Parity pins: every function below is pinned by tests/test_oracle_*.py against
+facts that do not come from this code (textbook suffix arrays, Python's own
+substring search and sort, collections.Counter prefix counts, a library
+scaled-dot-product attention, closed forms).  The paper prints no worked
+numerical example, so no paper-printed values exist to compare with.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from dataclasses import dataclass
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "rest_oracle.c")
+_LIB = os.path.join(_HERE, "librest_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile rest_oracle.c with gcc into librest_oracle.so next to it."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-Wall", "-Wextra",
+                               "-o", _LIB, _SRC])
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = ctypes.CDLL(_LIB)
+        _lib.oracle_check_suffix_array.restype = ctypes.c_int64
+    return _lib
+
+
+def _ptr(a: np.ndarray):
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _token_bytes(corpus: np.ndarray) -> int:
+    if corpus.dtype == np.int32:
+        return 4
+    if corpus.dtype == np.uint16:
+        return 2
+    raise TypeError("corpus must be int32 or uint16")
+
+
+# ---------------------------------------------------------------------------
+# Suffix array ("Retrieving from the datastore": exact match via a suffix array)
+# ---------------------------------------------------------------------------
+def suffix_array(corpus: np.ndarray) -> np.ndarray:
+    """int64 suffix array by sorting all suffixes (end of stream smallest)."""
+    corpus = np.ascontiguousarray(corpus)
+    sa = np.empty(corpus.shape[0], dtype=np.int64)
+    rc = _load().oracle_suffix_array(_ptr(corpus), ctypes.c_uint64(corpus.shape[0]),
+                                     _token_bytes(corpus), _ptr(sa))
+    assert rc == 0
+    return sa
+
+
+def check_suffix_array(corpus: np.ndarray, sa: np.ndarray) -> int:
+    """-1 if `sa` is the suffix array of `corpus` by definition (a permutation
+    whose adjacent suffixes strictly increase), else the first bad rank."""
+    corpus = np.ascontiguousarray(corpus)
+    sa = np.ascontiguousarray(sa)
+    assert sa.dtype in (np.int32, np.int64) and sa.shape[0] == corpus.shape[0]
+    return int(_load().oracle_check_suffix_array(_ptr(corpus), ctypes.c_uint64(corpus.shape[0]),
+                                                 _token_bytes(corpus), _ptr(sa), sa.dtype.itemsize))
+
+
+# ---------------------------------------------------------------------------
+# Algorithm 1: Retrieve(D, s)
+# ---------------------------------------------------------------------------
+@dataclass
+class Retrieved:
+    matched_len: int          # n of the longest matching suffix (0: none)
+    match_count: int          # number of occurrences of that suffix
+    row_pos: np.ndarray       # [R] stream position of each kept occurrence, suffix order
+    rows: np.ndarray          # [R, m] continuation tokens, -1 padded
+    row_len: np.ndarray       # [R]
+
+
+def retrieve(corpus: np.ndarray, context: np.ndarray, n_max: int = 16, n_min: int = 2,
+             max_matches: int = 5000, cont_len: int = 10, one_pass: bool = False) -> Retrieved:
+    corpus = np.ascontiguousarray(corpus)
+    s = np.ascontiguousarray(context, dtype=np.int32)
+    K, m = int(max_matches), int(cont_len)
+    ml = ctypes.c_int32(0)
+    mc = ctypes.c_int64(0)
+    nr = ctypes.c_int64(0)
+    row_pos = np.zeros(K, dtype=np.int64)
+    rows = np.full((K, max(m, 1)), -1, dtype=np.int32)
+    row_len = np.zeros(K, dtype=np.int32)
+    rc = _load().oracle_retrieve(_ptr(corpus), ctypes.c_uint64(corpus.shape[0]), _token_bytes(corpus),
+                                 _ptr(s), ctypes.c_int32(s.shape[0]),
+                                 ctypes.c_int32(n_max), ctypes.c_int32(n_min), ctypes.c_int64(K),
+                                 ctypes.c_int32(m), ctypes.c_int32(1 if one_pass else 0),
+                                 ctypes.byref(ml), ctypes.byref(mc), ctypes.byref(nr),
+                                 _ptr(row_pos), _ptr(rows), _ptr(row_len))
+    assert rc == 0, rc
+    R = nr.value
+    return Retrieved(ml.value, mc.value, row_pos[:R].copy(), rows[:R, :m].copy(), row_len[:R].copy())
+
+
+# ---------------------------------------------------------------------------
+# Algorithm 2 + breadth-first pseudo sequence + tree attention mask
+# ---------------------------------------------------------------------------
+@dataclass
+class DraftTree:
+    n_nodes: int
+    draft_tokens: np.ndarray   # [c] int32, -1 padded
+    parent_idx: np.ndarray     # [c] int32, -1 = child of the last context token (and padding)
+    pos_ids: np.ndarray        # [c] int32 depth, 0 padded
+    node_weight: np.ndarray    # [c] int32
+    tree_mask: np.ndarray      # [c, ceil(c/64)] uint64
+    matched_len: int = 0
+    match_count: int = 0
+    total_trie_nodes: int = 0
+
+
+def select_drafts(rows: np.ndarray, row_len: np.ndarray, max_nodes: int,
+                  order: np.ndarray | None = None) -> DraftTree:
+    """Trie over all prefixes of all rows, the max_nodes heaviest nodes, laid
+    out breadth first with the mask.  `order` is the insertion order of the
+    rows (default: as given)."""
+    rows = np.ascontiguousarray(rows, dtype=np.int32)
+    row_len = np.ascontiguousarray(row_len, dtype=np.int32)
+    R = rows.shape[0]
+    m = rows.shape[1] if rows.ndim == 2 else 0
+    c = int(max_nodes)
+    words = max(1, (c + 63) // 64)
+    n = ctypes.c_int32(0)
+    tot = ctypes.c_int64(0)
+    tok = np.zeros(max(c, 1), dtype=np.int32)
+    par = np.zeros(max(c, 1), dtype=np.int32)
+    pos = np.zeros(max(c, 1), dtype=np.int32)
+    wgt = np.zeros(max(c, 1), dtype=np.int32)
+    mask = np.zeros((max(c, 1), words), dtype=np.uint64)
+    if order is not None:
+        order = np.ascontiguousarray(order, dtype=np.int64)
+        assert order.shape[0] == R
+    if m == 0:
+        rows = np.zeros((max(R, 1), 1), dtype=np.int32)
+    rc = _load().oracle_select_drafts(_ptr(rows), _ptr(row_len),
+                                      _ptr(order) if order is not None else None,
+                                      ctypes.c_int64(R), ctypes.c_int32(max(m, 1)),
+                                      ctypes.c_int32(c), ctypes.c_int32(words),
+                                      ctypes.byref(n), _ptr(tok), _ptr(par), _ptr(pos), _ptr(wgt),
+                                      _ptr(mask), ctypes.byref(tot))
+    assert rc == 0, rc
+    return DraftTree(n.value, tok[:c], par[:c], pos[:c], wgt[:c], mask[:c], 0, 0, tot.value)
+
+
+def draft_tree(corpus: np.ndarray, context: np.ndarray, n_max: int = 16, n_min: int = 2,
+               max_matches: int = 5000, cont_len: int = 10, max_nodes: int = 64,
+               one_pass: bool = False) -> DraftTree:
+    """One context -> draft tree: Algorithm 1, then Algorithm 2 with the
+    candidates inserted in stream-position order, then the layout."""
+    got = retrieve(corpus, context, n_max, n_min, max_matches, cont_len, one_pass)
+    order = np.argsort(got.row_pos, kind="stable").astype(np.int64)
+    tree = select_drafts(got.rows, got.row_len, max_nodes, order)
+    tree.matched_len = got.matched_len
+    tree.match_count = got.match_count
+    return tree
+
+
+def mask_from_parents(parent_idx: np.ndarray, n_nodes: int, words: int | None = None) -> np.ndarray:
+    """Tree attention mask from parent pointers: row i has bit j set iff j is i
+    or an ancestor of i ("Draft verification")."""
+    c = parent_idx.shape[0]
+    words = words or max(1, (c + 63) // 64)
+    mask = np.zeros((c, words), dtype=np.uint64)
+    for i in range(n_nodes):
+        v = i
+        while v != -1:
+            mask[i, v // 64] |= np.uint64(1) << np.uint64(v % 64)
+            v = int(parent_idx[v])
+    return mask
+
+
+# ---------------------------------------------------------------------------
+# Tree attention ("Draft verification"): every draft token attends to the whole
+# cached context and, among the draft tokens, only to itself and its ancestors.
+# ---------------------------------------------------------------------------
+def tree_attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, mask: np.ndarray,
+                   prefix_len: int, scale: float) -> np.ndarray:
+    """float64 softmax attention with the tree mask, by the definition.
+
+    q [..., Tq, D]; k, v [..., P+Tk, D] (exact values of the inputs, any float
+    dtype, promoted to float64); mask [Tq, ceil(Tk/64)] uint64 shared by all
+    leading dims, or [..., Tq, words] matching them.  Query row i sees keys
+    0..P-1 and key P+j iff bit j of mask row i is set.  Returns float64
+    [..., Tq, D]."""
+    q = np.asarray(q, dtype=np.float64)
+    k = np.asarray(k, dtype=np.float64)
+    v = np.asarray(v, dtype=np.float64)
+    Tq = q.shape[-2]
+    Lk = k.shape[-2]
+    P = int(prefix_len)
+    Tk = Lk - P
+    bits = np.zeros(mask.shape[:-1] + (Lk,), dtype=bool)
+    bits[..., :P] = True
+    for j in range(Tk):
+        bits[..., P + j] = (mask[..., j // 64] >> np.uint64(j % 64)) & np.uint64(1) != 0
+    assert bits.shape[-2] == Tq
+    s = scale * np.matmul(q, np.swapaxes(k, -1, -2))
+    s = np.where(bits, s, -np.inf)
+    s = s - np.max(s, axis=-1, keepdims=True)
+    p = np.exp(s)
+    p = p / np.sum(p, axis=-1, keepdims=True)
+    return np.matmul(p, v)
+
+
+def tree_attention_loops(q, k, v, mask, prefix_len: int, scale: float) -> np.ndarray:
+    """The same definition as explicit Python loops for one [Tq, D] / [Lk, D]
+    slab (small cases only)."""
+    import math
+    Tq, D = q.shape
+    Lk = k.shape[0]
+    P = prefix_len
+    out = np.zeros((Tq, D), dtype=np.float64)
+    for i in range(Tq):
+        vis = [j for j in range(Lk)
+               if j < P or (int(mask[i, (j - P) // 64]) >> ((j - P) % 64)) & 1]
+        logits = [scale * sum(float(q[i, d]) * float(k[j, d]) for d in range(D)) for j in vis]
+        mx = max(logits)
+        e = [math.exp(x - mx) for x in logits]
+        z = sum(e)
+        for w, j in zip(e, vis):
+            for d in range(D):
+                out[i, d] += (w / z) * float(v[j, d])
+    return out
+
+
+# ---------------------------------------------------------------------------
+# Acceptance ("Draft acceptance of REST")
+# ---------------------------------------------------------------------------
+def accept(ids: np.ndarray, draft_tokens: np.ndarray, parent_idx: np.ndarray, n_nodes: int,
+           path_cap: int):
+    """ids[0] = model token after the context, ids[1+i] = after node i.
+    Returns (accept_len, accept_path[path_cap] node indices -1 padded, next_token)."""
+    ids = np.ascontiguousarray(ids, dtype=np.int32)
+    tok = np.ascontiguousarray(draft_tokens, dtype=np.int32)
+    par = np.ascontiguousarray(parent_idx, dtype=np.int32)
+    al = ctypes.c_int32(0)
+    nt = ctypes.c_int32(0)
+    path = np.full(max(path_cap, 1), -1, dtype=np.int32)
+    rc = _load().oracle_accept(_ptr(ids), _ptr(tok), _ptr(par), ctypes.c_int32(n_nodes),
+                               ctypes.c_int32(path_cap), ctypes.byref(al), _ptr(path), ctypes.byref(nt))
+    assert rc == 0
+    return al.value, path[:path_cap], nt.value
+
+
+# ---------------------------------------------------------------------------
+# The decoding loop the acceptance rule is claimed to preserve: with a
+# deterministic next-token function, REST's draft/verify/accept loop must emit
+# exactly the tokens of one-token-at-a-time greedy decoding.
+# ---------------------------------------------------------------------------
+def greedy_decode(next_token_fn, prompt, n_new: int):
+    seq = list(int(x) for x in prompt)
+    for _ in range(n_new):
+        seq.append(int(next_token_fn(seq)))
+    return seq[len(prompt):]
+
+
+def rest_decode(next_token_fn, prompt, n_new: int, corpus: np.ndarray, n_max=16, n_min=2,
+                max_matches=1000, cont_len=10, max_nodes=32):
+    """Returns (generated tokens, number of verification steps)."""
+    seq = list(int(x) for x in prompt)
+    base = len(seq)
+    steps = 0
+    while len(seq) - base < n_new:
+        tree = draft_tree(corpus, np.asarray(seq, dtype=np.int32), n_max, n_min,
+                          max_matches, cont_len, max_nodes)
+        # one "forward pass": the model's token at the root and after every draft node
+        ids = np.zeros(1 + max_nodes, dtype=np.int32)
+        ids[0] = next_token_fn(seq)
+        for i in range(tree.n_nodes):
+            path, v = [], i
+            while v != -1:
+                path.append(int(tree.draft_tokens[v]))
+                v = int(tree.parent_idx[v])
+            ids[1 + i] = next_token_fn(seq + path[::-1])
+        n_acc, path, nxt = accept(ids, tree.draft_tokens, tree.parent_idx, tree.n_nodes, cont_len)
+        for j in range(n_acc):
+            seq.append(int(tree.draft_tokens[path[j]]))
+        seq.append(int(nxt))
+        steps += 1
+    return seq[base:base + n_new], steps
