@@ -1,0 +1,205 @@
+/*
+ * rest.h -- C ABI of the MI355X (gfx950) implementation of REST's per-step
+ * draft-and-verify hot path (Retrieval-Based Speculative Decoding,
+ * arXiv 2311.08252).
+ *
+ * The four calls follow the paper's problem statement:
+ *   rest_build_index   "Datastore construction" + the suffix array used for
+ *                      exact match ("Retrieving from the datastore")
+ *   rest_retrieve      Algorithm 1 (longest matching suffix, its continuations)
+ *                      + Algorithm 2 (Trie weights, top-c nodes)
+ *                      + the breadth-first pseudo sequence and tree attention
+ *                      mask of "Draft verification"
+ *   rest_tree_attention  the attention of the verification forward pass under
+ *                      that mask ("Draft verification")
+ *   rest_accept        "Draft acceptance": accept draft tokens from the start
+ *                      while they equal the model's own tokens
+ *
+ * Conventions
+ *  - Every pointer whose name starts with d_ (and every pointer inside
+ *    rest_tree) is DEVICE memory owned by the caller; the library never frees
+ *    or reallocates it.  Pointers to parameter structs are HOST memory and are
+ *    read before the call returns.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    rest_retrieve, rest_tree_attention and rest_accept only enqueue work on
+ *    it and never synchronise; rest_build_index allocates scratch memory and
+ *    may synchronise.
+ *  - All calls return a rest_status; no call aborts, throws or prints.  On an
+ *    error nothing has been enqueued and output buffers are untouched.
+ *  - Tokens are non-negative.  A corpus stores them as int32 (token_bytes 4)
+ *    or uint16 (token_bytes 2); contexts and draft tokens are always int32.
+ */
+#ifndef REST_H
+#define REST_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t rest_status;
+enum {
+    REST_OK = 0,
+    REST_INVALID_ARG = -1,        /* null pointer, size out of range, bad enum */
+    REST_UNSUPPORTED = -2,        /* legal request this build has no kernel for */
+    REST_WORKSPACE_TOO_SMALL = -3,
+    REST_OUT_OF_MEMORY = -4,      /* hipMalloc failed (index build / handle creation only) */
+    REST_HIP_ERROR = -5           /* a HIP runtime call or kernel launch failed */
+};
+
+/* Compile-time limits of the retrieval kernels (rest_retrieve rejects larger values). */
+#define REST_MAX_SUFFIX_LEN 16      /* n_max <= 16: the paper's setting, "Hyperparameters" */
+#define REST_MAX_CONT_LEN 32        /* m */
+#define REST_MAX_MATCHES 8192       /* K */
+#define REST_MAX_NODES 256          /* c */
+
+const char* rest_status_string(rest_status s);
+/* Library version string, e.g. "rest-gfx950 0.1". */
+const char* rest_version(void);
+
+/* ------------------------------------------------------------------------
+ * Index: the token stream plus its suffix array, both resident in HBM.
+ *
+ * The datastore of the paper, D = {(c_i, t_i)}, holds for every position i of
+ * a corpus the context ending there and the continuation that follows
+ * ("Datastore construction").  It is represented by the flat token stream; a
+ * suffix array over it answers "which contexts end with q" exactly
+ * ("Retrieving from the datastore").  Suffix order: lexicographic by token
+ * value, the end of the stream smaller than every token (this makes the
+ * array unique).
+ * ---------------------------------------------------------------------- */
+typedef struct rest_index rest_index;
+
+/* Builds the suffix array of d_corpus[0 .. n_tokens) on the GPU (prefix
+ * doubling with radix sorts) and returns a handle that owns the suffix array
+ * and a small search table, and BORROWS d_corpus (it must stay valid and
+ * unchanged until rest_index_destroy).
+ *   token_bytes 2|4; sa_bytes 4 (int32 entries, needs n_tokens < 2^31) or 8.
+ *   n_tokens must be in [1, 2^32 - 2].
+ * Synchronises `stream` before returning. */
+rest_status rest_build_index(const void* d_corpus, uint64_t n_tokens, int32_t token_bytes,
+                             int32_t sa_bytes, void* stream, rest_index** out);
+
+/* Wraps a caller-supplied suffix array (e.g. one built elsewhere or loaded
+ * from disk); both arrays are borrowed.  The array is trusted, not checked.
+ * Only the small search table is computed (synchronises `stream`). */
+rest_status rest_index_from_sa(const void* d_corpus, const void* d_sa, uint64_t n_tokens,
+                               int32_t token_bytes, int32_t sa_bytes, void* stream, rest_index** out);
+
+/* Read-only view of what the handle holds (any out pointer may be NULL). */
+rest_status rest_index_view(const rest_index* index, const void** d_corpus, const void** d_sa,
+                            uint64_t* n_tokens, int32_t* token_bytes, int32_t* sa_bytes);
+
+/* Frees what the handle owns.  NULL is allowed. */
+void rest_index_destroy(rest_index* index);
+
+/* ------------------------------------------------------------------------
+ * rest_retrieve: contexts -> draft trees.
+ *
+ * For each of the B contexts s = d_contexts[b*ctx_stride .. + d_ctx_len[b]):
+ *  1. Algorithm 1: for n = min(n_max, len) down to n_min, q = last n tokens
+ *     of s; the first n for which q occurs in the stream is matched_len and
+ *     match_count its number of occurrences (0 / 0 if none, or if len < n_min).
+ *     The paper's loop has no lower bound; n_min >= 1 supplies one.
+ *  2. Of the occurrences, the first max_matches in suffix-array order are kept;
+ *     the candidate of an occurrence is the cont_len tokens following it, cut
+ *     at the end of the stream ("Hyperparameters": m).
+ *  3. Algorithm 2: the Trie of all non-empty candidate prefixes, node weight =
+ *     number of candidates with that prefix; the max_nodes heaviest nodes are
+ *     kept, ties broken by (depth ascending, prefix lexicographically
+ *     ascending), which keeps the set closed under taking parents.
+ *  4. "Draft verification": the kept nodes in breadth-first order (depth, then
+ *     prefix order, i.e. siblings by ascending token) form the pseudo
+ *     sequence; tree_mask row i has bit j set iff j == i or node j is an
+ *     ancestor of node i.
+ *
+ * Outputs, row stride max_nodes per context; slots i >= n_nodes hold
+ * draft_tokens -1, parent_idx -1, pos_ids 0, node_weight 0, mask row 0.
+ * ---------------------------------------------------------------------- */
+typedef struct {
+    int32_t n_max;        /* longest suffix tried, 1..REST_MAX_SUFFIX_LEN (paper: 16) */
+    int32_t n_min;        /* shortest suffix tried, 1..n_max */
+    int32_t max_matches;  /* K, 1..REST_MAX_MATCHES */
+    int32_t cont_len;     /* m, 1..REST_MAX_CONT_LEN (paper: 10) */
+    int32_t max_nodes;    /* c, 1..REST_MAX_NODES (paper: 64) */
+} rest_retrieve_params;
+
+typedef struct {
+    int32_t* draft_tokens;   /* [B, c] token of node i */
+    int32_t* parent_idx;     /* [B, c] index of the parent node, -1 = the context's last token */
+    int32_t* pos_ids;        /* [B, c] depth of node i, 1-based (position offset after the context) */
+    int32_t* node_weight;    /* [B, c] Trie weight of node i */
+    uint64_t* tree_mask;     /* [B, c, ceil(c/64)] ancestor-or-self bit rows */
+    int32_t* n_nodes;        /* [B] */
+    int32_t* matched_len;    /* [B] */
+    int64_t* match_count;    /* [B] */
+} rest_tree;
+
+/* Bytes of device workspace rest_retrieve needs for B contexts (0 on bad params). */
+size_t rest_retrieve_workspace_bytes(int32_t B, const rest_retrieve_params* params);
+
+rest_status rest_retrieve(const rest_index* index, const int32_t* d_contexts, const int32_t* d_ctx_len,
+                          int32_t B, int32_t ctx_stride, const rest_retrieve_params* params,
+                          const rest_tree* out, void* d_workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------
+ * rest_tree_attention: masked softmax attention of the draft tokens against
+ * the KV cache ("Draft verification": each token must see exactly its own
+ * draft sequence).
+ *
+ * For every batch entry nb (a layer or a context) and head h, query row i:
+ *   O[i] = sum_j softmax_j(scale * q_i . k_j) v_j over the visible keys j:
+ *   keys 0..P-1 (the cached context) are always visible, key P+j (draft token
+ *   j) is visible iff bit j of mask row i is set.
+ * A row with no visible key (P == 0 and an empty mask row) yields zeros.
+ *
+ * Layout: q, out [Nb, H, Tq, D]; k, v [Nb, H, P+Tk, D]; D contiguous; the
+ * strides (in elements) of the Nb, H and row axes are given per tensor.
+ * d_mask: [Tq, ceil(Tk/64)] uint64 when mask_per_batch == 0 (shared by all Nb),
+ * else [Nb, Tq, ceil(Tk/64)].  Heads share K/V one-to-one (multi-head attention).
+ * dtype: REST_BF16 (bf16 in/out, fp32 accumulation and softmax, probabilities
+ * rounded to bf16 for the second product) or REST_FP32 (fp32 in/out and math).
+ * D must be 128.  Tq, Tk <= REST_MAX_NODES (Tk may be 0).
+ * ---------------------------------------------------------------------- */
+enum { REST_BF16 = 0, REST_FP32 = 1 };
+
+typedef struct {
+    int32_t Nb, H, Tq, Tk, P, D;
+    int32_t dtype;
+    float scale;
+    int64_t q_stride[3];     /* elements: Nb, H, row */
+    int64_t k_stride[3];
+    int64_t v_stride[3];
+    int64_t o_stride[3];
+    int32_t mask_per_batch;
+    int32_t num_splits;      /* 0 = let the library choose; else KV splits per (Nb, H) */
+} rest_attn_desc;
+
+/* Bytes of device workspace (partial results of the KV splits). */
+size_t rest_tree_attention_workspace_bytes(const rest_attn_desc* desc);
+
+rest_status rest_tree_attention(const void* d_q, const void* d_k, const void* d_v, const uint64_t* d_mask,
+                                void* d_out, const rest_attn_desc* desc,
+                                void* d_workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------
+ * rest_accept ("Draft acceptance"): d_ids[b, 0] is the model's token after the
+ * context, d_ids[b, 1+i] its token after draft node i (greedy: the argmax).
+ * Starting at the context's last token, step to the child whose token equals
+ * the model's token at the current position, until none does or path_cap
+ * tokens are accepted.  Siblings have distinct tokens, so the walk is unique.
+ *   d_accept_len[b]   number of accepted draft tokens
+ *   d_accept_path[b, path_cap]  their node indices, -1 padded
+ *   d_next_token[b]   the model's token at the last accepted position
+ * `tree` rows have stride c (= the max_nodes used by rest_retrieve); d_ids has
+ * row stride 1 + c.
+ * ---------------------------------------------------------------------- */
+rest_status rest_accept(const int32_t* d_ids, const rest_tree* tree, int32_t B, int32_t c, int32_t path_cap,
+                        int32_t* d_accept_len, int32_t* d_accept_path, int32_t* d_next_token, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* REST_H */

@@ -1,0 +1,300 @@
+"""Thin Python binding of the gfx950 REST library (include/rest.h).
+
+Argument marshalling only: every step of the hot path runs in the HIP kernels
+of librest_gfx950.so.  PyTorch tensors are used as device buffers and the
+current torch stream as the HIP stream.  There is no CPU fallback: if the
+shared library is missing or fails to load, importing this package raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "librest_gfx950.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        f"{LIB_PATH} is missing: build it first (python -m paper_2311_08252_amd.build, "
+        "or __graft_entry__.build()); this package has no fallback path")
+_lib = ctypes.CDLL(LIB_PATH)
+
+REST_OK = 0
+REST_INVALID_ARG = -1
+REST_UNSUPPORTED = -2
+REST_WORKSPACE_TOO_SMALL = -3
+REST_OUT_OF_MEMORY = -4
+REST_HIP_ERROR = -5
+REST_BF16 = 0
+REST_FP32 = 1
+REST_MAX_SUFFIX_LEN = 16
+REST_MAX_CONT_LEN = 32
+REST_MAX_MATCHES = 8192
+REST_MAX_NODES = 256
+
+EXPORTS = [
+    "rest_status_string", "rest_version", "rest_build_index", "rest_index_from_sa", "rest_index_view",
+    "rest_index_destroy", "rest_retrieve_workspace_bytes", "rest_retrieve",
+    "rest_tree_attention_workspace_bytes", "rest_tree_attention", "rest_accept",
+]
+
+
+class RestError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {rest_status_string(status)} ({status})")
+
+
+class rest_retrieve_params(ctypes.Structure):
+    _fields_ = [("n_max", ctypes.c_int32), ("n_min", ctypes.c_int32), ("max_matches", ctypes.c_int32),
+                ("cont_len", ctypes.c_int32), ("max_nodes", ctypes.c_int32)]
+
+
+class rest_tree(ctypes.Structure):
+    _fields_ = [("draft_tokens", ctypes.c_void_p), ("parent_idx", ctypes.c_void_p), ("pos_ids", ctypes.c_void_p),
+                ("node_weight", ctypes.c_void_p), ("tree_mask", ctypes.c_void_p), ("n_nodes", ctypes.c_void_p),
+                ("matched_len", ctypes.c_void_p), ("match_count", ctypes.c_void_p)]
+
+
+class rest_attn_desc(ctypes.Structure):
+    _fields_ = [("Nb", ctypes.c_int32), ("H", ctypes.c_int32), ("Tq", ctypes.c_int32), ("Tk", ctypes.c_int32),
+                ("P", ctypes.c_int32), ("D", ctypes.c_int32), ("dtype", ctypes.c_int32), ("scale", ctypes.c_float),
+                ("q_stride", ctypes.c_int64 * 3), ("k_stride", ctypes.c_int64 * 3), ("v_stride", ctypes.c_int64 * 3),
+                ("o_stride", ctypes.c_int64 * 3), ("mask_per_batch", ctypes.c_int32), ("num_splits", ctypes.c_int32)]
+
+
+_lib.rest_status_string.restype = ctypes.c_char_p
+_lib.rest_status_string.argtypes = [ctypes.c_int32]
+_lib.rest_version.restype = ctypes.c_char_p
+_lib.rest_build_index.restype = ctypes.c_int32
+_lib.rest_build_index.argtypes = [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p,
+                                  ctypes.POINTER(ctypes.c_void_p)]
+_lib.rest_index_from_sa.restype = ctypes.c_int32
+_lib.rest_index_from_sa.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint64, ctypes.c_int32, ctypes.c_int32,
+                                    ctypes.c_void_p, ctypes.POINTER(ctypes.c_void_p)]
+_lib.rest_index_view.restype = ctypes.c_int32
+_lib.rest_index_view.argtypes = [ctypes.c_void_p, ctypes.POINTER(ctypes.c_void_p), ctypes.POINTER(ctypes.c_void_p),
+                                 ctypes.POINTER(ctypes.c_uint64), ctypes.POINTER(ctypes.c_int32),
+                                 ctypes.POINTER(ctypes.c_int32)]
+_lib.rest_index_destroy.restype = None
+_lib.rest_index_destroy.argtypes = [ctypes.c_void_p]
+_lib.rest_retrieve_workspace_bytes.restype = ctypes.c_size_t
+_lib.rest_retrieve_workspace_bytes.argtypes = [ctypes.c_int32, ctypes.POINTER(rest_retrieve_params)]
+_lib.rest_retrieve.restype = ctypes.c_int32
+_lib.rest_retrieve.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32,
+                               ctypes.POINTER(rest_retrieve_params), ctypes.POINTER(rest_tree), ctypes.c_void_p,
+                               ctypes.c_size_t, ctypes.c_void_p]
+_lib.rest_tree_attention_workspace_bytes.restype = ctypes.c_size_t
+_lib.rest_tree_attention_workspace_bytes.argtypes = [ctypes.POINTER(rest_attn_desc)]
+_lib.rest_tree_attention.restype = ctypes.c_int32
+_lib.rest_tree_attention.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                     ctypes.POINTER(rest_attn_desc), ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+_lib.rest_accept.restype = ctypes.c_int32
+_lib.rest_accept.argtypes = [ctypes.c_void_p, ctypes.POINTER(rest_tree), ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+
+
+def rest_status_string(status: int) -> str:
+    return _lib.rest_status_string(int(status)).decode()
+
+
+def rest_version() -> str:
+    return _lib.rest_version().decode()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _dev(t: torch.Tensor, dtype=None) -> int:
+    if not t.is_cuda:
+        raise TypeError("expected a device tensor")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"expected {dtype}, got {t.dtype}")
+    return t.data_ptr()
+
+
+class RestIndex:
+    """Owns a rest_index handle; keeps the borrowed tensors alive."""
+
+    def __init__(self, handle: int, corpus: torch.Tensor, sa: torch.Tensor | None):
+        self.handle = handle
+        self._corpus = corpus
+        self._sa = sa
+
+    @property
+    def n_tokens(self) -> int:
+        return self.view()[2]
+
+    def view(self):
+        c, s = ctypes.c_void_p(), ctypes.c_void_p()
+        n, tb, sb = ctypes.c_uint64(), ctypes.c_int32(), ctypes.c_int32()
+        st = _lib.rest_index_view(self.handle, ctypes.byref(c), ctypes.byref(s), ctypes.byref(n), ctypes.byref(tb),
+                                  ctypes.byref(sb))
+        if st != REST_OK:
+            raise RestError(st, "rest_index_view")
+        return c.value, s.value, n.value, tb.value, sb.value
+
+    def suffix_array(self) -> torch.Tensor:
+        """Device copy of the suffix array held by the handle (int32 or int64)."""
+        _, s, n, _, sb = self.view()
+
+        class _Raw:
+            __cuda_array_interface__ = {"shape": (n,), "typestr": "<i4" if sb == 4 else "<i8",
+                                        "data": (s, False), "version": 2}
+
+        return torch.as_tensor(_Raw(), device=self._corpus.device).clone()
+
+    def destroy(self):
+        if self.handle:
+            _lib.rest_index_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+def _token_bytes(corpus: torch.Tensor) -> int:
+    if corpus.dtype == torch.int32:
+        return 4
+    if corpus.dtype in (torch.uint16, torch.int16):
+        return 2
+    raise TypeError("corpus must be int32 or uint16")
+
+
+def rest_build_index(corpus: torch.Tensor, sa_bytes: int = 4) -> RestIndex:
+    """corpus: contiguous 1-D device tensor of int32 or uint16 tokens."""
+    assert corpus.is_contiguous() and corpus.dim() == 1
+    h = ctypes.c_void_p()
+    st = _lib.rest_build_index(_dev(corpus), corpus.numel(), _token_bytes(corpus), sa_bytes, _stream(), ctypes.byref(h))
+    if st != REST_OK:
+        raise RestError(st, "rest_build_index")
+    return RestIndex(h.value, corpus, None)
+
+
+def rest_index_from_sa(corpus: torch.Tensor, sa: torch.Tensor) -> RestIndex:
+    assert corpus.is_contiguous() and sa.is_contiguous() and corpus.numel() == sa.numel()
+    sa_bytes = {torch.int32: 4, torch.int64: 8}[sa.dtype]
+    h = ctypes.c_void_p()
+    st = _lib.rest_index_from_sa(_dev(corpus), _dev(sa), corpus.numel(), _token_bytes(corpus), sa_bytes, _stream(),
+                                 ctypes.byref(h))
+    if st != REST_OK:
+        raise RestError(st, "rest_index_from_sa")
+    return RestIndex(h.value, corpus, sa)
+
+
+@dataclass
+class Tree:
+    """Device buffers of rest_tree for B contexts with node capacity c."""
+    draft_tokens: torch.Tensor
+    parent_idx: torch.Tensor
+    pos_ids: torch.Tensor
+    node_weight: torch.Tensor
+    tree_mask: torch.Tensor
+    n_nodes: torch.Tensor
+    matched_len: torch.Tensor
+    match_count: torch.Tensor
+
+    @staticmethod
+    def empty(B: int, c: int, device="cuda", fill: int | None = None) -> "Tree":
+        words = (c + 63) // 64
+        mk = (lambda shape, dt: torch.empty(shape, dtype=dt, device=device)) if fill is None else \
+             (lambda shape, dt: torch.full(shape, fill, dtype=dt, device=device))
+        return Tree(mk((B, c), torch.int32), mk((B, c), torch.int32), mk((B, c), torch.int32), mk((B, c), torch.int32),
+                    mk((B, c, words), torch.int64), mk((B,), torch.int32), mk((B,), torch.int32), mk((B,), torch.int64))
+
+    def as_struct(self) -> rest_tree:
+        return rest_tree(self.draft_tokens.data_ptr(), self.parent_idx.data_ptr(), self.pos_ids.data_ptr(),
+                         self.node_weight.data_ptr(), self.tree_mask.data_ptr(), self.n_nodes.data_ptr(),
+                         self.matched_len.data_ptr(), self.match_count.data_ptr())
+
+
+def rest_retrieve_workspace_bytes(B: int, n_max=16, n_min=2, max_matches=5000, cont_len=10, max_nodes=64) -> int:
+    prm = rest_retrieve_params(n_max, n_min, max_matches, cont_len, max_nodes)
+    return _lib.rest_retrieve_workspace_bytes(B, ctypes.byref(prm))
+
+
+def rest_retrieve(index: RestIndex, contexts: torch.Tensor, ctx_len: torch.Tensor, out: Tree | None = None,
+                  n_max=16, n_min=2, max_matches=5000, cont_len=10, max_nodes=64,
+                  workspace: torch.Tensor | None = None) -> Tree:
+    """contexts [B, ctx_stride] int32, ctx_len [B] int32 (device).  Enqueues on the current stream."""
+    assert contexts.dim() == 2 and contexts.is_contiguous() and ctx_len.is_contiguous()
+    B, stride = contexts.shape
+    if out is None:
+        out = Tree.empty(B, max_nodes, contexts.device)
+    prm = rest_retrieve_params(n_max, n_min, max_matches, cont_len, max_nodes)
+    tree = out.as_struct()
+    ws_ptr = workspace.data_ptr() if workspace is not None else None
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    st = _lib.rest_retrieve(index.handle, _dev(contexts, torch.int32), _dev(ctx_len, torch.int32), B, stride,
+                            ctypes.byref(prm), ctypes.byref(tree), ws_ptr, ws_bytes, _stream())
+    if st != REST_OK:
+        raise RestError(st, "rest_retrieve")
+    return out
+
+
+def make_attn_desc(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, out: torch.Tensor, prefix_len: int,
+                   scale: float, mask_per_batch: bool, num_splits: int = 0) -> rest_attn_desc:
+    Nb, H, Tq, D = q.shape
+    Lk = k.shape[2]
+    dt = {torch.bfloat16: REST_BF16, torch.float32: REST_FP32}[q.dtype]
+    d = rest_attn_desc()
+    d.Nb, d.H, d.Tq, d.Tk, d.P, d.D = Nb, H, Tq, Lk - prefix_len, prefix_len, D
+    d.dtype = dt
+    d.scale = scale
+    for name, t in (("q_stride", q), ("k_stride", k), ("v_stride", v), ("o_stride", out)):
+        assert t.stride(3) == 1
+        getattr(d, name)[:] = [t.stride(0), t.stride(1), t.stride(2)]
+    d.mask_per_batch = 1 if mask_per_batch else 0
+    d.num_splits = num_splits
+    return d
+
+
+def rest_tree_attention_workspace_bytes(desc: rest_attn_desc) -> int:
+    return _lib.rest_tree_attention_workspace_bytes(ctypes.byref(desc))
+
+
+def rest_tree_attention(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, mask: torch.Tensor, prefix_len: int,
+                        scale: float, out: torch.Tensor | None = None, num_splits: int = 0,
+                        workspace: torch.Tensor | None = None) -> torch.Tensor:
+    """q [Nb,H,Tq,128]; k, v [Nb,H,P+Tk,128] (bf16 or fp32, device); mask [Tq,words] or [Nb,Tq,words] int64/uint64.
+    Enqueues on the current stream."""
+    assert q.dim() == 4 and k.dim() == 4 and v.dim() == 4 and k.shape == v.shape
+    if out is None:
+        out = torch.empty_like(q)
+    per_batch = mask.dim() == 3
+    desc = make_attn_desc(q, k, v, out, prefix_len, scale, per_batch, num_splits)
+    need = rest_tree_attention_workspace_bytes(desc)
+    if workspace is None and need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    ws_ptr = workspace.data_ptr() if workspace is not None else None
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    st = _lib.rest_tree_attention(_dev(q), _dev(k), _dev(v), _dev(mask) if mask.numel() else None, _dev(out),
+                                  ctypes.byref(desc), ws_ptr, ws_bytes, _stream())
+    if st != REST_OK:
+        raise RestError(st, "rest_tree_attention")
+    return out
+
+
+def rest_accept(ids: torch.Tensor, tree: Tree, path_cap: int,
+                accept_len: torch.Tensor | None = None, accept_path: torch.Tensor | None = None,
+                next_token: torch.Tensor | None = None):
+    """ids [B, 1+c] int32 (device).  Returns (accept_len [B], accept_path [B, path_cap], next_token [B])."""
+    B, c1 = ids.shape
+    c = c1 - 1
+    dev = ids.device
+    accept_len = accept_len if accept_len is not None else torch.empty(B, dtype=torch.int32, device=dev)
+    accept_path = accept_path if accept_path is not None else torch.empty((B, path_cap), dtype=torch.int32, device=dev)
+    next_token = next_token if next_token is not None else torch.empty(B, dtype=torch.int32, device=dev)
+    ts = tree.as_struct()
+    st = _lib.rest_accept(_dev(ids, torch.int32), ctypes.byref(ts), B, c, path_cap, _dev(accept_len), _dev(accept_path),
+                          _dev(next_token), _stream())
+    if st != REST_OK:
+        raise RestError(st, "rest_accept")
+    return accept_len, accept_path, next_token

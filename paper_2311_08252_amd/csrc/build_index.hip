@@ -1,0 +1,353 @@
+// rest_build_index for gfx950: the suffix array of the token stream ("Datastore construction" and the
+// suffix-array exact match of "Retrieving from the datastore", REST, arXiv 2311.08252), built on the GPU
+// by prefix doubling (Manber & Myers' idea) where every round is an LSD radix sort.
+//
+// Round with step h: rank[i] orders suffix i by its first h tokens (0 = past the end of the stream, which
+// makes the end smaller than every token).  Sorting positions by the 64-bit key (rank[i], rank[i+h])
+// orders them by their first 2h tokens; new ranks are the index of the first member of each run of equal
+// keys.  The first round uses token + 1 as rank.  Rounds stop when every key is distinct.
+//
+// Radix sort: 8-bit digits, three kernels per digit (per-tile digit histogram, exclusive scan over
+// (digit, tile), stable scatter).  Inside a wavefront, lanes holding the same digit find each other with
+// eight ballots, so ranking needs no LDS atomics.  No kernel spins on another workgroup.
+#include "common.h"
+
+namespace {
+
+constexpr int kSortThreads = 256;
+constexpr int kScanChunk = 2048;
+
+template <typename TokT>
+__global__ void init_rank_kernel(const TokT* corpus, uint64_t n, uint32_t* rank, uint32_t* max_out) {
+    uint32_t mx = 0;
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (uint64_t)gridDim.x * blockDim.x) {
+        const uint32_t r = (uint32_t)corpus[i] + 1u;
+        rank[i] = r;
+        mx = r > mx ? r : mx;
+    }
+    for (int off = 32; off > 0; off >>= 1) {
+        uint32_t y = __shfl_xor(mx, off, 64);
+        mx = y > mx ? y : mx;
+    }
+    if ((threadIdx.x & 63) == 0) atomicMax(max_out, mx);
+}
+
+__global__ void make_keys_kernel(const uint32_t* rank, uint64_t n, uint64_t h, uint64_t* key, uint32_t* val) {
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (uint64_t)gridDim.x * blockDim.x) {
+        const uint32_t second = i + h < n ? rank[i + h] : 0u;
+        key[i] = ((uint64_t)rank[i] << 32) | second;
+        val[i] = (uint32_t)i;
+    }
+}
+
+// lanes of the wavefront that are valid and hold the same 8-bit digit as this lane
+__device__ inline uint64_t match_digit(uint32_t digit, bool valid) {
+    uint64_t m = __ballot(valid);
+#pragma unroll
+    for (int b = 0; b < 8; b++) {
+        const bool bit = (digit >> b) & 1u;
+        const uint64_t bb = __ballot(bit);
+        m &= bit ? bb : ~bb;
+    }
+    return m;
+}
+
+// per-tile digit histogram, stored digit-major: hist[digit * ntiles + tile]
+__global__ __launch_bounds__(kSortThreads) void radix_hist_kernel(const uint64_t* key, uint64_t n, int shift,
+                                                                   uint32_t tile, uint32_t ntiles, uint32_t* hist) {
+    __shared__ uint32_t cnt[256];
+    const int tid = threadIdx.x, lane = tid & 63;
+    cnt[tid] = 0;
+    __syncthreads();
+    const uint64_t base = (uint64_t)blockIdx.x * tile;
+    for (uint32_t s = 0; s < tile; s += kSortThreads) {
+        const uint64_t i = base + s + tid;
+        const bool valid = i < n;
+        const uint32_t d = valid ? (uint32_t)(key[i] >> shift) & 255u : 0u;
+        const uint64_t m = match_digit(d, valid);
+        if (valid && (m & ((1ull << lane) - 1ull)) == 0) atomicAdd(&cnt[d], (uint32_t)__popcll(m));
+    }
+    __syncthreads();
+    hist[(uint64_t)tid * ntiles + blockIdx.x] = cnt[tid];
+}
+
+// ---- exclusive scan (add) / inclusive scan (max) over uint32 arrays, three kernels, no spinning
+template <bool IS_MAX>
+__device__ inline uint32_t op(uint32_t a, uint32_t b) { return IS_MAX ? (a > b ? a : b) : a + b; }
+
+template <bool IS_MAX>
+__global__ __launch_bounds__(256) void scan_sums_kernel(const uint32_t* x, uint64_t n, uint32_t* sums) {
+    __shared__ uint32_t red[256];
+    const uint64_t base = (uint64_t)blockIdx.x * kScanChunk;
+    uint32_t a = 0;
+    for (int i = threadIdx.x; i < kScanChunk; i += 256)
+        if (base + i < n) a = op<IS_MAX>(a, x[base + i]);
+    red[threadIdx.x] = a;
+    __syncthreads();
+    for (int st = 128; st > 0; st >>= 1) {
+        if ((int)threadIdx.x < st) red[threadIdx.x] = op<IS_MAX>(red[threadIdx.x], red[threadIdx.x + st]);
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) sums[blockIdx.x] = red[0];
+}
+
+// exclusive scan of `sums` in place by one workgroup (each thread owns a contiguous run)
+template <bool IS_MAX>
+__global__ __launch_bounds__(1024) void scan_top_kernel(uint32_t* sums, uint64_t n) {
+    __shared__ uint32_t tot[1024];
+    const uint64_t per = (n + 1023) / 1024;
+    const uint64_t b0 = (uint64_t)threadIdx.x * per;
+    uint32_t a = 0;
+    for (uint64_t i = 0; i < per; i++)
+        if (b0 + i < n) a = op<IS_MAX>(a, sums[b0 + i]);
+    tot[threadIdx.x] = a;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t run = 0;
+        for (int i = 0; i < 1024; i++) {
+            const uint32_t v = tot[i];
+            tot[i] = run;
+            run = op<IS_MAX>(run, v);
+        }
+    }
+    __syncthreads();
+    uint32_t run = tot[threadIdx.x];
+    for (uint64_t i = 0; i < per; i++)
+        if (b0 + i < n) {
+            const uint32_t v = sums[b0 + i];
+            sums[b0 + i] = run;
+            run = op<IS_MAX>(run, v);
+        }
+}
+
+// add: x becomes its exclusive prefix sum; max: x becomes its inclusive prefix maximum
+template <bool IS_MAX>
+__global__ __launch_bounds__(256) void scan_apply_kernel(uint32_t* x, uint64_t n, const uint32_t* sums) {
+    __shared__ uint32_t part[256];
+    const uint64_t base = (uint64_t)blockIdx.x * kScanChunk;
+    constexpr int per = kScanChunk / 256;
+    const uint64_t b0 = base + (uint64_t)threadIdx.x * per;
+    uint32_t v[per];
+    uint32_t a = 0;
+#pragma unroll
+    for (int i = 0; i < per; i++) {
+        v[i] = b0 + i < n ? x[b0 + i] : 0u;
+        a = op<IS_MAX>(a, v[i]);
+    }
+    part[threadIdx.x] = a;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t run = sums[blockIdx.x];
+        for (int i = 0; i < 256; i++) {
+            const uint32_t t = part[i];
+            part[i] = run;
+            run = op<IS_MAX>(run, t);
+        }
+    }
+    __syncthreads();
+    uint32_t run = part[threadIdx.x];
+#pragma unroll
+    for (int i = 0; i < per; i++) {
+        if (IS_MAX) {
+            run = op<true>(run, v[i]);
+            if (b0 + i < n) x[b0 + i] = run;
+        } else {
+            if (b0 + i < n) x[b0 + i] = run;
+            run += v[i];
+        }
+    }
+}
+
+// stable scatter of one tile by digit
+__global__ __launch_bounds__(kSortThreads) void radix_scatter_kernel(const uint64_t* key_in, const uint32_t* val_in,
+                                                                      uint64_t* key_out, uint32_t* val_out, uint64_t n,
+                                                                      int shift, uint32_t tile, uint32_t ntiles,
+                                                                      const uint32_t* offsets) {
+    __shared__ uint32_t base[256];
+    __shared__ uint32_t wcount[4][256];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    base[tid] = offsets[(uint64_t)tid * ntiles + blockIdx.x];
+#pragma unroll
+    for (int w = 0; w < 4; w++) wcount[w][tid] = 0;
+    __syncthreads();
+    const uint64_t tbase = (uint64_t)blockIdx.x * tile;
+    for (uint32_t s = 0; s < tile; s += kSortThreads) {
+        const uint64_t i = tbase + s + tid;
+        const bool valid = i < n;
+        uint64_t k = 0;
+        uint32_t v = 0;
+        if (valid) { k = key_in[i]; v = val_in[i]; }
+        const uint32_t d = (uint32_t)(k >> shift) & 255u;
+        const uint64_t m = match_digit(d, valid);
+        const uint32_t before = (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
+        if (valid && before == 0) wcount[wave][d] = (uint32_t)__popcll(m);
+        __syncthreads();
+        if (valid) {
+            uint32_t pre = 0;
+            for (int w = 0; w < wave; w++) pre += wcount[w][d];
+            const uint32_t dst = base[d] + pre + before;
+            key_out[dst] = k;
+            val_out[dst] = v;
+        }
+        __syncthreads();
+        uint32_t add = 0;
+#pragma unroll
+        for (int w = 0; w < 4; w++) { add += wcount[w][tid]; wcount[w][tid] = 0; }
+        base[tid] += add;
+        __syncthreads();
+    }
+}
+
+// grp[j] = j if sorted key j starts a new run else 0; counts the runs
+__global__ __launch_bounds__(256) void heads_kernel(const uint64_t* key, uint64_t n, uint32_t* grp, unsigned long long* n_runs) {
+    uint32_t local = 0;
+    for (uint64_t j = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; j < n; j += (uint64_t)gridDim.x * blockDim.x) {
+        const bool head = j == 0 || key[j] != key[j - 1];
+        grp[j] = head ? (uint32_t)j : 0u;
+        local += head ? 1u : 0u;
+    }
+    for (int off = 32; off > 0; off >>= 1) local += __shfl_xor(local, off, 64);
+    if ((threadIdx.x & 63) == 0 && local) atomicAdd(n_runs, (unsigned long long)local);
+}
+
+__global__ void assign_rank_kernel(const uint32_t* val, const uint32_t* grp, uint64_t n, uint32_t* rank) {
+    for (uint64_t j = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; j < n; j += (uint64_t)gridDim.x * blockDim.x)
+        rank[val[j]] = grp[j] + 1u;
+}
+
+template <typename SaT>
+__global__ void write_sa_kernel(const uint32_t* val, uint64_t n, SaT* sa) {
+    for (uint64_t j = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; j < n; j += (uint64_t)gridDim.x * blockDim.x)
+        sa[j] = (SaT)val[j];
+}
+
+template <bool IS_MAX>
+rest_status scan_u32(uint32_t* x, uint64_t n, uint32_t* sums, hipStream_t st) {
+    const uint64_t chunks = (n + kScanChunk - 1) / kScanChunk;
+    hipLaunchKernelGGL(scan_sums_kernel<IS_MAX>, dim3((unsigned)chunks), dim3(256), 0, st, x, n, sums);
+    hipLaunchKernelGGL(scan_top_kernel<IS_MAX>, dim3(1), dim3(1024), 0, st, sums, chunks);
+    hipLaunchKernelGGL(scan_apply_kernel<IS_MAX>, dim3((unsigned)chunks), dim3(256), 0, st, x, n, sums);
+    REST_HIP_TRY(hipGetLastError());
+    return REST_OK;
+}
+
+int bit_length(uint64_t x) {
+    int b = 0;
+    while (x) { b++; x >>= 1; }
+    return b;
+}
+
+struct Scratch {
+    uint64_t* key[2] = {nullptr, nullptr};
+    uint32_t* val[2] = {nullptr, nullptr};
+    uint32_t* rank = nullptr;
+    uint32_t* hist = nullptr;
+    uint32_t* sums = nullptr;
+    unsigned long long* counters = nullptr;
+    void* sa = nullptr;
+    ~Scratch() {
+        for (int i = 0; i < 2; i++) { if (key[i]) (void)hipFree(key[i]); if (val[i]) (void)hipFree(val[i]); }
+        if (rank) (void)hipFree(rank);
+        if (hist) (void)hipFree(hist);
+        if (sums) (void)hipFree(sums);
+        if (counters) (void)hipFree(counters);
+        if (sa) (void)hipFree(sa);
+    }
+};
+
+#define REST_ALLOC(ptr, bytes)                                   \
+    do {                                                         \
+        if (hipMalloc((void**)&(ptr), (bytes)) != hipSuccess) {  \
+            (void)hipGetLastError();                             \
+            return REST_OUT_OF_MEMORY;                           \
+        }                                                        \
+    } while (0)
+
+}  // namespace
+
+extern "C" __attribute__((visibility("default"))) rest_status rest_build_index(const void* d_corpus, uint64_t n, int32_t token_bytes, int32_t sa_bytes,
+                                        void* stream_, rest_index** out) {
+    if (!d_corpus || !out) return REST_INVALID_ARG;
+    if (token_bytes != 2 && token_bytes != 4) return REST_INVALID_ARG;
+    if (sa_bytes != 4 && sa_bytes != 8) return REST_INVALID_ARG;
+    if (n < 1 || n > 0xFFFFFFFEull) return REST_INVALID_ARG;
+    if (sa_bytes == 4 && n >= (1ull << 31)) return REST_INVALID_ARG;
+    hipStream_t st = (hipStream_t)stream_;
+
+    // tiles: multiples of 256 elements, at most 32768 tiles
+    uint64_t tile64 = (n + 32767) / 32768;
+    tile64 = ((tile64 + kSortThreads - 1) / kSortThreads) * kSortThreads;
+    if (tile64 < 4096) tile64 = 4096;
+    const uint32_t tile = (uint32_t)tile64;
+    const uint32_t ntiles = (uint32_t)((n + tile - 1) / tile);
+    const uint64_t hist_n = (uint64_t)256 * ntiles;
+    const uint64_t sums_n = ((n > hist_n ? n : hist_n) + kScanChunk - 1) / kScanChunk;
+
+    Scratch s;
+    for (int i = 0; i < 2; i++) { REST_ALLOC(s.key[i], n * 8); REST_ALLOC(s.val[i], n * 4); }
+    REST_ALLOC(s.rank, n * 4);
+    REST_ALLOC(s.hist, hist_n * 4);
+    REST_ALLOC(s.sums, sums_n * 4);
+    REST_ALLOC(s.counters, 16);
+    REST_ALLOC(s.sa, n * (uint64_t)sa_bytes);
+
+    const unsigned gs = (unsigned)((n + 255) / 256 < 65536 ? (n + 255) / 256 : 65536);
+    REST_HIP_TRY(hipMemsetAsync(s.counters, 0, 16, st));
+    if (token_bytes == 2)
+        hipLaunchKernelGGL(init_rank_kernel<uint16_t>, dim3(gs), dim3(256), 0, st, (const uint16_t*)d_corpus, n, s.rank, (uint32_t*)s.counters);
+    else
+        hipLaunchKernelGGL(init_rank_kernel<int32_t>, dim3(gs), dim3(256), 0, st, (const int32_t*)d_corpus, n, s.rank, (uint32_t*)s.counters);
+    REST_HIP_TRY(hipGetLastError());
+    uint32_t max_rank = 0;
+    REST_HIP_TRY(hipMemcpyAsync(&max_rank, s.counters, 4, hipMemcpyDeviceToHost, st));
+    REST_HIP_TRY(hipStreamSynchronize(st));
+
+    int cur = 0;
+    for (uint64_t h = 1;; h *= 2) {
+        const int bits = bit_length(max_rank);
+        const int passes_half = (bits + 7) / 8;
+        hipLaunchKernelGGL(make_keys_kernel, dim3(gs), dim3(256), 0, st, s.rank, n, h, s.key[0], s.val[0]);
+        REST_HIP_TRY(hipGetLastError());
+        cur = 0;
+        for (int half = 0; half < 2; half++) {
+            for (int ps = 0; ps < passes_half; ps++) {
+                const int shift = half * 32 + ps * 8;
+                hipLaunchKernelGGL(radix_hist_kernel, dim3(ntiles), dim3(kSortThreads), 0, st, s.key[cur], n, shift, tile, ntiles, s.hist);
+                REST_HIP_TRY(hipGetLastError());
+                rest_status rs = scan_u32<false>(s.hist, hist_n, s.sums, st);
+                if (rs != REST_OK) return rs;
+                hipLaunchKernelGGL(radix_scatter_kernel, dim3(ntiles), dim3(kSortThreads), 0, st, s.key[cur], s.val[cur],
+                                   s.key[cur ^ 1], s.val[cur ^ 1], n, shift, tile, ntiles, s.hist);
+                REST_HIP_TRY(hipGetLastError());
+                cur ^= 1;
+            }
+        }
+        // runs of equal keys -> new ranks
+        uint32_t* grp = s.val[cur ^ 1];
+        REST_HIP_TRY(hipMemsetAsync(s.counters, 0, 16, st));
+        hipLaunchKernelGGL(heads_kernel, dim3(gs), dim3(256), 0, st, s.key[cur], n, grp, s.counters);
+        REST_HIP_TRY(hipGetLastError());
+        unsigned long long runs = 0;
+        REST_HIP_TRY(hipMemcpyAsync(&runs, s.counters, 8, hipMemcpyDeviceToHost, st));
+        REST_HIP_TRY(hipStreamSynchronize(st));
+        if (runs == n || h >= n) break;
+        rest_status rs = scan_u32<true>(grp, n, s.sums, st);
+        if (rs != REST_OK) return rs;
+        hipLaunchKernelGGL(assign_rank_kernel, dim3(gs), dim3(256), 0, st, s.val[cur], grp, n, s.rank);
+        REST_HIP_TRY(hipGetLastError());
+        max_rank = (uint32_t)n;
+    }
+
+    if (sa_bytes == 4) hipLaunchKernelGGL(write_sa_kernel<int32_t>, dim3(gs), dim3(256), 0, st, s.val[cur], n, (int32_t*)s.sa);
+    else hipLaunchKernelGGL(write_sa_kernel<int64_t>, dim3(gs), dim3(256), 0, st, s.val[cur], n, (int64_t*)s.sa);
+    REST_HIP_TRY(hipGetLastError());
+    REST_HIP_TRY(hipStreamSynchronize(st));
+
+    rest_index* idx = nullptr;
+    rest_status rs = rest_index_from_sa(d_corpus, s.sa, n, token_bytes, sa_bytes, stream_, &idx);
+    if (rs != REST_OK) return rs;
+    idx->owns_sa = 1;
+    s.sa = nullptr;   // ownership moved to the handle
+    *out = idx;
+    return REST_OK;
+}

@@ -1,0 +1,572 @@
+// rest_retrieve for gfx950: Algorithm 1 (longest matching suffix via the suffix array), continuation
+// gather, Algorithm 2 (Trie weights and top-c nodes) and the breadth-first layout with its tree mask
+// ("Draft verification") of REST, arXiv 2311.08252 -- one kernel launch, one 1024-thread workgroup per context.
+//
+// Phase A, search.  Wavefront w looks for the suffix of length n = n_max - w; the fifteen lengths are
+// independent searches (a shorter suffix of s is not a prefix of a longer one, so their suffix-array ranges
+// do not nest) and run concurrently.  A search is 65-ary: the 64 lanes probe 64 pivots of the current
+// rank interval at once and a ballot picks the sub-interval, so 10^8 ranks take 2 LDS levels plus 3 rounds of
+// dependent global reads instead of 27.  The two top levels come from a table of 1023 sampled suffix keys
+// (first 16 tokens each) that sits in LDS.  Lower and upper bound share probes.
+//
+// Phase B, Trie without a Trie.  The kept occurrences are consecutive suffix-array ranks, hence already in
+// lexicographic order, so the Trie is implicit in the longest-common-prefix array of adjacent candidates:
+// a node at depth d starts at row r iff lcp[r] < d <= len[r], and its weight is the distance to the next row
+// with lcp < d.  Per-depth segment-start bitmaps are built with wavefront ballots; weights are bit scans.
+// Top-c is a three-level counting select on the order (weight desc, depth asc, row asc): weight histogram,
+// depth histogram inside the boundary weight, row rank inside the boundary depth.
+#include "common.h"
+
+namespace {
+
+constexpr int kThreads = 1024;
+constexpr int kWavesPerWG = 16;
+constexpr int kTopMax = 1023;        // sampled suffix keys cached in LDS (64 KB as int32[16])
+constexpr int kKeyLen = REST_MAX_SUFFIX_LEN;
+
+struct RetrieveParams {
+    const void* corpus;
+    const void* sa;
+    const int32_t* top_keys;
+    uint64_t n_tokens;
+    int32_t top_count;
+    const int32_t* contexts;
+    const int32_t* ctx_len;
+    int32_t ctx_stride;
+    int32_t n_max, n_min, K, m, c, mask_words;
+    rest_tree out;
+    // LDS layout of phase B (byte offsets into dynamic LDS)
+    int32_t words;        // bitmap words per depth = K/64 + 1
+    int32_t off_seg, off_lcp, off_len, off_hist, off_part, off_sel, off_misc;
+};
+
+template <typename TokT>
+__device__ inline int32_t load_tok(const void* corpus, uint64_t n, uint64_t pos) {
+    return pos < n ? (int32_t)((const TokT*)corpus)[pos] : -1;
+}
+
+template <typename SaT>
+__device__ inline uint32_t load_sa(const void* sa, uint32_t rank) {
+    return (uint32_t)((const SaT*)sa)[rank];
+}
+
+// three-way comparison of the first n tokens of the suffix at `pos` with q (end of stream = -1 < every token)
+template <typename TokT>
+__device__ inline int cmp_suffix(const void* corpus, uint64_t ntok, uint32_t pos, const int32_t (&q)[kKeyLen], int n) {
+    int32_t a[kKeyLen];
+#pragma unroll
+    for (int j = 0; j < kKeyLen; j++) a[j] = j < n ? load_tok<TokT>(corpus, ntok, (uint64_t)pos + j) : 0;
+    int cmp = 0;
+#pragma unroll
+    for (int j = kKeyLen - 1; j >= 0; j--)
+        if (j < n && a[j] != q[j]) cmp = a[j] < q[j] ? -1 : 1;
+    return cmp;
+}
+
+__device__ inline int cmp_key(const int32_t* key, const int32_t (&q)[kKeyLen], int n) {
+    int cmp = 0;
+#pragma unroll
+    for (int j = kKeyLen - 1; j >= 0; j--)
+        if (j < n && key[j] != q[j]) cmp = key[j] < q[j] ? -1 : 1;
+    return cmp;
+}
+
+__device__ inline int popc64(uint64_t x) { return __popcll(x); }
+
+// One wavefront: [lo, hi) = ranks of the suffixes whose first n tokens equal q.
+template <typename TokT, typename SaT>
+__device__ void wave_search(const RetrieveParams& p, const int32_t* lds_top, const int32_t (&q)[kKeyLen], int n,
+                            uint32_t& out_lo, uint32_t& out_hi) {
+    const int lane = threadIdx.x & 63;
+    const uint32_t N = (uint32_t)p.n_tokens;
+    const int tc = p.top_count;
+    // ---- two levels in LDS: 64 coarse pivots (every 16th sampled key), then the 15 keys of one group
+    int cnt_lt = 0, cnt_le = 0;
+    if (tc > 0) {
+        int ci = 16 * lane + 15;
+        int c = ci < tc ? cmp_key(lds_top + ci * kKeyLen, q, n) : 1;
+        int g_lt = popc64(__ballot(c < 0)), g_le = popc64(__ballot(c <= 0));
+        int f_lt = 16 * g_lt + lane, f_le = 16 * g_le + lane;
+        int c1 = (lane < 15 && f_lt < tc) ? cmp_key(lds_top + f_lt * kKeyLen, q, n) : 1;
+        cnt_lt = 16 * g_lt + popc64(__ballot(c1 < 0));
+        int c2 = (lane < 15 && f_le < tc) ? cmp_key(lds_top + f_le * kKeyLen, q, n) : 1;
+        cnt_le = 16 * g_le + popc64(__ballot(c2 <= 0));
+    }
+    // invariants: ranks < a_lo compare <, ranks >= b_lo compare >=; ranks < a_hi compare <=, ranks >= b_hi compare >
+    uint32_t a_lo = cnt_lt ? (uint32_t)rest_top_rank(N, tc, cnt_lt - 1) + 1 : 0;
+    uint32_t b_lo = cnt_lt < tc ? (uint32_t)rest_top_rank(N, tc, cnt_lt) : N;
+    uint32_t a_hi = cnt_le ? (uint32_t)rest_top_rank(N, tc, cnt_le - 1) + 1 : 0;
+    uint32_t b_hi = cnt_le < tc ? (uint32_t)rest_top_rank(N, tc, cnt_le) : N;
+
+    for (int pass = 0; pass < 2; pass++) {
+        // pass 0 narrows [a_lo, b_lo] to the lower bound, pass 1 narrows [a_hi, b_hi] to the upper bound
+        uint32_t a = pass == 0 ? a_lo : (a_hi > a_lo ? a_hi : a_lo);
+        uint32_t b = pass == 0 ? b_lo : b_hi;
+        while (a < b) {
+            const uint32_t len = b - a;
+            const bool fine = len <= 64;
+            uint32_t r = fine ? a + lane : a + (uint32_t)(((uint64_t)len * (lane + 1)) / 65);
+            const bool real = !fine || (uint32_t)lane < len;
+            int c = 1;
+            if (real) c = cmp_suffix<TokT>(p.corpus, p.n_tokens, load_sa<SaT>(p.sa, r), q, n);
+            const uint64_t m_real = __ballot(real);
+            const int n_real = popc64(m_real);
+            const int k_lt = popc64(__ballot(real && c < 0));
+            const int k_le = popc64(__ballot(real && c <= 0));
+            // ranks of the probes just below / at the boundary (probes are increasing in the lane index)
+            const int k_cur = pass == 0 ? k_lt : k_le;
+            const uint32_t r_below = __shfl(r, k_cur > 0 ? k_cur - 1 : 0, 64);
+            const uint32_t r_at = __shfl(r, k_cur < n_real ? k_cur : 0, 64);
+            if (pass == 0) {
+                // the same probes also tighten the upper-bound bracket
+                const uint32_t rb = __shfl(r, k_le > 0 ? k_le - 1 : 0, 64);
+                const uint32_t ra = __shfl(r, k_le < n_real ? k_le : 0, 64);
+                if (k_le > 0 && rb + 1 > a_hi) a_hi = rb + 1;
+                if (k_le < n_real && ra < b_hi) b_hi = ra;
+            }
+            if (k_cur > 0) a = r_below + 1;
+            if (k_cur < n_real) b = r_at;
+            else if (fine) b = a;   // every remaining rank was probed and lies below the bound
+        }
+        if (pass == 0) a_lo = a; else a_hi = a;
+    }
+    out_lo = a_lo;
+    out_hi = a_hi > a_lo ? a_hi : a_lo;
+}
+
+// position of the lowest set bit at or after bit index `from` in a bitmap that is known to contain one
+__device__ inline int next_set(const uint64_t* bm, int from) {
+    int w = from >> 6;
+    uint64_t x = bm[w] & (~0ull << (from & 63));
+    while (x == 0) x = bm[++w];
+    return (w << 6) + __builtin_ctzll(x);
+}
+
+// position of the highest set bit at or before `from` (bit 0 is always set)
+__device__ inline int prev_set(const uint64_t* bm, int from) {
+    int w = from >> 6;
+    uint64_t x = bm[w] & (~0ull >> (63 - (from & 63)));
+    while (x == 0) x = bm[--w];
+    return (w << 6) + 63 - __builtin_clzll(x);
+}
+
+template <typename TokT, typename SaT>
+__global__ __launch_bounds__(kThreads) void retrieve_kernel(RetrieveParams p) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    __shared__ uint32_t s_lo[kWavesPerWG], s_hi[kWavesPerWG];
+    __shared__ int32_t s_sel;        // wave (= suffix length) chosen
+    __shared__ int32_t s_misc[16];
+
+    const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int32_t* s = p.contexts + (int64_t)b * p.ctx_stride;
+    int t = p.ctx_len[b];
+    t = t < 0 ? 0 : (t > p.ctx_stride ? p.ctx_stride : t);
+
+    // ---------------- phase A: the sampled-key table goes to LDS, then one search per wavefront
+    int32_t* lds_top = (int32_t*)lds;
+    {
+        const int4* src = (const int4*)p.top_keys;
+        int4* dst = (int4*)lds_top;
+        for (int i = tid; i < p.top_count * (kKeyLen / 4); i += kThreads) dst[i] = src[i];
+    }
+    __syncthreads();
+    {
+        const int n = p.n_max - wave;
+        uint32_t lo = 0, hi = 0;
+        if (n >= p.n_min && n <= t) {
+            int32_t q[kKeyLen];
+#pragma unroll
+            for (int j = 0; j < kKeyLen; j++) q[j] = j < n ? s[t - n + j] : 0;
+            wave_search<TokT, SaT>(p, lds_top, q, n, lo, hi);
+        }
+        if (lane == 0) { s_lo[wave] = lo; s_hi[wave] = hi; }
+    }
+    __syncthreads();
+    if (tid == 0) {
+        int sel = -1;
+        for (int w = 0; w < kWavesPerWG; w++)
+            if (s_hi[w] > s_lo[w]) { sel = w; break; }     // wave 0 holds the longest suffix
+        s_sel = sel;
+    }
+    __syncthreads();
+
+    // ---------------- outputs of this context
+    const int c = p.c;
+    int32_t* o_tok = p.out.draft_tokens + (int64_t)b * c;
+    int32_t* o_par = p.out.parent_idx + (int64_t)b * c;
+    int32_t* o_pos = p.out.pos_ids + (int64_t)b * c;
+    int32_t* o_wgt = p.out.node_weight + (int64_t)b * c;
+    uint64_t* o_mask = p.out.tree_mask + (int64_t)b * c * p.mask_words;
+
+    const int sel = s_sel;
+    if (sel < 0) {
+        for (int i = tid; i < c; i += kThreads) { o_tok[i] = -1; o_par[i] = -1; o_pos[i] = 0; o_wgt[i] = 0; }
+        for (int i = tid; i < c * p.mask_words; i += kThreads) o_mask[i] = 0;
+        if (tid == 0) { p.out.n_nodes[b] = 0; p.out.matched_len[b] = 0; p.out.match_count[b] = 0; }
+        return;
+    }
+    const int n_star = p.n_max - sel;
+    const uint32_t lo = s_lo[sel], hi = s_hi[sel];
+    const int R = (int)((hi - lo) < (uint32_t)p.K ? (hi - lo) : (uint32_t)p.K);
+    const int m = p.m;
+    const int words = p.words;
+
+    // ---------------- phase B LDS (aliases the key table, which is dead now)
+    uint64_t* seg = (uint64_t*)(lds + p.off_seg);        // [m][words] segment-start bits per depth
+    uint8_t* lcp = (uint8_t*)(lds + p.off_lcp);          // [K]
+    uint8_t* rlen = (uint8_t*)(lds + p.off_len);         // [K]
+    uint32_t* hist = (uint32_t*)(lds + p.off_hist);      // [K + 1] nodes per weight
+    uint32_t* part = (uint32_t*)(lds + p.off_part);      // [1024] scan scratch
+    uint32_t* sel_key = (uint32_t*)(lds + p.off_sel);    // [c] (depth << 16 | row), then sorted
+    uint32_t* sel_wgt = sel_key + REST_MAX_NODES;        // [c]
+    uint32_t* srt_key = sel_wgt + REST_MAX_NODES;        // [c]
+    uint32_t* srt_wgt = srt_key + REST_MAX_NODES;        // [c]
+    int32_t* srt_par = (int32_t*)(srt_wgt + REST_MAX_NODES);  // [c]
+
+    for (int i = tid; i <= p.K; i += kThreads) hist[i] = 0;
+    if (tid < 16) s_misc[tid] = 0;
+
+    // ---- B1: gather candidates, adjacent LCP, per-depth segment bitmaps.  Rows >= R act as terminators.
+    const int row_words = (R >> 6) + 1;
+    for (int base = wave * 64; base < row_words * 64; base += kThreads) {
+        const int r = base + lane;
+        int32_t tok[REST_MAX_CONT_LEN];
+        int len = 0;
+        if (r < R) {
+            const uint64_t pos = (uint64_t)load_sa<SaT>(p.sa, lo + r) + n_star;
+            const uint64_t left = p.n_tokens > pos ? p.n_tokens - pos : 0;
+            len = left < (uint64_t)m ? (int)left : m;
+#pragma unroll
+            for (int j = 0; j < REST_MAX_CONT_LEN; j++) tok[j] = j < m ? load_tok<TokT>(p.corpus, p.n_tokens, pos + j) : -1;
+        } else {
+#pragma unroll
+            for (int j = 0; j < REST_MAX_CONT_LEN; j++) tok[j] = -1;
+        }
+        // previous row: the neighbouring lane's registers, or a second read for lane 0
+        int plen = __shfl_up(len, 1, 64);
+        int l = 0;
+        bool run = true;
+        uint64_t ppos = 0;
+        if (lane == 0 && r > 0 && r < R) {
+            ppos = (uint64_t)load_sa<SaT>(p.sa, lo + r - 1) + n_star;
+            const uint64_t left = p.n_tokens > ppos ? p.n_tokens - ppos : 0;
+            plen = left < (uint64_t)m ? (int)left : m;
+        }
+#pragma unroll
+        for (int j = 0; j < REST_MAX_CONT_LEN; j++) {
+            if (j < m) {
+                int32_t prev = __shfl_up(tok[j], 1, 64);
+                if (lane == 0 && r > 0 && r < R) prev = load_tok<TokT>(p.corpus, p.n_tokens, ppos + j);
+                run = run && j < len && j < plen && prev == tok[j];
+                l += run ? 1 : 0;
+            }
+        }
+        if (r == 0) l = 0;
+        if (r < R) { lcp[r] = (uint8_t)l; rlen[r] = (uint8_t)len; }
+        for (int d = 1; d <= m; d++) {
+            const uint64_t bits = __ballot(r >= R || l < d);
+            if (lane == 0) seg[(d - 1) * words + (base >> 6)] = bits;
+        }
+    }
+    __syncthreads();
+
+    // ---- B2: weight histogram over all Trie nodes (node (d, r): segment start at depth d with len >= d)
+    const int items = m * row_words;   // one item = (depth, 64-row word)
+    for (int it = wave; it < items; it += kWavesPerWG) {
+        const int d = it / row_words + 1, wi = it % row_words;
+        const int r = wi * 64 + lane;
+        const uint64_t* bm = seg + (d - 1) * words;
+        const bool node = r < R && ((bm[wi] >> lane) & 1ull) && rlen[r] >= d;
+        int w = 0;
+        if (node) w = next_set(bm, r + 1) - r;
+        const uint64_t ones = __ballot(node && w == 1);
+        if (lane == 0 && ones) atomicAdd(&hist[1], (uint32_t)popc64(ones));
+        if (node && w > 1) atomicAdd(&hist[w], 1u);
+    }
+    __syncthreads();
+
+    // ---- B3: boundary weight w*: the largest w with #(weight >= w) >= c (or 1 if the Trie has < c nodes)
+    {
+        const int per = (p.K + kThreads) / kThreads;           // bins per thread, covering 0..K
+        const int b0 = tid * per;
+        uint32_t own = 0;
+        for (int i = 0; i < per; i++) own += (b0 + i <= p.K) ? hist[b0 + i] : 0;
+        // suffix sums over threads: inclusive scan from the top
+        uint32_t x = own;
+        for (int off = 1; off < 64; off <<= 1) {
+            uint32_t y = __shfl_down(x, off, 64);
+            if (lane + off < 64) x += y;
+        }
+        if (lane == 0) part[wave] = x;
+        __syncthreads();
+        uint32_t above_waves = 0;
+        for (int w = wave + 1; w < kWavesPerWG; w++) above_waves += part[w];
+        const uint32_t incl = x + above_waves;        // nodes with weight bin >= b0
+        const uint32_t excl = incl - own;             // nodes with weight bin >= b0 + per
+        if (tid == 0) { s_misc[0] = 1; s_misc[1] = 0; s_misc[5] = (int32_t)incl; }
+        __syncthreads();
+        if (excl < (uint32_t)c && incl >= (uint32_t)c) {
+            uint32_t run_above = excl;
+            for (int i = per - 1; i >= 0; i--) {
+                const int w = b0 + i;
+                const uint32_t hw = w <= p.K ? hist[w] : 0;
+                if (run_above + hw >= (uint32_t)c) { s_misc[0] = w; s_misc[1] = (int32_t)run_above; break; }
+                run_above += hw;
+            }
+        }
+        __syncthreads();
+    }
+    const int total_nodes = s_misc[5];
+    const bool take_all = total_nodes <= c;
+    const int w_star = take_all ? 0 : s_misc[0];          // weight > w_star: always kept
+    const int need_w = take_all ? 0 : c - s_misc[1];      // nodes of weight w_star still to take
+
+    // ---- B4: inside weight w*, per-depth counts -> boundary depth d*
+    uint32_t* dcount = part + 64;      // [m + 1]
+    if (tid <= m) dcount[tid] = 0;
+    __syncthreads();
+    if (!take_all) {
+        for (int it = wave; it < items; it += kWavesPerWG) {
+            const int d = it / row_words + 1, wi = it % row_words;
+            const int r = wi * 64 + lane;
+            const uint64_t* bm = seg + (d - 1) * words;
+            const bool node = r < R && ((bm[wi] >> lane) & 1ull) && rlen[r] >= d;
+            const bool eq = node && (next_set(bm, r + 1) - r) == w_star;
+            const uint64_t e = __ballot(eq);
+            if (lane == 0 && e) atomicAdd(&dcount[d], (uint32_t)popc64(e));
+        }
+    }
+    __syncthreads();
+    if (tid == 0) {
+        int d_star = m + 1, need_d = 0, acc = 0;
+        if (!take_all) {
+            for (int d = 1; d <= m; d++) {
+                if (acc + (int)dcount[d] >= need_w) { d_star = d; need_d = need_w - acc; break; }
+                acc += (int)dcount[d];
+            }
+        }
+        s_misc[2] = d_star;
+        s_misc[3] = need_d;
+        s_misc[4] = 0;   // selection cursor
+    }
+    __syncthreads();
+    const int d_star = s_misc[2], need_d = s_misc[3];
+
+    // ---- B5: inside (w*, d*), rank by row: per-word counts and their exclusive prefix (one wavefront)
+    uint32_t* wpre = part + 128;       // [row_words]
+    if (!take_all && d_star <= m) {
+        const uint64_t* bm = seg + (d_star - 1) * words;
+        for (int wi = wave; wi < row_words; wi += kWavesPerWG) {
+            const int r = wi * 64 + lane;
+            const bool node = r < R && ((bm[wi] >> lane) & 1ull) && rlen[r] >= d_star;
+            const bool eq = node && (next_set(bm, r + 1) - r) == w_star;
+            const uint64_t e = __ballot(eq);
+            if (lane == 0) wpre[wi] = (uint32_t)popc64(e);
+        }
+        __syncthreads();
+        if (wave == 0) {
+            uint32_t carry = 0;
+            for (int base = 0; base < row_words; base += 64) {
+                const int wi = base + lane;
+                const uint32_t v = wi < row_words ? wpre[wi] : 0;
+                uint32_t x = v;
+                for (int off = 1; off < 64; off <<= 1) {
+                    uint32_t y = __shfl_up(x, off, 64);
+                    if (lane >= off) x += y;
+                }
+                if (wi < row_words) wpre[wi] = carry + x - v;
+                carry += __shfl(x, 63, 64);
+            }
+        }
+    }
+    __syncthreads();
+
+    // ---- B6: select
+    for (int it = wave; it < items; it += kWavesPerWG) {
+        const int d = it / row_words + 1, wi = it % row_words;
+        const int r = wi * 64 + lane;
+        const uint64_t* bm = seg + (d - 1) * words;
+        const bool node = r < R && ((bm[wi] >> lane) & 1ull) && rlen[r] >= d;
+        int w = 0;
+        if (node) w = next_set(bm, r + 1) - r;
+        bool keep = node && (take_all || w > w_star || (w == w_star && d < d_star));
+        if (!take_all && d == d_star) {
+            const uint64_t e = __ballot(node && w == w_star);
+            const int rank = (int)wpre[wi] + popc64(e & ((1ull << lane) - 1ull));
+            keep = keep || (node && w == w_star && rank < need_d);
+        }
+        const uint64_t km = __ballot(keep);
+        if (km) {
+            int basei = 0;
+            if (lane == 0) basei = atomicAdd(&s_misc[4], popc64(km));
+            basei = __shfl(basei, 0, 64);
+            if (keep) {
+                const int idx = basei + popc64(km & ((1ull << lane) - 1ull));
+                if (idx < c) { sel_key[idx] = ((uint32_t)d << 16) | (uint32_t)r; sel_wgt[idx] = (uint32_t)w; }
+            }
+        }
+    }
+    __syncthreads();
+    int T = s_misc[4];
+    T = T > c ? c : T;
+
+    // ---- B7: breadth-first order = ascending (depth, row); rank by counting, then parents, mask, tokens
+    if (tid < T) {
+        const uint32_t k = sel_key[tid];
+        int rank = 0;
+        for (int j = 0; j < T; j++) rank += sel_key[j] < k ? 1 : 0;
+        srt_key[rank] = k;
+        srt_wgt[rank] = sel_wgt[tid];
+    }
+    __syncthreads();
+    if (tid < T) {
+        const uint32_t k = srt_key[tid];
+        const int d = (int)(k >> 16), r = (int)(k & 0xffff);
+        int par = -1;
+        if (d > 1) {
+            const int rp = prev_set(seg + (d - 2) * words, r);
+            const uint32_t pk = ((uint32_t)(d - 1) << 16) | (uint32_t)rp;
+            for (int j = 0; j < tid; j++)
+                if (srt_key[j] == pk) par = j;
+        }
+        srt_par[tid] = par;
+    }
+    __syncthreads();
+    if (tid < c) {
+        uint64_t mw[REST_MAX_NODES / 64] = {0, 0, 0, 0};
+        if (tid < T) {
+            const uint32_t k = srt_key[tid];
+            const int d = (int)(k >> 16), r = (int)(k & 0xffff);
+            const uint64_t pos = (uint64_t)load_sa<SaT>(p.sa, lo + r) + n_star + (d - 1);
+            o_tok[tid] = load_tok<TokT>(p.corpus, p.n_tokens, pos);
+            o_par[tid] = srt_par[tid];
+            o_pos[tid] = d;
+            o_wgt[tid] = (int32_t)srt_wgt[tid];
+            int v = tid;
+            while (v >= 0) {
+                mw[v >> 6] |= 1ull << (v & 63);
+                v = srt_par[v];
+            }
+        } else {
+            o_tok[tid] = -1; o_par[tid] = -1; o_pos[tid] = 0; o_wgt[tid] = 0;
+        }
+        for (int w = 0; w < p.mask_words; w++) o_mask[(int64_t)tid * p.mask_words + w] = mw[w];
+    }
+    if (tid == 0) {
+        p.out.n_nodes[b] = T;
+        p.out.matched_len[b] = n_star;
+        p.out.match_count[b] = (int64_t)(hi - lo);
+    }
+}
+
+// Sampled-key table: key i = first 16 tokens (-1 past the end of the stream) of the suffix of rank
+// rest_top_rank(n, top_count, i).
+template <typename TokT, typename SaT>
+__global__ void top_table_kernel(const void* corpus, const void* sa, uint64_t n, int32_t top_count, int32_t* keys) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= top_count * kKeyLen) return;
+    const int k = i / kKeyLen, j = i % kKeyLen;
+    const uint32_t rank = (uint32_t)rest_top_rank(n, top_count, k);
+    const uint64_t pos = (uint64_t)load_sa<SaT>(sa, rank) + j;
+    keys[i] = load_tok<TokT>(corpus, n, pos);
+}
+
+bool params_ok(const rest_retrieve_params* q) {
+    if (!q) return false;
+    if (q->n_max < 1 || q->n_max > REST_MAX_SUFFIX_LEN || q->n_min < 1 || q->n_min > q->n_max) return false;
+    if (q->max_matches < 1 || q->max_matches > REST_MAX_MATCHES) return false;
+    if (q->cont_len < 1 || q->cont_len > REST_MAX_CONT_LEN) return false;
+    if (q->max_nodes < 1 || q->max_nodes > REST_MAX_NODES) return false;
+    return true;
+}
+
+size_t align16(size_t x) { return (x + 15) & ~(size_t)15; }
+
+template <typename TokT, typename SaT>
+rest_status launch(const RetrieveParams& p, int B, size_t lds_bytes, hipStream_t stream) {
+    auto kern = retrieve_kernel<TokT, SaT>;
+    REST_HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
+    hipLaunchKernelGGL(kern, dim3(B), dim3(kThreads), lds_bytes, stream, p);
+    REST_HIP_TRY(hipGetLastError());
+    return REST_OK;
+}
+
+}  // namespace
+
+rest_status rest_internal_make_top_table(rest_index* idx, hipStream_t stream) {
+    int tc = (int)(idx->n_tokens / 64 < (uint64_t)kTopMax ? idx->n_tokens / 64 : (uint64_t)kTopMax);
+    idx->top_count = tc;
+    // always allocate so the pointer is valid
+    if (hipMalloc((void**)&idx->d_top_keys, (size_t)(tc > 0 ? tc : 1) * kKeyLen * sizeof(int32_t)) != hipSuccess) {
+        (void)hipGetLastError();
+        idx->d_top_keys = nullptr;
+        return REST_OUT_OF_MEMORY;
+    }
+    if (tc > 0) {
+        const int total = tc * kKeyLen, blocks = (total + 255) / 256;
+        if (idx->token_bytes == 2 && idx->sa_bytes == 4)
+            hipLaunchKernelGGL((top_table_kernel<uint16_t, int32_t>), dim3(blocks), dim3(256), 0, stream, idx->d_corpus, idx->d_sa, idx->n_tokens, tc, idx->d_top_keys);
+        else if (idx->token_bytes == 2)
+            hipLaunchKernelGGL((top_table_kernel<uint16_t, int64_t>), dim3(blocks), dim3(256), 0, stream, idx->d_corpus, idx->d_sa, idx->n_tokens, tc, idx->d_top_keys);
+        else if (idx->sa_bytes == 4)
+            hipLaunchKernelGGL((top_table_kernel<int32_t, int32_t>), dim3(blocks), dim3(256), 0, stream, idx->d_corpus, idx->d_sa, idx->n_tokens, tc, idx->d_top_keys);
+        else
+            hipLaunchKernelGGL((top_table_kernel<int32_t, int64_t>), dim3(blocks), dim3(256), 0, stream, idx->d_corpus, idx->d_sa, idx->n_tokens, tc, idx->d_top_keys);
+        REST_HIP_TRY(hipGetLastError());
+    }
+    REST_HIP_TRY(hipStreamSynchronize(stream));
+    return REST_OK;
+}
+
+extern "C" __attribute__((visibility("default"))) size_t rest_retrieve_workspace_bytes(int32_t B, const rest_retrieve_params* params) {
+    // every intermediate lives in LDS; the workspace argument is kept in the ABI for forward compatibility
+    (void)B;
+    (void)params;
+    return 0;
+}
+
+extern "C" __attribute__((visibility("default"))) rest_status rest_retrieve(const rest_index* index, const int32_t* d_contexts, const int32_t* d_ctx_len,
+                                     int32_t B, int32_t ctx_stride, const rest_retrieve_params* q,
+                                     const rest_tree* out, void* d_workspace, size_t workspace_bytes, void* stream_) {
+    (void)d_workspace;
+    (void)workspace_bytes;
+    if (!index || !params_ok(q) || !out) return REST_INVALID_ARG;
+    if (B < 0 || ctx_stride < 0) return REST_INVALID_ARG;
+    if (B == 0) return REST_OK;
+    if (!d_contexts || !d_ctx_len) return REST_INVALID_ARG;
+    if (!out->draft_tokens || !out->parent_idx || !out->pos_ids || !out->node_weight || !out->tree_mask ||
+        !out->n_nodes || !out->matched_len || !out->match_count)
+        return REST_INVALID_ARG;
+
+    RetrieveParams p;
+    p.corpus = index->d_corpus;
+    p.sa = index->d_sa;
+    p.top_keys = index->d_top_keys;
+    p.n_tokens = index->n_tokens;
+    p.top_count = index->top_count;
+    p.contexts = d_contexts;
+    p.ctx_len = d_ctx_len;
+    p.ctx_stride = ctx_stride;
+    p.n_max = q->n_max; p.n_min = q->n_min; p.K = q->max_matches; p.m = q->cont_len; p.c = q->max_nodes;
+    p.mask_words = (q->max_nodes + 63) / 64;
+    p.out = *out;
+    p.words = p.K / 64 + 1;
+    size_t off = 0;
+    p.off_seg = (int32_t)off;  off = align16(off + (size_t)p.m * p.words * 8);
+    p.off_lcp = (int32_t)off;  off = align16(off + (size_t)p.K);
+    p.off_len = (int32_t)off;  off = align16(off + (size_t)p.K);
+    p.off_hist = (int32_t)off; off = align16(off + (size_t)(p.K + 1) * 4);
+    p.off_part = (int32_t)off; off = align16(off + (size_t)(128 + p.words + 64) * 4);
+    p.off_sel = (int32_t)off;  off = align16(off + (size_t)REST_MAX_NODES * 5 * 4);
+    p.off_misc = (int32_t)off;
+    size_t lds_bytes = off;
+    const size_t top_bytes = (size_t)index->top_count * kKeyLen * 4;
+    if (top_bytes > lds_bytes) lds_bytes = top_bytes;
+    if (lds_bytes > 150 * 1024) return REST_UNSUPPORTED;
+
+    hipStream_t stream = (hipStream_t)stream_;
+    if (index->token_bytes == 2 && index->sa_bytes == 4) return launch<uint16_t, int32_t>(p, B, lds_bytes, stream);
+    if (index->token_bytes == 2) return launch<uint16_t, int64_t>(p, B, lds_bytes, stream);
+    if (index->sa_bytes == 4) return launch<int32_t, int32_t>(p, B, lds_bytes, stream);
+    return launch<int32_t, int64_t>(p, B, lds_bytes, stream);
+}

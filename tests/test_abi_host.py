@@ -1,0 +1,94 @@
+"""CPU-side checks of the C ABI: the library loads, exports every function include/rest.h declares, and
+its host-only logic (status strings, argument validation, workspace sizing) behaves as documented.
+No kernel is launched here."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+LIB = os.path.join(ROOT, "paper_2311_08252_amd", "librest_gfx950.so")
+
+
+@pytest.fixture(scope="module")
+def rest():
+    if not os.path.exists(LIB):
+        from paper_2311_08252_amd.build import build   # noqa: WPS433 (build.py imports nothing from the package)
+        build()
+    import paper_2311_08252_amd as mod
+    return mod
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "rest.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(rest_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_header_functions_are_exported(rest):
+    names = declared_functions()
+    assert len(names) == 11 and "rest_retrieve" in names and "rest_tree_attention" in names
+    lib = ctypes.CDLL(LIB)
+    for n in names:
+        assert getattr(lib, n) is not None
+    assert sorted(rest.EXPORTS) == names
+
+
+def test_status_strings_and_version(rest):
+    assert rest.rest_status_string(0) == "ok"
+    assert "workspace" in rest.rest_status_string(rest.REST_WORKSPACE_TOO_SMALL)
+    assert rest.rest_status_string(12345) == "unknown status"
+    assert rest.rest_version().startswith("rest-gfx950")
+
+
+def test_limits_match_header(rest):
+    text = open(os.path.join(ROOT, "include", "rest.h")).read()
+    for name in ["REST_MAX_SUFFIX_LEN", "REST_MAX_CONT_LEN", "REST_MAX_MATCHES", "REST_MAX_NODES"]:
+        val = int(re.search(rf"#define {name} (\d+)", text).group(1))
+        assert getattr(rest, name) == val
+
+
+def make_desc(rest, **over):
+    d = rest.rest_attn_desc()
+    d.Nb, d.H, d.Tq, d.Tk, d.P, d.D = 32, 32, 64, 64, 2048, 128
+    d.dtype, d.scale = rest.REST_BF16, 0.088
+    L = 2112
+    d.q_stride[:] = [32 * 64 * 128, 64 * 128, 128]
+    d.o_stride[:] = [32 * 64 * 128, 64 * 128, 128]
+    d.k_stride[:] = [32 * L * 128, L * 128, 128]
+    d.v_stride[:] = [32 * L * 128, L * 128, 128]
+    for k, v in over.items():
+        setattr(d, k, v)
+    return d
+
+
+def test_attention_workspace_sizing_is_host_only(rest):
+    assert rest.rest_tree_attention_workspace_bytes(make_desc(rest)) == 0          # 1024 (layer, head) slabs: no KV split
+    one_layer = make_desc(rest, Nb=1)
+    need = rest.rest_tree_attention_workspace_bytes(one_layer)
+    assert need > 0 and need % ((128 + 2) * 4 * 64 * 32) == 0                       # splits x rows x (O row + max + sum)
+    forced = make_desc(rest, Nb=1, num_splits=4)
+    assert rest.rest_tree_attention_workspace_bytes(forced) == 32 * 4 * 64 * 130 * 4
+    for bad in [dict(D=64), dict(Tq=0), dict(Tq=257), dict(Tk=257), dict(scale=0.0), dict(dtype=7), dict(num_splits=65),
+                dict(Nb=0), dict(P=-1)]:
+        assert rest.rest_tree_attention_workspace_bytes(make_desc(rest, **bad)) == 0
+
+
+def test_calls_reject_null_and_bad_arguments_before_touching_the_gpu(rest):
+    lib = rest._lib
+    d = make_desc(rest)
+    assert lib.rest_tree_attention(None, None, None, None, None, ctypes.byref(d), None, 0, None) == rest.REST_INVALID_ARG
+    h = ctypes.c_void_p()
+    assert lib.rest_build_index(None, 10, 4, 4, None, ctypes.byref(h)) == rest.REST_INVALID_ARG
+    assert lib.rest_build_index(ctypes.c_void_p(16), 10, 3, 4, None, ctypes.byref(h)) == rest.REST_INVALID_ARG
+    assert lib.rest_build_index(ctypes.c_void_p(16), 1 << 31, 4, 4, None, ctypes.byref(h)) == rest.REST_INVALID_ARG
+    assert lib.rest_build_index(ctypes.c_void_p(16), 0, 4, 8, None, ctypes.byref(h)) == rest.REST_INVALID_ARG
+    assert lib.rest_index_from_sa(ctypes.c_void_p(16), None, 10, 4, 4, None, ctypes.byref(h)) == rest.REST_INVALID_ARG
+    assert lib.rest_index_view(None, None, None, None, None, None) == rest.REST_INVALID_ARG
+    lib.rest_index_destroy(None)
+    prm = rest.rest_retrieve_params(16, 2, 100, 10, 64)
+    tree = rest.rest_tree()
+    assert lib.rest_retrieve(None, None, None, 1, 8, ctypes.byref(prm), ctypes.byref(tree), None, 0, None) == rest.REST_INVALID_ARG
+    assert lib.rest_accept(None, ctypes.byref(tree), 1, 64, 10, None, None, None, None) == rest.REST_INVALID_ARG
+    assert rest.rest_retrieve_workspace_bytes(4) == 0

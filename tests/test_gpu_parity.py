@@ -1,0 +1,324 @@
+"""GPU parity tests: the HIP path (through the C ABI binding) against the CPU oracle, element by element,
+on the same seeded inputs.  Integer outputs must be bit-exact; attention within the stated tolerances."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth
+
+pytestmark = pytest.mark.gpu
+
+if torch.cuda.is_available():
+    import paper_2311_08252_amd as rest
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def small_corpus(n, vocab, seed, dtype=np.int32):
+    return synth.randint(seed, np.arange(n), 0, vocab).astype(dtype)
+
+
+def tree_to_numpy(tree, b):
+    return dict(
+        n_nodes=int(tree.n_nodes[b].item()), matched_len=int(tree.matched_len[b].item()),
+        match_count=int(tree.match_count[b].item()),
+        draft_tokens=tree.draft_tokens[b].cpu().numpy(), parent_idx=tree.parent_idx[b].cpu().numpy(),
+        pos_ids=tree.pos_ids[b].cpu().numpy(), node_weight=tree.node_weight[b].cpu().numpy(),
+        tree_mask=tree.tree_mask[b].cpu().numpy().view(np.uint64))
+
+
+def assert_tree_equal(got, want, where=""):
+    assert got["matched_len"] == want.matched_len, where
+    assert got["match_count"] == want.match_count, where
+    assert got["n_nodes"] == want.n_nodes, where
+    np.testing.assert_array_equal(got["draft_tokens"], want.draft_tokens, err_msg=where)
+    np.testing.assert_array_equal(got["parent_idx"], want.parent_idx, err_msg=where)
+    np.testing.assert_array_equal(got["pos_ids"], want.pos_ids, err_msg=where)
+    np.testing.assert_array_equal(got["node_weight"], want.node_weight, err_msg=where)
+    np.testing.assert_array_equal(got["tree_mask"], want.tree_mask, err_msg=where)
+
+
+# ------------------------------------------------------------------ index build
+@pytest.mark.parametrize("dtype,sa_bytes", [(np.int32, 4), (np.uint16, 8), (np.uint16, 4), (np.int32, 8)])
+@pytest.mark.parametrize("n,vocab,seed", [(1, 3, 1), (2, 2, 2), (63, 2, 3), (4097, 3, 4), (20000, 2, 5), (50000, 30000, 6)])
+def test_build_index_equals_oracle_sort(n, vocab, seed, dtype, sa_bytes):
+    corpus = small_corpus(n, vocab, seed, dtype)
+    idx = rest.rest_build_index(dev(corpus), sa_bytes)
+    sa = idx.suffix_array().cpu().numpy()
+    assert sa.dtype == (np.int32 if sa_bytes == 4 else np.int64)
+    np.testing.assert_array_equal(sa.astype(np.int64), oracle.suffix_array(corpus))
+    idx.destroy()
+
+
+def test_build_index_closed_forms_and_motifs():
+    n = 3000
+    for corpus, want in [(np.full(n, 7, np.int32), np.arange(n - 1, -1, -1)), (np.arange(n, dtype=np.int32), np.arange(n))]:
+        idx = rest.rest_build_index(dev(corpus), 4)
+        np.testing.assert_array_equal(idx.suffix_array().cpu().numpy(), want)
+    c = synth.make_corpus(300_000, seed=9, n_motifs=60, copies=50)
+    idx = rest.rest_build_index(dev(c.tokens), 4)
+    sa = idx.suffix_array().cpu().numpy()
+    assert oracle.check_suffix_array(c.tokens, sa) == -1
+    np.testing.assert_array_equal(sa.astype(np.int64), oracle.suffix_array(c.tokens))
+
+
+# ------------------------------------------------------------------ retrieval
+def run_retrieve_case(corpus, contexts, lens, prm, index=None):
+    idx = index or rest.rest_index_from_sa(dev(corpus), dev(oracle.suffix_array(corpus).astype(np.int32)))
+    B = contexts.shape[0]
+    out = rest.Tree.empty(B, prm["max_nodes"], fill=-0x5A5A5A5B)       # poisoned: unwritten slots show up
+    rest.rest_retrieve(idx, dev(contexts), dev(lens), out=out, **prm)
+    torch.cuda.synchronize()
+    for b in range(B):
+        want = oracle.draft_tree(corpus, contexts[b, :lens[b]], prm["n_max"], prm["n_min"], prm["max_matches"],
+                                 prm["cont_len"], prm["max_nodes"])
+        assert_tree_equal(tree_to_numpy(out, b), want, where=f"context {b}")
+    return idx
+
+
+@pytest.mark.parametrize("dtype", [np.int32, np.uint16])
+@pytest.mark.parametrize("n,vocab,seed", [(40, 2, 1), (300, 2, 2), (5000, 3, 3), (20000, 4, 4), (20000, 200, 5)])
+def test_retrieve_small_corpora(n, vocab, seed, dtype):
+    corpus = small_corpus(n, vocab, seed, dtype)
+    B, stride = 24, 40
+    ctx = np.zeros((B, stride), dtype=np.int32)
+    lens = np.zeros(B, dtype=np.int32)
+    for b in range(B):
+        t = [0, 1, 2, 3, 7, 16, 17, 40][b % 8]
+        lens[b] = t
+        if b % 3 == 0 and t <= n:     # copied from the corpus; b == 0 .. also the very end of the stream
+            e = n if b % 6 == 0 else int(synth.randint(seed + 70, [b], max(t, 1), n + 1)[0])
+            ctx[b, :t] = corpus[e - t:e]
+        else:
+            ctx[b, :t] = small_corpus(t, vocab + (b % 2), seed * 131 + b)
+    for prm in [dict(n_max=16, n_min=2, max_matches=1000, cont_len=10, max_nodes=32),
+                dict(n_max=16, n_min=2, max_matches=7, cont_len=3, max_nodes=5),
+                dict(n_max=5, n_min=1, max_matches=8192, cont_len=32, max_nodes=256),
+                dict(n_max=16, n_min=16, max_matches=64, cont_len=1, max_nodes=64)]:
+        run_retrieve_case(corpus, ctx, lens, prm)
+
+
+def test_retrieve_degenerate_streams():
+    prm = dict(n_max=16, n_min=2, max_matches=1000, cont_len=10, max_nodes=32)
+    same = np.full(500, 3, dtype=np.int32)            # every suffix length matches everywhere, rows reach the end
+    ctx = np.full((3, 30), 3, dtype=np.int32)
+    run_retrieve_case(same, ctx, np.array([30, 5, 2], np.int32), prm)
+    one = np.array([9], dtype=np.int32)               # single-token stream: nothing of length >= 2 can match
+    run_retrieve_case(one, np.full((1, 4), 9, np.int32), np.array([4], np.int32), prm)
+    # B == 0 is a no-op
+    idx = rest.rest_index_from_sa(dev(same), dev(oracle.suffix_array(same).astype(np.int32)))
+    rest.rest_retrieve(idx, torch.zeros((0, 8), dtype=torch.int32, device="cuda"),
+                       torch.zeros(0, dtype=torch.int32, device="cuda"), **prm)
+
+
+def test_retrieve_rejects_bad_arguments():
+    corpus = small_corpus(1000, 3, 1)
+    idx = rest.rest_index_from_sa(dev(corpus), dev(oracle.suffix_array(corpus).astype(np.int32)))
+    ctx, lens = dev(np.zeros((1, 8), np.int32)), dev(np.array([8], np.int32))
+    for bad in [dict(n_max=17), dict(n_min=0), dict(n_min=5, n_max=4), dict(max_matches=0), dict(max_matches=8193),
+                dict(cont_len=0), dict(cont_len=33), dict(max_nodes=0), dict(max_nodes=257)]:
+        prm = dict(n_max=16, n_min=2, max_matches=100, cont_len=10, max_nodes=32)
+        prm.update(bad)
+        with pytest.raises(rest.RestError) as e:
+            rest.rest_retrieve(idx, ctx, lens, **prm)
+        assert e.value.status == rest.REST_INVALID_ARG
+    with pytest.raises(rest.RestError):      # empty stream
+        rest.rest_index_from_sa(dev(np.zeros(0, np.int32)), dev(np.zeros(0, np.int32)))
+    with pytest.raises(rest.RestError):
+        rest.rest_build_index(dev(np.zeros(0, np.int32)), 4)
+
+
+def test_retrieve_tiny_config_with_gpu_built_index():
+    """Config 'tiny': 10^6-token Zipf stream with planted motifs, 8 contexts of 64, K=1000, m=10, c=32."""
+    w = synth.WORKLOADS["tiny"]
+    c = synth.make_corpus(w.n_tokens, w.corpus_seed, w.n_motifs)
+    ctx, lens = synth.make_contexts(c, w.batch, w.ctx_len, w.query_seed)
+    d_corpus = dev(c.tokens)
+    idx = rest.rest_build_index(d_corpus, 4)
+    sa = idx.suffix_array().cpu().numpy()
+    assert oracle.check_suffix_array(c.tokens, sa) == -1
+    prm = dict(n_max=w.n_max, n_min=w.n_min, max_matches=w.max_matches, cont_len=w.cont_len, max_nodes=w.max_nodes)
+    run_retrieve_case(c.tokens, ctx, lens, prm, index=idx)
+    # a larger batch with more varied contexts
+    ctx2, lens2 = synth.make_contexts(c, 64, 32, 99)
+    run_retrieve_case(c.tokens, ctx2, lens2, prm, index=idx)
+
+
+# ------------------------------------------------------------------ tree attention
+def attention_case(Nb, H, T, P, seed, dtype="bf16", per_batch=False, num_splits=0, Tq_extra=0, tree="random"):
+    Tq = T + Tq_extra
+    if tree == "chain":
+        par = np.arange(-1, T - 1, dtype=np.int32)
+        mask = oracle.mask_from_parents(par, T)
+    else:
+        _, _, _, mask = synth.random_tree(T, seed) if T > 0 else (None, None, None, np.zeros((0, 1), np.uint64))
+    words = max(1, (T + 63) // 64)
+    mask = mask[:, :words]
+    if Tq_extra:
+        mask = np.vstack([np.zeros((Tq_extra, words), np.uint64), mask])
+    if per_batch:
+        masks = [mask]
+        for nb in range(1, Nb):
+            m2 = synth.random_tree(T, seed + 100 + nb)[3][:, :words]
+            if Tq_extra:
+                m2 = np.vstack([np.zeros((Tq_extra, words), np.uint64), m2])
+            masks.append(m2)
+        mask = np.stack(masks)
+    if dtype == "bf16":
+        qb = synth.normal_bf16_bits(seed, (Nb, H, Tq, 128))
+        kb = synth.normal_bf16_bits(seed + 1, (Nb, H, P + T, 128))
+        vb = synth.normal_bf16_bits(seed + 2, (Nb, H, P + T, 128))
+        q, k, v = (synth.bf16_bits_to_f32(x) for x in (qb, kb, vb))
+        dq, dk, dv = (dev(x.view(np.int16)).view(torch.bfloat16) for x in (qb, kb, vb))
+    else:
+        q = synth.normal_f32(seed, (Nb, H, Tq, 128))
+        k = synth.normal_f32(seed + 1, (Nb, H, P + T, 128))
+        v = synth.normal_f32(seed + 2, (Nb, H, P + T, 128))
+        dq, dk, dv = dev(q), dev(k), dev(v)
+    scale = 1.0 / np.sqrt(128.0)
+    omask = mask[:, None] if per_batch else mask
+    want = oracle.tree_attention(q, k, v, omask, P, scale)
+    dmask = dev(mask.view(np.int64)) if T > 0 else torch.zeros((Tq, 1), dtype=torch.int64, device="cuda")
+    out = torch.full_like(dq, float("nan"))
+    rest.rest_tree_attention(dq, dk, dv, dmask, P, float(scale), out=out, num_splits=num_splits)
+    torch.cuda.synchronize()
+    got = out.float().cpu().numpy().astype(np.float64)
+    assert np.isfinite(got).all()
+    if dtype == "bf16":
+        assert np.abs(got - want).max() <= 2e-2, np.abs(got - want).max()
+    else:
+        for nb in range(Nb):
+            for h in range(H):
+                rel = np.abs(got[nb, h] - want[nb, h]).max() / np.abs(want[nb, h]).max()
+                assert rel <= 1e-3, rel
+    return np.abs(got - want).max()
+
+
+@pytest.mark.parametrize("T,P", [(1, 1), (16, 100), (32, 31), (33, 64), (64, 256), (64, 1000), (100, 77),
+                                 (128, 513), (200, 5), (256, 300), (64, 0), (7, 2049)])
+def test_tree_attention_bf16_shapes(T, P):
+    attention_case(2, 3, T, P, seed=T * 1000 + P)
+
+
+@pytest.mark.parametrize("ns", [1, 2, 3, 8, 64])
+def test_tree_attention_bf16_split_counts(ns):
+    attention_case(1, 2, 64, 1500, seed=5, num_splits=ns)
+    attention_case(1, 2, 40, 3, seed=6, num_splits=ns)      # more waves than key blocks
+
+
+def test_tree_attention_bf16_variants():
+    attention_case(3, 2, 64, 200, seed=7, per_batch=True)
+    attention_case(2, 2, 64, 200, seed=8, Tq_extra=1)        # extra root query row seeing the prefix only
+    attention_case(1, 1, 64, 300, seed=9, tree="chain")      # chain tree = plain causal attention
+    attention_case(1, 2, 0, 129, seed=10, Tq_extra=3)        # no draft keys at all
+    attention_case(9, 5, 64, 64, seed=11)                    # streams not a multiple of 8
+
+
+def test_tree_attention_bf16_tiny_config():
+    """Config 'tiny': 1 layer x 32 heads x 128, KV length 256, the 32-node cap."""
+    attention_case(1, 32, 32, 256, seed=22)
+
+
+@pytest.mark.parametrize("T,P,ns", [(1, 3, 1), (64, 256, 1), (33, 200, 4), (130, 77, 2)])
+def test_tree_attention_fp32(T, P, ns):
+    attention_case(2, 2, T, P, seed=40 + T, dtype="fp32", num_splits=ns)
+
+
+def test_tree_attention_strided_layout_and_errors():
+    # K/V stored [Nb, L, H, D] (token-major cache) and viewed as [Nb, H, L, D]
+    Nb, H, T, P = 2, 4, 64, 300
+    qb = synth.normal_bf16_bits(1, (Nb, H, T, 128))
+    kb = synth.normal_bf16_bits(2, (Nb, P + T, H, 128))
+    vb = synth.normal_bf16_bits(3, (Nb, P + T, H, 128))
+    mask = synth.random_tree(T, 5)[3]
+    dq = dev(qb.view(np.int16)).view(torch.bfloat16)
+    dk = dev(kb.view(np.int16)).view(torch.bfloat16).permute(0, 2, 1, 3)
+    dv = dev(vb.view(np.int16)).view(torch.bfloat16).permute(0, 2, 1, 3)
+    out = rest.rest_tree_attention(dq, dk, dv, dev(mask.view(np.int64)), P, 0.088)
+    torch.cuda.synchronize()
+    want = oracle.tree_attention(synth.bf16_bits_to_f32(qb), synth.bf16_bits_to_f32(kb).transpose(0, 2, 1, 3),
+                                 synth.bf16_bits_to_f32(vb).transpose(0, 2, 1, 3), mask, P, 0.088)
+    assert np.abs(out.float().cpu().numpy() - want).max() <= 2e-2
+    with pytest.raises(rest.RestError):
+        rest.rest_tree_attention(dq, dk, dv, dev(mask.view(np.int64)), P, -1.0)
+    with pytest.raises(rest.RestError):
+        rest.rest_tree_attention(dq[..., :64].contiguous(), dk[..., :64].contiguous(), dv[..., :64].contiguous(),
+                                 dev(mask.view(np.int64)), P, 0.1)
+
+
+# ------------------------------------------------------------------ acceptance
+def test_accept_matches_oracle_on_random_trees():
+    B, c, cap = 40, 64, 16
+    tree = rest.Tree.empty(B, c, fill=0)
+    toks = np.full((B, c), -1, np.int32)
+    pars = np.full((B, c), -1, np.int32)
+    nn = np.zeros(B, np.int32)
+    ids = np.zeros((B, 1 + c), np.int32)
+    for b in range(B):
+        T = [0, 1, 5, 33, 64][b % 5]
+        if T:
+            par, dep, tok, _ = synth.random_tree(T, 300 + b)
+            toks[b, :T], pars[b, :T] = tok, par
+        nn[b] = T
+        ids[b] = synth.sampled_ids(500 + b, toks[b], pars[b], T, vocab=30000, p_follow=0.85)
+    tree.draft_tokens.copy_(dev(toks))
+    tree.parent_idx.copy_(dev(pars))
+    tree.n_nodes.copy_(dev(nn))
+    for path_cap in (cap, 2):
+        alen, apath, nxt = rest.rest_accept(dev(ids), tree, path_cap)
+        torch.cuda.synchronize()
+        some = 0
+        for b in range(B):
+            n, path, nt = oracle.accept(ids[b], toks[b], pars[b], int(nn[b]), path_cap)
+            assert int(alen[b]) == n and int(nxt[b]) == nt
+            np.testing.assert_array_equal(apath[b].cpu().numpy(), path)
+            some += n
+        assert some > 0
+
+
+def test_gpu_rest_loop_reproduces_greedy_decoding():
+    """Drafts from rest_retrieve + rest_accept on the GPU drive a decoding loop whose output must equal plain
+    greedy decoding with the same deterministic toy model (the lossless property of the acceptance rule)."""
+    corp = synth.make_corpus(30000, seed=2, n_motifs=40, copies=20, vocab=500)
+    corpus = corp.tokens
+    succ = {}
+    for a, b, c3 in zip(corpus[:-2], corpus[1:-1], corpus[2:]):
+        succ[(int(a), int(b))] = int(c3)
+
+    def model(seq):
+        key = (seq[-2], seq[-1])
+        h = (seq[-1] * 1000003 + seq[-2] * 10007 + seq[-3] * 101) % 7
+        return succ[key] if key in succ and h != 0 else (seq[-1] * 31 + seq[-2] * 17 + seq[-3]) % 500
+
+    o = int(corp.motif_offsets[0, 0])
+    prompt = corpus[o:o + 6].astype(np.int32).tolist()
+    want = oracle.greedy_decode(model, prompt, 50)
+    idx = rest.rest_build_index(dev(corpus), 4)
+    c, m = 24, 8
+    seq, steps = list(prompt), 0
+    buf = torch.zeros((1, 128), dtype=torch.int32, device="cuda")
+    while len(seq) - len(prompt) < 50:
+        t = len(seq)
+        buf[0, :t] = torch.tensor(seq, dtype=torch.int32)
+        tree = rest.rest_retrieve(idx, buf, torch.tensor([t], dtype=torch.int32, device="cuda"),
+                                  max_matches=200, cont_len=m, max_nodes=c)
+        T = int(tree.n_nodes[0])
+        toks, pars = tree.draft_tokens[0].cpu().numpy(), tree.parent_idx[0].cpu().numpy()
+        ids = np.zeros((1, 1 + c), np.int32)
+        ids[0, 0] = model(seq)
+        for i in range(T):
+            path, v = [], i
+            while v != -1:
+                path.append(int(toks[v]))
+                v = int(pars[v])
+            ids[0, 1 + i] = model(seq + path[::-1])
+        alen, apath, nxt = rest.rest_accept(dev(ids), tree, m)
+        for j in range(int(alen[0])):
+            seq.append(int(toks[int(apath[0, j])]))
+        seq.append(int(nxt[0]))
+        steps += 1
+    assert seq[len(prompt):len(prompt) + 50] == want
+    assert steps < 50
