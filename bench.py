@@ -1,0 +1,255 @@
+#!/usr/bin/env python3
+"""Benchmark of REST's draft-and-verify hot path on one MI355X.
+
+One step = rest_retrieve (1 context) -> rest_tree_attention (all layers x heads, one launch, mask straight
+from the retrieve output in HBM) -> rest_accept, on the Llama-2-7B-shaped synthetic workload:
+100M-token Zipf(1.1) datastore with planted motifs, contexts of 512 tokens, K=5000, m=16, c=64,
+32 layers x 32 heads x 128, KV length 2048, bf16.  All inputs are resident in HBM before timing starts.
+
+Prints ONE JSON line (see README for the fields).  The CPU oracle is used only for the
+`cpu_baseline` leg and a sampled parity check, never inside the timed region.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="llama7b", choices=["llama7b", "tiny"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="skip the per-layer and batched-retrieval side measurements")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run a plain 1 GiB device-to-device copy five times (reference for rocprofv3 --pmc byte counters)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import synth
+    import paper_2311_08252_amd as rest
+
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+    if args.copy_calibration:
+        a = torch.zeros(1 << 28, dtype=torch.int32, device=dev)     # 1 GiB read + 1 GiB written per copy
+        b = torch.ones(1 << 28, dtype=torch.int32, device=dev)
+        for _ in range(5):
+            a.copy_(b)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes_read": 1 << 30, "copy_calibration_bytes_written": 1 << 30}))
+        return 0
+    w = synth.WORKLOADS[args.workload]
+    n_ctx = 16          # the timed steps rotate over these contexts (half copied from the stream, half i.i.d.)
+
+    # ---------------- inputs, resident in HBM
+    t0 = time.time()
+    corp = synth.make_corpus(w.n_tokens, w.corpus_seed, w.n_motifs, dtype=w.token_dtype)
+    ctx_np, len_np = synth.make_contexts(corp, n_ctx, w.ctx_len, w.query_seed)
+    t_gen = time.time() - t0
+    d_corpus = torch.from_numpy(corp.tokens).to(dev)
+    d_ctx = torch.from_numpy(ctx_np).to(dev)
+    d_len = torch.from_numpy(len_np).to(dev)
+    torch.cuda.synchronize()
+    t0 = time.time()
+    index = rest.rest_build_index(d_corpus, w.sa_bytes)
+    torch.cuda.synchronize()
+    t_build = time.time() - t0
+
+    Nb, H, D, P, c = w.layers, w.heads, w.head_dim, w.kv_len, w.max_nodes
+    Lk = P + c
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(w.qkv_seed)
+    q = torch.randn((Nb, H, c, D), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    k = torch.randn((Nb, H, Lk, D), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    v = torch.randn((Nb, H, Lk, D), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    out = torch.empty_like(q)
+    scale = 1.0 / float(np.sqrt(D))
+    prm = dict(n_max=w.n_max, n_min=w.n_min, max_matches=w.max_matches, cont_len=w.cont_len, max_nodes=c)
+
+    trees = [rest.Tree.empty(1, c, dev) for _ in range(n_ctx)]
+    ids = []
+    for i in range(n_ctx):      # model token ids per position (inputs of rest_accept), derived once from the trees
+        rest.rest_retrieve(index, d_ctx[i:i + 1], d_len[i:i + 1], out=trees[i], **prm)
+        torch.cuda.synchronize()
+        ids_np = synth.sampled_ids(w.qkv_seed + 100 + i, trees[i].draft_tokens[0].cpu().numpy(),
+                                   trees[i].parent_idx[0].cpu().numpy(), int(trees[i].n_nodes[0]))
+        ids.append(torch.from_numpy(ids_np[None]).to(dev))
+    alen = torch.empty(1, dtype=torch.int32, device=dev)
+    apath = torch.empty((1, w.cont_len), dtype=torch.int32, device=dev)
+    nxt = torch.empty(1, dtype=torch.int32, device=dev)
+    desc = rest.make_attn_desc(q, k, v, out, P, scale, False)
+    ws_bytes = rest.rest_tree_attention_workspace_bytes(desc)
+    ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=dev)
+
+    ctx_rows = [d_ctx[i:i + 1] for i in range(n_ctx)]
+    len_rows = [d_len[i:i + 1] for i in range(n_ctx)]
+    masks = [t.tree_mask[0] for t in trees]      # [c, words] views: one mask shared by all layers
+
+    def step(i, ev=None):
+        j = i % n_ctx
+        tree = trees[j]
+        rest.rest_retrieve(index, ctx_rows[j], len_rows[j], out=tree, **prm)
+        if ev is not None:
+            ev[0].record()
+        rest.rest_tree_attention(q, k, v, masks[j], P, scale, out=out, workspace=ws)
+        if ev is not None:
+            ev[1].record()
+        rest.rest_accept(ids[j], tree, w.cont_len, alen, apath, nxt)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i, events[i])
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed * 1e3 / args.steps
+    attn_ms = sum(a.elapsed_time(b) for a, b in events) / args.steps
+
+    slabs = Nb * H
+    alg_bytes = slabs * (2 * Lk * D * 2 + 2 * c * D * 2) + c * ((c + 63) // 64) * 8
+    achieved = alg_bytes / (attn_ms * 1e-3) / 1e9
+
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "tree_attn_bf16_llama7b_traffic.json")
+    if args.workload == "llama7b" and os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
+        except Exception:
+            traffic = None
+
+    result = {
+        "metric": "draft-verify steps/s (retrieve+tree-attn+accept) at 7B shape" if args.workload == "llama7b"
+                  else "draft-verify steps/s (retrieve+tree-attn+accept), tiny config",
+        "value": round(1e3 / ms_per_step, 2), "unit": "steps/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{w.name}: {w.n_tokens}-token Zipf(1.1)+motif datastore, 1 context x {w.ctx_len} per step "
+                               f"(rotating over {n_ctx}), K={w.max_matches}, m={w.cont_len}, c={c}, tree attention "
+                               f"{Nb} layers x {H} heads x {D}, KV length {P}+{c}, one launch over all layers",
+                   "global_batch": 1, "kv_len": P, "tree_nodes": c},
+        "roofline": {"bound": "hbm", "kernel": "tree_attn_bf16_kernel<2>", "achieved": round(achieved, 1),
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     "traffic": traffic, "algorithmic_bytes_per_launch": alg_bytes,
+                     "avg_launch_us": round(attn_ms * 1e3, 2)},
+        "extra": {"index_build_s": round(t_build, 3), "corpus_gen_s": round(t_gen, 2),
+                  "tree_nodes_per_context": [int(t.n_nodes[0]) for t in trees],
+                  "matched_len_per_context": [int(t.matched_len[0]) for t in trees]},
+    }
+
+    if not args.no_extras:
+        result["extra"].update(side_measurements(rest, torch, synth, corp, index, w, q, k, v, out, trees[0], P, scale, prm))
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"], result["extra"]["parity_sample_max_abs_err"] = cpu_baseline(
+            np, torch, corp, ctx_np, w, q, k, v, out, trees, ids, P, scale, step)
+    print(json.dumps(result))
+    return 0
+
+
+def side_measurements(rest, torch, synth, corp, index, w, q, k, v, out, tree, P, scale, prm):
+    """Untimed-in-`value` extras: retrieval alone (batch 1 and a 4096-context batch), attention launched layer
+    by layer, acceptance alone."""
+    dev = q.device
+    res = {}
+
+    def timed(fn, iters):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(iters):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / iters
+
+    ctx_b, len_b = synth.make_contexts(corp, 4096, w.ctx_len, w.query_seed + 1)
+    d_ctx, d_len = torch.from_numpy(ctx_b).to(dev), torch.from_numpy(len_b).to(dev)
+    big = rest.Tree.empty(4096, w.max_nodes, dev)
+    ms = timed(lambda: rest.rest_retrieve(index, d_ctx, d_len, out=big, **prm), 10)
+    res["retrieve_batch4096_contexts_per_s"] = round(4096 / (ms * 1e-3), 1)
+    one = rest.Tree.empty(1, w.max_nodes, dev)
+    lat = []
+    for j in range(8):
+        lat.append(timed(lambda: rest.rest_retrieve(index, d_ctx[j:j + 1], d_len[j:j + 1], out=one, **prm), 20))
+    res["retrieve_batch1_us"] = [round(x * 1e3, 1) for x in lat]
+
+    Nb = q.shape[0]
+    mask = tree.tree_mask[0]
+
+    def per_layer():
+        for nb in range(Nb):
+            rest.rest_tree_attention(q[nb:nb + 1], k[nb:nb + 1], v[nb:nb + 1], mask, P, scale, out=out[nb:nb + 1],
+                                     workspace=ws_layer)
+
+    d1 = rest.make_attn_desc(q[:1], k[:1], v[:1], out[:1], P, scale, False)
+    ws_layer = torch.empty(max(rest.rest_tree_attention_workspace_bytes(d1), 16), dtype=torch.uint8, device=dev)
+    ms = timed(per_layer, 10)
+    res["attn_per_layer_launches_us_total"] = round(ms * 1e3, 1)
+    ms = timed(lambda: rest.rest_tree_attention(q, k, v, mask, P, scale, out=out), 20)
+    res["attn_single_launch_us"] = round(ms * 1e3, 1)
+    return res
+
+
+def cpu_baseline(np, torch, corp, ctx_np, w, q, k, v, out, trees, ids, P, scale, step):
+    """The plain CPU oracle on a bounded sample of the same workload, on this machine's host cores."""
+    import oracle
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    n_ret = 3
+    t0 = time.perf_counter()
+    cpu_trees = [oracle.draft_tree(corp.tokens, ctx_np[i], w.n_max, w.n_min, w.max_matches, w.cont_len, w.max_nodes)
+                 for i in range(n_ret)]
+    t_ret = (time.perf_counter() - t0) / n_ret
+    # attention: a seeded sample of (layer, head) slabs incl. the first and the last
+    step(0)
+    torch.cuda.synchronize()
+    Nb, H = q.shape[0], q.shape[1]
+    rng = np.random.default_rng(1234)
+    picks = {(0, 0), (Nb - 1, H - 1)}
+    while len(picks) < 48:
+        picks.add((int(rng.integers(Nb)), int(rng.integers(H))))
+    picks = sorted(picks)
+    mask = trees[0].tree_mask[0].cpu().numpy().view(np.uint64)
+    slabs = [(q[a, b].float().cpu().numpy(), k[a, b].float().cpu().numpy(), v[a, b].float().cpu().numpy()) for a, b in picks]
+    t0 = time.perf_counter()
+    refs = [oracle.tree_attention(qq, kk, vv, mask, P, scale) for qq, kk, vv in slabs]
+    t_attn = (time.perf_counter() - t0) * (Nb * H) / len(picks)
+    err = max(float(np.abs(out[a, b].float().cpu().numpy() - r).max()) for (a, b), r in zip(picks, refs))
+    t0 = time.perf_counter()
+    for i in range(n_ret):
+        oracle.accept(ids[i][0].cpu().numpy(), cpu_trees[i].draft_tokens, cpu_trees[i].parent_idx, cpu_trees[i].n_nodes, w.cont_len)
+    t_acc = (time.perf_counter() - t0) / n_ret
+    total = t_ret + t_attn + t_acc
+    base = {"value": round(1.0 / total, 4), "unit": "steps/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"retrieval+Trie: {n_ret} of the rotating contexts, mean {t_ret:.3f} s; attention: {len(picks)} of "
+                      f"{Nb * H} (layer, head) slabs in float64, scaled to all: {t_attn:.3f} s; accept {t_acc * 1e6:.0f} us"}
+    return base, err
+
+
+if __name__ == "__main__":
+    sys.exit(main())
