@@ -3,17 +3,25 @@
 // its ancestors only.
 //
 // bf16 kernel design (HBM-bound: ~T flop per KV byte, far below the chip's balance point):
-//  * one wavefront = one independent stream over a contiguous range of 32-key blocks, for up to 64
-//    queries; no workgroup barrier inside the streaming loop;
-//  * a block's K and V (8 KB each) are fetched with coalesced 16-byte loads one block ahead of the
-//    arithmetic, kept in registers while in flight, then parked in wave-private LDS with an XOR swizzle;
+//  * the work is the flat sequence of 32-key blocks of all (batch, head, query-group) units; it is cut into
+//    equal contiguous spans, one per wavefront (stream-K style).  A wavefront is a fully independent stream
+//    for up to 64 queries: no workgroup barrier anywhere.  A span that covers a whole unit writes the final
+//    output; the at most two partially covered units at its ends leave (reference, sum, O) partials that a
+//    small second kernel merges;
+//  * a block's K and V (8 KB each) are fetched with coalesced 16-byte non-temporal loads one block ahead of the
+//    arithmetic, wait in registers while in flight, and are then parked in a wave-private LDS tile; the XOR
+//    swizzle that keeps the LDS reads conflict free is applied by choosing which 16-byte piece of a row each
+//    lane fetches, so the parking stores are plain lane-linear 16-byte writes;
+//  * the query rows sit in wave-private LDS as well (same swizzle) and are re-read as MFMA B operands per block,
+//    which keeps the register file for the O accumulators and the in-flight K/V;
 //  * S^T = K Q^T and O^T += V^T P^T run on v_mfma_f32_32x32x16_bf16.  With keys on the MFMA row axis a
 //    lane owns one query column, so the softmax statistics are per lane; V^T fragments come out of LDS
 //    through ds_read_b64_tr_b16; the probabilities go from the S accumulator straight into the B
 //    operand of the second product (the key permutation this implies is applied to V^T as well);
-//  * the four waves of a workgroup merge their (max, sum, O) through LDS; several workgroups per
-//    (batch, head) write partials that a small second kernel merges.
-//  * tree-mask bit rows are staged in LDS and only consulted for the blocks that reach past the prefix.
+//  * the softmax reference is only moved when a block's maximum exceeds it by more than 2^8, so the O
+//    accumulators are rescaled a handful of times per unit instead of once per block (the result does not
+//    depend on the reference);
+//  * tree-mask bit rows are held in wave-private LDS and only consulted for blocks that reach past the prefix.
 #include "common.h"
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -30,6 +38,8 @@ constexpr int kBlk = 32;           // keys per block
 constexpr int kWaves = 4;          // waves per workgroup
 constexpr int kTileBytes = kBlk * kD * 2;   // 8 KB: one K or V block in bf16
 constexpr float kNegBig = -1.0e30f;
+constexpr float kLazy = 8.0f;      // log2 units the running maximum may exceed the softmax reference
+constexpr int kMaxWaves = 1024;    // default number of streams: one wavefront per SIMD on 256 CUs
 
 struct AttnParams {
     const __bf16* q;
@@ -37,309 +47,341 @@ struct AttnParams {
     const __bf16* v;
     const uint64_t* mask;
     __bf16* out;
-    float* ws_o;      // [streams][qrows][128] partial O (un-normalised), only when nsplit > 1
-    float* ws_ml;     // [streams][qrows][2]   (max, sum)
+    float* ws_o;      // bf16 path: [W][2][QT*32][128] partial O; fp32 path: [rows][128]
+    float* ws_ml;     // bf16 path: [W][2][QT*32][2] (reference in log2 units, sum); fp32 path: [rows][2]
     int32_t Nb, H, Tq, Tk, P, Lk;
     int32_t nsplit, qgroups, mask_words, mask_per_batch;
     int32_t nblk;     // ceil(Lk / 32)
-    int32_t nstreams; // Nb * H * nsplit
+    int32_t units;    // Nb * H * qgroups
+    int32_t n_streams;  // W: wavefronts that share the work
     float c;          // scale * log2(e)
     int64_t qs[3], ks[3], vs[3], os[3];
 };
 
 __device__ inline float wave_xor32(float x) { return __shfl_xor(x, 32, 64); }
 
+// first block of stream w when `total` blocks are cut into `n` contiguous spans
+__host__ __device__ inline int64_t span_begin(int64_t total, int32_t n, int64_t w) { return (total * w) / n; }
+// the stream whose span contains block b
+__host__ __device__ inline int32_t span_owner(int64_t total, int32_t n, int64_t b) {
+    return (int32_t)(((b + 1) * n - 1) / total);
+}
+
 template <int QT>
 __global__ __launch_bounds__(256) void tree_attn_bf16_kernel(AttnParams p) {
-    __shared__ __attribute__((aligned(16))) unsigned char lds_stage[kWaves * 2 * kTileBytes];  // 64 KB
-    __shared__ uint64_t lds_mask[QT * 32 * 4];   // QT*32 query rows x 4 mask words
-    __shared__ float lds_ml[kWaves][QT][2][64];
+    // one (K, V) tile pair per wave: 4 waves x 16 KB = 64 KB, plus the waves' mask rows and query rows
+    __shared__ __attribute__((aligned(1024))) unsigned char lds_stage[kWaves * 2 * kTileBytes];
+    __shared__ uint64_t lds_mask[kWaves][QT * 32 * 4];
+    // the waves' query rows (bf16, 256 B each), 16-byte pieces swizzled like the K tile
+    __shared__ __attribute__((aligned(16))) unsigned char lds_q[kWaves][QT * 32 * 256];
 
-    // ---- XCD-aware decode of the flat workgroup id: consecutive ids go to different XCDs, so the
-    // q-groups that stream the same K/V are given ids that land on one XCD (shared L2).
-    const int id = blockIdx.x;
-    const int xcd = id & 7, slot = id >> 3;
-    const int qg = slot % p.qgroups;
-    const int stream = (slot / p.qgroups) * 8 + xcd;
-    if (stream >= p.nstreams) return;
-    const int split = stream % p.nsplit;
-    const int slab = stream / p.nsplit;
-    const int h = slab % p.H, nb = slab / p.H;
-
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int hh = lane >> 5;      // which half of the wave (selects the k-slice of MFMA operands)
     const int col = lane & 31;     // MFMA column = query within a 32-query tile
-    const int qbase = qg * (QT * 32);
+    const int lrow = lane >> 4, lpc = lane & 15;
 
-    // ---- stage this q-group's mask rows in LDS
-    {
-        const uint64_t* mrow = p.mask + (p.mask_per_batch ? (int64_t)nb * p.Tq * p.mask_words : 0);
-        for (int i = tid; i < QT * 32 * 4; i += 256) {
-            int qi = qbase + (i >> 2), w = i & 3;
-            lds_mask[i] = (qi < p.Tq && w < p.mask_words) ? mrow[(int64_t)qi * p.mask_words + w] : 0ull;
-        }
-    }
+    const int64_t total = (int64_t)p.units * p.nblk;
+    const int gw = blockIdx.x * kWaves + wave;
+    if (gw >= p.n_streams) return;
+    const int64_t g_begin = span_begin(total, p.n_streams, gw), g_end = span_begin(total, p.n_streams, gw + 1);
+    if (g_begin >= g_end) return;
 
-    // ---- Q fragments (B operand of S^T = K Q^T): lane holds query `col`, d = 16*ks + 8*hh .. +8
-    bf16x8 qf[QT][8];
-    {
-        const __bf16* qp = p.q + nb * p.qs[0] + h * p.qs[1];
-#pragma unroll
-        for (int qt = 0; qt < QT; qt++) {
-            int qi = qbase + qt * 32 + col;
-#pragma unroll
-            for (int ks = 0; ks < 8; ks++) {
-                bf16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
-                if (qi < p.Tq) z = *(const bf16x8*)(qp + qi * p.qs[2] + 16 * ks + 8 * hh);
-                qf[qt][ks] = z;
-            }
-        }
-    }
-    __syncthreads();
-
-    // ---- this wave's block range
-    const int gw = split * kWaves + wave, nw = p.nsplit * kWaves;
-    const int jb = (int)(((int64_t)p.nblk * gw) / nw), je = (int)(((int64_t)p.nblk * (gw + 1)) / nw);
+    unsigned char* const stage = lds_stage + wave * (2 * kTileBytes);   // [K | V]
+    uint64_t* const my_mask = lds_mask[wave];
+    unsigned char* const my_q = lds_q[wave];
+    const int64_t k_row_bytes = p.ks[2] * 2, v_row_bytes = p.vs[2] * 2;
     const int plain_end = p.P / kBlk;   // blocks below this hold prefix keys only
 
-    const __bf16* kp = p.k + nb * p.ks[0] + h * p.ks[1];
-    const __bf16* vp = p.v + nb * p.vs[0] + h * p.vs[1];
-    unsigned char* ldsK = lds_stage + wave * 2 * kTileBytes;
-    unsigned char* ldsV = ldsK + kTileBytes;
+    // Global -> LDS.  Chunk i of a tile is 4 rows x 256 B = 64 lanes x 16 B and lands at LDS tile + i*1024 +
+    // lane*16, i.e. row i*4 + (lane >> 4), piece slot lane & 15.  The slot holds row piece (slot ^ swizzle(row)),
+    // so that is the piece this lane fetches.  K: swizzle = row & 15; V: swizzle = (row & 3) << 2.
+    uint32_t k_off[4];
+#pragma unroll
+    for (int x = 0; x < 4; x++) k_off[x] = (uint32_t)(lrow * k_row_bytes) + ((lpc ^ (x * 4 + lrow)) << 4);
+    const uint32_t v_off = (uint32_t)(lrow * v_row_bytes) + ((lpc ^ (lrow << 2)) << 4);
 
-    f32x16 o[QT][4];
-    float m_run[QT], l_run[QT];
-#pragma unroll
-    for (int qt = 0; qt < QT; qt++) {
-        m_run[qt] = kNegBig;
-        l_run[qt] = 0.f;
-#pragma unroll
-        for (int dt = 0; dt < 4; dt++)
-#pragma unroll
-            for (int r = 0; r < 16; r++) o[qt][dt][r] = 0.f;
-    }
+    auto unit_bases = [&](int unit, const char*& kp, const char*& vp) {
+        const int slab = unit / p.qgroups;
+        const int h = slab % p.H, nb = slab / p.H;
+        kp = (const char*)(p.k + nb * p.ks[0] + h * p.ks[1]);
+        vp = (const char*)(p.v + nb * p.vs[0] + h * p.vs[1]);
+    };
 
+    // ---- load side: a cursor one block ahead of the arithmetic
+    int ld_unit = (int)(g_begin / p.nblk), ld_j = (int)(g_begin % p.nblk);
+    const char *ld_kp, *ld_vp;
+    unit_bases(ld_unit, ld_kp, ld_vp);
+    // issues the loads of the cursor's block into the staging registers and advances the cursor
     i32x4 kr[8], vr[8];
-    const int lrow = lane >> 4, lpc = lane & 15;
-    auto issue = [&](int j) {
+    auto issue = [&]() {
+        const int j = ld_j;
+        if ((j + 1) * kBlk <= p.Lk) {
 #pragma unroll
-        for (int i = 0; i < 8; i++) {
-            int row = j * kBlk + i * 4 + lrow;
-            row = row < p.Lk ? row : p.Lk - 1;
-            kr[i] = __builtin_nontemporal_load((const i32x4*)(kp + row * p.ks[2] + lpc * 8));
-            vr[i] = __builtin_nontemporal_load((const i32x4*)(vp + row * p.vs[2] + lpc * 8));
+            for (int i = 0; i < 8; i++) {
+                const int64_t row = (int64_t)j * kBlk + i * 4;
+                kr[i] = __builtin_nontemporal_load((const i32x4*)(ld_kp + row * k_row_bytes + k_off[i & 3]));
+                vr[i] = __builtin_nontemporal_load((const i32x4*)(ld_vp + row * v_row_bytes + v_off));
+            }
+        } else {
+            // last, partial block of a unit: rows past the end re-read the last row; those keys are never visible
+#pragma unroll
+            for (int i = 0; i < 8; i++) {
+                int64_t row = (int64_t)j * kBlk + i * 4 + lrow;
+                row = row < p.Lk ? row : p.Lk - 1;
+                const int sw_k = (lpc ^ ((i & 3) * 4 + lrow)) << 4, sw_v = (lpc ^ (lrow << 2)) << 4;
+                kr[i] = __builtin_nontemporal_load((const i32x4*)(ld_kp + row * k_row_bytes + sw_k));
+                vr[i] = __builtin_nontemporal_load((const i32x4*)(ld_vp + row * v_row_bytes + sw_v));
+            }
+        }
+        if (++ld_j == p.nblk) {
+            ld_j = 0;
+            ld_unit++;
+            if (ld_unit < p.units) unit_bases(ld_unit, ld_kp, ld_vp);
         }
     };
+    // staging registers -> LDS tile: lane l's piece of chunk i goes to tile + i*1024 + l*16
     auto park = [&]() {
 #pragma unroll
         for (int i = 0; i < 8; i++) {
-            int r = i * 4 + lrow;
-            *(i32x4*)(ldsK + r * 256 + ((lpc ^ (r & 15)) << 4)) = kr[i];
-            *(i32x4*)(ldsV + r * 256 + ((lpc ^ ((r & 3) << 2)) << 4)) = vr[i];
+            *(i32x4*)(stage + i * 1024 + lane * 16) = kr[i];
+            *(i32x4*)(stage + kTileBytes + i * 1024 + lane * 16) = vr[i];
         }
     };
 
-    if (jb < je) issue(jb);
-    for (int j = jb; j < je; j++) {
-        park();
-        if (j + 1 < je) issue(j + 1);
+    // ---- LDS read addresses (byte offsets inside a K or V tile), loop invariant
+    const uint32_t ka0 = col * 256 + ((hh ^ (col & 15)) << 4);                     // ^ (ks << 5) per k-step
+    const int vq = (lane & 15) >> 2;                                                 // V row inside a 4-row group
+    const uint32_t va0 = (4 * hh + vq) * 256 + ((2 * ((lane >> 4) & 1) + ((lane & 3) >> 1)) << 4) + (lane & 1) * 8;
+    const uint32_t vsw = (uint32_t)vq << 2;                                          // V swizzle of that row
 
-        // ---- S^T[key][query] = K Q^T
-        f32x16 s[QT];
-#pragma unroll
-        for (int qt = 0; qt < QT; qt++)
-#pragma unroll
-            for (int r = 0; r < 16; r++) s[qt][r] = 0.f;
-#pragma unroll
-        for (int ks = 0; ks < 8; ks++) {
-            bf16x8 a = *(const bf16x8*)(ldsK + col * 256 + (((2 * ks + hh) ^ (col & 15)) << 4));
-#pragma unroll
-            for (int qt = 0; qt < QT; qt++)
-                s[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[qt][ks], s[qt], 0, 0, 0);
-        }
+    int64_t g = g_begin;
+    issue();
+    while (g < g_end) {
+        // ================= one segment: the part of unit `unit` inside this span
+        const int unit = (int)(g / p.nblk);
+        const int64_t unit_begin = (int64_t)unit * p.nblk;
+        const int64_t seg_end = g_end < unit_begin + p.nblk ? g_end : unit_begin + p.nblk;
+        const bool whole = g == unit_begin && seg_end == unit_begin + p.nblk;
+        const bool first_seg = g_begin >= unit_begin;
+        const int qg = unit % p.qgroups, slab = unit / p.qgroups;
+        const int h = slab % p.H, nb = slab / p.H;
+        const int qbase = qg * (QT * 32);
 
-        // ---- visibility (only blocks that reach past the prefix): one 32-bit word per lane says which of
-        // the block's 32 keys its query sees; bit i <-> key j*32 + i
-        if (j >= plain_end) {
-            const int kb = j * kBlk - p.P;          // draft-token index of the block's first key (may be < 0)
-            const int end = p.Tk - kb;              // keys at block offset >= end are past the last key
-            const uint32_t in_range = end >= 32 ? 0xffffffffu : (end > 0 ? (1u << end) - 1u : 0u);
+        // mask rows of this unit's queries -> wave-private LDS (lane = query; the halves write words 0,1 / 2,3)
+        {
+            const uint64_t* mrow = p.mask + (p.mask_per_batch ? (int64_t)nb * p.Tq * p.mask_words : 0);
 #pragma unroll
             for (int qt = 0; qt < QT; qt++) {
-                const uint64_t* mw = &lds_mask[(qt * 32 + col) * 4];
-                uint32_t vbits;
-                if (kb < 0) {
-                    vbits = ((1u << (-kb)) - 1u) | ((uint32_t)mw[0] << (-kb));
-                } else {
-                    const int w = kb >> 6, sh = kb & 63;
-                    const uint64_t lo = mw[w];
-                    const uint64_t hi = (w + 1 < 4) ? mw[w + 1] : 0ull;
-                    vbits = (uint32_t)(lo >> sh);
-                    if (sh > 32) vbits |= (uint32_t)(hi << (64 - sh));
-                }
-                vbits &= in_range;
-                vbits >>= 4 * hh;
+                const int qi = qbase + qt * 32 + col;
 #pragma unroll
-                for (int r = 0; r < 16; r++) {
-                    const bool vis = (vbits >> (8 * (r >> 2) + (r & 3))) & 1u;
-                    s[qt][r] = vis ? s[qt][r] : -INFINITY;
+                for (int w = 0; w < 2; w++) {
+                    const int ww = 2 * hh + w;
+                    my_mask[(qt * 32 + col) * 4 + ww] = (qi < p.Tq && ww < p.mask_words) ? mrow[(int64_t)qi * p.mask_words + ww] : 0ull;
+                }
+            }
+        }
+        // Q rows -> wave-private LDS.  The B operand of S^T = K Q^T for k-step ks is, for lane (col, hh), the
+        // 16-byte piece 2*ks + hh of query row col; pieces are stored at (piece ^ (row & 15)) like K rows.
+        {
+            const __bf16* qp = p.q + nb * p.qs[0] + h * p.qs[1];
+#pragma unroll
+            for (int qt = 0; qt < QT; qt++) {
+                const int qi = qbase + qt * 32 + col;
+#pragma unroll
+                for (int ks = 0; ks < 8; ks++) {
+                    i32x4 z = {0, 0, 0, 0};
+                    if (qi < p.Tq) z = *(const i32x4*)(qp + qi * p.qs[2] + 16 * ks + 8 * hh);
+                    *(i32x4*)(my_q + qt * 8192 + (ka0 ^ (ks << 5))) = z;
                 }
             }
         }
 
-        // ---- online softmax, per lane = per query column
-        bf16x8 pf[QT][2];
+        f32x16 o[QT][4];
+        float m_ref[QT], l_run[QT];     // m_ref in log2 units (logit * c)
 #pragma unroll
         for (int qt = 0; qt < QT; qt++) {
-            float mx = s[qt][0];
-#pragma unroll
-            for (int r = 1; r < 16; r++) mx = fmaxf(mx, s[qt][r]);
-            mx = fmaxf(mx, wave_xor32(mx));
-            float m_new = fmaxf(m_run[qt], mx);
-            float alpha = __builtin_amdgcn_exp2f((m_run[qt] - m_new) * p.c);
-            float mc = m_new * p.c;
-            float sum = 0.f;
-#pragma unroll
-            for (int r = 0; r < 16; r++) {
-                float e = __builtin_amdgcn_exp2f(__builtin_fmaf(s[qt][r], p.c, -mc));
-                sum += e;
-                pf[qt][r >> 3][r & 7] = (__bf16)e;
-            }
-            l_run[qt] = l_run[qt] * alpha + sum;
-            m_run[qt] = m_new;
-            if (__any(alpha != 1.0f)) {
-#pragma unroll
-                for (int dt = 0; dt < 4; dt++)
-#pragma unroll
-                    for (int r = 0; r < 16; r++) o[qt][dt][r] *= alpha;
-            }
-        }
-
-        // ---- O^T[d][query] += V^T P^T
-#pragma unroll
-        for (int ss = 0; ss < 2; ss++) {
-            const int rowA = 16 * ss + 4 * hh + ((lane & 15) >> 2);
-            const int sw = (rowA & 3) << 2;
-#pragma unroll
-            for (int dt = 0; dt < 4; dt++) {
-                const int pc = dt * 4 + 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1);
-                const unsigned char* a0 = ldsV + rowA * 256 + ((pc ^ sw) << 4) + (lane & 1) * 8;
-                s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)a0);
-                s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(a0 + 8 * 256));
-                union { struct { s16x4 lo, hi; } sp; bf16x8 v; } u;
-                u.sp.lo = lo;
-                u.sp.hi = hi;
-#pragma unroll
-                for (int qt = 0; qt < QT; qt++)
-                    o[qt][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(u.v, pf[qt][ss], o[qt][dt], 0, 0, 0);
-            }
-        }
-    }
-
-    // ---- combine the two key halves of the wave
-#pragma unroll
-    for (int qt = 0; qt < QT; qt++) l_run[qt] += wave_xor32(l_run[qt]);
-
-    // ---- merge the four waves through LDS: 1 -> 0 and 3 -> 2, then 2 -> 0
-    float* xch = (float*)lds_stage;   // [2 slots][QT*4*16][64] floats: 32 KB per slot at QT = 2
-    for (int round = 0; round < 2; round++) {
-        __syncthreads();
-        const bool sender = round == 0 ? (wave & 1) : (wave == 2);
-        const bool receiver = round == 0 ? !(wave & 1) : (wave == 0);
-        const int slotw = round == 0 ? (wave >> 1) : 0;
-        float* xs = xch + slotw * (QT * 64 * 64);
-        if (sender) {
-#pragma unroll
-            for (int qt = 0; qt < QT; qt++) {
-                lds_ml[wave][qt][0][lane] = m_run[qt];
-                lds_ml[wave][qt][1][lane] = l_run[qt];
-#pragma unroll
-                for (int dt = 0; dt < 4; dt++)
-#pragma unroll
-                    for (int r = 0; r < 16; r++) xs[((qt * 4 + dt) * 16 + r) * 64 + lane] = o[qt][dt][r];
-            }
-        }
-        __syncthreads();
-        if (receiver) {
-            const int from = round == 0 ? wave + 1 : 2;
-#pragma unroll
-            for (int qt = 0; qt < QT; qt++) {
-                float mo = lds_ml[from][qt][0][lane], lo = lds_ml[from][qt][1][lane];
-                float m_new = fmaxf(m_run[qt], mo);
-                float a = __builtin_amdgcn_exp2f((m_run[qt] - m_new) * p.c);
-                float b = __builtin_amdgcn_exp2f((mo - m_new) * p.c);
-                l_run[qt] = l_run[qt] * a + lo * b;
-                m_run[qt] = m_new;
-#pragma unroll
-                for (int dt = 0; dt < 4; dt++)
-#pragma unroll
-                    for (int r = 0; r < 16; r++)
-                        o[qt][dt][r] = o[qt][dt][r] * a + xs[((qt * 4 + dt) * 16 + r) * 64 + lane] * b;
-            }
-        }
-    }
-
-    // ---- wave 0 holds the workgroup's result
-    if (wave != 0) return;
-#pragma unroll
-    for (int qt = 0; qt < QT; qt++) {
-        const int qi = qbase + qt * 32 + col;
-        if (qi >= p.Tq) continue;
-        if (p.nsplit == 1) {
-            const float inv = l_run[qt] > 0.f ? 1.0f / l_run[qt] : 0.f;
-            __bf16* op = p.out + nb * p.os[0] + h * p.os[1] + qi * p.os[2];
+            m_ref[qt] = kNegBig;
+            l_run[qt] = 0.f;
 #pragma unroll
             for (int dt = 0; dt < 4; dt++)
 #pragma unroll
-                for (int g = 0; g < 4; g++) {
-                    bf16x4 w;
+                for (int r = 0; r < 16; r++) o[qt][dt][r] = 0.f;
+        }
+
+        for (; g < seg_end; g++) {
+            // the block's K and V move from the staging registers to LDS, then the loads of the next block
+            // (possibly of the next unit) fly while this one is consumed
+            park();
+            if (g + 1 < g_end) issue();
+            const int j = (int)(g - unit_begin);
+            const unsigned char* ldsK = stage;
+            const unsigned char* ldsV = ldsK + kTileBytes;
+
+            // ---- S^T[key][query] = K Q^T
+            f32x16 s[QT];
 #pragma unroll
-                    for (int e = 0; e < 4; e++) w[e] = (__bf16)(o[qt][dt][4 * g + e] * inv);
-                    *(bf16x4*)(op + dt * 32 + 8 * g + 4 * hh) = w;
+            for (int qt = 0; qt < QT; qt++)
+#pragma unroll
+                for (int r = 0; r < 16; r++) s[qt][r] = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < 8; ks++) {
+                const bf16x8 a = *(const bf16x8*)(ldsK + (ka0 ^ (ks << 5)));
+#pragma unroll
+                for (int qt = 0; qt < QT; qt++) {
+                    const bf16x8 bq = *(const bf16x8*)(my_q + qt * 8192 + (ka0 ^ (ks << 5)));
+                    s[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bq, s[qt], 0, 0, 0);
                 }
-        } else {
-            const int64_t row = (int64_t)stream * p.Tq + qi;
-            float* wo = p.ws_o + row * kD;
+            }
+
+            // ---- visibility (only blocks that reach past the prefix): one 32-bit word per lane says which of
+            // the block's 32 keys its query sees; bit i <-> key j*32 + i
+            if (j >= plain_end) {
+                const int kb = j * kBlk - p.P;          // draft-token index of the block's first key (may be < 0)
+                const int end = p.Tk - kb;              // keys at block offset >= end are past the last key
+                const uint32_t in_range = end >= 32 ? 0xffffffffu : (end > 0 ? (1u << end) - 1u : 0u);
 #pragma unroll
-            for (int dt = 0; dt < 4; dt++)
+                for (int qt = 0; qt < QT; qt++) {
+                    const uint64_t* mw = &my_mask[(qt * 32 + col) * 4];
+                    uint32_t vbits;
+                    if (kb < 0) {
+                        vbits = ((1u << (-kb)) - 1u) | ((uint32_t)mw[0] << (-kb));
+                    } else {
+                        const int w = kb >> 6, sh = kb & 63;
+                        const uint64_t lo = mw[w];
+                        const uint64_t hi = (w + 1 < 4) ? mw[w + 1] : 0ull;
+                        vbits = (uint32_t)(lo >> sh);
+                        if (sh > 32) vbits |= (uint32_t)(hi << (64 - sh));
+                    }
+                    vbits &= in_range;
+                    vbits >>= 4 * hh;
 #pragma unroll
-                for (int g = 0; g < 4; g++) {
-                    f32x4 w;
-#pragma unroll
-                    for (int e = 0; e < 4; e++) w[e] = o[qt][dt][4 * g + e];
-                    *(f32x4*)(wo + dt * 32 + 8 * g + 4 * hh) = w;
+                    for (int r = 0; r < 16; r++) {
+                        const bool vis = (vbits >> (8 * (r >> 2) + (r & 3))) & 1u;
+                        s[qt][r] = vis ? s[qt][r] : -INFINITY;
+                    }
                 }
-            if (hh == 0) {
-                p.ws_ml[row * 2 + 0] = m_run[qt];
-                p.ws_ml[row * 2 + 1] = l_run[qt];
+            }
+
+            // ---- softmax numerators against a lazily updated reference, per lane = per query column
+            bf16x8 pf[QT][2];
+#pragma unroll
+            for (int qt = 0; qt < QT; qt++) {
+                float mx = s[qt][0];
+#pragma unroll
+                for (int r = 1; r < 16; r++) mx = fmaxf(mx, s[qt][r]);
+                mx = fmaxf(mx, wave_xor32(mx)) * p.c;
+                if (__any(mx > m_ref[qt] + kLazy)) {
+                    const float m_new = fmaxf(m_ref[qt], mx);
+                    const float alpha = __builtin_amdgcn_exp2f(m_ref[qt] - m_new);
+                    m_ref[qt] = m_new;
+                    l_run[qt] *= alpha;
+#pragma unroll
+                    for (int dt = 0; dt < 4; dt++)
+#pragma unroll
+                        for (int r = 0; r < 16; r++) o[qt][dt][r] *= alpha;
+                }
+                const float mr = m_ref[qt];
+                float sum = 0.f;
+#pragma unroll
+                for (int r = 0; r < 16; r++) {
+                    const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(s[qt][r], p.c, -mr));
+                    sum += e;
+                    pf[qt][r >> 3][r & 7] = (__bf16)e;
+                }
+                l_run[qt] += sum;
+            }
+
+            // ---- O^T[d][query] += V^T P^T
+#pragma unroll
+            for (int ss = 0; ss < 2; ss++) {
+#pragma unroll
+                for (int dt = 0; dt < 4; dt++) {
+                    const unsigned char* a0 = ldsV + va0 + ss * 4096 + ((((uint32_t)dt << 2) ^ vsw) << 4);
+                    s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)a0);
+                    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(a0 + 8 * 256));
+                    union { struct { s16x4 lo, hi; } sp; bf16x8 v; } u;
+                    u.sp.lo = lo;
+                    u.sp.hi = hi;
+#pragma unroll
+                    for (int qt = 0; qt < QT; qt++)
+                        o[qt][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(u.v, pf[qt][ss], o[qt][dt], 0, 0, 0);
+                }
+            }
+        }
+
+        // ================= end of segment: the two key halves of the wave hold disjoint keys
+#pragma unroll
+        for (int qt = 0; qt < QT; qt++) {
+            l_run[qt] += wave_xor32(l_run[qt]);
+            const int qi = qbase + qt * 32 + col;
+            if (qi >= p.Tq) continue;
+            if (whole) {
+                const float inv = l_run[qt] > 0.f ? 1.0f / l_run[qt] : 0.f;
+                __bf16* op = p.out + nb * p.os[0] + h * p.os[1] + qi * p.os[2];
+#pragma unroll
+                for (int dt = 0; dt < 4; dt++)
+#pragma unroll
+                    for (int gq = 0; gq < 4; gq++) {
+                        bf16x4 w;
+#pragma unroll
+                        for (int e = 0; e < 4; e++) w[e] = (__bf16)(o[qt][dt][4 * gq + e] * inv);
+                        *(bf16x4*)(op + dt * 32 + 8 * gq + 4 * hh) = w;
+                    }
+            } else {
+                const int64_t row = ((int64_t)gw * 2 + (first_seg ? 0 : 1)) * (QT * 32) + qt * 32 + col;
+                float* wo = p.ws_o + row * kD;
+#pragma unroll
+                for (int dt = 0; dt < 4; dt++)
+#pragma unroll
+                    for (int gq = 0; gq < 4; gq++) {
+                        f32x4 w;
+#pragma unroll
+                        for (int e = 0; e < 4; e++) w[e] = o[qt][dt][4 * gq + e];
+                        *(f32x4*)(wo + dt * 32 + 8 * gq + 4 * hh) = w;
+                    }
+                if (hh == 0) {
+                    p.ws_ml[row * 2 + 0] = m_ref[qt];
+                    p.ws_ml[row * 2 + 1] = l_run[qt];
+                }
             }
         }
     }
 }
 
-// Merges the partial (max, sum, O) of the KV splits of one (batch, head, query): one 128-thread block per row.
-template <typename OutT>
-__global__ __launch_bounds__(128) void tree_attn_merge_kernel(const float* ws_o, const float* ws_ml, OutT* out,
-                                                              int32_t H, int32_t Tq, int32_t nsplit, float c,
-                                                              int64_t os0, int64_t os1, int64_t os2) {
-    const int64_t rowid = blockIdx.x;            // (slab, qi)
-    const int qi = (int)(rowid % Tq);
-    const int64_t slab = rowid / Tq;
-    const int h = (int)(slab % H);
-    const int64_t nb = slab / H;
+// Merges the partials of every unit that was cut between streams: one 128-thread block per (unit, query).
+template <int QT>
+__global__ __launch_bounds__(128) void tree_attn_streamk_merge_kernel(AttnParams p) {
+    const int unit = blockIdx.x / (QT * 32), ql = blockIdx.x % (QT * 32);
+    const int qg = unit % p.qgroups, slab = unit / p.qgroups;
+    const int qi = qg * (QT * 32) + ql;
+    if (qi >= p.Tq) return;
+    const int64_t total = (int64_t)p.units * p.nblk;
+    const int64_t ub = (int64_t)unit * p.nblk, ue = ub + p.nblk;
+    const int w0 = span_owner(total, p.n_streams, ub), w1 = span_owner(total, p.n_streams, ue - 1);
+    if (w0 == w1) return;     // one stream covered the whole unit and wrote the output itself
     const int d = threadIdx.x;
     float m = kNegBig;
-    for (int s = 0; s < nsplit; s++) m = fmaxf(m, ws_ml[((slab * nsplit + s) * Tq + qi) * 2]);
-    float l = 0.f, acc = 0.f;
-    for (int s = 0; s < nsplit; s++) {
-        const int64_t row = (slab * nsplit + s) * Tq + qi;
-        float w = __builtin_amdgcn_exp2f((ws_ml[row * 2] - m) * c);
-        l += ws_ml[row * 2 + 1] * w;
-        acc += ws_o[row * kD + d] * w;
+    for (int w = w0; w <= w1; w++) {
+        const int64_t sb = span_begin(total, p.n_streams, w), se = span_begin(total, p.n_streams, w + 1);
+        if (sb >= se) continue;
+        const int64_t row = ((int64_t)w * 2 + (sb >= ub ? 0 : 1)) * (QT * 32) + ql;
+        m = fmaxf(m, p.ws_ml[row * 2]);
     }
-    out[nb * os0 + h * os1 + qi * os2 + d] = (OutT)(l > 0.f ? acc / l : 0.f);
+    float l = 0.f, acc = 0.f;
+    for (int w = w0; w <= w1; w++) {
+        const int64_t sb = span_begin(total, p.n_streams, w), se = span_begin(total, p.n_streams, w + 1);
+        if (sb >= se) continue;
+        const int64_t row = ((int64_t)w * 2 + (sb >= ub ? 0 : 1)) * (QT * 32) + ql;
+        const float wgt = __builtin_amdgcn_exp2f(p.ws_ml[row * 2] - m);
+        l += p.ws_ml[row * 2 + 1] * wgt;
+        acc += p.ws_o[row * kD + d] * wgt;
+    }
+    const int h = slab % p.H, nb = slab / p.H;
+    p.out[nb * p.os[0] + h * p.os[1] + qi * p.os[2] + d] = (__bf16)(l > 0.f ? acc / l : 0.f);
 }
 
+// ---------------------------------------------------------------------------------------------------------
 // fp32 path: plain fp32 arithmetic, one 128-thread block per (batch, head, query), one KV split per
 // blockIdx.y.  Exists for accuracy checks with fp32 inputs; not a throughput path.
 __global__ __launch_bounds__(128) void tree_attn_f32_kernel(const float* q, const float* k, const float* v,
@@ -413,19 +455,63 @@ __global__ __launch_bounds__(128) void tree_attn_f32_kernel(const float* q, cons
     }
 }
 
-int choose_splits(const rest_attn_desc* d) {
-    if (d->num_splits > 0) return d->num_splits;
+__global__ __launch_bounds__(128) void tree_attn_f32_merge_kernel(const float* ws_o, const float* ws_ml, float* out,
+                                                                  int32_t H, int32_t Tq, int32_t nsplit, float c,
+                                                                  int64_t os0, int64_t os1, int64_t os2) {
+    const int64_t rowid = blockIdx.x;            // (slab, qi)
+    const int qi = (int)(rowid % Tq);
+    const int64_t slab = rowid / Tq;
+    const int h = (int)(slab % H);
+    const int64_t nb = slab / H;
+    const int d = threadIdx.x;
+    float m = kNegBig;
+    for (int s = 0; s < nsplit; s++) m = fmaxf(m, ws_ml[((slab * nsplit + s) * Tq + qi) * 2]);
+    float l = 0.f, acc = 0.f;
+    for (int s = 0; s < nsplit; s++) {
+        const int64_t row = (slab * nsplit + s) * Tq + qi;
+        float w = __builtin_amdgcn_exp2f((ws_ml[row * 2] - m) * c);
+        l += ws_ml[row * 2 + 1] * w;
+        acc += ws_o[row * kD + d] * w;
+    }
+    out[nb * os0 + h * os1 + qi * os2 + d] = l > 0.f ? acc / l : 0.f;
+}
+
+// ---------------------------------------------------------------------------------------------------------
+struct Plan {
+    int qt, qgroups, nblk, units, n_streams, nsplit_f32;
+    bool need_merge;
+};
+
+Plan make_plan(const rest_attn_desc* d) {
+    Plan pl{};
     const int Lk = d->P + d->Tk;
-    const int64_t slabs = (int64_t)d->Nb * d->H;
-    if (d->dtype == REST_FP32) return 1;
-    const int nblk = (Lk + kBlk - 1) / kBlk;
-    // aim for about two workgroups per compute unit, but keep >= 4 key blocks per wavefront
-    int want = (int)((512 + slabs - 1) / slabs);
-    int cap = nblk / (kWaves * 4);
-    if (want > cap) want = cap;
-    if (want < 1) want = 1;
-    if (want > 64) want = 64;
-    return want;
+    pl.nblk = (Lk + kBlk - 1) / kBlk;
+    if (d->dtype == REST_FP32) {
+        pl.nsplit_f32 = d->num_splits > 0 ? d->num_splits : 1;
+        return pl;
+    }
+    pl.qt = d->Tq <= 32 ? 1 : 2;
+    pl.qgroups = (d->Tq + pl.qt * 32 - 1) / (pl.qt * 32);
+    pl.units = d->Nb * d->H * pl.qgroups;
+    const int64_t total = (int64_t)pl.units * pl.nblk;
+    int64_t w;
+    if (d->num_splits > 0) {
+        w = (int64_t)pl.units * d->num_splits;       // explicit request: num_splits streams per unit
+        if (w > 16384) w = 16384;
+    } else {
+        // one wavefront per SIMD of the chip, but at least four key blocks per stream
+        w = total / 4;
+        if (w > kMaxWaves) w = kMaxWaves;
+    }
+    if (w > total) w = total;
+    if (w < 1) w = 1;
+    pl.n_streams = (int)w;
+    pl.need_merge = false;
+    for (int u = 0; u < pl.units && !pl.need_merge; u++) {
+        const int64_t ub = (int64_t)u * pl.nblk;
+        if (span_owner(total, pl.n_streams, ub) != span_owner(total, pl.n_streams, ub + pl.nblk - 1)) pl.need_merge = true;
+    }
+    return pl;
 }
 
 bool desc_ok(const rest_attn_desc* d) {
@@ -443,6 +529,8 @@ bool desc_ok(const rest_attn_desc* d) {
     for (int i = 0; i < 3; i++)
         if (d->q_stride[i] % al || d->k_stride[i] % al || d->v_stride[i] % al || d->o_stride[i] % 4) return false;
     if (d->q_stride[2] < kD || d->k_stride[2] < kD || d->v_stride[2] < kD || d->o_stride[2] < kD) return false;
+    // four consecutive rows are addressed with a 32-bit byte offset
+    if (d->k_stride[2] > (1 << 26) || d->v_stride[2] > (1 << 26)) return false;
     return true;
 }
 
@@ -450,10 +538,13 @@ bool desc_ok(const rest_attn_desc* d) {
 
 extern "C" __attribute__((visibility("default"))) size_t rest_tree_attention_workspace_bytes(const rest_attn_desc* d) {
     if (!desc_ok(d)) return 0;
-    const int ns = choose_splits(d);
-    if (ns == 1) return 0;
-    const size_t rows = (size_t)d->Nb * d->H * ns * d->Tq;
-    return rows * (kD + 2) * sizeof(float);
+    const Plan pl = make_plan(d);
+    if (d->dtype == REST_FP32) {
+        if (pl.nsplit_f32 == 1) return 0;
+        return (size_t)d->Nb * d->H * pl.nsplit_f32 * d->Tq * (kD + 2) * sizeof(float);
+    }
+    if (!pl.need_merge) return 0;
+    return (size_t)pl.n_streams * 2 * (pl.qt * 32) * (kD + 2) * sizeof(float);
 }
 
 extern "C" __attribute__((visibility("default"))) rest_status rest_tree_attention(const void* d_q, const void* d_k, const void* d_v, const uint64_t* d_mask,
@@ -463,7 +554,7 @@ extern "C" __attribute__((visibility("default"))) rest_status rest_tree_attentio
     if (d->Tk > 0 && !d_mask) return REST_INVALID_ARG;
     if (((uintptr_t)d_q | (uintptr_t)d_k | (uintptr_t)d_v | (uintptr_t)d_out) & 15) return REST_INVALID_ARG;
     hipStream_t stream = (hipStream_t)stream_;
-    const int ns = choose_splits(d);
+    const Plan pl = make_plan(d);
     const size_t need = rest_tree_attention_workspace_bytes(d);
     if (need > workspace_bytes || (need && !d_workspace)) return REST_WORKSPACE_TOO_SMALL;
 
@@ -475,36 +566,43 @@ extern "C" __attribute__((visibility("default"))) rest_status rest_tree_attentio
     p.mask = d_mask ? d_mask : (const uint64_t*)d_q;
     p.out = (__bf16*)d_out;
     p.Nb = d->Nb; p.H = d->H; p.Tq = d->Tq; p.Tk = d->Tk; p.P = d->P; p.Lk = d->P + d->Tk;
-    p.nsplit = ns;
     p.mask_words = (d->Tk + 63) / 64;
     p.mask_per_batch = d->mask_per_batch ? 1 : 0;
-    p.nblk = (p.Lk + kBlk - 1) / kBlk;
-    p.nstreams = d->Nb * d->H * ns;
+    p.nblk = pl.nblk;
     p.c = d->scale * 1.4426950408889634f;
     for (int i = 0; i < 3; i++) { p.qs[i] = d->q_stride[i]; p.ks[i] = d->k_stride[i]; p.vs[i] = d->v_stride[i]; p.os[i] = d->o_stride[i]; }
-    const size_t rows = (size_t)p.nstreams * d->Tq;
     p.ws_o = (float*)d_workspace;
-    p.ws_ml = p.ws_o ? p.ws_o + rows * kD : nullptr;
 
     if (d->dtype == REST_BF16) {
-        const int qt = d->Tq <= 32 ? 1 : 2;
-        p.qgroups = (d->Tq + qt * 32 - 1) / (qt * 32);
-        const int grid = ((p.nstreams + 7) / 8) * 8 * p.qgroups;
-        if (qt == 1) hipLaunchKernelGGL(tree_attn_bf16_kernel<1>, dim3(grid), dim3(256), 0, stream, p);
+        p.nsplit = 1;
+        p.qgroups = pl.qgroups;
+        p.units = pl.units;
+        p.n_streams = pl.n_streams;
+        const size_t rows = (size_t)pl.n_streams * 2 * (pl.qt * 32);
+        p.ws_ml = p.ws_o ? p.ws_o + rows * kD : nullptr;
+        const int grid = (pl.n_streams + kWaves - 1) / kWaves;
+        if (pl.qt == 1) hipLaunchKernelGGL(tree_attn_bf16_kernel<1>, dim3(grid), dim3(256), 0, stream, p);
         else hipLaunchKernelGGL(tree_attn_bf16_kernel<2>, dim3(grid), dim3(256), 0, stream, p);
         REST_HIP_TRY(hipGetLastError());
-        if (ns > 1) {
-            hipLaunchKernelGGL(tree_attn_merge_kernel<__bf16>, dim3(d->Nb * d->H * d->Tq), dim3(128), 0, stream,
-                               p.ws_o, p.ws_ml, (__bf16*)d_out, d->H, d->Tq, ns, p.c, p.os[0], p.os[1], p.os[2]);
+        if (pl.need_merge) {
+            const int mgrid = pl.units * pl.qt * 32;
+            if (pl.qt == 1) hipLaunchKernelGGL(tree_attn_streamk_merge_kernel<1>, dim3(mgrid), dim3(128), 0, stream, p);
+            else hipLaunchKernelGGL(tree_attn_streamk_merge_kernel<2>, dim3(mgrid), dim3(128), 0, stream, p);
             REST_HIP_TRY(hipGetLastError());
         }
     } else {
+        const int ns = pl.nsplit_f32;
+        p.nsplit = ns;
         p.qgroups = 1;
+        p.units = 0;
+        p.n_streams = 0;
+        const size_t rows = (size_t)d->Nb * d->H * ns * d->Tq;
+        p.ws_ml = p.ws_o ? p.ws_o + rows * kD : nullptr;
         hipLaunchKernelGGL(tree_attn_f32_kernel, dim3(d->Nb * d->H * d->Tq, ns), dim3(128), 0, stream,
                            (const float*)d_q, (const float*)d_k, (const float*)d_v, p.mask, (float*)d_out, p.ws_o, p.ws_ml, p);
         REST_HIP_TRY(hipGetLastError());
         if (ns > 1) {
-            hipLaunchKernelGGL(tree_attn_merge_kernel<float>, dim3(d->Nb * d->H * d->Tq), dim3(128), 0, stream,
+            hipLaunchKernelGGL(tree_attn_f32_merge_kernel, dim3(d->Nb * d->H * d->Tq), dim3(128), 0, stream,
                                p.ws_o, p.ws_ml, (float*)d_out, d->H, d->Tq, ns, p.c, p.os[0], p.os[1], p.os[2]);
             REST_HIP_TRY(hipGetLastError());
         }

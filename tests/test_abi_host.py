@@ -64,12 +64,15 @@ def make_desc(rest, **over):
 
 
 def test_attention_workspace_sizing_is_host_only(rest):
-    assert rest.rest_tree_attention_workspace_bytes(make_desc(rest)) == 0          # 1024 (layer, head) slabs: no KV split
+    # 1024 (layer, head) units over 1024 streams: every stream owns whole units, no partial results
+    assert rest.rest_tree_attention_workspace_bytes(make_desc(rest)) == 0
+    # one layer: 32 units x 66 key blocks = 2112 blocks over 2112 / 4 = 528 streams, two partial slots each
     one_layer = make_desc(rest, Nb=1)
-    need = rest.rest_tree_attention_workspace_bytes(one_layer)
-    assert need > 0 and need % ((128 + 2) * 4 * 64 * 32) == 0                       # splits x rows x (O row + max + sum)
+    assert rest.rest_tree_attention_workspace_bytes(one_layer) == 528 * 2 * 64 * (128 + 2) * 4
     forced = make_desc(rest, Nb=1, num_splits=4)
-    assert rest.rest_tree_attention_workspace_bytes(forced) == 32 * 4 * 64 * 130 * 4
+    assert rest.rest_tree_attention_workspace_bytes(forced) == 32 * 4 * 2 * 64 * 130 * 4
+    fp32 = make_desc(rest, Nb=1, dtype=rest.REST_FP32, num_splits=3)
+    assert rest.rest_tree_attention_workspace_bytes(fp32) == 32 * 3 * 64 * 130 * 4
     for bad in [dict(D=64), dict(Tq=0), dict(Tq=257), dict(Tk=257), dict(scale=0.0), dict(dtype=7), dict(num_splits=65),
                 dict(Nb=0), dict(P=-1)]:
         assert rest.rest_tree_attention_workspace_bytes(make_desc(rest, **bad)) == 0
