@@ -11,6 +11,9 @@ LIB = os.path.join(HERE, "librest_gfx950.so")
 SOURCES = ["api.hip", "attention.hip", "retrieve.hip", "accept.hip", "build_index.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fvisibility=hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+# per-source extras: keep the MFMA accumulators of the attention kernel in ordinary vector registers; the
+# compiler's default choice shuttles all 128 of them through the accumulation file on every loop trip
+EXTRA = {"attention.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
 
 
 def build(verbose: bool = False) -> str:
@@ -20,7 +23,7 @@ def build(verbose: bool = False) -> str:
     os.makedirs(bdir, exist_ok=True)
     for src in SOURCES:
         obj = os.path.join(bdir, src.replace(".hip", ".o"))
-        cmd = ["hipcc", "-c", os.path.join(CSRC, src), "-o", obj] + [f for f in FLAGS if f != "-shared"]
+        cmd = ["hipcc", "-c", os.path.join(CSRC, src), "-o", obj] + [f for f in FLAGS if f != "-shared"] + EXTRA.get(src, [])
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
         objs.append(obj)
     failed = False

@@ -112,16 +112,16 @@ __global__ __launch_bounds__(256) void tree_attn_bf16_kernel(AttnParams p) {
     int ld_unit = (int)(g_begin / p.nblk), ld_j = (int)(g_begin % p.nblk);
     const char *ld_kp, *ld_vp;
     unit_bases(ld_unit, ld_kp, ld_vp);
-    // issues the loads of the cursor's block into the staging registers and advances the cursor
+    // Staging registers for the block under the cursor.  K and V halves are issued and parked at different
+    // points of the loop body, so one half is always in flight while the other is being moved to LDS.
     i32x4 kr[8], vr[8];
-    auto issue = [&]() {
+    auto issue_half = [&](i32x4 (&dst)[8], const char* base, int64_t row_bytes, bool is_k) {
         const int j = ld_j;
         if ((j + 1) * kBlk <= p.Lk) {
 #pragma unroll
             for (int i = 0; i < 8; i++) {
                 const int64_t row = (int64_t)j * kBlk + i * 4;
-                kr[i] = __builtin_nontemporal_load((const i32x4*)(ld_kp + row * k_row_bytes + k_off[i & 3]));
-                vr[i] = __builtin_nontemporal_load((const i32x4*)(ld_vp + row * v_row_bytes + v_off));
+                dst[i] = __builtin_nontemporal_load((const i32x4*)(base + row * row_bytes + (is_k ? k_off[i & 3] : v_off)));
             }
         } else {
             // last, partial block of a unit: rows past the end re-read the last row; those keys are never visible
@@ -129,11 +129,15 @@ __global__ __launch_bounds__(256) void tree_attn_bf16_kernel(AttnParams p) {
             for (int i = 0; i < 8; i++) {
                 int64_t row = (int64_t)j * kBlk + i * 4 + lrow;
                 row = row < p.Lk ? row : p.Lk - 1;
-                const int sw_k = (lpc ^ ((i & 3) * 4 + lrow)) << 4, sw_v = (lpc ^ (lrow << 2)) << 4;
-                kr[i] = __builtin_nontemporal_load((const i32x4*)(ld_kp + row * k_row_bytes + sw_k));
-                vr[i] = __builtin_nontemporal_load((const i32x4*)(ld_vp + row * v_row_bytes + sw_v));
+                const int sw = is_k ? (lpc ^ ((i & 3) * 4 + lrow)) << 4 : (lpc ^ (lrow << 2)) << 4;
+                dst[i] = __builtin_nontemporal_load((const i32x4*)(base + row * row_bytes + sw));
             }
         }
+    };
+    auto issue_k = [&]() { issue_half(kr, ld_kp, k_row_bytes, true); };
+    // V follows K of the same block; then the cursor advances
+    auto issue_v = [&]() {
+        issue_half(vr, ld_vp, v_row_bytes, false);
         if (++ld_j == p.nblk) {
             ld_j = 0;
             ld_unit++;
@@ -141,12 +145,13 @@ __global__ __launch_bounds__(256) void tree_attn_bf16_kernel(AttnParams p) {
         }
     };
     // staging registers -> LDS tile: lane l's piece of chunk i goes to tile + i*1024 + l*16
-    auto park = [&]() {
+    auto park_k = [&]() {
 #pragma unroll
-        for (int i = 0; i < 8; i++) {
-            *(i32x4*)(stage + i * 1024 + lane * 16) = kr[i];
-            *(i32x4*)(stage + kTileBytes + i * 1024 + lane * 16) = vr[i];
-        }
+        for (int i = 0; i < 8; i++) *(i32x4*)(stage + i * 1024 + lane * 16) = kr[i];
+    };
+    auto park_v = [&]() {
+#pragma unroll
+        for (int i = 0; i < 8; i++) *(i32x4*)(stage + kTileBytes + i * 1024 + lane * 16) = vr[i];
     };
 
     // ---- LDS read addresses (byte offsets inside a K or V tile), loop invariant
@@ -156,7 +161,8 @@ __global__ __launch_bounds__(256) void tree_attn_bf16_kernel(AttnParams p) {
     const uint32_t vsw = (uint32_t)vq << 2;                                          // V swizzle of that row
 
     int64_t g = g_begin;
-    issue();
+    issue_k();
+    issue_v();
     while (g < g_end) {
         // ================= one segment: the part of unit `unit` inside this span
         const int unit = (int)(g / p.nblk);
@@ -210,10 +216,13 @@ __global__ __launch_bounds__(256) void tree_attn_bf16_kernel(AttnParams p) {
         }
 
         for (; g < seg_end; g++) {
-            // the block's K and V move from the staging registers to LDS, then the loads of the next block
-            // (possibly of the next unit) fly while this one is consumed
-            park();
-            if (g + 1 < g_end) issue();
+            // K of this block moves from its staging registers to LDS and K of the next block (possibly of the
+            // next unit) is requested; V of this block is still in flight
+            park_k();
+            if (g + 1 < g_end) issue_k();
+            // compiler barrier: the query fragments are re-read from LDS for every block instead of being
+            // hoisted into 64 registers for the whole segment
+            asm volatile("" ::: "memory");
             const int j = (int)(g - unit_begin);
             const unsigned char* ldsK = stage;
             const unsigned char* ldsV = ldsK + kTileBytes;
@@ -291,6 +300,11 @@ __global__ __launch_bounds__(256) void tree_attn_bf16_kernel(AttnParams p) {
                 }
                 l_run[qt] += sum;
             }
+
+            // ---- V of this block -> LDS, V of the next block requested
+            park_v();
+            if (g + 1 < g_end) issue_v();
+            asm volatile("" ::: "memory");
 
             // ---- O^T[d][query] += V^T P^T
 #pragma unroll
