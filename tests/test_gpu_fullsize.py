@@ -1,0 +1,142 @@
+"""Full-size GPU parity: the benchmark's own shapes and launch configuration, checked on sampled outputs the
+oracle can compute one by one (whole contexts for retrieval, whole (layer, head) slabs for attention) and on
+the suffix array's defining property.  The 13B-shaped and 2-billion-token workloads are marked `big`."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth
+
+pytestmark = pytest.mark.gpu
+
+if torch.cuda.is_available():
+    import paper_2311_08252_amd as rest
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def check_retrieval(corp, index, w, n_contexts, seed, sample):
+    ctx, lens = synth.make_contexts(corp, n_contexts, w.ctx_len, seed)
+    prm = dict(n_max=w.n_max, n_min=w.n_min, max_matches=w.max_matches, cont_len=w.cont_len, max_nodes=w.max_nodes)
+    out = rest.Tree.empty(n_contexts, w.max_nodes, fill=-0x5A5A5A5B)
+    rest.rest_retrieve(index, dev(ctx), dev(lens), out=out, **prm)
+    torch.cuda.synchronize()
+    tok, par = out.draft_tokens.cpu().numpy(), out.parent_idx.cpu().numpy()
+    pos, wgt = out.pos_ids.cpu().numpy(), out.node_weight.cpu().numpy()
+    msk = out.tree_mask.cpu().numpy().view(np.uint64)
+    nn, ml, mc = out.n_nodes.cpu().numpy(), out.matched_len.cpu().numpy(), out.match_count.cpu().numpy()
+    lens_seen = set()
+    for b in sample:
+        want = oracle.draft_tree(corp.tokens, ctx[b], w.n_max, w.n_min, w.max_matches, w.cont_len, w.max_nodes, one_pass=True)
+        assert (int(ml[b]), int(mc[b]), int(nn[b])) == (want.matched_len, want.match_count, want.n_nodes), b
+        np.testing.assert_array_equal(tok[b], want.draft_tokens)
+        np.testing.assert_array_equal(par[b], want.parent_idx)
+        np.testing.assert_array_equal(pos[b], want.pos_ids)
+        np.testing.assert_array_equal(wgt[b], want.node_weight)
+        np.testing.assert_array_equal(msk[b], want.tree_mask)
+        lens_seen.add(want.matched_len)
+    # properties that hold for every context at any size
+    T = nn.astype(np.int64)
+    cols = np.arange(w.max_nodes)[None, :]
+    live = cols < T[:, None]
+    assert ((par < cols) | ~live).all() and (par[~live] == -1).all() and (tok[~live] == -1).all()
+    assert ((pos >= 1) & (pos <= w.cont_len))[live].all() and (pos[~live] == 0).all()
+    assert (mc >= 0).all() and ((ml == 0) == (mc == 0)).all() and (ml <= w.n_max).all()
+    return lens_seen
+
+
+def sampled_attention_check(Nb, H, T, P, seed, n_sample, mask_np):
+    """Inputs from torch's seeded GPU generator (as bench.py does), one launch over all Nb x H slabs, parity on a
+    seeded sample of slabs including the first and the last."""
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    q = torch.randn((Nb, H, T, 128), generator=g, device="cuda").to(torch.bfloat16)
+    k = torch.randn((Nb, H, P + T, 128), generator=g, device="cuda").to(torch.bfloat16)
+    v = torch.randn((Nb, H, P + T, 128), generator=g, device="cuda").to(torch.bfloat16)
+    out = torch.full_like(q, float("nan"))
+    scale = 1.0 / np.sqrt(128.0)
+    rest.rest_tree_attention(q, k, v, dev(mask_np.view(np.int64)), P, float(scale), out=out)
+    torch.cuda.synchronize()
+    assert torch.isfinite(out.float()).all()
+    rng = np.random.default_rng(seed)
+    picks = {(0, 0), (Nb - 1, H - 1)}
+    while len(picks) < n_sample:
+        picks.add((int(rng.integers(Nb)), int(rng.integers(H))))
+    worst = 0.0
+    for a, b in sorted(picks):
+        ref = oracle.tree_attention(q[a, b].float().cpu().numpy(), k[a, b].float().cpu().numpy(),
+                                    v[a, b].float().cpu().numpy(), mask_np, P, scale)
+        worst = max(worst, float(np.abs(out[a, b].float().cpu().numpy() - ref).max()))
+    assert worst <= 2e-2, worst
+    return worst
+
+
+def test_llama7b_index_retrieval_attention_at_benchmark_shape():
+    w = synth.WORKLOADS["llama7b"]
+    corp = synth.make_corpus(w.n_tokens, w.corpus_seed, w.n_motifs)
+    d_corpus = dev(corp.tokens)
+    index = rest.rest_build_index(d_corpus, 4)
+    sa = index.suffix_array().cpu().numpy()
+    assert oracle.check_suffix_array(corp.tokens, sa) == -1          # permutation + strictly increasing suffixes
+    del sa
+    # the 16 contexts the benchmark rotates over: every one of them against the oracle
+    seen = check_retrieval(corp, index, w, 16, w.query_seed, range(16))
+    assert 16 in seen and min(seen) <= 4                              # long planted matches and short fallbacks
+    # the batched throughput set: 4096 contexts in one launch, a sample of them against the oracle
+    check_retrieval(corp, index, w, 4096, w.query_seed + 1, [0, 1, 2, 3, 1000, 2047, 4094, 4095])
+    # attention in the benchmark's launch configuration, with the tree of context 0
+    tree = oracle.draft_tree(corp.tokens, synth.make_contexts(corp, 1, w.ctx_len, w.query_seed)[0][0],
+                             w.n_max, w.n_min, w.max_matches, w.cont_len, w.max_nodes, one_pass=True)
+    sampled_attention_check(w.layers, w.heads, w.max_nodes, w.kv_len, w.qkv_seed, 24, tree.tree_mask)
+
+
+@pytest.mark.parametrize("T,P", [(16, 1024), (64, 8192), (128, 4096), (256, 1024), (256, 8192)])
+def test_sweep_shapes_random_trees(T, P):
+    """Tree-size / KV-length sweep at the 7B head shape with random tries (branching <= 8, depth <= 16)."""
+    mask = synth.random_tree(T, 14 + T)[3]
+    sampled_attention_check(32, 32, T, P, 100 + T + P, 6, mask)
+
+
+@pytest.mark.big
+def test_llama13b_shape():
+    w = synth.WORKLOADS["llama13b"]
+    corp = synth.make_corpus(w.n_tokens, w.corpus_seed, w.n_motifs)
+    index = rest.rest_build_index(dev(corp.tokens), 4)
+    sa = index.suffix_array().cpu().numpy()
+    assert oracle.check_suffix_array(corp.tokens, sa) == -1
+    del sa
+    check_retrieval(corp, index, w, 8, w.query_seed, range(8))
+    mask = synth.random_tree(w.max_nodes, 3)[3]
+    sampled_attention_check(w.layers, w.heads, w.max_nodes, w.kv_len, w.qkv_seed, 12, mask)
+
+
+@pytest.mark.big
+def test_batched_2b_uint16_int64():
+    w = synth.WORKLOADS["batched2b"]
+    corp = synth.make_corpus(w.n_tokens, w.corpus_seed, w.n_motifs, dtype=np.uint16, workers=16)
+    index = rest.rest_build_index(dev(corp.tokens), 8)
+    if os.environ.get("REST_BIG_CHECK_SA", "1") == "1":
+        sa = index.suffix_array().cpu().numpy()
+        assert sa.dtype == np.int64
+        assert oracle.check_suffix_array(corp.tokens, sa) == -1
+        del sa
+    check_retrieval(corp, index, w, w.batch, w.query_seed, [0, 1, 2, 3, 30, 31])
+    # 32 contexts, one layer, per-context masks
+    g = torch.Generator(device="cuda")
+    g.manual_seed(w.qkv_seed)
+    Nb, H, T, P = w.batch, w.heads, w.max_nodes, w.kv_len
+    masks = np.stack([synth.random_tree(T, 500 + i)[3] for i in range(Nb)])
+    q = torch.randn((Nb, H, T, 128), generator=g, device="cuda").to(torch.bfloat16)
+    k = torch.randn((Nb, H, P + T, 128), generator=g, device="cuda").to(torch.bfloat16)
+    v = torch.randn((Nb, H, P + T, 128), generator=g, device="cuda").to(torch.bfloat16)
+    out = rest.rest_tree_attention(q, k, v, dev(masks.view(np.int64)), P, float(1 / np.sqrt(128.0)))
+    torch.cuda.synchronize()
+    for a, b in [(0, 0), (5, 17), (31, 31)]:
+        ref = oracle.tree_attention(q[a, b].float().cpu().numpy(), k[a, b].float().cpu().numpy(),
+                                    v[a, b].float().cpu().numpy(), masks[a], P, 1 / np.sqrt(128.0))
+        assert np.abs(out[a, b].float().cpu().numpy() - ref).max() <= 2e-2
