@@ -32,6 +32,8 @@ def main() -> int:
     ap.add_argument("--workload", default="llama7b", choices=["llama7b", "tiny"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the per-layer and batched-retrieval side measurements")
+    ap.add_argument("--sweep", action="store_true",
+                    help="also time tree attention over the tree-size / KV-length sweep (random tries, 32 x 32 heads)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device-to-device copy five times (reference for rocprofv3 --pmc byte counters)")
     args = ap.parse_args()
@@ -159,6 +161,8 @@ def main() -> int:
 
     if not args.no_extras:
         result["extra"].update(side_measurements(rest, torch, synth, corp, index, w, q, k, v, out, trees[0], P, scale, prm))
+    if args.sweep:
+        result["extra"]["attention_sweep"] = attention_sweep(rest, torch, synth, np, dev)
     if not args.no_cpu_baseline:
         result["cpu_baseline"], result["extra"]["parity_sample_max_abs_err"] = cpu_baseline(
             np, torch, corp, ctx_np, w, q, k, v, out, trees, ids, P, scale, step)
@@ -210,6 +214,39 @@ def side_measurements(rest, torch, synth, corp, index, w, q, k, v, out, tree, P,
     ms = timed(lambda: rest.rest_tree_attention(q, k, v, mask, P, scale, out=out), 20)
     res["attn_single_launch_us"] = round(ms * 1e3, 1)
     return res
+
+
+def attention_sweep(rest, torch, synth, np, dev):
+    """Tree attention alone over draft-tree sizes and KV lengths at the 7B head shape (32 layers x 32 heads x 128,
+    one launch), random tries with branching <= 8 and depth <= 16."""
+    rows = []
+    for T in (16, 64, 128, 256):
+        mask = torch.from_numpy(synth.random_tree(T, 14 + T)[3].view(np.int64)).to(dev)
+        for P in (1024, 4096, 8192):
+            g = torch.Generator(device=dev)
+            g.manual_seed(T * 100000 + P)
+            q = torch.randn((32, 32, T, 128), generator=g, device=dev).to(torch.bfloat16)
+            k = torch.randn((32, 32, P + T, 128), generator=g, device=dev).to(torch.bfloat16)
+            v = torch.randn((32, 32, P + T, 128), generator=g, device=dev).to(torch.bfloat16)
+            out = torch.empty_like(q)
+            scale = 1.0 / float(np.sqrt(128.0))
+            desc = rest.make_attn_desc(q, k, v, out, P, scale, False)
+            ws = torch.empty(max(rest.rest_tree_attention_workspace_bytes(desc), 16), dtype=torch.uint8, device=dev)
+            for _ in range(3):
+                rest.rest_tree_attention(q, k, v, mask, P, scale, out=out, workspace=ws)
+            torch.cuda.synchronize()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(10):
+                rest.rest_tree_attention(q, k, v, mask, P, scale, out=out, workspace=ws)
+            b.record()
+            torch.cuda.synchronize()
+            us = a.elapsed_time(b) / 10 * 1e3
+            alg = 1024 * (2 * (P + T) * 128 * 2 + 2 * T * 128 * 2) + T * ((T + 63) // 64) * 8
+            rows.append({"T": T, "P": P, "us": round(us, 1), "GB/s": round(alg / us / 1e3, 1),
+                         "frac_of_8TB/s": round(alg / us / 1e3 / HBM_PEAK_GBS, 3)})
+            del q, k, v, out, ws
+    return rows
 
 
 def cpu_baseline(np, torch, corp, ctx_np, w, q, k, v, out, trees, ids, P, scale, step):

@@ -35,11 +35,10 @@ namespace {
 
 constexpr int kD = 128;            // head dim
 constexpr int kBlk = 32;           // keys per block
-constexpr int kWaves = 4;          // waves per workgroup
 constexpr int kTileBytes = kBlk * kD * 2;   // 8 KB: one K or V block in bf16
 constexpr float kNegBig = -1.0e30f;
 constexpr float kLazy = 8.0f;      // log2 units the running maximum may exceed the softmax reference
-constexpr int kMaxWaves = 1024;    // default number of streams: one wavefront per SIMD on 256 CUs
+constexpr int kMaxWaves = 1024;    // default number of streams: four two-wave streams on each of 256 CUs
 
 struct AttnParams {
     const __bf16* q;
@@ -67,35 +66,32 @@ __host__ __device__ inline int32_t span_owner(int64_t total, int32_t n, int64_t 
     return (int32_t)(((b + 1) * n - 1) / total);
 }
 
-template <int QT>
-__global__ __launch_bounds__(256) void tree_attn_bf16_kernel(AttnParams p) {
-    // one (K, V) tile pair per wave: 4 waves x 16 KB = 64 KB, plus the waves' mask rows and query rows
-    __shared__ __attribute__((aligned(1024))) unsigned char lds_stage[kWaves * 2 * kTileBytes];
-    __shared__ uint64_t lds_mask[kWaves][QT * 32 * 4];
-    // the waves' query rows (bf16, 256 B each), 16-byte pieces swizzled like the K tile
-    __shared__ __attribute__((aligned(16))) unsigned char lds_q[kWaves][QT * 32 * 256];
+// One stream = one workgroup of two wavefronts.  Both see the same K/V tile in LDS (each loads half of it);
+// wavefront w owns queries [32w, 32w+32) of the unit's 64.  Four streams fit a compute unit (2 waves per SIMD),
+// so one wave's MFMA, exponentials, LDS latency and load waits overlap the other's.
+__global__ __launch_bounds__(128, 2) void tree_attn_bf16_kernel(AttnParams p) {
+    __shared__ __attribute__((aligned(1024))) unsigned char lds_tile[2][2 * kTileBytes];   // [buffer][K | V], 32 KB
+    __shared__ uint64_t lds_mask[64 * 4];                                                   // 64 query rows x 4 words
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int hh = lane >> 5;      // which half of the wave (selects the k-slice of MFMA operands)
-    const int col = lane & 31;     // MFMA column = query within a 32-query tile
+    const int col = lane & 31;     // MFMA column = query within this wave's 32-query tile
     const int lrow = lane >> 4, lpc = lane & 15;
 
     const int64_t total = (int64_t)p.units * p.nblk;
-    const int gw = blockIdx.x * kWaves + wave;
-    if (gw >= p.n_streams) return;
+    const int gw = blockIdx.x;     // stream index
     const int64_t g_begin = span_begin(total, p.n_streams, gw), g_end = span_begin(total, p.n_streams, gw + 1);
     if (g_begin >= g_end) return;
 
-    unsigned char* const stage = lds_stage + wave * (2 * kTileBytes);   // [K | V]
-    uint64_t* const my_mask = lds_mask[wave];
-    unsigned char* const my_q = lds_q[wave];
+    uint64_t* const my_mask = lds_mask + wave * (32 * 4);
     const int64_t k_row_bytes = p.ks[2] * 2, v_row_bytes = p.vs[2] * 2;
     const int plain_end = p.P / kBlk;   // blocks below this hold prefix keys only
 
-    // Global -> LDS.  Chunk i of a tile is 4 rows x 256 B = 64 lanes x 16 B and lands at LDS tile + i*1024 +
-    // lane*16, i.e. row i*4 + (lane >> 4), piece slot lane & 15.  The slot holds row piece (slot ^ swizzle(row)),
-    // so that is the piece this lane fetches.  K: swizzle = row & 15; V: swizzle = (row & 3) << 2.
+    // Global -> registers -> LDS.  Chunk i of a tile is 4 rows x 256 B = 64 lanes x 16 B and is parked at
+    // tile + i*1024 + lane*16, i.e. row i*4 + (lane >> 4), piece slot lane & 15.  The slot holds row piece
+    // (slot ^ swizzle(row)), so that is the piece this lane fetches.  K: swizzle = row & 15; V: (row & 3) << 2.
+    // Wavefront w moves chunks 4w .. 4w+3 of K and of V.
     uint32_t k_off[4];
 #pragma unroll
     for (int x = 0; x < 4; x++) k_off[x] = (uint32_t)(lrow * k_row_bytes) + ((lpc ^ (x * 4 + lrow)) << 4);
@@ -112,46 +108,39 @@ __global__ __launch_bounds__(256) void tree_attn_bf16_kernel(AttnParams p) {
     int ld_unit = (int)(g_begin / p.nblk), ld_j = (int)(g_begin % p.nblk);
     const char *ld_kp, *ld_vp;
     unit_bases(ld_unit, ld_kp, ld_vp);
-    // Staging registers for the block under the cursor.  K and V halves are issued and parked at different
-    // points of the loop body, so one half is always in flight while the other is being moved to LDS.
-    i32x4 kr[8], vr[8];
-    auto issue_half = [&](i32x4 (&dst)[8], const char* base, int64_t row_bytes, bool is_k) {
+    i32x4 kr[4], vr[4];
+    auto issue = [&]() {
         const int j = ld_j;
         if ((j + 1) * kBlk <= p.Lk) {
 #pragma unroll
-            for (int i = 0; i < 8; i++) {
-                const int64_t row = (int64_t)j * kBlk + i * 4;
-                dst[i] = __builtin_nontemporal_load((const i32x4*)(base + row * row_bytes + (is_k ? k_off[i & 3] : v_off)));
+            for (int i = 0; i < 4; i++) {
+                const int64_t row = (int64_t)j * kBlk + (4 * wave + i) * 4;
+                kr[i] = __builtin_nontemporal_load((const i32x4*)(ld_kp + row * k_row_bytes + k_off[i]));
+                vr[i] = __builtin_nontemporal_load((const i32x4*)(ld_vp + row * v_row_bytes + v_off));
             }
         } else {
             // last, partial block of a unit: rows past the end re-read the last row; those keys are never visible
 #pragma unroll
-            for (int i = 0; i < 8; i++) {
-                int64_t row = (int64_t)j * kBlk + i * 4 + lrow;
+            for (int i = 0; i < 4; i++) {
+                int64_t row = (int64_t)j * kBlk + (4 * wave + i) * 4 + lrow;
                 row = row < p.Lk ? row : p.Lk - 1;
-                const int sw = is_k ? (lpc ^ ((i & 3) * 4 + lrow)) << 4 : (lpc ^ (lrow << 2)) << 4;
-                dst[i] = __builtin_nontemporal_load((const i32x4*)(base + row * row_bytes + sw));
+                const int sw_k = (lpc ^ (i * 4 + lrow)) << 4, sw_v = (lpc ^ (lrow << 2)) << 4;
+                kr[i] = __builtin_nontemporal_load((const i32x4*)(ld_kp + row * k_row_bytes + sw_k));
+                vr[i] = __builtin_nontemporal_load((const i32x4*)(ld_vp + row * v_row_bytes + sw_v));
             }
         }
-    };
-    auto issue_k = [&]() { issue_half(kr, ld_kp, k_row_bytes, true); };
-    // V follows K of the same block; then the cursor advances
-    auto issue_v = [&]() {
-        issue_half(vr, ld_vp, v_row_bytes, false);
         if (++ld_j == p.nblk) {
             ld_j = 0;
             ld_unit++;
             if (ld_unit < p.units) unit_bases(ld_unit, ld_kp, ld_vp);
         }
     };
-    // staging registers -> LDS tile: lane l's piece of chunk i goes to tile + i*1024 + l*16
-    auto park_k = [&]() {
+    auto park = [&](unsigned char* tile) {
 #pragma unroll
-        for (int i = 0; i < 8; i++) *(i32x4*)(stage + i * 1024 + lane * 16) = kr[i];
-    };
-    auto park_v = [&]() {
-#pragma unroll
-        for (int i = 0; i < 8; i++) *(i32x4*)(stage + kTileBytes + i * 1024 + lane * 16) = vr[i];
+        for (int i = 0; i < 4; i++) {
+            *(i32x4*)(tile + (4 * wave + i) * 1024 + lane * 16) = kr[i];
+            *(i32x4*)(tile + kTileBytes + (4 * wave + i) * 1024 + lane * 16) = vr[i];
+        }
     };
 
     // ---- LDS read addresses (byte offsets inside a K or V tile), loop invariant
@@ -160,9 +149,9 @@ __global__ __launch_bounds__(256) void tree_attn_bf16_kernel(AttnParams p) {
     const uint32_t va0 = (4 * hh + vq) * 256 + ((2 * ((lane >> 4) & 1) + ((lane & 3) >> 1)) << 4) + (lane & 1) * 8;
     const uint32_t vsw = (uint32_t)vq << 2;                                          // V swizzle of that row
 
+    int buf = 0;
     int64_t g = g_begin;
-    issue_k();
-    issue_v();
+    issue();
     while (g < g_end) {
         // ================= one segment: the part of unit `unit` inside this span
         const int unit = (int)(g / p.nblk);
@@ -172,75 +161,57 @@ __global__ __launch_bounds__(256) void tree_attn_bf16_kernel(AttnParams p) {
         const bool first_seg = g_begin >= unit_begin;
         const int qg = unit % p.qgroups, slab = unit / p.qgroups;
         const int h = slab % p.H, nb = slab / p.H;
-        const int qbase = qg * (QT * 32);
+        const int qi = qg * 64 + wave * 32 + col;        // this lane's query row
 
-        // mask rows of this unit's queries -> wave-private LDS (lane = query; the halves write words 0,1 / 2,3)
+        // mask row of this lane's query -> LDS (the halves write words 0,1 / 2,3); only this wave reads it back
         {
             const uint64_t* mrow = p.mask + (p.mask_per_batch ? (int64_t)nb * p.Tq * p.mask_words : 0);
 #pragma unroll
-            for (int qt = 0; qt < QT; qt++) {
-                const int qi = qbase + qt * 32 + col;
-#pragma unroll
-                for (int w = 0; w < 2; w++) {
-                    const int ww = 2 * hh + w;
-                    my_mask[(qt * 32 + col) * 4 + ww] = (qi < p.Tq && ww < p.mask_words) ? mrow[(int64_t)qi * p.mask_words + ww] : 0ull;
-                }
+            for (int w = 0; w < 2; w++) {
+                const int ww = 2 * hh + w;
+                my_mask[col * 4 + ww] = (qi < p.Tq && ww < p.mask_words) ? mrow[(int64_t)qi * p.mask_words + ww] : 0ull;
             }
         }
-        // Q rows -> wave-private LDS.  The B operand of S^T = K Q^T for k-step ks is, for lane (col, hh), the
-        // 16-byte piece 2*ks + hh of query row col; pieces are stored at (piece ^ (row & 15)) like K rows.
+        // Q fragments (B operand of S^T = K Q^T): lane holds query `col`, d = 16*ks + 8*hh .. +8
+        bf16x8 qf[8];
         {
             const __bf16* qp = p.q + nb * p.qs[0] + h * p.qs[1];
 #pragma unroll
-            for (int qt = 0; qt < QT; qt++) {
-                const int qi = qbase + qt * 32 + col;
-#pragma unroll
-                for (int ks = 0; ks < 8; ks++) {
-                    i32x4 z = {0, 0, 0, 0};
-                    if (qi < p.Tq) z = *(const i32x4*)(qp + qi * p.qs[2] + 16 * ks + 8 * hh);
-                    *(i32x4*)(my_q + qt * 8192 + (ka0 ^ (ks << 5))) = z;
-                }
+            for (int ks = 0; ks < 8; ks++) {
+                bf16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
+                if (qi < p.Tq) z = *(const bf16x8*)(qp + qi * p.qs[2] + 16 * ks + 8 * hh);
+                qf[ks] = z;
             }
         }
 
-        f32x16 o[QT][4];
-        float m_ref[QT], l_run[QT];     // m_ref in log2 units (logit * c)
+        f32x16 o[4];
+        float m_ref = kNegBig, l_run = 0.f;     // m_ref in log2 units (logit * c)
 #pragma unroll
-        for (int qt = 0; qt < QT; qt++) {
-            m_ref[qt] = kNegBig;
-            l_run[qt] = 0.f;
+        for (int dt = 0; dt < 4; dt++)
 #pragma unroll
-            for (int dt = 0; dt < 4; dt++)
-#pragma unroll
-                for (int r = 0; r < 16; r++) o[qt][dt][r] = 0.f;
-        }
+            for (int r = 0; r < 16; r++) o[dt][r] = 0.f;
 
-        for (; g < seg_end; g++) {
-            // K of this block moves from its staging registers to LDS and K of the next block (possibly of the
-            // next unit) is requested; V of this block is still in flight
-            park_k();
-            if (g + 1 < g_end) issue_k();
-            // compiler barrier: the query fragments are re-read from LDS for every block instead of being
-            // hoisted into 64 registers for the whole segment
-            asm volatile("" ::: "memory");
+        for (; g < seg_end; g++, buf ^= 1) {
+            // my half of block g moves from the staging registers to tile `buf`, my half of block g+1 (possibly
+            // of the next unit) is requested, and after the barrier the whole tile is visible to both waves.
+            // Tile buf^1 may still be read by the other wave (block g-1); tile `buf` was last read for block
+            // g-2, which both waves finished before the previous barrier.
+            unsigned char* tile = lds_tile[buf];
+            park(tile);
+            if (g + 1 < g_end) issue();
+            __syncthreads();
             const int j = (int)(g - unit_begin);
-            const unsigned char* ldsK = stage;
-            const unsigned char* ldsV = ldsK + kTileBytes;
+            const unsigned char* ldsK = tile;
+            const unsigned char* ldsV = tile + kTileBytes;
 
             // ---- S^T[key][query] = K Q^T
-            f32x16 s[QT];
+            f32x16 s;
 #pragma unroll
-            for (int qt = 0; qt < QT; qt++)
-#pragma unroll
-                for (int r = 0; r < 16; r++) s[qt][r] = 0.f;
+            for (int r = 0; r < 16; r++) s[r] = 0.f;
 #pragma unroll
             for (int ks = 0; ks < 8; ks++) {
                 const bf16x8 a = *(const bf16x8*)(ldsK + (ka0 ^ (ks << 5)));
-#pragma unroll
-                for (int qt = 0; qt < QT; qt++) {
-                    const bf16x8 bq = *(const bf16x8*)(my_q + qt * 8192 + (ka0 ^ (ks << 5)));
-                    s[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bq, s[qt], 0, 0, 0);
-                }
+                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], s, 0, 0, 0);
             }
 
             // ---- visibility (only blocks that reach past the prefix): one 32-bit word per lane says which of
@@ -249,62 +220,52 @@ __global__ __launch_bounds__(256) void tree_attn_bf16_kernel(AttnParams p) {
                 const int kb = j * kBlk - p.P;          // draft-token index of the block's first key (may be < 0)
                 const int end = p.Tk - kb;              // keys at block offset >= end are past the last key
                 const uint32_t in_range = end >= 32 ? 0xffffffffu : (end > 0 ? (1u << end) - 1u : 0u);
+                const uint64_t* mw = &my_mask[col * 4];
+                uint32_t vbits;
+                if (kb < 0) {
+                    vbits = ((1u << (-kb)) - 1u) | ((uint32_t)mw[0] << (-kb));
+                } else {
+                    const int w = kb >> 6, sh = kb & 63;
+                    const uint64_t lo = mw[w];
+                    const uint64_t hi = (w + 1 < 4) ? mw[w + 1] : 0ull;
+                    vbits = (uint32_t)(lo >> sh);
+                    if (sh > 32) vbits |= (uint32_t)(hi << (64 - sh));
+                }
+                vbits &= in_range;
+                vbits >>= 4 * hh;
 #pragma unroll
-                for (int qt = 0; qt < QT; qt++) {
-                    const uint64_t* mw = &my_mask[(qt * 32 + col) * 4];
-                    uint32_t vbits;
-                    if (kb < 0) {
-                        vbits = ((1u << (-kb)) - 1u) | ((uint32_t)mw[0] << (-kb));
-                    } else {
-                        const int w = kb >> 6, sh = kb & 63;
-                        const uint64_t lo = mw[w];
-                        const uint64_t hi = (w + 1 < 4) ? mw[w + 1] : 0ull;
-                        vbits = (uint32_t)(lo >> sh);
-                        if (sh > 32) vbits |= (uint32_t)(hi << (64 - sh));
-                    }
-                    vbits &= in_range;
-                    vbits >>= 4 * hh;
-#pragma unroll
-                    for (int r = 0; r < 16; r++) {
-                        const bool vis = (vbits >> (8 * (r >> 2) + (r & 3))) & 1u;
-                        s[qt][r] = vis ? s[qt][r] : -INFINITY;
-                    }
+                for (int r = 0; r < 16; r++) {
+                    const bool vis = (vbits >> (8 * (r >> 2) + (r & 3))) & 1u;
+                    s[r] = vis ? s[r] : -INFINITY;
                 }
             }
 
             // ---- softmax numerators against a lazily updated reference, per lane = per query column
-            bf16x8 pf[QT][2];
+            bf16x8 pf[2];
+            {
+                float mx = s[0];
 #pragma unroll
-            for (int qt = 0; qt < QT; qt++) {
-                float mx = s[qt][0];
-#pragma unroll
-                for (int r = 1; r < 16; r++) mx = fmaxf(mx, s[qt][r]);
+                for (int r = 1; r < 16; r++) mx = fmaxf(mx, s[r]);
                 mx = fmaxf(mx, wave_xor32(mx)) * p.c;
-                if (__any(mx > m_ref[qt] + kLazy)) {
-                    const float m_new = fmaxf(m_ref[qt], mx);
-                    const float alpha = __builtin_amdgcn_exp2f(m_ref[qt] - m_new);
-                    m_ref[qt] = m_new;
-                    l_run[qt] *= alpha;
+                if (__any(mx > m_ref + kLazy)) {
+                    const float m_new = fmaxf(m_ref, mx);
+                    const float alpha = __builtin_amdgcn_exp2f(m_ref - m_new);
+                    m_ref = m_new;
+                    l_run *= alpha;
 #pragma unroll
                     for (int dt = 0; dt < 4; dt++)
 #pragma unroll
-                        for (int r = 0; r < 16; r++) o[qt][dt][r] *= alpha;
+                        for (int r = 0; r < 16; r++) o[dt][r] *= alpha;
                 }
-                const float mr = m_ref[qt];
                 float sum = 0.f;
 #pragma unroll
                 for (int r = 0; r < 16; r++) {
-                    const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(s[qt][r], p.c, -mr));
+                    const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], p.c, -m_ref));
                     sum += e;
-                    pf[qt][r >> 3][r & 7] = (__bf16)e;
+                    pf[r >> 3][r & 7] = (__bf16)e;
                 }
-                l_run[qt] += sum;
+                l_run += sum;
             }
-
-            // ---- V of this block -> LDS, V of the next block requested
-            park_v();
-            if (g + 1 < g_end) issue_v();
-            asm volatile("" ::: "memory");
 
             // ---- O^T[d][query] += V^T P^T
 #pragma unroll
@@ -317,21 +278,16 @@ __global__ __launch_bounds__(256) void tree_attn_bf16_kernel(AttnParams p) {
                     union { struct { s16x4 lo, hi; } sp; bf16x8 v; } u;
                     u.sp.lo = lo;
                     u.sp.hi = hi;
-#pragma unroll
-                    for (int qt = 0; qt < QT; qt++)
-                        o[qt][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(u.v, pf[qt][ss], o[qt][dt], 0, 0, 0);
+                    o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(u.v, pf[ss], o[dt], 0, 0, 0);
                 }
             }
         }
 
         // ================= end of segment: the two key halves of the wave hold disjoint keys
-#pragma unroll
-        for (int qt = 0; qt < QT; qt++) {
-            l_run[qt] += wave_xor32(l_run[qt]);
-            const int qi = qbase + qt * 32 + col;
-            if (qi >= p.Tq) continue;
+        l_run += wave_xor32(l_run);
+        if (qi < p.Tq) {
             if (whole) {
-                const float inv = l_run[qt] > 0.f ? 1.0f / l_run[qt] : 0.f;
+                const float inv = l_run > 0.f ? 1.0f / l_run : 0.f;
                 __bf16* op = p.out + nb * p.os[0] + h * p.os[1] + qi * p.os[2];
 #pragma unroll
                 for (int dt = 0; dt < 4; dt++)
@@ -339,11 +295,11 @@ __global__ __launch_bounds__(256) void tree_attn_bf16_kernel(AttnParams p) {
                     for (int gq = 0; gq < 4; gq++) {
                         bf16x4 w;
 #pragma unroll
-                        for (int e = 0; e < 4; e++) w[e] = (__bf16)(o[qt][dt][4 * gq + e] * inv);
+                        for (int e = 0; e < 4; e++) w[e] = (__bf16)(o[dt][4 * gq + e] * inv);
                         *(bf16x4*)(op + dt * 32 + 8 * gq + 4 * hh) = w;
                     }
             } else {
-                const int64_t row = ((int64_t)gw * 2 + (first_seg ? 0 : 1)) * (QT * 32) + qt * 32 + col;
+                const int64_t row = ((int64_t)gw * 2 + (first_seg ? 0 : 1)) * 64 + wave * 32 + col;
                 float* wo = p.ws_o + row * kD;
 #pragma unroll
                 for (int dt = 0; dt < 4; dt++)
@@ -351,12 +307,12 @@ __global__ __launch_bounds__(256) void tree_attn_bf16_kernel(AttnParams p) {
                     for (int gq = 0; gq < 4; gq++) {
                         f32x4 w;
 #pragma unroll
-                        for (int e = 0; e < 4; e++) w[e] = o[qt][dt][4 * gq + e];
+                        for (int e = 0; e < 4; e++) w[e] = o[dt][4 * gq + e];
                         *(f32x4*)(wo + dt * 32 + 8 * gq + 4 * hh) = w;
                     }
                 if (hh == 0) {
-                    p.ws_ml[row * 2 + 0] = m_ref[qt];
-                    p.ws_ml[row * 2 + 1] = l_run[qt];
+                    p.ws_ml[row * 2 + 0] = m_ref;
+                    p.ws_ml[row * 2 + 1] = l_run;
                 }
             }
         }
@@ -364,11 +320,10 @@ __global__ __launch_bounds__(256) void tree_attn_bf16_kernel(AttnParams p) {
 }
 
 // Merges the partials of every unit that was cut between streams: one 128-thread block per (unit, query).
-template <int QT>
 __global__ __launch_bounds__(128) void tree_attn_streamk_merge_kernel(AttnParams p) {
-    const int unit = blockIdx.x / (QT * 32), ql = blockIdx.x % (QT * 32);
+    const int unit = blockIdx.x / 64, ql = blockIdx.x % 64;
     const int qg = unit % p.qgroups, slab = unit / p.qgroups;
-    const int qi = qg * (QT * 32) + ql;
+    const int qi = qg * 64 + ql;
     if (qi >= p.Tq) return;
     const int64_t total = (int64_t)p.units * p.nblk;
     const int64_t ub = (int64_t)unit * p.nblk, ue = ub + p.nblk;
@@ -379,14 +334,14 @@ __global__ __launch_bounds__(128) void tree_attn_streamk_merge_kernel(AttnParams
     for (int w = w0; w <= w1; w++) {
         const int64_t sb = span_begin(total, p.n_streams, w), se = span_begin(total, p.n_streams, w + 1);
         if (sb >= se) continue;
-        const int64_t row = ((int64_t)w * 2 + (sb >= ub ? 0 : 1)) * (QT * 32) + ql;
+        const int64_t row = ((int64_t)w * 2 + (sb >= ub ? 0 : 1)) * 64 + ql;
         m = fmaxf(m, p.ws_ml[row * 2]);
     }
     float l = 0.f, acc = 0.f;
     for (int w = w0; w <= w1; w++) {
         const int64_t sb = span_begin(total, p.n_streams, w), se = span_begin(total, p.n_streams, w + 1);
         if (sb >= se) continue;
-        const int64_t row = ((int64_t)w * 2 + (sb >= ub ? 0 : 1)) * (QT * 32) + ql;
+        const int64_t row = ((int64_t)w * 2 + (sb >= ub ? 0 : 1)) * 64 + ql;
         const float wgt = __builtin_amdgcn_exp2f(p.ws_ml[row * 2] - m);
         l += p.ws_ml[row * 2 + 1] * wgt;
         acc += p.ws_o[row * kD + d] * wgt;
@@ -504,8 +459,8 @@ Plan make_plan(const rest_attn_desc* d) {
         pl.nsplit_f32 = d->num_splits > 0 ? d->num_splits : 1;
         return pl;
     }
-    pl.qt = d->Tq <= 32 ? 1 : 2;
-    pl.qgroups = (d->Tq + pl.qt * 32 - 1) / (pl.qt * 32);
+    pl.qt = 2;                                   // a stream (two wavefronts) covers 64 queries
+    pl.qgroups = (d->Tq + 63) / 64;
     pl.units = d->Nb * d->H * pl.qgroups;
     const int64_t total = (int64_t)pl.units * pl.nblk;
     int64_t w;
@@ -513,7 +468,7 @@ Plan make_plan(const rest_attn_desc* d) {
         w = (int64_t)pl.units * d->num_splits;       // explicit request: num_splits streams per unit
         if (w > 16384) w = 16384;
     } else {
-        // one wavefront per SIMD of the chip, but at least four key blocks per stream
+        // four streams (eight wavefronts) per compute unit, but at least four key blocks per stream
         w = total / 4;
         if (w > kMaxWaves) w = kMaxWaves;
     }
@@ -594,14 +549,10 @@ extern "C" __attribute__((visibility("default"))) rest_status rest_tree_attentio
         p.n_streams = pl.n_streams;
         const size_t rows = (size_t)pl.n_streams * 2 * (pl.qt * 32);
         p.ws_ml = p.ws_o ? p.ws_o + rows * kD : nullptr;
-        const int grid = (pl.n_streams + kWaves - 1) / kWaves;
-        if (pl.qt == 1) hipLaunchKernelGGL(tree_attn_bf16_kernel<1>, dim3(grid), dim3(256), 0, stream, p);
-        else hipLaunchKernelGGL(tree_attn_bf16_kernel<2>, dim3(grid), dim3(256), 0, stream, p);
+        hipLaunchKernelGGL(tree_attn_bf16_kernel, dim3(pl.n_streams), dim3(128), 0, stream, p);
         REST_HIP_TRY(hipGetLastError());
         if (pl.need_merge) {
-            const int mgrid = pl.units * pl.qt * 32;
-            if (pl.qt == 1) hipLaunchKernelGGL(tree_attn_streamk_merge_kernel<1>, dim3(mgrid), dim3(128), 0, stream, p);
-            else hipLaunchKernelGGL(tree_attn_streamk_merge_kernel<2>, dim3(mgrid), dim3(128), 0, stream, p);
+            hipLaunchKernelGGL(tree_attn_streamk_merge_kernel, dim3(pl.units * 64), dim3(128), 0, stream, p);
             REST_HIP_TRY(hipGetLastError());
         }
     } else {
