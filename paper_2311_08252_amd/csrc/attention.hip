@@ -319,8 +319,11 @@ __global__ __launch_bounds__(128, 2) void tree_attn_bf16_kernel(AttnParams p) {
     }
 }
 
-// Merges the partials of every unit that was cut between streams: one 128-thread block per (unit, query).
-__global__ __launch_bounds__(128) void tree_attn_streamk_merge_kernel(AttnParams p) {
+// Merges the partials of every unit that was cut between streams: one 256-thread block per (unit, query);
+// the four wavefronts take every fourth stream (a lane owns two of the 128 output columns), then combine in LDS.
+__global__ __launch_bounds__(256) void tree_attn_streamk_merge_kernel(AttnParams p) {
+    __shared__ float red_m[4], red_l[4];
+    __shared__ float red_o[4][kD];
     const int unit = blockIdx.x / 64, ql = blockIdx.x % 64;
     const int qg = unit % p.qgroups, slab = unit / p.qgroups;
     const int qi = qg * 64 + ql;
@@ -329,25 +332,40 @@ __global__ __launch_bounds__(128) void tree_attn_streamk_merge_kernel(AttnParams
     const int64_t ub = (int64_t)unit * p.nblk, ue = ub + p.nblk;
     const int w0 = span_owner(total, p.n_streams, ub), w1 = span_owner(total, p.n_streams, ue - 1);
     if (w0 == w1) return;     // one stream covered the whole unit and wrote the output itself
-    const int d = threadIdx.x;
-    float m = kNegBig;
-    for (int w = w0; w <= w1; w++) {
-        const int64_t sb = span_begin(total, p.n_streams, w), se = span_begin(total, p.n_streams, w + 1);
-        if (sb >= se) continue;
-        const int64_t row = ((int64_t)w * 2 + (sb >= ub ? 0 : 1)) * 64 + ql;
-        m = fmaxf(m, p.ws_ml[row * 2]);
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    // Only the first stream can have started before this unit (its partial sits in slot 1); every later stream
+    // starts inside the unit, so this is its first segment (slot 0).  Streams are never empty (W <= blocks).
+    const int slot0 = span_begin(total, p.n_streams, w0) >= ub ? 0 : 1;
+    float m = kNegBig, l = 0.f, a0 = 0.f, a1 = 0.f;
+#pragma unroll 4
+    for (int w = w0 + wv; w <= w1; w += 4) {
+        const int64_t row = ((int64_t)w * 2 + (w == w0 ? slot0 : 0)) * 64 + ql;
+        const float mi = p.ws_ml[row * 2], li = p.ws_ml[row * 2 + 1];
+        const float2 oi = *(const float2*)(p.ws_o + row * kD + 2 * lane);
+        const float m_new = fmaxf(m, mi);
+        const float sa = __builtin_amdgcn_exp2f(m - m_new), sb = __builtin_amdgcn_exp2f(mi - m_new);
+        l = l * sa + li * sb;
+        a0 = a0 * sa + oi.x * sb;
+        a1 = a1 * sa + oi.y * sb;
+        m = m_new;
     }
-    float l = 0.f, acc = 0.f;
-    for (int w = w0; w <= w1; w++) {
-        const int64_t sb = span_begin(total, p.n_streams, w), se = span_begin(total, p.n_streams, w + 1);
-        if (sb >= se) continue;
-        const int64_t row = ((int64_t)w * 2 + (sb >= ub ? 0 : 1)) * 64 + ql;
-        const float wgt = __builtin_amdgcn_exp2f(p.ws_ml[row * 2] - m);
-        l += p.ws_ml[row * 2 + 1] * wgt;
-        acc += p.ws_o[row * kD + d] * wgt;
+    if (lane == 0) { red_m[wv] = m; red_l[wv] = l; }
+    red_o[wv][2 * lane] = a0;
+    red_o[wv][2 * lane + 1] = a1;
+    __syncthreads();
+    if (threadIdx.x < kD) {
+        const int d = threadIdx.x;
+        float mm = fmaxf(fmaxf(red_m[0], red_m[1]), fmaxf(red_m[2], red_m[3]));
+        float ll = 0.f, acc = 0.f;
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+            const float sc = __builtin_amdgcn_exp2f(red_m[i] - mm);
+            ll += red_l[i] * sc;
+            acc += red_o[i][d] * sc;
+        }
+        const int h = slab % p.H, nb = slab / p.H;
+        p.out[nb * p.os[0] + h * p.os[1] + qi * p.os[2] + d] = (__bf16)(ll > 0.f ? acc / ll : 0.f);
     }
-    const int h = slab % p.H, nb = slab / p.H;
-    p.out[nb * p.os[0] + h * p.os[1] + qi * p.os[2] + d] = (__bf16)(l > 0.f ? acc / l : 0.f);
 }
 
 // ---------------------------------------------------------------------------------------------------------
@@ -552,7 +570,7 @@ extern "C" __attribute__((visibility("default"))) rest_status rest_tree_attentio
         hipLaunchKernelGGL(tree_attn_bf16_kernel, dim3(pl.n_streams), dim3(128), 0, stream, p);
         REST_HIP_TRY(hipGetLastError());
         if (pl.need_merge) {
-            hipLaunchKernelGGL(tree_attn_streamk_merge_kernel, dim3(pl.units * 64), dim3(128), 0, stream, p);
+            hipLaunchKernelGGL(tree_attn_streamk_merge_kernel, dim3(pl.units * 64), dim3(256), 0, stream, p);
             REST_HIP_TRY(hipGetLastError());
         }
     } else {
