@@ -9,6 +9,11 @@
 // dependent global reads instead of 27.  The two top levels come from a table of 1023 sampled suffix keys
 // (first 16 tokens each) that sits in LDS.  Lower and upper bound share probes.
 //
+// Every probe touches its own cache line, and a compute unit resolves such fully divergent reads at about one
+// lane per clock, so the number of load instructions -- not memory latency -- sets the time of a search.  Tokens
+// are therefore read four at a time (one 16-byte read at token alignment) and a probe reads on only while it
+// still ties with the query.
+//
 // Phase B, Trie without a Trie.  The kept occurrences are consecutive suffix-array ranks, hence already in
 // lexicographic order, so the Trie is implicit in the longest-common-prefix array of adjacent candidates:
 // a node at depth d starts at row r iff lcp[r] < d <= len[r], and its weight is the distance to the next row
@@ -50,16 +55,35 @@ __device__ inline uint32_t load_sa(const void* sa, uint32_t rank) {
     return (uint32_t)((const SaT*)sa)[rank];
 }
 
-// three-way comparison of the first n tokens of the suffix at `pos` with q (end of stream = -1 < every token)
+// tokens pos .. pos+3 of the stream with one read (element-wise, -1 past the end, for the last three positions)
+template <typename TokT>
+__device__ inline void load_tok4(const void* corpus, uint64_t n, uint64_t pos, int32_t (&out)[4]) {
+    if (pos + 4 <= n) {
+        TokT v[4];
+        __builtin_memcpy(v, (const TokT*)corpus + pos, sizeof(v));
+#pragma unroll
+        for (int j = 0; j < 4; j++) out[j] = (int32_t)v[j];
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; j++) out[j] = load_tok<TokT>(corpus, n, pos + j);
+    }
+}
+
+// three-way comparison of the first n tokens of the suffix at `pos` with q (end of stream = -1 < every token);
+// reads four tokens at a time and stops at the first group that differs
 template <typename TokT>
 __device__ inline int cmp_suffix(const void* corpus, uint64_t ntok, uint32_t pos, const int32_t (&q)[kKeyLen], int n) {
-    int32_t a[kKeyLen];
-#pragma unroll
-    for (int j = 0; j < kKeyLen; j++) a[j] = j < n ? load_tok<TokT>(corpus, ntok, (uint64_t)pos + j) : 0;
     int cmp = 0;
 #pragma unroll
-    for (int j = kKeyLen - 1; j >= 0; j--)
-        if (j < n && a[j] != q[j]) cmp = a[j] < q[j] ? -1 : 1;
+    for (int g = 0; g < kKeyLen / 4; g++) {
+        if (cmp == 0 && 4 * g < n) {
+            int32_t a[4];
+            load_tok4<TokT>(corpus, ntok, (uint64_t)pos + 4 * g, a);
+#pragma unroll
+            for (int j = 3; j >= 0; j--)
+                if (4 * g + j < n && a[j] != q[4 * g + j]) cmp = a[j] < q[4 * g + j] ? -1 : 1;
+        }
+    }
     return cmp;
 }
 
@@ -237,7 +261,12 @@ __global__ __launch_bounds__(kThreads) void retrieve_kernel(RetrieveParams p) {
             const uint64_t left = p.n_tokens > pos ? p.n_tokens - pos : 0;
             len = left < (uint64_t)m ? (int)left : m;
 #pragma unroll
-            for (int j = 0; j < REST_MAX_CONT_LEN; j++) tok[j] = j < m ? load_tok<TokT>(p.corpus, p.n_tokens, pos + j) : -1;
+            for (int g = 0; g < REST_MAX_CONT_LEN / 4; g++) {
+                int32_t a[4] = {-1, -1, -1, -1};
+                if (4 * g < m) load_tok4<TokT>(p.corpus, p.n_tokens, pos + 4 * g, a);
+#pragma unroll
+                for (int j = 0; j < 4; j++) tok[4 * g + j] = a[j];
+            }
         } else {
 #pragma unroll
             for (int j = 0; j < REST_MAX_CONT_LEN; j++) tok[j] = -1;
@@ -485,7 +514,15 @@ size_t align16(size_t x) { return (x + 15) & ~(size_t)15; }
 template <typename TokT, typename SaT>
 rest_status launch(const RetrieveParams& p, int B, size_t lds_bytes, hipStream_t stream) {
     auto kern = retrieve_kernel<TokT, SaT>;
-    REST_HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
+    // raise the kernel's dynamic-LDS limit once per (instantiation, device) and only when a call needs more
+    static size_t granted[64] = {0};
+    int dev = 0;
+    REST_HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= 64) return REST_UNSUPPORTED;
+    if (lds_bytes > granted[dev]) {
+        REST_HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
+        granted[dev] = lds_bytes;
+    }
     hipLaunchKernelGGL(kern, dim3(B), dim3(kThreads), lds_bytes, stream, p);
     REST_HIP_TRY(hipGetLastError());
     return REST_OK;
