@@ -18,7 +18,8 @@
 struct rest_index {
     const void* d_corpus;   // borrowed
     const void* d_sa;       // owned iff owns_sa
-    int32_t* d_top_keys;    // owned: [top_count][REST_MAX_SUFFIX_LEN] first tokens of sampled suffixes (-1 past the end)
+    int32_t* d_top_keys;    // owned: table of top_count sampled suffixes (ranks and first REST_MAX_SUFFIX_LEN tokens,
+                            // -1 past the end), in the layout the retrieval kernel copies to LDS
     uint64_t n_tokens;
     int32_t token_bytes;
     int32_t sa_bytes;

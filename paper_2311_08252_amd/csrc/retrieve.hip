@@ -7,7 +7,8 @@
 // do not nest) and run concurrently.  A search is 65-ary: the 64 lanes probe 64 pivots of the current
 // rank interval at once and a ballot picks the sub-interval, so 10^8 ranks take 2 LDS levels plus 3 rounds of
 // dependent global reads instead of 27.  The two top levels come from a table of 1023 sampled suffix keys
-// (first 16 tokens each) that sits in LDS.  Lower and upper bound share probes.
+// (first 16 tokens each) that sits in LDS.  Lower and upper bound advance in the same rounds, and a wavefront
+// stops as soon as a longer suffix is known to match.
 //
 // Every probe touches its own cache line, and a compute unit resolves such fully divergent reads at about one
 // lane per clock, so the number of load instructions -- not memory latency -- sets the time of a search.  Tokens
@@ -26,8 +27,17 @@ namespace {
 
 constexpr int kThreads = 1024;
 constexpr int kWavesPerWG = 16;
-constexpr int kTopMax = 1023;        // sampled suffix keys cached in LDS (64 KB as int32[16])
+constexpr int kTopMax = 1023;        // sampled suffix keys cached in LDS
 constexpr int kKeyLen = REST_MAX_SUFFIX_LEN;
+// Sampled-key table, as int32 words (the same layout in global memory and in LDS):
+//   [0, kCoarse)           coarse pivots, token-major: word j * 64 + l = token j of key 16 l + 15
+//   [kCoarse, kTabKeys)    suffix-array rank of key k
+//   [kTabKeys, ...)        keys in groups of 16, token-major inside a group: word g * 256 + j * 16 + l = token j of
+//                          key 16 g + l
+// Both levels are read by consecutive lanes at consecutive words, i.e. without LDS bank conflicts.
+constexpr int kCoarse = 64 * kKeyLen;
+constexpr int kTabKeys = kCoarse + 1024;
+__host__ __device__ constexpr int table_words(int top_count) { return kTabKeys + ((top_count + 15) / 16) * 16 * kKeyLen; }
 
 struct RetrieveParams {
     const void* corpus;
@@ -42,7 +52,7 @@ struct RetrieveParams {
     rest_tree out;
     // LDS layout of phase B (byte offsets into dynamic LDS)
     int32_t words;        // bitmap words per depth = K/64 + 1
-    int32_t off_seg, off_lcp, off_len, off_hist, off_part, off_sel, off_misc;
+    int32_t off_seg, off_lcp, off_len, off_hist, off_part, off_sel, off_pos, off_misc;
 };
 
 template <typename TokT>
@@ -69,93 +79,126 @@ __device__ inline void load_tok4(const void* corpus, uint64_t n, uint64_t pos, i
     }
 }
 
-// three-way comparison of the first n tokens of the suffix at `pos` with q (end of stream = -1 < every token);
-// reads four tokens at a time and stops at the first group that differs
+// Three-way comparison of the first n tokens of two suffixes (at pos1 for lanes with on1, at pos2 for lanes with
+// on2) with q; end of stream = -1 < every token.  Tokens are read four at a time, both suffixes' reads of a group
+// are issued together, and a suffix reads on only while it still ties.
 template <typename TokT>
-__device__ inline int cmp_suffix(const void* corpus, uint64_t ntok, uint32_t pos, const int32_t (&q)[kKeyLen], int n) {
-    int cmp = 0;
+__device__ inline void cmp_suffix2(const void* corpus, uint64_t ntok, uint32_t pos1, bool on1, uint32_t pos2, bool on2,
+                                   const int32_t (&q)[kKeyLen], int n, int& c1, int& c2) {
+    c1 = 0;
+    c2 = 0;
 #pragma unroll
     for (int g = 0; g < kKeyLen / 4; g++) {
-        if (cmp == 0 && 4 * g < n) {
-            int32_t a[4];
-            load_tok4<TokT>(corpus, ntok, (uint64_t)pos + 4 * g, a);
+        if (4 * g < n) {
+            const bool t1 = on1 && c1 == 0, t2 = on2 && c2 == 0;
+            int32_t a1[4] = {0, 0, 0, 0}, a2[4] = {0, 0, 0, 0};
+            if (t1) load_tok4<TokT>(corpus, ntok, (uint64_t)pos1 + 4 * g, a1);
+            if (t2) load_tok4<TokT>(corpus, ntok, (uint64_t)pos2 + 4 * g, a2);
 #pragma unroll
-            for (int j = 3; j >= 0; j--)
-                if (4 * g + j < n && a[j] != q[4 * g + j]) cmp = a[j] < q[4 * g + j] ? -1 : 1;
+            for (int j = 3; j >= 0; j--) {
+                if (t1 && 4 * g + j < n && a1[j] != q[4 * g + j]) c1 = a1[j] < q[4 * g + j] ? -1 : 1;
+                if (t2 && 4 * g + j < n && a2[j] != q[4 * g + j]) c2 = a2[j] < q[4 * g + j] ? -1 : 1;
+            }
         }
     }
-    return cmp;
-}
-
-__device__ inline int cmp_key(const int32_t* key, const int32_t (&q)[kKeyLen], int n) {
-    int cmp = 0;
-#pragma unroll
-    for (int j = kKeyLen - 1; j >= 0; j--)
-        if (j < n && key[j] != q[j]) cmp = key[j] < q[j] ? -1 : 1;
-    return cmp;
 }
 
 __device__ inline int popc64(uint64_t x) { return __popcll(x); }
 
-// One wavefront: [lo, hi) = ranks of the suffixes whose first n tokens equal q.
+// Bracket of one bound: ranks below `a` lie under the bound, ranks from `b` on do not; closed when a == b.
+struct Bracket {
+    uint32_t a, b;
+    __device__ bool open() const { return a < b; }
+    // 64 probes of an open bracket, increasing in the lane index: every rank if it holds at most 64, else pivots
+    __device__ uint32_t probe(int lane, bool& real) const {
+        const uint32_t len = b - a;
+        const bool fine = len <= 64;
+        real = !fine || (uint32_t)lane < len;
+        return fine ? a + lane : a + (uint32_t)(((uint64_t)len * (lane + 1)) / 65);
+    }
+    // k of the n_real probes (ranks r, increasing over the first n_real lanes) lie under the bound
+    __device__ void tighten(uint32_t r, int k, int n_real) {
+        const uint32_t below = __shfl(r, k > 0 ? k - 1 : 0, 64), at = __shfl(r, k < n_real ? k : 0, 64);
+        if (k > 0 && below + 1 > a) a = below + 1;
+        if (k < n_real && at < b) b = at;
+    }
+};
+
+// One wavefront: [lo, hi) = ranks of the suffixes whose first n tokens equal q.  `best` (LDS) is the smallest
+// wavefront index known to have a match: a wavefront with a larger index (a shorter suffix) stops as soon as it
+// sees a smaller one there and reports an empty range, which the caller never selects.
 template <typename TokT, typename SaT>
-__device__ void wave_search(const RetrieveParams& p, const int32_t* lds_top, const int32_t (&q)[kKeyLen], int n,
-                            uint32_t& out_lo, uint32_t& out_hi) {
+__device__ void wave_search(const RetrieveParams& p, const int32_t* lds_tab, const int32_t (&q)[kKeyLen], int n,
+                            int wave, int32_t* best, uint32_t& out_lo, uint32_t& out_hi) {
     const int lane = threadIdx.x & 63;
     const uint32_t N = (uint32_t)p.n_tokens;
     const int tc = p.top_count;
     // ---- two levels in LDS: 64 coarse pivots (every 16th sampled key), then the 15 keys of one group
+    const int32_t* coarse = lds_tab;
+    const uint32_t* rank = (const uint32_t*)(lds_tab + kCoarse);
+    const int32_t* keys = lds_tab + kTabKeys;
+    auto cmp_word = [&](const int32_t* col, int stride) {     // token j of the key at col[j * stride]
+        int c = 0;
+#pragma unroll
+        for (int j = kKeyLen - 1; j >= 0; j--) {
+            const int32_t x = col[j * stride];
+            if (j < n && x != q[j]) c = x < q[j] ? -1 : 1;
+        }
+        return c;
+    };
     int cnt_lt = 0, cnt_le = 0;
     if (tc > 0) {
-        int ci = 16 * lane + 15;
-        int c = ci < tc ? cmp_key(lds_top + ci * kKeyLen, q, n) : 1;
-        int g_lt = popc64(__ballot(c < 0)), g_le = popc64(__ballot(c <= 0));
-        int f_lt = 16 * g_lt + lane, f_le = 16 * g_le + lane;
-        int c1 = (lane < 15 && f_lt < tc) ? cmp_key(lds_top + f_lt * kKeyLen, q, n) : 1;
+        const int c = 16 * lane + 15 < tc ? cmp_word(coarse + lane, 64) : 1;
+        const int g_lt = popc64(__ballot(c < 0)), g_le = popc64(__ballot(c <= 0));
+        const int c1 = (lane < 15 && 16 * g_lt + lane < tc) ? cmp_word(keys + g_lt * 256 + lane, 16) : 1;
         cnt_lt = 16 * g_lt + popc64(__ballot(c1 < 0));
-        int c2 = (lane < 15 && f_le < tc) ? cmp_key(lds_top + f_le * kKeyLen, q, n) : 1;
+        int c2 = c1;
+        if (g_le != g_lt) c2 = (lane < 15 && 16 * g_le + lane < tc) ? cmp_word(keys + g_le * 256 + lane, 16) : 1;
         cnt_le = 16 * g_le + popc64(__ballot(c2 <= 0));
+        if (cnt_le > cnt_lt && lane == 0) atomicMin(best, wave);      // a sampled key equals q
     }
-    // invariants: ranks < a_lo compare <, ranks >= b_lo compare >=; ranks < a_hi compare <=, ranks >= b_hi compare >
-    uint32_t a_lo = cnt_lt ? (uint32_t)rest_top_rank(N, tc, cnt_lt - 1) + 1 : 0;
-    uint32_t b_lo = cnt_lt < tc ? (uint32_t)rest_top_rank(N, tc, cnt_lt) : N;
-    uint32_t a_hi = cnt_le ? (uint32_t)rest_top_rank(N, tc, cnt_le - 1) + 1 : 0;
-    uint32_t b_hi = cnt_le < tc ? (uint32_t)rest_top_rank(N, tc, cnt_le) : N;
+    // lower bound: ranks under it compare <; upper bound: ranks under it compare <=
+    Bracket lo, hi;
+    lo.a = cnt_lt ? rank[cnt_lt - 1] + 1 : 0;
+    lo.b = cnt_lt < tc ? rank[cnt_lt] : N;
+    hi.a = cnt_le ? rank[cnt_le - 1] + 1 : 0;
+    hi.b = cnt_le < tc ? rank[cnt_le] : N;
 
-    for (int pass = 0; pass < 2; pass++) {
-        // pass 0 narrows [a_lo, b_lo] to the lower bound, pass 1 narrows [a_hi, b_hi] to the upper bound
-        uint32_t a = pass == 0 ? a_lo : (a_hi > a_lo ? a_hi : a_lo);
-        uint32_t b = pass == 0 ? b_lo : b_hi;
-        while (a < b) {
-            const uint32_t len = b - a;
-            const bool fine = len <= 64;
-            uint32_t r = fine ? a + lane : a + (uint32_t)(((uint64_t)len * (lane + 1)) / 65);
-            const bool real = !fine || (uint32_t)lane < len;
-            int c = 1;
-            if (real) c = cmp_suffix<TokT>(p.corpus, p.n_tokens, load_sa<SaT>(p.sa, r), q, n);
-            const uint64_t m_real = __ballot(real);
-            const int n_real = popc64(m_real);
-            const int k_lt = popc64(__ballot(real && c < 0));
-            const int k_le = popc64(__ballot(real && c <= 0));
-            // ranks of the probes just below / at the boundary (probes are increasing in the lane index)
-            const int k_cur = pass == 0 ? k_lt : k_le;
-            const uint32_t r_below = __shfl(r, k_cur > 0 ? k_cur - 1 : 0, 64);
-            const uint32_t r_at = __shfl(r, k_cur < n_real ? k_cur : 0, 64);
-            if (pass == 0) {
-                // the same probes also tighten the upper-bound bracket
-                const uint32_t rb = __shfl(r, k_le > 0 ? k_le - 1 : 0, 64);
-                const uint32_t ra = __shfl(r, k_le < n_real ? k_le : 0, 64);
-                if (k_le > 0 && rb + 1 > a_hi) a_hi = rb + 1;
-                if (k_le < n_real && ra < b_hi) b_hi = ra;
-            }
-            if (k_cur > 0) a = r_below + 1;
-            if (k_cur < n_real) b = r_at;
-            else if (fine) b = a;   // every remaining rank was probed and lies below the bound
+    // Global rounds.  A round probes the lower bound's bracket and, when it is a different interval, the upper
+    // bound's bracket too; the reads of both probe sets are in flight together and every probe tightens both
+    // brackets, so the two bounds cost the rounds of the slower one.
+    while (lo.open() || hi.open()) {
+        if (*(volatile int32_t*)best < wave) {
+            out_lo = out_hi = 0;
+            return;
         }
-        if (pass == 0) a_lo = a; else a_hi = a;
+        const bool go1 = lo.open();
+        const bool go2 = hi.open() && !(go1 && hi.a == lo.a && hi.b == lo.b);
+        bool real1 = false, real2 = false;
+        uint32_t r1 = 0, r2 = 0;
+        if (go1) r1 = lo.probe(lane, real1);
+        if (go2) r2 = hi.probe(lane, real2);
+        uint32_t pos1 = 0, pos2 = 0;
+        if (real1) pos1 = load_sa<SaT>(p.sa, r1);
+        if (real2) pos2 = load_sa<SaT>(p.sa, r2);
+        int c1, c2;
+        cmp_suffix2<TokT>(p.corpus, p.n_tokens, pos1, real1, pos2, real2, q, n, c1, c2);
+        if (__ballot((real1 && c1 == 0) || (real2 && c2 == 0)) && lane == 0) atomicMin(best, wave);
+        if (go1) {
+            const int n_real = popc64(__ballot(real1));
+            const int k_lt = popc64(__ballot(real1 && c1 < 0)), k_le = popc64(__ballot(real1 && c1 <= 0));
+            lo.tighten(r1, k_lt, n_real);
+            hi.tighten(r1, k_le, n_real);
+        }
+        if (go2) {
+            const int n_real = popc64(__ballot(real2));
+            const int k_lt = popc64(__ballot(real2 && c2 < 0)), k_le = popc64(__ballot(real2 && c2 <= 0));
+            lo.tighten(r2, k_lt, n_real);
+            hi.tighten(r2, k_le, n_real);
+        }
     }
-    out_lo = a_lo;
-    out_hi = a_hi > a_lo ? a_hi : a_lo;
+    out_lo = lo.a;
+    out_hi = hi.a > lo.a ? hi.a : lo.a;
 }
 
 // position of the lowest set bit at or after bit index `from` in a bitmap that is known to contain one
@@ -179,6 +222,7 @@ __global__ __launch_bounds__(kThreads) void retrieve_kernel(RetrieveParams p) {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     __shared__ uint32_t s_lo[kWavesPerWG], s_hi[kWavesPerWG];
     __shared__ int32_t s_sel;        // wave (= suffix length) chosen
+    __shared__ int32_t s_best;       // smallest wave index known to have a match while the searches run
     __shared__ int32_t s_misc[16];
 
     const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -187,11 +231,12 @@ __global__ __launch_bounds__(kThreads) void retrieve_kernel(RetrieveParams p) {
     t = t < 0 ? 0 : (t > p.ctx_stride ? p.ctx_stride : t);
 
     // ---------------- phase A: the sampled-key table goes to LDS, then one search per wavefront
-    int32_t* lds_top = (int32_t*)lds;
+    const int32_t* lds_tab = (const int32_t*)lds;
     {
         const int4* src = (const int4*)p.top_keys;
-        int4* dst = (int4*)lds_top;
-        for (int i = tid; i < p.top_count * (kKeyLen / 4); i += kThreads) dst[i] = src[i];
+        int4* dst = (int4*)lds;
+        for (int i = tid; i < table_words(p.top_count) / 4; i += kThreads) dst[i] = src[i];
+        if (tid == 0) s_best = kWavesPerWG;
     }
     __syncthreads();
     {
@@ -201,7 +246,7 @@ __global__ __launch_bounds__(kThreads) void retrieve_kernel(RetrieveParams p) {
             int32_t q[kKeyLen];
 #pragma unroll
             for (int j = 0; j < kKeyLen; j++) q[j] = j < n ? s[t - n + j] : 0;
-            wave_search<TokT, SaT>(p, lds_top, q, n, lo, hi);
+            wave_search<TokT, SaT>(p, lds_tab, q, n, wave, &s_best, lo, hi);
         }
         if (lane == 0) { s_lo[wave] = lo; s_hi[wave] = hi; }
     }
@@ -246,6 +291,7 @@ __global__ __launch_bounds__(kThreads) void retrieve_kernel(RetrieveParams p) {
     uint32_t* srt_key = sel_wgt + REST_MAX_NODES;        // [c]
     uint32_t* srt_wgt = srt_key + REST_MAX_NODES;        // [c]
     int32_t* srt_par = (int32_t*)(srt_wgt + REST_MAX_NODES);  // [c]
+    uint32_t* rowpos = (uint32_t*)(lds + p.off_pos);     // [K] suffix-array entry of each kept row
 
     for (int i = tid; i <= p.K; i += kThreads) hist[i] = 0;
     if (tid < 16) s_misc[tid] = 0;
@@ -257,7 +303,9 @@ __global__ __launch_bounds__(kThreads) void retrieve_kernel(RetrieveParams p) {
         int32_t tok[REST_MAX_CONT_LEN];
         int len = 0;
         if (r < R) {
-            const uint64_t pos = (uint64_t)load_sa<SaT>(p.sa, lo + r) + n_star;
+            const uint32_t start = load_sa<SaT>(p.sa, lo + r);
+            rowpos[r] = start;
+            const uint64_t pos = (uint64_t)start + n_star;
             const uint64_t left = p.n_tokens > pos ? p.n_tokens - pos : 0;
             len = left < (uint64_t)m ? (int)left : m;
 #pragma unroll
@@ -466,7 +514,7 @@ __global__ __launch_bounds__(kThreads) void retrieve_kernel(RetrieveParams p) {
         if (tid < T) {
             const uint32_t k = srt_key[tid];
             const int d = (int)(k >> 16), r = (int)(k & 0xffff);
-            const uint64_t pos = (uint64_t)load_sa<SaT>(p.sa, lo + r) + n_star + (d - 1);
+            const uint64_t pos = (uint64_t)rowpos[r] + n_star + (d - 1);
             o_tok[tid] = load_tok<TokT>(p.corpus, p.n_tokens, pos);
             o_par[tid] = srt_par[tid];
             o_pos[tid] = d;
@@ -488,16 +536,22 @@ __global__ __launch_bounds__(kThreads) void retrieve_kernel(RetrieveParams p) {
     }
 }
 
-// Sampled-key table: key i = first 16 tokens (-1 past the end of the stream) of the suffix of rank
-// rest_top_rank(n, top_count, i).
+// Fills the sampled-key table: key k = first 16 tokens (-1 past the end of the stream) of the suffix of rank
+// rest_top_rank(n, top_count, k); words that belong to no key are 0.
 template <typename TokT, typename SaT>
-__global__ void top_table_kernel(const void* corpus, const void* sa, uint64_t n, int32_t top_count, int32_t* keys) {
+__global__ void top_table_kernel(const void* corpus, const void* sa, uint64_t n, int32_t top_count, int32_t* tab) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= top_count * kKeyLen) return;
-    const int k = i / kKeyLen, j = i % kKeyLen;
-    const uint32_t rank = (uint32_t)rest_top_rank(n, top_count, k);
-    const uint64_t pos = (uint64_t)load_sa<SaT>(sa, rank) + j;
-    keys[i] = load_tok<TokT>(corpus, n, pos);
+    if (i >= table_words(top_count)) return;
+    int k, j = -1;                                   // j = -1: the rank itself
+    if (i < kCoarse) { j = i / 64; k = 16 * (i % 64) + 15; }
+    else if (i < kTabKeys) k = i - kCoarse;
+    else { const int w = i - kTabKeys; k = 16 * (w / 256) + w % 16; j = (w % 256) / 16; }
+    int32_t v = 0;
+    if (k < top_count) {
+        const uint32_t rank = (uint32_t)rest_top_rank(n, top_count, k);
+        v = j < 0 ? (int32_t)rank : load_tok<TokT>(corpus, n, (uint64_t)load_sa<SaT>(sa, rank) + j);
+    }
+    tab[i] = v;
 }
 
 bool params_ok(const rest_retrieve_params* q) {
@@ -534,13 +588,13 @@ rest_status rest_internal_make_top_table(rest_index* idx, hipStream_t stream) {
     int tc = (int)(idx->n_tokens / 64 < (uint64_t)kTopMax ? idx->n_tokens / 64 : (uint64_t)kTopMax);
     idx->top_count = tc;
     // always allocate so the pointer is valid
-    if (hipMalloc((void**)&idx->d_top_keys, (size_t)(tc > 0 ? tc : 1) * kKeyLen * sizeof(int32_t)) != hipSuccess) {
+    if (hipMalloc((void**)&idx->d_top_keys, (size_t)table_words(tc) * sizeof(int32_t)) != hipSuccess) {
         (void)hipGetLastError();
         idx->d_top_keys = nullptr;
         return REST_OUT_OF_MEMORY;
     }
     if (tc > 0) {
-        const int total = tc * kKeyLen, blocks = (total + 255) / 256;
+        const int total = table_words(tc), blocks = (total + 255) / 256;
         if (idx->token_bytes == 2 && idx->sa_bytes == 4)
             hipLaunchKernelGGL((top_table_kernel<uint16_t, int32_t>), dim3(blocks), dim3(256), 0, stream, idx->d_corpus, idx->d_sa, idx->n_tokens, tc, idx->d_top_keys);
         else if (idx->token_bytes == 2)
@@ -595,9 +649,10 @@ extern "C" __attribute__((visibility("default"))) rest_status rest_retrieve(cons
     p.off_hist = (int32_t)off; off = align16(off + (size_t)(p.K + 1) * 4);
     p.off_part = (int32_t)off; off = align16(off + (size_t)(128 + p.words + 64) * 4);
     p.off_sel = (int32_t)off;  off = align16(off + (size_t)REST_MAX_NODES * 5 * 4);
+    p.off_pos = (int32_t)off;  off = align16(off + (size_t)p.K * 4);
     p.off_misc = (int32_t)off;
     size_t lds_bytes = off;
-    const size_t top_bytes = (size_t)index->top_count * kKeyLen * 4;
+    const size_t top_bytes = (size_t)table_words(index->top_count) * 4;
     if (top_bytes > lds_bytes) lds_bytes = top_bytes;
     if (lds_bytes > 150 * 1024) return REST_UNSUPPORTED;
 
