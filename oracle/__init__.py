@@ -11,6 +11,13 @@ selection, breadth-first pseudo sequence + tree mask, acceptance) live in
 rest_oracle.c and are reached through ctypes; tree attention is written here
 with numpy in float64.
 
+The steps either side of verification inside one model layer (rotary position
+embedding of the draft tokens, appending their keys and values behind the
+cached context, keeping the accepted path's rows afterwards) are written here
+with numpy in float64 as well; the paper only implies them ("Draft
+acceptance": accepted tokens become context), so their exact definition is a
+stated reading.
+
 Parity pins: every function below is pinned by tests/test_oracle_*.py against
 facts that do not come from this code (textbook suffix arrays, Python's own
 substring search and sort, collections.Counter prefix counts, a library
@@ -245,6 +252,62 @@ def tree_attention_loops(q, k, v, mask, prefix_len: int, scale: float) -> np.nda
         for w, j in zip(e, vis):
             for d in range(D):
                 out[i, d] += (w / z) * float(v[j, d])
+    return out
+
+
+# ---------------------------------------------------------------------------
+# Around verification, inside one layer.  "Draft verification" builds the
+# pseudo sequence and its mask but leaves positions unsaid; "Draft acceptance"
+# turns accepted draft tokens into context.  For a model with rotary position
+# embedding and a key/value cache that means: a draft node at depth d behind a
+# context whose last token has position p0 is embedded at position p0 + d; its
+# key and value are appended behind the cached context so that verification
+# can read them; and after acceptance the accepted path's rows are the ones
+# that stay, moved up to directly follow the context.
+# ---------------------------------------------------------------------------
+def rope(x: np.ndarray, positions: np.ndarray, theta: float = 10000.0) -> np.ndarray:
+    """Rotary position embedding (Su et al., RoFormer) in the half-split layout
+    of the Llama-family models the paper evaluates: with h = D/2, components
+    (i, i+h) of row t form a plane vector that is rotated by the angle
+    positions[t] * theta**(-2i/D).  x [..., T, D]; positions [T] or matching
+    the leading dims [..., T]; returns float64."""
+    x = np.asarray(x, dtype=np.float64)
+    D = x.shape[-1]
+    h = D // 2
+    assert 2 * h == D
+    freq = theta ** (-2.0 * np.arange(h, dtype=np.float64) / D)
+    ang = np.asarray(positions, dtype=np.float64)[..., None] * freq
+    c, s = np.cos(ang), np.sin(ang)
+    a, b = x[..., :h], x[..., h:]
+    return np.concatenate([a * c - b * s, a * s + b * c], axis=-1)
+
+
+def rope_append(q, k_new, v_new, k_cache, v_cache, pos_ids, pos_offset: int, prefix_len: int,
+                theta: float = 10000.0):
+    """One layer's step before verification.  q, k_new, v_new [..., T, D] belong to
+    the T draft tokens, pos_ids [T] (or [..., T]) are their depths; caches
+    [..., L, D] with L >= prefix_len + T.  Returns (q embedded, k_cache with the
+    embedded keys in rows prefix_len .. prefix_len+T-1, v_cache with the values
+    there), all float64; other cache rows are unchanged."""
+    pos = np.asarray(pos_ids, dtype=np.int64) + int(pos_offset)
+    T = np.asarray(q).shape[-2]
+    P = int(prefix_len)
+    qr = rope(q, pos, theta)
+    kc = np.array(k_cache, dtype=np.float64, copy=True)
+    vc = np.array(v_cache, dtype=np.float64, copy=True)
+    kc[..., P:P + T, :] = rope(k_new, pos, theta)
+    vc[..., P:P + T, :] = np.asarray(v_new, dtype=np.float64)
+    return qr, kc, vc
+
+
+def kv_compact(cache: np.ndarray, prefix_len: int, accept_path: np.ndarray, accept_len: int) -> np.ndarray:
+    """After acceptance: row prefix_len + i of the result is row prefix_len +
+    accept_path[i] of the input for i < accept_len; every other row is
+    unchanged (rows from prefix_len + accept_len on are dead).  cache [..., L, D]."""
+    out = np.array(cache, copy=True)
+    P = int(prefix_len)
+    for i in range(int(accept_len)):
+        out[..., P + i, :] = cache[..., P + int(accept_path[i]), :]
     return out
 
 
