@@ -220,6 +220,24 @@ def side_measurements(rest, torch, synth, corp, index, w, q, k, v, out, tree, P,
     res["attn_per_layer_launches_us_total"] = round(ms * 1e3, 1)
     ms = timed(lambda: rest.rest_tree_attention(q, k, v, mask, P, scale, out=out), 20)
     res["attn_single_launch_us"] = round(ms * 1e3, 1)
+
+    # the cache steps either side of verification, all layers in one call each: rotary embedding of the draft
+    # tokens + append of their keys/values (reads q, k, v of the T tokens, writes q and two cache rows per token),
+    # and the move of the accepted path's rows (here: a path of 8)
+    T, H = q.shape[2], q.shape[1]
+    q2, kn, vn = torch.empty_like(q), torch.empty_like(q), torch.empty_like(q)
+    for t in (q2, kn, vn):
+        t.copy_(q)
+    pos = tree.pos_ids[0]
+    ms = timed(lambda: rest.rest_rope_append(q2, kn, vn, k, v, pos, P), 20)
+    by = 6 * Nb * H * T * 128 * 2
+    res["rope_append_us"] = round(ms * 1e3, 1)
+    res["rope_append_GBps"] = round(by / (ms * 1e-3) / 1e9, 1)
+    apath = torch.tensor([[0, 2, 5, 9, 14, 20, 27, 35] + [-1] * (w.cont_len - 8)], dtype=torch.int32, device=dev)
+    alen = torch.tensor([8], dtype=torch.int32, device=dev)
+    ms = timed(lambda: rest.rest_kv_compact(k, v, apath, alen, T, P), 20)
+    res["kv_compact_path8_us"] = round(ms * 1e3, 1)
+    res["kv_compact_GBps"] = round(4 * Nb * H * 8 * 128 * 2 / (ms * 1e-3) / 1e9, 1)
     return res
 
 

@@ -3,7 +3,7 @@
  * draft-and-verify hot path (Retrieval-Based Speculative Decoding,
  * arXiv 2311.08252).
  *
- * The four calls follow the paper's problem statement:
+ * The four main calls follow the paper's problem statement:
  *   rest_build_index   "Datastore construction" + the suffix array used for
  *                      exact match ("Retrieving from the datastore")
  *   rest_retrieve      Algorithm 1 (longest matching suffix, its continuations)
@@ -14,6 +14,8 @@
  *                      that mask ("Draft verification")
  *   rest_accept        "Draft acceptance": accept draft tokens from the start
  *                      while they equal the model's own tokens
+ * rest_rope_append and rest_kv_compact are the cache steps before and after
+ * verification that "Draft acceptance" implies.
  *
  * Conventions
  *  - Every pointer whose name starts with d_ (and every pointer inside
@@ -21,8 +23,8 @@
  *    or reallocates it.  Pointers to parameter structs are HOST memory and are
  *    read before the call returns.
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
- *    rest_retrieve, rest_tree_attention and rest_accept only enqueue work on
- *    it and never synchronise; rest_build_index allocates scratch memory and
+ *    rest_retrieve, rest_tree_attention, rest_accept, rest_rope_append and
+ *    rest_kv_compact only enqueue work on it and never synchronise; rest_build_index allocates scratch memory and
  *    may synchronise.
  *  - All calls return a rest_status; no call aborts, throws or prints.  On an
  *    error nothing has been enqueued and output buffers are untouched.
@@ -198,6 +200,57 @@ rest_status rest_tree_attention(const void* d_q, const void* d_k, const void* d_
  * ---------------------------------------------------------------------- */
 rest_status rest_accept(const int32_t* d_ids, const rest_tree* tree, int32_t B, int32_t c, int32_t path_cap,
                         int32_t* d_accept_len, int32_t* d_accept_path, int32_t* d_next_token, void* stream);
+
+/* ------------------------------------------------------------------------
+ * The steps either side of verification inside one model layer.  The paper
+ * implies them ("Draft acceptance": accepted draft tokens become context; the
+ * pseudo sequence of "Draft verification" needs positions that reflect each
+ * token's place in its own draft) without describing them; the definitions
+ * below are this library's reading for models with rotary position embedding
+ * and a key/value cache.
+ *
+ * rest_rope_append, before rest_tree_attention: draft node t (depth
+ * d_pos_ids[t], as emitted by rest_retrieve) gets position
+ * pos_offset + d_pos_ids[t]; pos_offset is the position of the context's last
+ * token (P - 1 when the cache holds the whole context).  Its query and key are
+ * rotated by the rotary embedding of that position -- half-split layout: with
+ * h = D/2, components (i, i+h) form a plane vector turned by the angle
+ * position * theta^(-2i/D) -- in fp32 with angles formed in fp64, and rounded to
+ * bf16.  The query is rewritten in place; the rotated key and the value are
+ * written to row P + t of the caches.
+ *   d_q, d_k_new, d_v_new  [Nb, H, T, D] bf16
+ *   d_k_cache, d_v_cache   [Nb, H, >= P + T, D] bf16
+ *   d_pos_ids              [T] int32 (per_batch == 0) or [Nb, T]
+ *
+ * rest_kv_compact, after rest_accept: for i < accept_len, cache row P + i
+ * becomes what row P + accept_path[i] was (all reads happen before any write);
+ * rows from P + accept_len on are dead afterwards.
+ *   d_accept_path  [path_cap] int32 (per_batch == 0) or [Nb, path_cap]
+ *   d_accept_len   [1] or [Nb] int32; entries outside [0, T) end the moves
+ * path_cap <= REST_MAX_CONT_LEN.
+ *
+ * D must be 128; strides are in elements for the Nb, H and row axes, D
+ * contiguous, rows 16-byte aligned.  Both calls only enqueue work on `stream`.
+ * ---------------------------------------------------------------------- */
+typedef struct {
+    int32_t Nb, H, T, D;
+    int32_t P;
+    int32_t pos_offset;
+    int32_t per_batch;       /* 0: one d_pos_ids / d_accept_path row for all Nb; 1: one per Nb */
+    int32_t dtype;           /* REST_BF16 */
+    double theta;            /* rotary base, e.g. 10000 */
+    int64_t q_stride[3];
+    int64_t kn_stride[3];
+    int64_t vn_stride[3];
+    int64_t kc_stride[3];
+    int64_t vc_stride[3];
+} rest_kv_desc;
+
+rest_status rest_rope_append(void* d_q, const void* d_k_new, const void* d_v_new, void* d_k_cache, void* d_v_cache,
+                             const int32_t* d_pos_ids, const rest_kv_desc* desc, void* stream);
+
+rest_status rest_kv_compact(void* d_k_cache, void* d_v_cache, const int32_t* d_accept_path,
+                            const int32_t* d_accept_len, int32_t path_cap, const rest_kv_desc* desc, void* stream);
 
 #ifdef __cplusplus
 }

@@ -39,6 +39,7 @@ EXPORTS = [
     "rest_status_string", "rest_version", "rest_build_index", "rest_index_from_sa", "rest_index_view",
     "rest_index_destroy", "rest_retrieve_workspace_bytes", "rest_retrieve",
     "rest_tree_attention_workspace_bytes", "rest_tree_attention", "rest_accept",
+    "rest_rope_append", "rest_kv_compact",
 ]
 
 
@@ -64,6 +65,14 @@ class rest_attn_desc(ctypes.Structure):
                 ("P", ctypes.c_int32), ("D", ctypes.c_int32), ("dtype", ctypes.c_int32), ("scale", ctypes.c_float),
                 ("q_stride", ctypes.c_int64 * 3), ("k_stride", ctypes.c_int64 * 3), ("v_stride", ctypes.c_int64 * 3),
                 ("o_stride", ctypes.c_int64 * 3), ("mask_per_batch", ctypes.c_int32), ("num_splits", ctypes.c_int32)]
+
+
+class rest_kv_desc(ctypes.Structure):
+    _fields_ = [("Nb", ctypes.c_int32), ("H", ctypes.c_int32), ("T", ctypes.c_int32), ("D", ctypes.c_int32),
+                ("P", ctypes.c_int32), ("pos_offset", ctypes.c_int32), ("per_batch", ctypes.c_int32),
+                ("dtype", ctypes.c_int32), ("theta", ctypes.c_double),
+                ("q_stride", ctypes.c_int64 * 3), ("kn_stride", ctypes.c_int64 * 3), ("vn_stride", ctypes.c_int64 * 3),
+                ("kc_stride", ctypes.c_int64 * 3), ("vc_stride", ctypes.c_int64 * 3)]
 
 
 _lib.rest_status_string.restype = ctypes.c_char_p
@@ -95,6 +104,12 @@ _lib.rest_tree_attention.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_
 _lib.rest_accept.restype = ctypes.c_int32
 _lib.rest_accept.argtypes = [ctypes.c_void_p, ctypes.POINTER(rest_tree), ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
                              ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+_lib.rest_rope_append.restype = ctypes.c_int32
+_lib.rest_rope_append.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                  ctypes.c_void_p, ctypes.POINTER(rest_kv_desc), ctypes.c_void_p]
+_lib.rest_kv_compact.restype = ctypes.c_int32
+_lib.rest_kv_compact.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32,
+                                 ctypes.POINTER(rest_kv_desc), ctypes.c_void_p]
 
 
 def rest_status_string(status: int) -> str:
@@ -298,3 +313,53 @@ def rest_accept(ids: torch.Tensor, tree: Tree, path_cap: int,
     if st != REST_OK:
         raise RestError(st, "rest_accept")
     return accept_len, accept_path, next_token
+
+
+def make_kv_desc(k_cache: torch.Tensor, v_cache: torch.Tensor, T: int, prefix_len: int, pos_offset: int | None = None,
+                 theta: float = 10000.0, per_batch: bool = False, q: torch.Tensor | None = None,
+                 k_new: torch.Tensor | None = None, v_new: torch.Tensor | None = None) -> rest_kv_desc:
+    Nb, H, _, D = k_cache.shape
+    d = rest_kv_desc()
+    d.Nb, d.H, d.T, d.D, d.P = Nb, H, T, D, prefix_len
+    d.pos_offset = prefix_len - 1 if pos_offset is None else pos_offset
+    d.per_batch = 1 if per_batch else 0
+    d.dtype = {torch.bfloat16: REST_BF16, torch.float32: REST_FP32}[k_cache.dtype]
+    d.theta = theta
+    for name, t in (("q_stride", q), ("kn_stride", k_new), ("vn_stride", v_new), ("kc_stride", k_cache),
+                    ("vc_stride", v_cache)):
+        if t is not None:
+            assert t.stride(3) == 1
+            getattr(d, name)[:] = [t.stride(0), t.stride(1), t.stride(2)]
+    return d
+
+
+def rest_rope_append(q: torch.Tensor, k_new: torch.Tensor, v_new: torch.Tensor, k_cache: torch.Tensor,
+                     v_cache: torch.Tensor, pos_ids: torch.Tensor, prefix_len: int, pos_offset: int | None = None,
+                     theta: float = 10000.0) -> None:
+    """q, k_new, v_new [Nb,H,T,128]; caches [Nb,H,>=P+T,128] (bf16, device); pos_ids [T] or [Nb,T] int32.
+    Rotates q in place and writes the rotated keys and the values to cache rows P .. P+T-1.  Enqueues on the
+    current stream."""
+    assert q.dim() == 4 and q.shape == k_new.shape == v_new.shape and k_cache.shape == v_cache.shape
+    T = q.shape[2]
+    assert k_cache.shape[2] >= prefix_len + T and pos_ids.shape[-1] == T and pos_ids.is_contiguous()
+    desc = make_kv_desc(k_cache, v_cache, T, prefix_len, pos_offset, theta, pos_ids.dim() == 2, q, k_new, v_new)
+    st = _lib.rest_rope_append(_dev(q), _dev(k_new), _dev(v_new), _dev(k_cache), _dev(v_cache),
+                               _dev(pos_ids, torch.int32), ctypes.byref(desc), _stream())
+    if st != REST_OK:
+        raise RestError(st, "rest_rope_append")
+
+
+def rest_kv_compact(k_cache: torch.Tensor, v_cache: torch.Tensor, accept_path: torch.Tensor, accept_len: torch.Tensor,
+                    T: int, prefix_len: int) -> None:
+    """caches [Nb,H,>=P+T,128] (bf16, device); accept_path [path_cap] or [Nb,path_cap], accept_len [1] or [Nb] int32
+    as written by rest_accept.  Moves the accepted rows up behind the prefix, in place.  Enqueues on the current
+    stream."""
+    assert k_cache.shape == v_cache.shape and accept_path.is_contiguous()
+    per_batch = accept_path.dim() == 2 and accept_path.shape[0] > 1
+    if per_batch:
+        assert accept_path.shape[0] == k_cache.shape[0] and accept_len.numel() == k_cache.shape[0]
+    desc = make_kv_desc(k_cache, v_cache, T, prefix_len, per_batch=per_batch)
+    st = _lib.rest_kv_compact(_dev(k_cache), _dev(v_cache), _dev(accept_path, torch.int32), _dev(accept_len, torch.int32),
+                              accept_path.shape[-1], ctypes.byref(desc), _stream())
+    if st != REST_OK:
+        raise RestError(st, "rest_kv_compact")

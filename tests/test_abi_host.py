@@ -28,7 +28,7 @@ def declared_functions():
 
 def test_header_functions_are_exported(rest):
     names = declared_functions()
-    assert len(names) == 11 and "rest_retrieve" in names and "rest_tree_attention" in names
+    assert len(names) == 13 and "rest_retrieve" in names and "rest_tree_attention" in names
     lib = ctypes.CDLL(LIB)
     for n in names:
         assert getattr(lib, n) is not None
@@ -95,3 +95,26 @@ def test_calls_reject_null_and_bad_arguments_before_touching_the_gpu(rest):
     assert lib.rest_retrieve(None, None, None, 1, 8, ctypes.byref(prm), ctypes.byref(tree), None, 0, None) == rest.REST_INVALID_ARG
     assert lib.rest_accept(None, ctypes.byref(tree), 1, 64, 10, None, None, None, None) == rest.REST_INVALID_ARG
     assert rest.rest_retrieve_workspace_bytes(4) == 0
+    kd = rest.rest_kv_desc()
+    kd.Nb, kd.H, kd.T, kd.D, kd.P, kd.pos_offset, kd.dtype, kd.theta = 2, 4, 8, 128, 16, 15, rest.REST_BF16, 10000.0
+    for name in ("q_stride", "kn_stride", "vn_stride"):
+        getattr(kd, name)[:] = [4 * 8 * 128, 8 * 128, 128]
+    for name in ("kc_stride", "vc_stride"):
+        getattr(kd, name)[:] = [4 * 32 * 128, 32 * 128, 128]
+    p16 = ctypes.c_void_p(16)
+    assert lib.rest_rope_append(None, p16, p16, p16, p16, p16, ctypes.byref(kd), None) == rest.REST_INVALID_ARG
+    assert lib.rest_rope_append(p16, p16, p16, p16, p16, None, ctypes.byref(kd), None) == rest.REST_INVALID_ARG
+    assert lib.rest_rope_append(ctypes.c_void_p(8), p16, p16, p16, p16, p16, ctypes.byref(kd), None) == rest.REST_INVALID_ARG
+    assert lib.rest_kv_compact(p16, p16, None, p16, 10, ctypes.byref(kd), None) == rest.REST_INVALID_ARG
+    assert lib.rest_kv_compact(p16, p16, p16, p16, 33, ctypes.byref(kd), None) == rest.REST_INVALID_ARG
+    for field, bad in (("D", 64), ("T", 0), ("T", 257), ("theta", 1.0), ("P", -1), ("Nb", 0)):
+        keep = getattr(kd, field)
+        setattr(kd, field, bad)
+        assert lib.rest_rope_append(p16, p16, p16, p16, p16, p16, ctypes.byref(kd), None) == rest.REST_INVALID_ARG
+        assert lib.rest_kv_compact(p16, p16, p16, p16, 10, ctypes.byref(kd), None) == rest.REST_INVALID_ARG
+        setattr(kd, field, keep)
+    kd.kc_stride[2] = 100          # rows must be 16-byte aligned and at least D long
+    assert lib.rest_kv_compact(p16, p16, p16, p16, 10, ctypes.byref(kd), None) == rest.REST_INVALID_ARG
+    kd.kc_stride[2] = 128
+    kd.dtype = rest.REST_FP32
+    assert lib.rest_kv_compact(p16, p16, p16, p16, 10, ctypes.byref(kd), None) == rest.REST_UNSUPPORTED

@@ -95,6 +95,47 @@ def test_llama7b_index_retrieval_attention_at_benchmark_shape():
     sampled_attention_check(w.layers, w.heads, w.max_nodes, w.kv_len, w.qkv_seed, 24, tree.tree_mask)
 
 
+def test_llama7b_cache_steps_at_benchmark_shape():
+    """rest_rope_append and rest_kv_compact over all 32 layers x 32 heads in one call each, as bench.py times them;
+    sampled (layer, head) slabs against the oracle."""
+    w = synth.WORKLOADS["llama7b"]
+    Nb, H, T, P = w.layers, w.heads, w.max_nodes, w.kv_len
+    g = torch.Generator(device="cuda")
+    g.manual_seed(w.qkv_seed + 7)
+    q, kn, vn = (torch.randn((Nb, H, T, 128), generator=g, device="cuda").to(torch.bfloat16) for _ in range(3))
+    kc, vc = (torch.randn((Nb, H, P + T, 128), generator=g, device="cuda").to(torch.bfloat16) for _ in range(2))
+    par, dep, tok, mask = synth.random_tree(T, 77)
+    q0, kc0, vc0 = q.clone(), kc.clone(), vc.clone()
+    rest.rest_rope_append(q, kn, vn, kc, vc, dev(dep.astype(np.int32)), P)
+    leaf = int(np.argmax(dep))
+    path = []
+    v = leaf
+    while v != -1:
+        path.append(v)
+        v = int(par[v])
+    path = np.array(path[::-1] + [-1] * (w.cont_len - len(path)), dtype=np.int32)
+    A = int(dep[leaf])
+    kc1, vc1 = kc.clone(), vc.clone()
+    rest.rest_kv_compact(kc, vc, dev(path[None]), dev(np.array([A], dtype=np.int32)), T, P)
+    torch.cuda.synchronize()
+    f64 = lambda t: t.float().cpu().numpy().astype(np.float64)
+    rng = np.random.default_rng(5)
+    picks = {(0, 0), (Nb - 1, H - 1)}
+    while len(picks) < 12:
+        picks.add((int(rng.integers(Nb)), int(rng.integers(H))))
+    for a, b in sorted(picks):
+        q_ref, k_ref, v_ref = oracle.rope_append(f64(q0[a, b]), f64(kn[a, b]), f64(vn[a, b]), f64(kc0[a, b]), f64(vc0[a, b]),
+                                                 dep, P - 1, P)
+        for got, ref, src in ((f64(q[a, b]), q_ref, f64(q0[a, b])), (f64(kc1[a, b])[P:], k_ref[P:], f64(kn[a, b]))):
+            mag = np.abs(src[:, :64]) + np.abs(src[:, 64:])
+            bound = 2.0 ** -8 * np.abs(ref) + 2.0 ** -21 * np.concatenate([mag, mag], axis=-1)
+            assert (np.abs(got - ref) <= bound).all()
+        np.testing.assert_array_equal(f64(kc1[a, b])[:P], f64(kc0[a, b])[:P])
+        np.testing.assert_array_equal(f64(vc1[a, b]), v_ref)
+        np.testing.assert_array_equal(f64(kc[a, b]), oracle.kv_compact(f64(kc1[a, b]), P, path, A))
+        np.testing.assert_array_equal(f64(vc[a, b]), oracle.kv_compact(f64(vc1[a, b]), P, path, A))
+
+
 @pytest.mark.parametrize("T,P", [(16, 1024), (64, 8192), (128, 4096), (256, 1024), (256, 8192)])
 def test_sweep_shapes_random_trees(T, P):
     """Tree-size / KV-length sweep at the 7B head shape with random tries (branching <= 8, depth <= 16)."""

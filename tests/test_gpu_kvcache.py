@@ -1,0 +1,175 @@
+"""GPU parity of rest_rope_append and rest_kv_compact against the CPU oracle.
+
+Rotated values: the library forms angles in fp64 and rotates in fp32, so a result differs from the oracle's
+float64 value by the final rounding to bf16 (half a unit in the last place, relative 2^-9) plus fp32 rounding of the
+two products (2^-23 of their magnitudes, which matters only where the products cancel).  The bound asserted is
+2^-8 |ref| + 2^-21 (|a| + |b|).  Values and moved rows are compared bit for bit."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth
+
+pytestmark = pytest.mark.gpu
+
+if torch.cuda.is_available():
+    import paper_2311_08252_amd as rest
+
+
+def bf16_tensor(shape, seed):
+    bits = synth.normal_bf16_bits(seed, shape)
+    return torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16), synth.bf16_bits_to_f32(bits).astype(np.float64)
+
+
+def to_np(t):
+    return t.float().cpu().numpy().astype(np.float64)
+
+
+def assert_rotated(got, ref, src):
+    """src: the unrotated input rows; |a| + |b| per plane bounds the products' rounding."""
+    h = src.shape[-1] // 2
+    mag = np.abs(src[..., :h]) + np.abs(src[..., h:])
+    mag = np.concatenate([mag, mag], axis=-1)
+    bound = 2.0 ** -8 * np.abs(ref) + 2.0 ** -21 * mag
+    err = np.abs(got - ref)
+    assert (err <= bound).all(), float((err - bound).max())
+
+
+@pytest.mark.parametrize("Nb,H,T,P,extra,per_batch,theta", [
+    (2, 3, 5, 7, 0, False, 10000.0),
+    (1, 8, 64, 200, 3, False, 10000.0),
+    (3, 5, 33, 100, 9, True, 1000000.0),
+    (4, 32, 64, 4096, 0, True, 500000.0),
+    (1, 1, 1, 0, 0, False, 10000.0),
+    (2, 9, 256, 17, 5, False, 10000.0),
+])
+def test_rope_append_matches_oracle(Nb, H, T, P, extra, per_batch, theta):
+    L = P + T + extra
+    q, q_np = bf16_tensor((Nb, H, T, 128), 1)
+    kn, kn_np = bf16_tensor((Nb, H, T, 128), 2)
+    vn, vn_np = bf16_tensor((Nb, H, T, 128), 3)
+    kc, kc_np = bf16_tensor((Nb, H, L, 128), 4)
+    vc, vc_np = bf16_tensor((Nb, H, L, 128), 5)
+    rng = np.random.default_rng(T + P)
+    pos_np = rng.integers(0, 17, size=(Nb, T) if per_batch else (T,)).astype(np.int32)
+    pos_b = pos_np[:, None, :] if per_batch else pos_np
+    off = P - 1 if P else 41
+    q_ref, k_ref, v_ref = oracle.rope_append(q_np, kn_np, vn_np, kc_np, vc_np,
+                                             np.broadcast_to(pos_b, (Nb, H, T)) if per_batch else pos_np, off, P, theta)
+    rest.rest_rope_append(q, kn, vn, kc, vc, torch.from_numpy(pos_np).cuda(), P, off, theta)
+    torch.cuda.synchronize()
+    assert_rotated(to_np(q), q_ref, q_np)
+    assert_rotated(to_np(kc)[:, :, P:P + T], k_ref[:, :, P:P + T], kn_np)
+    # untouched rows and the appended values are exact
+    np.testing.assert_array_equal(to_np(kc)[:, :, :P], kc_np[:, :, :P])
+    np.testing.assert_array_equal(to_np(kc)[:, :, P + T:], kc_np[:, :, P + T:])
+    np.testing.assert_array_equal(to_np(vc), v_ref)
+    # the inputs k_new / v_new are not modified
+    np.testing.assert_array_equal(to_np(kn), kn_np)
+
+
+def test_rope_append_strided_inputs_from_a_fused_projection():
+    """q, k, v as slices of one [Nb, T, 3, H, D] projection output; caches with padded rows."""
+    Nb, H, T, P = 2, 4, 10, 12
+    fused, fused_np = bf16_tensor((Nb, T, 3, H, 128), 7)
+    q, kn, vn = (fused[:, :, i].permute(0, 2, 1, 3) for i in range(3))
+    q_np, kn_np, vn_np = (fused_np[:, :, i].transpose(0, 2, 1, 3) for i in range(3))
+    big_k, big_k_np = bf16_tensor((Nb, H, P + T, 256), 8)
+    big_v, big_v_np = bf16_tensor((Nb, H, P + T, 256), 9)
+    kc, vc = big_k[..., :128], big_v[..., 128:]
+    pos = np.arange(1, T + 1, dtype=np.int32)
+    q_ref, k_ref, v_ref = oracle.rope_append(q_np, kn_np, vn_np, big_k_np[..., :128], big_v_np[..., 128:], pos, P - 1, P)
+    rest.rest_rope_append(q, kn, vn, kc, vc, torch.from_numpy(pos).cuda(), P)
+    torch.cuda.synchronize()
+    assert_rotated(to_np(q), q_ref, q_np)
+    assert_rotated(to_np(kc)[:, :, P:], k_ref[:, :, P:], kn_np)
+    np.testing.assert_array_equal(to_np(vc), v_ref)
+    # the halves of the padded rows that do not belong to the caches are untouched
+    np.testing.assert_array_equal(to_np(big_k[..., 128:]), big_k_np[..., 128:])
+    np.testing.assert_array_equal(to_np(big_v[..., :128]), big_v_np[..., :128])
+
+
+@pytest.mark.parametrize("Nb,H,T,P,cap,paths", [
+    (1, 2, 6, 3, 4, [[1, 3, -1, -1]]),
+    (2, 3, 8, 5, 5, [[0, 1, 2, 3, 4]]),                  # chain accepted in full: already in place
+    (2, 3, 8, 5, 5, [[1, 2, 5, -1, -1]]),                # row P+1 is read by move 0 and written by move 1
+    (3, 4, 16, 9, 6, [[2, 5, 9, 15, -1, -1], [-1] * 6, [0, 3, 4, 7, 8, 11]]),     # per batch, one empty
+    (1, 32, 64, 2048, 16, [[0, 2, 7, 12, 20, 33, 41, 63] + [-1] * 8]),
+    (1, 1, 40, 0, 32, [list(range(8, 40))]),             # the longest path the call takes
+])
+def test_kv_compact_matches_oracle_bit_for_bit(Nb, H, T, P, cap, paths):
+    kc, kc_np = bf16_tensor((Nb, H, P + T + 2, 128), 11)
+    vc, vc_np = bf16_tensor((Nb, H, P + T + 2, 128), 12)
+    path = np.array(paths, dtype=np.int32)
+    lens = np.array([sum(1 for x in row if x >= 0) for row in paths], dtype=np.int32)
+    k_ref, v_ref = kc_np.copy(), vc_np.copy()
+    for nb in range(Nb):
+        row = nb if len(paths) > 1 else 0
+        k_ref[nb] = oracle.kv_compact(kc_np[nb], P, path[row], lens[row])
+        v_ref[nb] = oracle.kv_compact(vc_np[nb], P, path[row], lens[row])
+    rest.rest_kv_compact(kc, vc, torch.from_numpy(path).cuda(), torch.from_numpy(lens).cuda(), T, P)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(to_np(kc), k_ref)
+    np.testing.assert_array_equal(to_np(vc), v_ref)
+
+
+def test_kv_compact_stops_at_an_entry_that_is_no_draft_row():
+    Nb, H, T, P = 1, 2, 8, 4
+    kc, kc_np = bf16_tensor((Nb, H, P + T, 128), 13)
+    vc, vc_np = bf16_tensor((Nb, H, P + T, 128), 14)
+    path = np.array([[3, 9, 5, -1]], dtype=np.int32)     # 9 >= T: only the first move is made, although len says 3
+    rest.rest_kv_compact(kc, vc, torch.from_numpy(path).cuda(), torch.tensor([3], dtype=torch.int32).cuda(), T, P)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(to_np(kc)[0], oracle.kv_compact(kc_np[0], P, path[0], 1))
+    np.testing.assert_array_equal(to_np(vc)[0], oracle.kv_compact(vc_np[0], P, path[0], 1))
+
+
+def test_layer_step_on_the_gpu_equals_plain_decoding_of_the_accepted_tokens():
+    """retrieve -> rope_append -> tree attention -> accept -> compact, all on the GPU, against the oracle's
+    token-by-token decoding of the accepted path (positions P, P+1, ...; causal attention)."""
+    w = synth.WORKLOADS["tiny"]
+    corp = synth.make_corpus(w.n_tokens, w.corpus_seed, w.n_motifs)
+    ctx, lens = synth.make_contexts(corp, 8, w.ctx_len, w.query_seed)
+    index = rest.rest_build_index(torch.from_numpy(corp.tokens).cuda(), 4)
+    c, m, H, P = w.max_nodes, w.cont_len, 4, 64
+    done = 0
+    for b in range(8):
+        tree = rest.rest_retrieve(index, torch.from_numpy(ctx[b:b + 1]).cuda(), torch.from_numpy(lens[b:b + 1]).cuda(),
+                                  n_max=w.n_max, n_min=w.n_min, max_matches=w.max_matches, cont_len=m, max_nodes=c)
+        torch.cuda.synchronize()
+        n = int(tree.n_nodes[0])
+        if n < 3:
+            continue
+        tok, par = tree.draft_tokens[0].cpu().numpy(), tree.parent_idx[0].cpu().numpy()
+        ids = synth.sampled_ids(900 + b, tok, par, n)
+        q, q_np = bf16_tensor((1, H, c, 128), 20 + b)
+        kn, kn_np = bf16_tensor((1, H, c, 128), 30 + b)
+        vn, vn_np = bf16_tensor((1, H, c, 128), 40 + b)
+        kc, kc_np = bf16_tensor((1, H, P + c, 128), 50 + b)
+        vc, vc_np = bf16_tensor((1, H, P + c, 128), 60 + b)
+        scale = 1.0 / np.sqrt(128.0)
+        rest.rest_rope_append(q, kn, vn, kc, vc, tree.pos_ids[0], P)
+        out = rest.rest_tree_attention(q, kc, vc, tree.tree_mask[0], P, float(scale))
+        alen, apath, nxt = rest.rest_accept(torch.from_numpy(ids[None]).cuda(), tree, m)
+        rest.rest_kv_compact(kc, vc, apath, alen, c, P)
+        torch.cuda.synchronize()
+        A = int(alen[0])
+        path = apath[0].cpu().numpy()[:A]
+        k_plain, v_plain = kc_np[0].copy(), vc_np[0].copy()
+        for i, node in enumerate(path):
+            pos = np.array([P + i])
+            # the cache holds bf16: plain decoding would store the rotated key rounded the same way
+            k_plain[:, P + i] = oracle.rope(kn_np[0, :, node:node + 1], pos)[:, 0]
+            v_plain[:, P + i] = vn_np[0, :, node]
+            assert_rotated(to_np(kc)[0, :, P + i], k_plain[:, P + i], kn_np[0, :, node])
+            k_plain[:, P + i] = to_np(kc)[0, :, P + i]
+            np.testing.assert_array_equal(to_np(vc)[0, :, P + i], v_plain[:, P + i])
+            qi = to_np(q)[0, :, node:node + 1]
+            s = scale * np.einsum("hqd,hkd->hqk", qi, k_plain[:, :P + i + 1])
+            p = np.exp(s - s.max(-1, keepdims=True))
+            p /= p.sum(-1, keepdims=True)
+            o = np.einsum("hqk,hkd->hqd", p, v_plain[:, :P + i + 1])
+            assert np.abs(to_np(out)[0, :, node] - o[:, 0]).max() <= 2e-2
+        done += A > 0
+    assert done >= 2
