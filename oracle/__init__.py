@@ -331,6 +331,44 @@ def accept(ids: np.ndarray, draft_tokens: np.ndarray, parent_idx: np.ndarray, n_
 
 
 # ---------------------------------------------------------------------------
+# Nucleus sampling ("Sampling strategies"): the model's token at a position is
+# drawn from the most probable tokens whose cumulative probability reaches the
+# threshold p; REST accepts a draft token only if it equals the token sampled
+# at its position, so acceptance is the same walk as in the greedy case on
+# sampled ids.  The paper fixes temperature and top-p (Table 1 caption) but not
+# the mechanics; the reading here: probabilities = softmax(logits /
+# temperature); tokens ordered by probability, highest first, equal
+# probabilities by ascending token id; the nucleus is the shortest prefix of
+# that order whose mass is >= top_p; the draw is inverse-CDF on the
+# renormalised nucleus with a uniform number u in [0, 1) supplied by the caller.
+# ---------------------------------------------------------------------------
+def nucleus_sample(logits: np.ndarray, temperature: float, top_p: float, u: float):
+    """Returns (token, margin).  margin is the distance, in probability mass, between the
+    decision thresholds (top_p for the nucleus boundary, u * nucleus mass for the draw)
+    and the nearest cumulative sum: results of two float64 implementations can differ
+    only where it is at rounding level."""
+    z = np.asarray(logits, dtype=np.float64) / float(temperature)
+    z = z - z.max()
+    p = np.exp(z)
+    p = p / p.sum()
+    order = np.lexsort((np.arange(p.size), -p))          # probability descending, token id ascending
+    cum = np.cumsum(p[order])
+    hit = np.nonzero(cum >= top_p)[0]
+    k = int(hit[0]) if hit.size else p.size - 1
+    mass = cum[k]
+    target = float(u) * mass
+    j = int(np.nonzero(cum > target)[0][0])
+    margin = min(np.abs(cum[:k + 1] - top_p).min(), np.abs(cum[:k + 1] - target).min())
+    return int(order[j]), float(margin)
+
+
+def sample_ids(logits: np.ndarray, temperature: float, top_p: float, u: np.ndarray):
+    """logits [R, V], u [R] -> (ids [R] int32, margins [R])."""
+    out = [nucleus_sample(logits[r], temperature, top_p, u[r]) for r in range(logits.shape[0])]
+    return np.array([t for t, _ in out], dtype=np.int32), np.array([m for _, m in out])
+
+
+# ---------------------------------------------------------------------------
 # The decoding loop the acceptance rule is claimed to preserve: with a
 # deterministic next-token function, REST's draft/verify/accept loop must emit
 # exactly the tokens of one-token-at-a-time greedy decoding.
