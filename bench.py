@@ -238,6 +238,17 @@ def side_measurements(rest, torch, synth, corp, index, w, q, k, v, out, tree, P,
     ms = timed(lambda: rest.rest_kv_compact(k, v, apath, alen, T, P), 20)
     res["kv_compact_path8_us"] = round(ms * 1e3, 1)
     res["kv_compact_GBps"] = round(4 * Nb * H * 8 * 128 * 2 / (ms * 1e-3) / 1e9, 1)
+
+    # nucleus sampling of the model's token at the root and the T draft positions (vocabulary 32000, temperature 0.8,
+    # top-p 0.95: the paper's code-generation setting), the input of rest_accept when decoding is not greedy
+    g = torch.Generator(device=dev)
+    g.manual_seed(77)
+    logits = torch.randn((1 + T, 32000), generator=g, device=dev) * 2.0
+    logits[:, :8] += 9.0
+    u = torch.rand(1 + T, generator=g, device=dev)
+    sid = torch.empty(1 + T, dtype=torch.int32, device=dev)
+    ms = timed(lambda: rest.rest_sample_ids(logits, u, 0.8, 0.95, out=sid), 20)
+    res["sample_ids_65x32000_us"] = round(ms * 1e3, 1)
     return res
 
 

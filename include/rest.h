@@ -14,8 +14,9 @@
  *                      that mask ("Draft verification")
  *   rest_accept        "Draft acceptance": accept draft tokens from the start
  *                      while they equal the model's own tokens
- * rest_rope_append and rest_kv_compact are the cache steps before and after
- * verification that "Draft acceptance" implies.
+ * rest_sample_ids draws the model's token per position for nucleus sampling
+ * ("Sampling strategies"); rest_rope_append and rest_kv_compact are the cache
+ * steps before and after verification that "Draft acceptance" implies.
  *
  * Conventions
  *  - Every pointer whose name starts with d_ (and every pointer inside
@@ -23,8 +24,9 @@
  *    or reallocates it.  Pointers to parameter structs are HOST memory and are
  *    read before the call returns.
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
- *    rest_retrieve, rest_tree_attention, rest_accept, rest_rope_append and
- *    rest_kv_compact only enqueue work on it and never synchronise; rest_build_index allocates scratch memory and
+ *    rest_retrieve, rest_tree_attention, rest_accept, rest_sample_ids,
+ *    rest_rope_append and rest_kv_compact only enqueue work on it and never
+ *    synchronise; rest_build_index allocates scratch memory and
  *    may synchronise.
  *  - All calls return a rest_status; no call aborts, throws or prints.  On an
  *    error nothing has been enqueued and output buffers are untouched.
@@ -200,6 +202,24 @@ rest_status rest_tree_attention(const void* d_q, const void* d_k, const void* d_
  * ---------------------------------------------------------------------- */
 rest_status rest_accept(const int32_t* d_ids, const rest_tree* tree, int32_t B, int32_t c, int32_t path_cap,
                         int32_t* d_accept_len, int32_t* d_accept_path, int32_t* d_next_token, void* stream);
+
+/* ------------------------------------------------------------------------
+ * rest_sample_ids ("Sampling strategies"): nucleus sampling of the model's token
+ * at R positions (the context's last token and every draft node), so that
+ * rest_accept can compare sampled tokens, not arg-max tokens, with the drafts.
+ * Row r: probabilities = softmax(d_logits[r, :] / temperature); tokens ordered
+ * by probability, highest first, equal probabilities by ascending token id;
+ * the nucleus is the shortest prefix of that order whose mass is >= top_p;
+ * d_ids[r] = the first token of the order whose cumulative mass exceeds
+ * d_u[r] * (nucleus mass).  d_u[r] in [0, 1) is the caller's random number for
+ * that position: tie it to the position in the sequence and decoding with
+ * drafts emits exactly what one-token-at-a-time sampling emits.
+ * All arithmetic is fp64 on the fp32 logits; logits are finite or -inf, at
+ * least one finite per row.  d_logits [R, row_stride >= V] fp32.
+ * V <= 32768 (REST_UNSUPPORTED above); temperature > 0; 0 < top_p <= 1.
+ * ---------------------------------------------------------------------- */
+rest_status rest_sample_ids(const float* d_logits, int64_t row_stride, const float* d_u, int32_t R, int32_t V,
+                            float temperature, float top_p, int32_t* d_ids, void* stream);
 
 /* ------------------------------------------------------------------------
  * The steps either side of verification inside one model layer.  The paper

@@ -362,6 +362,30 @@ def nucleus_sample(logits: np.ndarray, temperature: float, top_p: float, u: floa
     return int(order[j]), float(margin)
 
 
+def nucleus_candidates(logits: np.ndarray, temperature: float, top_p: float, u: float, tol: float = 1e-9):
+    """Every token that nucleus_sample could return if each cumulative sum were off by up to `tol`
+    (another float64 implementation differs by rounding only): the nucleus may end one element
+    earlier or later when a cumulative sum is within tol of top_p, and the draw may fall on
+    either side of a cumulative sum within tol of its target.  A set; almost always one token."""
+    z = np.asarray(logits, dtype=np.float64) / float(temperature)
+    z = z - z.max()
+    p = np.exp(z)
+    p = p / p.sum()
+    order = np.lexsort((np.arange(p.size), -p))
+    cum = np.cumsum(p[order])
+    ends = [k for k in range(p.size) if cum[k] >= top_p - tol and (k == 0 or cum[k - 1] < top_p + tol)]
+    if not ends:
+        ends = [p.size - 1]
+    out = set()
+    for k in ends:
+        target = float(u) * cum[k]
+        for j in range(k + 1):
+            below = cum[j - 1] if j else 0.0
+            if below <= target + tol and cum[j] > target - tol:
+                out.add(int(order[j]))
+    return out
+
+
 def sample_ids(logits: np.ndarray, temperature: float, top_p: float, u: np.ndarray):
     """logits [R, V], u [R] -> (ids [R] int32, margins [R])."""
     out = [nucleus_sample(logits[r], temperature, top_p, u[r]) for r in range(logits.shape[0])]

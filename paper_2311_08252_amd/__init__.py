@@ -39,7 +39,7 @@ EXPORTS = [
     "rest_status_string", "rest_version", "rest_build_index", "rest_index_from_sa", "rest_index_view",
     "rest_index_destroy", "rest_retrieve_workspace_bytes", "rest_retrieve",
     "rest_tree_attention_workspace_bytes", "rest_tree_attention", "rest_accept",
-    "rest_rope_append", "rest_kv_compact",
+    "rest_rope_append", "rest_kv_compact", "rest_sample_ids",
 ]
 
 
@@ -104,6 +104,9 @@ _lib.rest_tree_attention.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_
 _lib.rest_accept.restype = ctypes.c_int32
 _lib.rest_accept.argtypes = [ctypes.c_void_p, ctypes.POINTER(rest_tree), ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
                              ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+_lib.rest_sample_ids.restype = ctypes.c_int32
+_lib.rest_sample_ids.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32,
+                                 ctypes.c_float, ctypes.c_float, ctypes.c_void_p, ctypes.c_void_p]
 _lib.rest_rope_append.restype = ctypes.c_int32
 _lib.rest_rope_append.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                   ctypes.c_void_p, ctypes.POINTER(rest_kv_desc), ctypes.c_void_p]
@@ -363,3 +366,19 @@ def rest_kv_compact(k_cache: torch.Tensor, v_cache: torch.Tensor, accept_path: t
                               accept_path.shape[-1], ctypes.byref(desc), _stream())
     if st != REST_OK:
         raise RestError(st, "rest_kv_compact")
+
+
+def rest_sample_ids(logits: torch.Tensor, u: torch.Tensor, temperature: float, top_p: float,
+                    out: torch.Tensor | None = None) -> torch.Tensor:
+    """logits [R, V] fp32 (rows may be strided), u [R] fp32 in [0, 1) (device).  Returns ids [R] int32: the nucleus
+    sample of every row.  Enqueues on the current stream."""
+    assert logits.dim() == 2 and logits.stride(1) == 1 and logits.dtype == torch.float32
+    R, V = logits.shape
+    assert u.numel() == R and u.is_contiguous()
+    if out is None:
+        out = torch.empty(R, dtype=torch.int32, device=logits.device)
+    st = _lib.rest_sample_ids(_dev(logits, torch.float32), logits.stride(0) if R > 1 else V, _dev(u, torch.float32), R, V,
+                              temperature, top_p, _dev(out, torch.int32), _stream())
+    if st != REST_OK:
+        raise RestError(st, "rest_sample_ids")
+    return out

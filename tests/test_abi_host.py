@@ -28,7 +28,7 @@ def declared_functions():
 
 def test_header_functions_are_exported(rest):
     names = declared_functions()
-    assert len(names) == 13 and "rest_retrieve" in names and "rest_tree_attention" in names
+    assert len(names) == 14 and "rest_retrieve" in names and "rest_tree_attention" in names
     lib = ctypes.CDLL(LIB)
     for n in names:
         assert getattr(lib, n) is not None
@@ -95,6 +95,13 @@ def test_calls_reject_null_and_bad_arguments_before_touching_the_gpu(rest):
     assert lib.rest_retrieve(None, None, None, 1, 8, ctypes.byref(prm), ctypes.byref(tree), None, 0, None) == rest.REST_INVALID_ARG
     assert lib.rest_accept(None, ctypes.byref(tree), 1, 64, 10, None, None, None, None) == rest.REST_INVALID_ARG
     assert rest.rest_retrieve_workspace_bytes(4) == 0
+    assert lib.rest_sample_ids(None, 100, p16 := ctypes.c_void_p(16), 1, 100, 1.0, 0.9, p16, None) == rest.REST_INVALID_ARG
+    assert lib.rest_sample_ids(p16, 99, p16, 1, 100, 1.0, 0.9, p16, None) == rest.REST_INVALID_ARG        # stride < V
+    assert lib.rest_sample_ids(p16, 100, p16, 1, 100, 0.0, 0.9, p16, None) == rest.REST_INVALID_ARG       # temperature
+    assert lib.rest_sample_ids(p16, 100, p16, 1, 100, 1.0, 0.0, p16, None) == rest.REST_INVALID_ARG       # top_p
+    assert lib.rest_sample_ids(p16, 100, p16, 1, 100, 1.0, 1.5, p16, None) == rest.REST_INVALID_ARG
+    assert lib.rest_sample_ids(p16, 40000, p16, 1, 40000, 1.0, 0.9, p16, None) == rest.REST_UNSUPPORTED
+    assert lib.rest_sample_ids(p16, 100, p16, 0, 100, 1.0, 0.9, p16, None) == rest.REST_OK                # nothing to do
     kd = rest.rest_kv_desc()
     kd.Nb, kd.H, kd.T, kd.D, kd.P, kd.pos_offset, kd.dtype, kd.theta = 2, 4, 8, 128, 16, 15, rest.REST_BF16, 10000.0
     for name in ("q_stride", "kn_stride", "vn_stride"):

@@ -127,3 +127,20 @@ def test_rest_decoding_with_sampled_acceptance_equals_plain_sampling():
     fast, steps = oracle.rest_decode(next_token, prompt, 48, corp.tokens, max_matches=200, cont_len=8, max_nodes=24)
     assert fast == plain
     assert steps < 48
+
+
+def test_candidate_sets_contain_the_sample_and_are_single_away_from_boundaries():
+    rng = np.random.default_rng(9)
+    lg = rng.standard_normal(300).astype(np.float32) * 3
+    for u in rng.random(50):
+        tok, margin = oracle.nucleus_sample(lg, 0.8, 0.9, u)
+        cands = oracle.nucleus_candidates(lg, 0.8, 0.9, u)
+        assert tok in cands
+        if margin > 1e-8:
+            assert cands == {tok}
+    # on a boundary both neighbours qualify: probabilities 1/2, 1/4, 1/4 and u = 1/2 exactly
+    lg = logits_of([0.5, 0.25, 0.25])
+    assert oracle.nucleus_candidates(lg, 1.0, 1.0, 0.5) == {0, 1}
+    assert oracle.nucleus_sample(lg, 1.0, 1.0, 0.5)[0] in (0, 1)        # float32 logits: 1/2 is not hit exactly
+    # top_p exactly on a cumulative sum: the nucleus may or may not take the next token
+    assert oracle.nucleus_candidates(lg, 1.0, 0.75, 0.99) == {1, 2}
