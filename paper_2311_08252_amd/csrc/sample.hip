@@ -44,7 +44,9 @@ struct Crossing {
 __global__ __launch_bounds__(kThreads) void sample_kernel(const float* logits, int64_t stride, const float* u, int V,
                                                           double temperature, double top_p, int32_t* ids) {
     extern __shared__ double acc[];                    // [16][kThreads]
-    __shared__ double bucket_mass[16];
+    __shared__ double level_mass[8][16];   // bucket masses of the first descent, per level
+    __shared__ double scratch_mass[16];
+    __shared__ uint32_t level_prefix[8];
     __shared__ float red_f[kWaves];
     __shared__ int red_i[kWaves];
     __shared__ int row_cnt[kPer][kWaves];
@@ -75,33 +77,50 @@ __global__ __launch_bounds__(kThreads) void sample_kernel(const float* logits, i
     }
 
     // descends the key to the element where the cumulative mass (largest key first) first reaches (strict: exceeds)
-    // `target`
-    auto select = [&](double target, bool strict) -> Crossing {
+    // `target`.  A recording descent keeps the bucket masses of its levels (1 KB); a later descent reuses them for as
+    // long as it follows the same prefix -- usually through the first levels (sign and exponent bits), which are the
+    // expensive ones because nearly every element takes part in them.
+    int levels_kept = 0;                           // same value in every thread
+    auto select = [&](double target, bool strict, bool record) -> Crossing {
         Crossing c{};
         uint32_t prefix = 0;
         double cum = 0.0;
         c.found = true;
+        bool follow = true;
         for (int lvl = 0; lvl < 8; lvl++) {
+            const double* masses = &level_mass[lvl][0];
+            follow = follow && lvl < levels_kept && level_prefix[lvl] == prefix;
+            if (!follow) {
 #pragma unroll
-            for (int d = 0; d < 16; d++) acc[d * kThreads + tid] = 0.0;
-            const int sh = 28 - 4 * lvl;
+                for (int d = 0; d < 16; d++) acc[d * kThreads + tid] = 0.0;
+                const int sh = 28 - 4 * lvl;
 #pragma unroll
-            for (int i = 0; i < kPer; i++) {
-                const bool match = lvl == 0 || (key[i] >> (sh + 4)) == prefix;
-                if (match) acc[((key[i] >> sh) & 15u) * kThreads + tid] += e[i];
+                for (int i = 0; i < kPer; i++) {
+                    const bool match = lvl == 0 || (key[i] >> (sh + 4)) == prefix;
+                    // a private slot: the atomic is only a read-modify-write the wavefront need not wait for
+                    if (match)
+                        __hip_atomic_fetch_add(&acc[((key[i] >> sh) & 15u) * kThreads + tid], e[i], __ATOMIC_RELAXED,
+                                               __HIP_MEMORY_SCOPE_WORKGROUP);
+                }
+                __syncthreads();
+                double* dst = record ? &level_mass[lvl][0] : &scratch_mass[0];
+                for (int b = wave; b < 16; b += kWaves) {
+                    double s = 0.0;
+#pragma unroll
+                    for (int t = 0; t < kThreads / 64; t++) s += acc[b * kThreads + lane + 64 * t];
+                    for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+                    if (lane == 0) dst[b] = s;
+                }
+                if (record) {
+                    if (tid == 0) level_prefix[lvl] = prefix;
+                    levels_kept = lvl + 1;          // deeper kept levels belonged to another prefix
+                }
+                __syncthreads();
+                masses = dst;
             }
-            __syncthreads();
-            for (int b = wave; b < 16; b += kWaves) {
-                double s = 0.0;
-#pragma unroll
-                for (int t = 0; t < kThreads / 64; t++) s += acc[b * kThreads + lane + 64 * t];
-                for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
-                if (lane == 0) bucket_mass[b] = s;
-            }
-            __syncthreads();
             int d = 15;
             for (; d >= 0; d--) {
-                const double next = cum + bucket_mass[d];
+                const double next = cum + masses[d];
                 if (strict ? next > target : next >= target) break;
                 cum = next;
             }
@@ -138,16 +157,13 @@ __global__ __launch_bounds__(kThreads) void sample_kernel(const float* logits, i
         return c;
     };
 
-    // the nucleus and its mass
-    double total = 0.0;
-    {
-        // total mass in the same fixed order as a level-0 walk: reuse select with an unreachable target
-        Crossing all = select(INFINITY, false);
-        total = all.above;
-    }
-    const Crossing nuc = select(top_p * total, false);
+    // the nucleus and its mass.  The total is the sum of the level-0 bucket masses in the order of a descent's walk,
+    // so the first descent is run with an unreachable target and stops after that level.
+    const double total = select(INFINITY, false, true).above;
+    // the nucleus descent reuses level 0 and records its own deeper levels; the draw follows it while it can
+    const Crossing nuc = select(top_p * total, false, true);
     const double mass = nuc.found ? nuc.above + (double)nuc.rank * nuc.each : nuc.above;
-    Crossing hit = select((double)u[row] * mass, true);
+    Crossing hit = select((double)u[row] * mass, true, false);
     if (!hit.found) hit = nuc;                         // cannot happen for u < 1 except through rounding
     if (!hit.found) {                                  // nor this: the total is positive
         if (tid == 0) ids[row] = 0;
