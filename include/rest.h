@@ -163,6 +163,11 @@ rest_status rest_retrieve(const rest_index* index, const int32_t* d_contexts, co
  * strides (in elements) of the Nb, H and row axes are given per tensor.
  * d_mask: [Tq, ceil(Tk/64)] uint64 when mask_per_batch == 0 (shared by all Nb),
  * else [Nb, Tq, ceil(Tk/64)].  Heads share K/V one-to-one (multi-head attention).
+ * Grouped-query attention (g query heads per K/V head) is the same call on a view: H = number
+ * of K/V heads, the g query heads of a group stacked along the row axis (Tq = g * T, row
+ * h_in_group * T + t; a plain reshape when the query heads are contiguous) and
+ * mask_rows = T, so that all g copies of node t use mask row t; each K/V byte is then read once
+ * per group.
  * dtype: REST_BF16 (bf16 in/out, fp32 accumulation and softmax, probabilities
  * rounded to bf16 for the second product) or REST_FP32 (fp32 in/out and math).
  * D must be 128.  Tq, Tk <= REST_MAX_NODES (Tk may be 0).
@@ -179,6 +184,7 @@ typedef struct {
     int64_t o_stride[3];
     int32_t mask_per_batch;
     int32_t num_splits;      /* 0 = let the library choose; else KV splits per (Nb, H) */
+    int32_t mask_rows;       /* 0 = Tq; else rows of one mask: query row i uses mask row i % mask_rows */
 } rest_attn_desc;
 
 /* Bytes of device workspace (partial results of the KV splits). */

@@ -64,7 +64,8 @@ class rest_attn_desc(ctypes.Structure):
     _fields_ = [("Nb", ctypes.c_int32), ("H", ctypes.c_int32), ("Tq", ctypes.c_int32), ("Tk", ctypes.c_int32),
                 ("P", ctypes.c_int32), ("D", ctypes.c_int32), ("dtype", ctypes.c_int32), ("scale", ctypes.c_float),
                 ("q_stride", ctypes.c_int64 * 3), ("k_stride", ctypes.c_int64 * 3), ("v_stride", ctypes.c_int64 * 3),
-                ("o_stride", ctypes.c_int64 * 3), ("mask_per_batch", ctypes.c_int32), ("num_splits", ctypes.c_int32)]
+                ("o_stride", ctypes.c_int64 * 3), ("mask_per_batch", ctypes.c_int32), ("num_splits", ctypes.c_int32),
+                ("mask_rows", ctypes.c_int32)]
 
 
 class rest_kv_desc(ctypes.Structure):
@@ -258,7 +259,7 @@ def rest_retrieve(index: RestIndex, contexts: torch.Tensor, ctx_len: torch.Tenso
 
 
 def make_attn_desc(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, out: torch.Tensor, prefix_len: int,
-                   scale: float, mask_per_batch: bool, num_splits: int = 0) -> rest_attn_desc:
+                   scale: float, mask_per_batch: bool, num_splits: int = 0, mask_rows: int = 0) -> rest_attn_desc:
     Nb, H, Tq, D = q.shape
     Lk = k.shape[2]
     dt = {torch.bfloat16: REST_BF16, torch.float32: REST_FP32}[q.dtype]
@@ -271,6 +272,7 @@ def make_attn_desc(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, out: torch
         getattr(d, name)[:] = [t.stride(0), t.stride(1), t.stride(2)]
     d.mask_per_batch = 1 if mask_per_batch else 0
     d.num_splits = num_splits
+    d.mask_rows = mask_rows
     return d
 
 
@@ -280,14 +282,14 @@ def rest_tree_attention_workspace_bytes(desc: rest_attn_desc) -> int:
 
 def rest_tree_attention(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, mask: torch.Tensor, prefix_len: int,
                         scale: float, out: torch.Tensor | None = None, num_splits: int = 0,
-                        workspace: torch.Tensor | None = None) -> torch.Tensor:
+                        workspace: torch.Tensor | None = None, mask_rows: int = 0) -> torch.Tensor:
     """q [Nb,H,Tq,128]; k, v [Nb,H,P+Tk,128] (bf16 or fp32, device); mask [Tq,words] or [Nb,Tq,words] int64/uint64.
     Enqueues on the current stream."""
     assert q.dim() == 4 and k.dim() == 4 and v.dim() == 4 and k.shape == v.shape
     if out is None:
         out = torch.empty_like(q)
     per_batch = mask.dim() == 3
-    desc = make_attn_desc(q, k, v, out, prefix_len, scale, per_batch, num_splits)
+    desc = make_attn_desc(q, k, v, out, prefix_len, scale, per_batch, num_splits, mask_rows)
     need = rest_tree_attention_workspace_bytes(desc)
     if workspace is None and need:
         workspace = torch.empty(need, dtype=torch.uint8, device=q.device)

@@ -50,6 +50,7 @@ struct AttnParams {
     float* ws_ml;     // bf16 path: [W][2][QT*32][2] (reference in log2 units, sum); fp32 path: [rows][2]
     int32_t Nb, H, Tq, Tk, P, Lk;
     int32_t nsplit, qgroups, mask_words, mask_per_batch;
+    int32_t mask_rows;   // rows of one mask: query row i uses mask row i % mask_rows
     int32_t nblk;     // ceil(Lk / 32)
     int32_t units;    // Nb * H * qgroups
     int32_t n_streams;  // W: wavefronts that share the work
@@ -165,11 +166,11 @@ __global__ __launch_bounds__(128, 2) void tree_attn_bf16_kernel(AttnParams p) {
 
         // mask row of this lane's query -> LDS (the halves write words 0,1 / 2,3); only this wave reads it back
         {
-            const uint64_t* mrow = p.mask + (p.mask_per_batch ? (int64_t)nb * p.Tq * p.mask_words : 0);
+            const uint64_t* mrow = p.mask + (p.mask_per_batch ? (int64_t)nb * p.mask_rows * p.mask_words : 0);
 #pragma unroll
             for (int w = 0; w < 2; w++) {
                 const int ww = 2 * hh + w;
-                my_mask[col * 4 + ww] = (qi < p.Tq && ww < p.mask_words) ? mrow[(int64_t)qi * p.mask_words + ww] : 0ull;
+                my_mask[col * 4 + ww] = (qi < p.Tq && ww < p.mask_words) ? mrow[(int64_t)(qi % p.mask_rows) * p.mask_words + ww] : 0ull;
             }
         }
         // Q fragments (B operand of S^T = K Q^T): lane holds query `col`, d = 16*ks + 8*hh .. +8
@@ -387,7 +388,7 @@ __global__ __launch_bounds__(128) void tree_attn_f32_kernel(const float* q, cons
     const float* qp = q + nb * p.qs[0] + h * p.qs[1] + qi * p.qs[2];
     const float* kp = k + nb * p.ks[0] + h * p.ks[1];
     const float* vp = v + nb * p.vs[0] + h * p.vs[1];
-    const uint64_t* mrow = mask + (p.mask_per_batch ? nb * p.Tq * p.mask_words : 0) + (int64_t)qi * p.mask_words;
+    const uint64_t* mrow = mask + (p.mask_per_batch ? nb * p.mask_rows * p.mask_words : 0) + (int64_t)(qi % p.mask_rows) * p.mask_words;
     qs[tid] = qp[tid];
     __syncthreads();
     const int chunk = (p.Lk + p.nsplit - 1) / p.nsplit;
@@ -508,6 +509,7 @@ bool desc_ok(const rest_attn_desc* d) {
     if (d->dtype != REST_BF16 && d->dtype != REST_FP32) return false;
     if (!(d->scale > 0.f) || !(d->scale < 1e30f)) return false;
     if (d->num_splits < 0 || d->num_splits > 64) return false;
+    if (d->mask_rows < 0 || d->mask_rows > d->Tq) return false;
     if ((int64_t)d->Nb * d->H * 64 > 0x7fffffff) return false;
     for (int i = 0; i < 3; i++)
         if (d->q_stride[i] < 0 || d->k_stride[i] < 0 || d->v_stride[i] < 0 || d->o_stride[i] < 0) return false;
@@ -555,6 +557,7 @@ extern "C" __attribute__((visibility("default"))) rest_status rest_tree_attentio
     p.Nb = d->Nb; p.H = d->H; p.Tq = d->Tq; p.Tk = d->Tk; p.P = d->P; p.Lk = d->P + d->Tk;
     p.mask_words = (d->Tk + 63) / 64;
     p.mask_per_batch = d->mask_per_batch ? 1 : 0;
+    p.mask_rows = d->mask_rows > 0 ? d->mask_rows : d->Tq;
     p.nblk = pl.nblk;
     p.c = d->scale * 1.4426950408889634f;
     for (int i = 0; i < 3; i++) { p.qs[i] = d->q_stride[i]; p.ks[i] = d->k_stride[i]; p.vs[i] = d->v_stride[i]; p.os[i] = d->o_stride[i]; }

@@ -74,7 +74,7 @@ def test_attention_workspace_sizing_is_host_only(rest):
     fp32 = make_desc(rest, Nb=1, dtype=rest.REST_FP32, num_splits=3)
     assert rest.rest_tree_attention_workspace_bytes(fp32) == 32 * 3 * 64 * 130 * 4
     for bad in [dict(D=64), dict(Tq=0), dict(Tq=257), dict(Tk=257), dict(scale=0.0), dict(dtype=7), dict(num_splits=65),
-                dict(Nb=0), dict(P=-1)]:
+                dict(Nb=0), dict(P=-1), dict(mask_rows=-1), dict(mask_rows=65)]:
         assert rest.rest_tree_attention_workspace_bytes(make_desc(rest, **bad)) == 0
 
 

@@ -249,6 +249,38 @@ def test_tree_attention_strided_layout_and_errors():
                                  dev(mask.view(np.int64)), P, 0.1)
 
 
+@pytest.mark.parametrize("dtype,Hkv,g,T,P,per_batch", [("bf16", 2, 4, 16, 100, False), ("bf16", 3, 4, 64, 515, True),
+                                                       ("bf16", 8, 2, 33, 64, False), ("fp32", 2, 3, 20, 40, False)])
+def test_grouped_query_attention_as_a_view(dtype, Hkv, g, T, P, per_batch):
+    """g query heads per K/V head: the call sees H = Hkv heads with g*T query rows each and mask_rows = T."""
+    Nb = 2
+    masks = np.stack([synth.random_tree(T, 60 + nb)[3] for nb in range(Nb)])
+    mask = masks if per_batch else masks[0]
+    if dtype == "bf16":
+        qb = synth.normal_bf16_bits(71, (Nb, Hkv * g, T, 128))
+        kb = synth.normal_bf16_bits(72, (Nb, Hkv, P + T, 128))
+        vb = synth.normal_bf16_bits(73, (Nb, Hkv, P + T, 128))
+        q, k, v = (synth.bf16_bits_to_f32(x) for x in (qb, kb, vb))
+        dq, dk, dv = (dev(x.view(np.int16)).view(torch.bfloat16) for x in (qb, kb, vb))
+    else:
+        q, k, v = (synth.normal_f32(71 + i, shp) for i, shp in enumerate([(Nb, Hkv * g, T, 128), (Nb, Hkv, P + T, 128),
+                                                                        (Nb, Hkv, P + T, 128)]))
+        dq, dk, dv = dev(q), dev(k), dev(v)
+    scale = 1.0 / np.sqrt(128.0)
+    out = torch.full_like(dq, float("nan"))
+    rest.rest_tree_attention(dq.view(Nb, Hkv, g * T, 128), dk, dv, dev(mask.view(np.int64)), P, float(scale),
+                             out=out.view(Nb, Hkv, g * T, 128), mask_rows=T)
+    torch.cuda.synchronize()
+    got = out.float().cpu().numpy().astype(np.float64)
+    for nb in range(Nb):
+        for h in range(Hkv * g):
+            want = oracle.tree_attention(q[nb, h], k[nb, h // g], v[nb, h // g], masks[nb] if per_batch else masks[0], P, scale)
+            if dtype == "bf16":
+                assert np.abs(got[nb, h] - want).max() <= 2e-2
+            else:
+                assert np.abs(got[nb, h] - want).max() / np.abs(want).max() <= 1e-3
+
+
 # ------------------------------------------------------------------ acceptance
 def test_accept_matches_oracle_on_random_trees():
     B, c, cap = 40, 64, 16
