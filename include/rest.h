@@ -50,7 +50,9 @@ enum {
     REST_UNSUPPORTED = -2,        /* legal request this build has no kernel for */
     REST_WORKSPACE_TOO_SMALL = -3,
     REST_OUT_OF_MEMORY = -4,      /* hipMalloc failed (index build / handle creation only) */
-    REST_HIP_ERROR = -5           /* a HIP runtime call or kernel launch failed */
+    REST_HIP_ERROR = -5,          /* a HIP runtime call or kernel launch failed */
+    REST_IO_ERROR = -6,           /* a file could not be opened, read or written in full */
+    REST_BAD_FILE = -7            /* not an index file, or not the index of this token stream */
 };
 
 /* Compile-time limits of the retrieval kernels (rest_retrieve rejects larger values). */
@@ -95,6 +97,18 @@ rest_status rest_index_from_sa(const void* d_corpus, const void* d_sa, uint64_t 
 /* Read-only view of what the handle holds (any out pointer may be NULL). */
 rest_status rest_index_view(const rest_index* index, const void** d_corpus, const void** d_sa,
                             uint64_t* n_tokens, int32_t* token_bytes, int32_t* sa_bytes);
+
+/* Datastore persistence ("Datastore construction": the index is built once and
+ * reused).  rest_index_save writes the suffix array behind a 64-byte header
+ * ("RESTSA01", n_tokens u64, token_bytes i32, sa_bytes i32, a 64-bit
+ * fingerprint of the token stream, zero padding; little endian) to the host
+ * file `path`.  rest_index_load reads such a file for the stream at d_corpus
+ * (borrowed, as in rest_build_index): length, token width and fingerprint
+ * must agree with the file's, else REST_BAD_FILE; the handle owns the array.
+ * Both synchronise `stream`. */
+rest_status rest_index_save(const rest_index* index, const char* path, void* stream);
+rest_status rest_index_load(const char* path, const void* d_corpus, uint64_t n_tokens, int32_t token_bytes,
+                            void* stream, rest_index** out);
 
 /* Frees what the handle owns.  NULL is allowed. */
 void rest_index_destroy(rest_index* index);

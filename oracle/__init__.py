@@ -202,6 +202,48 @@ def mask_from_parents(parent_idx: np.ndarray, n_nodes: int, words: int | None = 
 
 
 # ---------------------------------------------------------------------------
+# The index file ("Datastore construction": built once, reused): a 64-byte
+# little-endian header -- "RESTSA01", n_tokens u64, token_bytes i32, sa_bytes
+# i32, fingerprint u64, zeros -- then the suffix array.  The fingerprint ties
+# the array to its token stream: the sum over i of
+# splitmix64-finaliser(token_i + (i+1) * 0x9E3779B97F4A7C15) modulo 2^64.
+# ---------------------------------------------------------------------------
+def corpus_fingerprint(corpus: np.ndarray) -> int:
+    M = np.uint64
+    total = M(0)
+    with np.errstate(over="ignore"):
+        for c0 in range(0, corpus.size, 1 << 24):
+            tok = corpus[c0:c0 + (1 << 24)].astype(np.uint64)
+            z = tok + (np.arange(c0 + 1, c0 + 1 + tok.size, dtype=np.uint64)) * M(0x9E3779B97F4A7C15)
+            z = (z ^ (z >> M(30))) * M(0xBF58476D1CE4E5B9)
+            z = (z ^ (z >> M(27))) * M(0x94D049BB133111EB)
+            z = z ^ (z >> M(31))
+            total = total + np.add.reduce(z, dtype=np.uint64)
+    return int(total)
+
+
+def write_index_file(path: str, corpus: np.ndarray, sa: np.ndarray) -> None:
+    import struct
+    assert sa.dtype in (np.int32, np.int64) and sa.size == corpus.size
+    with open(path, "wb") as f:
+        f.write(b"RESTSA01" + struct.pack("<QiiQ", corpus.size, _token_bytes(corpus), sa.dtype.itemsize,
+                                          corpus_fingerprint(corpus)) + bytes(32))
+        f.write(np.ascontiguousarray(sa).tobytes())
+
+
+def read_index_file(path: str):
+    """Returns (n_tokens, token_bytes, sa_bytes, fingerprint, suffix array)."""
+    import struct
+    with open(path, "rb") as f:
+        head = f.read(64)
+        assert len(head) == 64 and head[:8] == b"RESTSA01" and head[32:] == bytes(32)
+        n, tb, sb, fp = struct.unpack("<QiiQ", head[8:32])
+        sa = np.frombuffer(f.read(), dtype=np.int32 if sb == 4 else np.int64)
+    assert sa.size == n
+    return n, tb, sb, fp, sa
+
+
+# ---------------------------------------------------------------------------
 # Tree attention ("Draft verification"): every draft token attends to the whole
 # cached context and, among the draft tokens, only to itself and its ancestors.
 # ---------------------------------------------------------------------------

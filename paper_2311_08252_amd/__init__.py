@@ -28,6 +28,8 @@ REST_UNSUPPORTED = -2
 REST_WORKSPACE_TOO_SMALL = -3
 REST_OUT_OF_MEMORY = -4
 REST_HIP_ERROR = -5
+REST_IO_ERROR = -6
+REST_BAD_FILE = -7
 REST_BF16 = 0
 REST_FP32 = 1
 REST_MAX_SUFFIX_LEN = 16
@@ -39,7 +41,7 @@ EXPORTS = [
     "rest_status_string", "rest_version", "rest_build_index", "rest_index_from_sa", "rest_index_view",
     "rest_index_destroy", "rest_retrieve_workspace_bytes", "rest_retrieve",
     "rest_tree_attention_workspace_bytes", "rest_tree_attention", "rest_accept",
-    "rest_rope_append", "rest_kv_compact", "rest_sample_ids",
+    "rest_rope_append", "rest_kv_compact", "rest_sample_ids", "rest_index_save", "rest_index_load",
 ]
 
 
@@ -89,6 +91,11 @@ _lib.rest_index_view.restype = ctypes.c_int32
 _lib.rest_index_view.argtypes = [ctypes.c_void_p, ctypes.POINTER(ctypes.c_void_p), ctypes.POINTER(ctypes.c_void_p),
                                  ctypes.POINTER(ctypes.c_uint64), ctypes.POINTER(ctypes.c_int32),
                                  ctypes.POINTER(ctypes.c_int32)]
+_lib.rest_index_save.restype = ctypes.c_int32
+_lib.rest_index_save.argtypes = [ctypes.c_void_p, ctypes.c_char_p, ctypes.c_void_p]
+_lib.rest_index_load.restype = ctypes.c_int32
+_lib.rest_index_load.argtypes = [ctypes.c_char_p, ctypes.c_void_p, ctypes.c_uint64, ctypes.c_int32, ctypes.c_void_p,
+                                 ctypes.POINTER(ctypes.c_void_p)]
 _lib.rest_index_destroy.restype = None
 _lib.rest_index_destroy.argtypes = [ctypes.c_void_p]
 _lib.rest_retrieve_workspace_bytes.restype = ctypes.c_size_t
@@ -206,6 +213,24 @@ def rest_index_from_sa(corpus: torch.Tensor, sa: torch.Tensor) -> RestIndex:
     if st != REST_OK:
         raise RestError(st, "rest_index_from_sa")
     return RestIndex(h.value, corpus, sa)
+
+
+def rest_index_save(index: RestIndex, path: str) -> None:
+    """Writes the index's suffix array (with a header naming the token stream it belongs to) to a host file."""
+    st = _lib.rest_index_save(index.handle, os.fsencode(path), _stream())
+    if st != REST_OK:
+        raise RestError(st, "rest_index_save")
+
+
+def rest_index_load(path: str, corpus: torch.Tensor) -> RestIndex:
+    """Reads a file written by rest_index_save for this (device) token stream."""
+    assert corpus.is_contiguous()
+    h = ctypes.c_void_p()
+    st = _lib.rest_index_load(os.fsencode(path), _dev(corpus), corpus.numel(), _token_bytes(corpus), _stream(),
+                              ctypes.byref(h))
+    if st != REST_OK:
+        raise RestError(st, "rest_index_load")
+    return RestIndex(h.value, corpus, None)
 
 
 @dataclass

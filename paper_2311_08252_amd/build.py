@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librest_gfx950.so")
-SOURCES = ["api.hip", "attention.hip", "retrieve.hip", "accept.hip", "build_index.hip", "kvcache.hip", "sample.hip"]
+SOURCES = ["api.hip", "attention.hip", "retrieve.hip", "accept.hip", "build_index.hip", "kvcache.hip", "sample.hip", "index_io.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fvisibility=hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 # per-source extras: keep the MFMA accumulators of the attention kernel in ordinary vector registers; the

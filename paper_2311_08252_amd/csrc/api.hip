@@ -10,6 +10,8 @@ extern "C" __attribute__((visibility("default"))) const char* rest_status_string
         case REST_WORKSPACE_TOO_SMALL: return "workspace too small";
         case REST_OUT_OF_MEMORY: return "out of device memory";
         case REST_HIP_ERROR: return "HIP runtime error";
+        case REST_IO_ERROR: return "file input/output error";
+        case REST_BAD_FILE: return "not an index file of this token stream";
         default: return "unknown status";
     }
 }

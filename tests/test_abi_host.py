@@ -28,7 +28,7 @@ def declared_functions():
 
 def test_header_functions_are_exported(rest):
     names = declared_functions()
-    assert len(names) == 14 and "rest_retrieve" in names and "rest_tree_attention" in names
+    assert len(names) == 16 and "rest_retrieve" in names and "rest_tree_attention" in names
     lib = ctypes.CDLL(LIB)
     for n in names:
         assert getattr(lib, n) is not None
@@ -38,6 +38,7 @@ def test_header_functions_are_exported(rest):
 def test_status_strings_and_version(rest):
     assert rest.rest_status_string(0) == "ok"
     assert "workspace" in rest.rest_status_string(rest.REST_WORKSPACE_TOO_SMALL)
+    assert "file" in rest.rest_status_string(rest.REST_IO_ERROR) and "file" in rest.rest_status_string(rest.REST_BAD_FILE)
     assert rest.rest_status_string(12345) == "unknown status"
     assert rest.rest_version().startswith("rest-gfx950")
 
@@ -102,6 +103,13 @@ def test_calls_reject_null_and_bad_arguments_before_touching_the_gpu(rest):
     assert lib.rest_sample_ids(p16, 100, p16, 1, 100, 1.0, 1.5, p16, None) == rest.REST_INVALID_ARG
     assert lib.rest_sample_ids(p16, 40000, p16, 1, 40000, 1.0, 0.9, p16, None) == rest.REST_UNSUPPORTED
     assert lib.rest_sample_ids(p16, 100, p16, 0, 100, 1.0, 0.9, p16, None) == rest.REST_OK                # nothing to do
+    hh = ctypes.c_void_p()
+    assert lib.rest_index_save(None, b"/tmp/x", None) == rest.REST_INVALID_ARG
+    assert lib.rest_index_load(None, p16, 10, 4, None, ctypes.byref(hh)) == rest.REST_INVALID_ARG
+    assert lib.rest_index_load(b"/tmp/x", None, 10, 4, None, ctypes.byref(hh)) == rest.REST_INVALID_ARG
+    assert lib.rest_index_load(b"/tmp/x", p16, 10, 3, None, ctypes.byref(hh)) == rest.REST_INVALID_ARG
+    # a file that is not there is reported before anything touches the GPU
+    assert lib.rest_index_load(b"/nonexistent-dir/none.restsa", p16, 10, 4, None, ctypes.byref(hh)) == rest.REST_IO_ERROR
     kd = rest.rest_kv_desc()
     kd.Nb, kd.H, kd.T, kd.D, kd.P, kd.pos_offset, kd.dtype, kd.theta = 2, 4, 8, 128, 16, 15, rest.REST_BF16, 10000.0
     for name in ("q_stride", "kn_stride", "vn_stride"):

@@ -281,6 +281,54 @@ def test_grouped_query_attention_as_a_view(dtype, Hkv, g, T, P, per_batch):
                 assert np.abs(got[nb, h] - want).max() / np.abs(want).max() <= 1e-3
 
 
+def test_index_file_round_trip_and_exchange_with_the_oracle(tmp_path):
+    corp = synth.make_corpus(300_000, 4, 30)
+    d_corpus = dev(corp.tokens)
+    index = rest.rest_build_index(d_corpus, 4)
+    p = str(tmp_path / "a.restsa")
+    rest.rest_index_save(index, p)
+    # the oracle reads what the library wrote: header, fingerprint, and the array is the suffix array by definition
+    n, tb, sb, fp, sa = oracle.read_index_file(p)
+    assert (n, tb, sb) == (300_000, 4, 4) and fp == oracle.corpus_fingerprint(corp.tokens)
+    assert oracle.check_suffix_array(corp.tokens, sa) == -1
+    # the library reads its own file back: same array, same retrieval results
+    loaded = rest.rest_index_load(p, d_corpus)
+    assert torch.equal(loaded.suffix_array(), index.suffix_array())
+    ctx, lens = synth.make_contexts(corp, 16, 64, 9)
+    a = rest.rest_retrieve(index, dev(ctx), dev(lens), max_matches=500, cont_len=8, max_nodes=32)
+    b = rest.rest_retrieve(loaded, dev(ctx), dev(lens), max_matches=500, cont_len=8, max_nodes=32)
+    torch.cuda.synchronize()
+    for name in ("draft_tokens", "parent_idx", "pos_ids", "node_weight", "tree_mask", "n_nodes", "matched_len", "match_count"):
+        assert torch.equal(getattr(a, name), getattr(b, name)), name
+    # the library reads a file the oracle wrote (uint16 tokens, 64-bit entries)
+    small = synth.make_corpus(5000, 5, 3, dtype=np.uint16)
+    q = str(tmp_path / "b.restsa")
+    oracle.write_index_file(q, small.tokens, oracle.suffix_array(small.tokens).astype(np.int64))
+    from_oracle = rest.rest_index_load(q, dev(small.tokens))
+    np.testing.assert_array_equal(from_oracle.suffix_array().cpu().numpy(), oracle.suffix_array(small.tokens))
+    # wrong stream, damaged and truncated files
+    other = corp.tokens.copy()
+    other[12345] ^= 1
+    with pytest.raises(rest.RestError) as e:
+        rest.rest_index_load(p, dev(other))
+    assert e.value.status == rest.REST_BAD_FILE
+    with pytest.raises(rest.RestError) as e:
+        rest.rest_index_load(p, dev(corp.tokens[:-1].copy()))
+    assert e.value.status == rest.REST_BAD_FILE
+    raw = open(p, "rb").read()
+    open(p, "wb").write(b"RESTSA02" + raw[8:])
+    with pytest.raises(rest.RestError) as e:
+        rest.rest_index_load(p, d_corpus)
+    assert e.value.status == rest.REST_BAD_FILE
+    open(p, "wb").write(raw[:-100])
+    with pytest.raises(rest.RestError) as e:
+        rest.rest_index_load(p, d_corpus)
+    assert e.value.status == rest.REST_IO_ERROR
+    with pytest.raises(rest.RestError) as e:
+        rest.rest_index_save(index, str(tmp_path / "no-such-dir" / "c.restsa"))
+    assert e.value.status == rest.REST_IO_ERROR
+
+
 # ------------------------------------------------------------------ acceptance
 def test_accept_matches_oracle_on_random_trees():
     B, c, cap = 40, 64, 16

@@ -359,3 +359,32 @@ def test_rest_loop_reproduces_greedy_decoding(seed):
     assert got == want
     assert steps <= 60
     assert steps < 60      # drafts are accepted at least sometimes on this corpus
+
+
+def test_index_file_fingerprint_and_round_trip(tmp_path):
+    # the splitmix64 generator seeded with 0 emits 0xE220A8397B1DCDAF, then 0x6E789E6AA1B965F4 (its published first
+    # outputs): these are the finaliser applied to 1 and 2 times the golden-ratio constant, i.e. the fingerprint
+    # terms of a stream of zero tokens
+    assert oracle.corpus_fingerprint(np.zeros(1, np.int32)) == 0xE220A8397B1DCDAF
+    assert oracle.corpus_fingerprint(np.zeros(2, np.int32)) == (0xE220A8397B1DCDAF + 0x6E789E6AA1B965F4) % 2 ** 64
+    # token value and position both count; uint16 and int32 streams of equal values agree
+    a = np.array([5, 7, 7, 1], np.int32)
+    assert oracle.corpus_fingerprint(a) != oracle.corpus_fingerprint(a[::-1].copy())
+    assert oracle.corpus_fingerprint(a) == oracle.corpus_fingerprint(a.astype(np.uint16))
+    py = 0
+    for i, t in enumerate(a):
+        z = (int(t) + (i + 1) * 0x9E3779B97F4A7C15) % 2 ** 64
+        z = ((z ^ (z >> 30)) * 0xBF58476D1CE4E5B9) % 2 ** 64
+        z = ((z ^ (z >> 27)) * 0x94D049BB133111EB) % 2 ** 64
+        py = (py + (z ^ (z >> 31))) % 2 ** 64
+    assert oracle.corpus_fingerprint(a) == py
+    corpus = np.array([1, 0, 1, 1, 0, 2], np.int32)
+    sa = oracle.suffix_array(corpus).astype(np.int32)
+    p = str(tmp_path / "x.restsa")
+    oracle.write_index_file(p, corpus, sa)
+    raw = open(p, "rb").read()
+    assert len(raw) == 64 + 6 * 4 and raw[:8] == b"RESTSA01" and raw[8:16] == (6).to_bytes(8, "little")
+    assert raw[16:20] == (4).to_bytes(4, "little") and raw[20:24] == (4).to_bytes(4, "little")
+    n, tb, sb, fp, back = oracle.read_index_file(p)
+    assert (n, tb, sb, fp) == (6, 4, 4, oracle.corpus_fingerprint(corpus))
+    np.testing.assert_array_equal(back, sa)
