@@ -174,12 +174,38 @@ def select_drafts(rows: np.ndarray, row_len: np.ndarray, max_nodes: int,
     return DraftTree(n.value, tok[:c], par[:c], pos[:c], wgt[:c], mask[:c], 0, 0, tot.value)
 
 
+def _mix64(z: int) -> int:
+    z &= (1 << 64) - 1
+    z = ((z ^ (z >> 30)) * 0xBF58476D1CE4E5B9) & ((1 << 64) - 1)
+    z = ((z ^ (z >> 27)) * 0x94D049BB133111EB) & ((1 << 64) - 1)
+    return z ^ (z >> 31)
+
+
+def random_rows(n_rows: int, n_seq: int, seed: int, ctx_index: int) -> np.ndarray:
+    """The candidates drawn by the random-selection strategy the paper compares the Trie with
+    ("Effect of draft token selecting strategies": at most eight sequences sampled from all
+    retrieved candidates).  The draws are the method's random numbers, so their generator is
+    part of the definition and counter based: with G = 0x9E3779B97F4A7C15 and mix = the
+    splitmix64 finaliser, h = mix(seed + G*(1 + ctx_index)), U_j = mix(h + G*(1 + j)) for
+    j < n_seq, and draw j is candidate floor(U_j * n_rows / 2^64).  Equal draws collapse.
+    Returns the distinct candidate indices in ascending order."""
+    G = 0x9E3779B97F4A7C15
+    h = _mix64(seed + G * (1 + ctx_index))
+    picks = {(_mix64(h + G * (1 + j)) * n_rows) >> 64 for j in range(n_seq)} if n_rows > 0 else set()
+    return np.array(sorted(picks), dtype=np.int64)
+
+
 def draft_tree(corpus: np.ndarray, context: np.ndarray, n_max: int = 16, n_min: int = 2,
                max_matches: int = 5000, cont_len: int = 10, max_nodes: int = 64,
-               one_pass: bool = False) -> DraftTree:
+               one_pass: bool = False, random_seqs: int = 0, seed: int = 0, ctx_index: int = 0) -> DraftTree:
     """One context -> draft tree: Algorithm 1, then Algorithm 2 with the
-    candidates inserted in stream-position order, then the layout."""
+    candidates inserted in stream-position order, then the layout.
+    random_seqs > 0: the ablation's strategy instead -- only random_seqs randomly drawn
+    candidates (each already cut to cont_len tokens) go into the Trie."""
     got = retrieve(corpus, context, n_max, n_min, max_matches, cont_len, one_pass)
+    if random_seqs > 0:
+        sel = random_rows(got.rows.shape[0], random_seqs, seed, ctx_index)
+        got = Retrieved(got.matched_len, got.match_count, got.row_pos[sel], got.rows[sel], got.row_len[sel])
     order = np.argsort(got.row_pos, kind="stable").astype(np.int64)
     tree = select_drafts(got.rows, got.row_len, max_nodes, order)
     tree.matched_len = got.matched_len

@@ -388,3 +388,52 @@ def test_index_file_fingerprint_and_round_trip(tmp_path):
     n, tb, sb, fp, back = oracle.read_index_file(p)
     assert (n, tb, sb, fp) == (6, 4, 4, oracle.corpus_fingerprint(corpus))
     np.testing.assert_array_equal(back, sa)
+
+
+def test_random_selection_strategy():
+    """The ablation's draft strategy: a few randomly drawn candidates instead of the whole Trie."""
+    # the generator: published first outputs of splitmix64 seeded with 0 are its finaliser at G and 2G
+    G = 0x9E3779B97F4A7C15
+    assert oracle._mix64(G) == 0xE220A8397B1DCDAF and oracle._mix64(2 * G) == 0x6E789E6AA1B965F4
+    # one candidate: every draw is that candidate; no candidates: nothing
+    np.testing.assert_array_equal(oracle.random_rows(1, 8, 3, 0), [0])
+    assert oracle.random_rows(0, 8, 3, 0).size == 0
+    # draws are in range, at most n_seq, sorted and distinct; contexts and seeds get different draws
+    seen = set()
+    for b in range(200):
+        r = oracle.random_rows(1000, 8, 7, b)
+        assert 1 <= r.size <= 8 and (np.diff(r) > 0).all() and r[0] >= 0 and r[-1] < 1000
+        seen.add(tuple(r))
+    assert len(seen) == 200 and tuple(oracle.random_rows(1000, 8, 8, 0)) not in seen
+    # roughly uniform: 8 * 4000 draws over 10 candidates, each expected 3200 times
+    hist = np.zeros(10)
+    for b in range(4000):
+        G1 = oracle._mix64(11 + G * (1 + b))
+        for j in range(8):
+            hist[(oracle._mix64(G1 + G * (1 + j)) * 10) >> 64] += 1
+    assert (np.abs(hist - 3200) < 5 * np.sqrt(3200)).all()
+    # the tree is the Trie of exactly the drawn candidates: compare with prefix counts of those rows
+    corp = synth.make_corpus(50_000, 2, 40)
+    ctx, lens = synth.make_contexts(corp, 12, 64, 5)
+    some = 0
+    for b in range(12):
+        got = oracle.retrieve(corp.tokens, ctx[b], max_matches=1000, cont_len=8)
+        tree = oracle.draft_tree(corp.tokens, ctx[b], max_matches=1000, cont_len=8, max_nodes=64, random_seqs=8, seed=21,
+                                 ctx_index=b)
+        if got.rows.shape[0] == 0:
+            assert tree.n_nodes == 0
+            continue
+        sel = oracle.random_rows(got.rows.shape[0], 8, 21, b)
+        counts = Counter()
+        for r in sel:
+            for d in range(1, got.row_len[r] + 1):
+                counts[tuple(got.rows[r, :d])] += 1
+        assert tree.n_nodes == len(counts) <= 64
+        for i in range(tree.n_nodes):
+            path, v = [], i
+            while v != -1:
+                path.append(int(tree.draft_tokens[v]))
+                v = int(tree.parent_idx[v])
+            assert counts[tuple(path[::-1])] == tree.node_weight[i]
+        some += tree.n_nodes > 8
+    assert some >= 2
