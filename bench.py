@@ -34,6 +34,9 @@ def main() -> int:
     ap.add_argument("--no-extras", action="store_true", help="skip the per-layer and batched-retrieval side measurements")
     ap.add_argument("--sweep", action="store_true",
                     help="also time tree attention over the tree-size / KV-length sweep (random tries, 32 x 32 heads)")
+    ap.add_argument("--ablation", action="store_true",
+                    help="only run the paper's ablation sweeps (draft strategy, n_max, c) with a toy model on the tiny "
+                         "synthetic datastore and print the mean generated length per step")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device-to-device copy five times (reference for rocprofv3 --pmc byte counters)")
     args = ap.parse_args()
@@ -56,6 +59,9 @@ def main() -> int:
             a.copy_(b)
         torch.cuda.synchronize()
         print(json.dumps({"copy_calibration_bytes_read": 1 << 30, "copy_calibration_bytes_written": 1 << 30}))
+        return 0
+    if args.ablation:
+        print(json.dumps({"ablation": ablation(rest, torch, synth, np, dev)}))
         return 0
     w = synth.WORKLOADS[args.workload]
     n_ctx = 16          # the timed steps rotate over these contexts (half copied from the stream, half i.i.d.)
@@ -283,6 +289,81 @@ def attention_sweep(rest, torch, synth, np, dev):
                          "frac_of_8TB/s": round(alg / us / 1e3 / HBM_PEAK_GBS, 3)})
             del q, k, v, out, ws
     return rows
+
+
+def ablation(rest, torch, synth, np, dev):
+    """The paper's ablations as sweeps on synthetic data: draft strategy (Trie top-c vs at most eight random candidates
+    of eight tokens), n_max and c, each reported as M = mean number of tokens generated per verification step
+    (accepted draft tokens + 1).  The "model" is a deterministic toy, a 4-gram model of the datastore with back-off
+    (most frequent continuation), so drafts hit often but not always, and suffixes longer than its order cannot
+    help.  Retrieval and acceptance run on the GPU through the library, the toy model on the host."""
+    w = synth.WORKLOADS["tiny"]
+    corp = synth.make_corpus(w.n_tokens, w.corpus_seed, w.n_motifs)
+    tok = corp.tokens.astype(np.int64)
+    V = 32000
+    tables = {}
+    for order in (4, 3, 2):                          # most frequent next token after each `order`-gram of the datastore
+        key = np.zeros(tok.size - order, dtype=np.int64)
+        for j in range(order):
+            key = key * V + tok[j:tok.size - order + j]
+        nxt = tok[order:]
+        idx = np.lexsort((nxt, key))
+        key, nxt = key[idx], nxt[idx]
+        run_start = np.flatnonzero(np.r_[True, (key[1:] != key[:-1]) | (nxt[1:] != nxt[:-1])])
+        run_len = np.diff(np.r_[run_start, key.size])
+        rk, rn = key[run_start], nxt[run_start]
+        best = np.lexsort((rn, -run_len, rk))         # per key: longest run first, smaller token on ties
+        first = np.r_[True, rk[best][1:] != rk[best][:-1]]
+        tables[order] = dict(zip(rk[best][first].tolist(), rn[best][first].tolist()))
+
+    def model(last4):
+        """next token given the last four tokens: the datastore's most frequent continuation of the longest of its
+        4-, 3-, 2-gram suffixes that occurs there, else a hash"""
+        for order in (4, 3, 2):
+            kk = 0
+            for t in last4[4 - order:]:
+                kk = kk * V + t
+            hit = tables[order].get(kk)
+            if hit is not None:
+                return hit
+        return (last4[-2] * 31 + last4[-1] * 17 + 7) % V
+
+    index = rest.rest_build_index(torch.from_numpy(corp.tokens).to(dev), 4)
+    prompts = [corp.tokens[s:s + 48].astype(np.int32) for s in (1000, 250_000, 500_000, 750_000)]
+
+    def run(n_max, c, random_seqs, cont_len, n_new=160):
+        gen, steps = 0, 0
+        for pi, prompt in enumerate(prompts):
+            seq = [int(x) for x in prompt]
+            made = 0
+            while made < n_new:
+                ctx = torch.tensor([seq[-64:]], dtype=torch.int32, device=dev)
+                ln = torch.tensor([ctx.shape[1]], dtype=torch.int32, device=dev)
+                tree = rest.rest_retrieve(index, ctx, ln, n_max=n_max, n_min=min(2, n_max), max_matches=w.max_matches,
+                                          cont_len=cont_len, max_nodes=c, random_seqs=random_seqs, seed=1000 * pi + steps)
+                n = int(tree.n_nodes[0])
+                t_tok = tree.draft_tokens[0, :n].cpu().tolist()
+                t_par = tree.parent_idx[0, :n].cpu().tolist()
+                ids = np.zeros((1, 1 + c), dtype=np.int32)
+                ids[0, 0] = model(seq[-4:])
+                paths = []
+                for i in range(n):           # the model's token after node i: a function of the last four tokens there
+                    path = (paths[t_par[i]] if t_par[i] >= 0 else seq[-4:]) + [t_tok[i]]
+                    paths.append(path[-4:])
+                    ids[0, 1 + i] = model(paths[i])
+                alen, apath, nxt = rest.rest_accept(torch.from_numpy(ids).to(dev), tree, cont_len)
+                a = int(alen[0])
+                seq += [t_tok[j] for j in apath[0, :a].cpu().tolist()] + [int(nxt[0])]
+                made += a + 1
+                gen += a + 1
+                steps += 1
+        return round(gen / steps, 3)
+
+    res = {"datastore_tokens": w.n_tokens, "prompts": len(prompts), "tokens_per_prompt": 160,
+           "M_trie_c64_nmax16": run(16, 64, 0, 10), "M_random_8x8_nmax16": run(16, 64, 8, 8),
+           "M_by_n_max_trie_c64": {n: run(n, 64, 0, 10) for n in (2, 4, 8, 16)},
+           "M_by_c_trie_nmax16": {c: run(16, c, 0, 10) for c in (4, 16, 64, 256)}}
+    return res
 
 
 def cpu_baseline(np, torch, corp, ctx_np, w, q, k, v, out, trees, ids, P, scale, step):

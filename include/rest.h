@@ -142,6 +142,15 @@ typedef struct {
     int32_t max_matches;  /* K, 1..REST_MAX_MATCHES */
     int32_t cont_len;     /* m, 1..REST_MAX_CONT_LEN (paper: 10) */
     int32_t max_nodes;    /* c, 1..REST_MAX_NODES (paper: 64) */
+    /* The draft strategy the paper compares the Trie with ("Effect of draft token selecting
+     * strategies": at most eight randomly sampled candidates, each cut to eight tokens).
+     * random_seqs == 0: the Trie over all kept candidates (steps 2-3 above).  random_seqs in
+     * 1..64: step 3 runs on random_seqs candidates drawn from the kept ones instead (cont_len is the
+     * cut).  Draw j of context b is candidate floor(U_j * R / 2^64), R = number of kept candidates,
+     * U_j = mix(mix(seed + G*(1 + b)) + G*(1 + j)), G = 0x9E3779B97F4A7C15, mix = the splitmix64
+     * finaliser; equal draws collapse. */
+    int32_t random_seqs;
+    uint64_t seed;
 } rest_retrieve_params;
 
 typedef struct {

@@ -49,6 +49,8 @@ struct RetrieveParams {
     const int32_t* ctx_len;
     int32_t ctx_stride;
     int32_t n_max, n_min, K, m, c, mask_words;
+    int32_t random_seqs;  // 0, or the number of randomly drawn candidates that replace the kept ones
+    uint64_t seed;
     rest_tree out;
     // LDS layout of phase B (byte offsets into dynamic LDS)
     int32_t words;        // bitmap words per depth = K/64 + 1
@@ -276,7 +278,42 @@ __global__ __launch_bounds__(kThreads) void retrieve_kernel(RetrieveParams p) {
     }
     const int n_star = p.n_max - sel;
     const uint32_t lo = s_lo[sel], hi = s_hi[sel];
-    const int R = (int)((hi - lo) < (uint32_t)p.K ? (hi - lo) : (uint32_t)p.K);
+    int R = (int)((hi - lo) < (uint32_t)p.K ? (hi - lo) : (uint32_t)p.K);
+
+    // Random-selection strategy of the ablation: a few drawn candidates take the place of the R kept ones.  Row r of
+    // phase B is then kept candidate s_pick[r]; the drawn candidates are sorted, so rows stay in suffix order.
+    __shared__ int32_t s_pick[64];
+    __shared__ int32_t s_npick;
+    const bool drawn = p.random_seqs > 0;
+    if (drawn) {
+        if (wave == 0) {
+            const uint64_t G = 0x9E3779B97F4A7C15ull;
+            auto mix = [](uint64_t z) {
+                z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+                z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+                return z ^ (z >> 31);
+            };
+            const uint64_t h = mix(p.seed + G * (uint64_t)(1 + b));
+            const bool active = lane < p.random_seqs;
+            const uint32_t r = active ? (uint32_t)__umul64hi(mix(h + G * (uint64_t)(1 + lane)), (uint64_t)R) : 0xffffffffu;
+            bool first = active;          // no lower lane drew the same candidate
+            for (int k = 0; k < 64; k++) {
+                const uint32_t o = __shfl(r, k, 64);
+                if (k < lane && o == r) first = false;
+            }
+            int rank = 0;                 // distinct candidates below mine
+            for (int k = 0; k < 64; k++) {
+                const uint32_t o = __shfl(r, k, 64);
+                const int of = __shfl((int)first, k, 64);
+                if (of && o < r) rank++;
+            }
+            if (first) s_pick[rank] = (int32_t)r;
+            const int n_first = __popcll(__ballot(first));
+            if (lane == 0) s_npick = n_first;
+        }
+        __syncthreads();
+        R = s_npick;
+    }
     const int m = p.m;
     const int words = p.words;
 
@@ -303,7 +340,7 @@ __global__ __launch_bounds__(kThreads) void retrieve_kernel(RetrieveParams p) {
         int32_t tok[REST_MAX_CONT_LEN];
         int len = 0;
         if (r < R) {
-            const uint32_t start = load_sa<SaT>(p.sa, lo + r);
+            const uint32_t start = load_sa<SaT>(p.sa, lo + (drawn ? (uint32_t)s_pick[r] : (uint32_t)r));
             rowpos[r] = start;
             const uint64_t pos = (uint64_t)start + n_star;
             const uint64_t left = p.n_tokens > pos ? p.n_tokens - pos : 0;
@@ -325,7 +362,7 @@ __global__ __launch_bounds__(kThreads) void retrieve_kernel(RetrieveParams p) {
         bool run = true;
         uint64_t ppos = 0;
         if (lane == 0 && r > 0 && r < R) {
-            ppos = (uint64_t)load_sa<SaT>(p.sa, lo + r - 1) + n_star;
+            ppos = (uint64_t)load_sa<SaT>(p.sa, lo + (drawn ? (uint32_t)s_pick[r - 1] : (uint32_t)(r - 1))) + n_star;
             const uint64_t left = p.n_tokens > ppos ? p.n_tokens - ppos : 0;
             plen = left < (uint64_t)m ? (int)left : m;
         }
@@ -560,6 +597,7 @@ bool params_ok(const rest_retrieve_params* q) {
     if (q->max_matches < 1 || q->max_matches > REST_MAX_MATCHES) return false;
     if (q->cont_len < 1 || q->cont_len > REST_MAX_CONT_LEN) return false;
     if (q->max_nodes < 1 || q->max_nodes > REST_MAX_NODES) return false;
+    if (q->random_seqs < 0 || q->random_seqs > 64) return false;
     return true;
 }
 
@@ -640,6 +678,8 @@ extern "C" __attribute__((visibility("default"))) rest_status rest_retrieve(cons
     p.ctx_stride = ctx_stride;
     p.n_max = q->n_max; p.n_min = q->n_min; p.K = q->max_matches; p.m = q->cont_len; p.c = q->max_nodes;
     p.mask_words = (q->max_nodes + 63) / 64;
+    p.random_seqs = q->random_seqs;
+    p.seed = q->seed;
     p.out = *out;
     p.words = p.K / 64 + 1;
     size_t off = 0;

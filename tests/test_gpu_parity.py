@@ -281,6 +281,29 @@ def test_grouped_query_attention_as_a_view(dtype, Hkv, g, T, P, per_batch):
                 assert np.abs(got[nb, h] - want).max() / np.abs(want).max() <= 1e-3
 
 
+@pytest.mark.parametrize("n_seq,m,c,seed", [(8, 8, 64, 1), (8, 8, 16, 2), (3, 5, 64, 3), (64, 10, 256, 4), (1, 16, 64, 5)])
+def test_random_selection_strategy_matches_oracle(n_seq, m, c, seed):
+    corp = synth.make_corpus(200_000, 6, 60)
+    ctx, lens = synth.make_contexts(corp, 24, 64, 17)
+    index = rest.rest_build_index(dev(corp.tokens), 4)
+    out = rest.rest_retrieve(index, dev(ctx), dev(lens), max_matches=700, cont_len=m, max_nodes=c, random_seqs=n_seq,
+                             seed=seed)
+    torch.cuda.synchronize()
+    words = (c + 63) // 64
+    rich = 0
+    for b in range(24):
+        want = oracle.draft_tree(corp.tokens, ctx[b], 16, 2, 700, m, c, random_seqs=n_seq, seed=seed, ctx_index=b)
+        assert (int(out.matched_len[b]), int(out.match_count[b]), int(out.n_nodes[b])) == \
+            (want.matched_len, want.match_count, want.n_nodes), b
+        np.testing.assert_array_equal(out.draft_tokens[b].cpu().numpy(), want.draft_tokens)
+        np.testing.assert_array_equal(out.parent_idx[b].cpu().numpy(), want.parent_idx)
+        np.testing.assert_array_equal(out.pos_ids[b].cpu().numpy(), want.pos_ids)
+        np.testing.assert_array_equal(out.node_weight[b].cpu().numpy(), want.node_weight)
+        np.testing.assert_array_equal(out.tree_mask[b].cpu().numpy().view(np.uint64).reshape(c, words), want.tree_mask)
+        rich += want.n_nodes > m
+    assert rich >= 3 or n_seq == 1
+
+
 def test_index_file_round_trip_and_exchange_with_the_oracle(tmp_path):
     corp = synth.make_corpus(300_000, 4, 30)
     d_corpus = dev(corp.tokens)
