@@ -54,7 +54,7 @@ struct RetrieveParams {
     rest_tree out;
     // LDS layout of phase B (byte offsets into dynamic LDS)
     int32_t words;        // bitmap words per depth = K/64 + 1
-    int32_t off_seg, off_lcp, off_len, off_hist, off_part, off_sel, off_pos, off_misc;
+    int32_t off_seg, off_lcp, off_len, off_hist, off_part, off_sel, off_pos, off_after, off_misc;
 };
 
 template <typename TokT>
@@ -203,12 +203,12 @@ __device__ void wave_search(const RetrieveParams& p, const int32_t* lds_tab, con
     out_hi = hi.a > lo.a ? hi.a : lo.a;
 }
 
-// position of the lowest set bit at or after bit index `from` in a bitmap that is known to contain one
-__device__ inline int next_set(const uint64_t* bm, int from) {
-    int w = from >> 6;
-    uint64_t x = bm[w] & (~0ull << (from & 63));
-    while (x == 0) x = bm[++w];
-    return (w << 6) + __builtin_ctzll(x);
+// Weight of the Trie node that starts at row r = 64 wi + lane of a depth's segment-start bitmap: the distance to
+// the next set bit, which lies in the same word or, for the last node of a word, at after[wi] (the first set bit of
+// any later word, tabulated once per depth).
+__device__ inline int node_weight(uint64_t word, int lane, int r, int32_t after) {
+    const uint64_t later = lane < 63 ? word & (~0ull << (lane + 1)) : 0ull;
+    return later ? __builtin_ctzll(later) - lane : after - r;
 }
 
 // position of the highest set bit at or before `from` (bit 0 is always set)
@@ -329,6 +329,7 @@ __global__ __launch_bounds__(kThreads) void retrieve_kernel(RetrieveParams p) {
     uint32_t* srt_wgt = srt_key + REST_MAX_NODES;        // [c]
     int32_t* srt_par = (int32_t*)(srt_wgt + REST_MAX_NODES);  // [c]
     uint32_t* rowpos = (uint32_t*)(lds + p.off_pos);     // [K] suffix-array entry of each kept row
+    int32_t* after = (int32_t*)(lds + p.off_after);      // [m][words] first set bit of seg[d] in any word after this one
 
     for (int i = tid; i <= p.K; i += kThreads) hist[i] = 0;
     if (tid < 16) s_misc[tid] = 0;
@@ -384,15 +385,34 @@ __global__ __launch_bounds__(kThreads) void retrieve_kernel(RetrieveParams p) {
     }
     __syncthreads();
 
+    // ---- B1b: per depth, where the next segment starts after each word (one wavefront per depth, words 64 at a
+    // time from the top; the terminator bits guarantee a set bit in the last word)
+    for (int d = wave; d < m; d += kWavesPerWG) {
+        const uint64_t* bm = seg + d * words;
+        int32_t carry = row_words * 64;                        // nothing after the last word
+        for (int base = ((row_words - 1) / 64) * 64; base >= 0; base -= 64) {
+            const int wi = base + lane;
+            const uint64_t x = wi < row_words ? bm[wi] : 0ull;
+            const uint64_t nz = __ballot(x != 0ull);
+            const int first_here = x ? wi * 64 + __builtin_ctzll(x) : 0;
+            const uint64_t above = lane < 63 ? nz & (~0ull << (lane + 1)) : 0ull;
+            const int src = above ? __builtin_ctzll(above) : 0;
+            const int from_lane = __shfl(first_here, src, 64);
+            if (wi < row_words) after[d * words + wi] = above ? from_lane : carry;
+            if (nz) carry = __shfl(first_here, __builtin_ctzll(nz), 64);
+        }
+    }
+    __syncthreads();
+
     // ---- B2: weight histogram over all Trie nodes (node (d, r): segment start at depth d with len >= d)
     const int items = m * row_words;   // one item = (depth, 64-row word)
-    for (int it = wave; it < items; it += kWavesPerWG) {
-        const int d = it / row_words + 1, wi = it % row_words;
+    // items (depth, word) are dealt to the wavefronts round robin; (d, wi) advance without divisions
+    for (int it = wave, d = 1, wi = wave; it < items; it += kWavesPerWG, wi += kWavesPerWG) {
+        while (wi >= row_words) { wi -= row_words; d++; }
         const int r = wi * 64 + lane;
         const uint64_t* bm = seg + (d - 1) * words;
         const bool node = r < R && ((bm[wi] >> lane) & 1ull) && rlen[r] >= d;
-        int w = 0;
-        if (node) w = next_set(bm, r + 1) - r;
+        const int w = node ? node_weight(bm[wi], lane, r, after[(d - 1) * words + wi]) : 0;
         const uint64_t ones = __ballot(node && w == 1);
         if (lane == 0 && ones) atomicAdd(&hist[1], (uint32_t)popc64(ones));
         if (node && w > 1) atomicAdd(&hist[w], 1u);
@@ -440,12 +460,13 @@ __global__ __launch_bounds__(kThreads) void retrieve_kernel(RetrieveParams p) {
     if (tid <= m) dcount[tid] = 0;
     __syncthreads();
     if (!take_all) {
-        for (int it = wave; it < items; it += kWavesPerWG) {
-            const int d = it / row_words + 1, wi = it % row_words;
+        // items (depth, word) are dealt to the wavefronts round robin; (d, wi) advance without divisions
+        for (int it = wave, d = 1, wi = wave; it < items; it += kWavesPerWG, wi += kWavesPerWG) {
+            while (wi >= row_words) { wi -= row_words; d++; }
             const int r = wi * 64 + lane;
             const uint64_t* bm = seg + (d - 1) * words;
             const bool node = r < R && ((bm[wi] >> lane) & 1ull) && rlen[r] >= d;
-            const bool eq = node && (next_set(bm, r + 1) - r) == w_star;
+            const bool eq = node && node_weight(bm[wi], lane, r, after[(d - 1) * words + wi]) == w_star;
             const uint64_t e = __ballot(eq);
             if (lane == 0 && e) atomicAdd(&dcount[d], (uint32_t)popc64(e));
         }
@@ -473,7 +494,7 @@ __global__ __launch_bounds__(kThreads) void retrieve_kernel(RetrieveParams p) {
         for (int wi = wave; wi < row_words; wi += kWavesPerWG) {
             const int r = wi * 64 + lane;
             const bool node = r < R && ((bm[wi] >> lane) & 1ull) && rlen[r] >= d_star;
-            const bool eq = node && (next_set(bm, r + 1) - r) == w_star;
+            const bool eq = node && node_weight(bm[wi], lane, r, after[(d_star - 1) * words + wi]) == w_star;
             const uint64_t e = __ballot(eq);
             if (lane == 0) wpre[wi] = (uint32_t)popc64(e);
         }
@@ -496,13 +517,13 @@ __global__ __launch_bounds__(kThreads) void retrieve_kernel(RetrieveParams p) {
     __syncthreads();
 
     // ---- B6: select
-    for (int it = wave; it < items; it += kWavesPerWG) {
-        const int d = it / row_words + 1, wi = it % row_words;
+    // items (depth, word) are dealt to the wavefronts round robin; (d, wi) advance without divisions
+    for (int it = wave, d = 1, wi = wave; it < items; it += kWavesPerWG, wi += kWavesPerWG) {
+        while (wi >= row_words) { wi -= row_words; d++; }
         const int r = wi * 64 + lane;
         const uint64_t* bm = seg + (d - 1) * words;
         const bool node = r < R && ((bm[wi] >> lane) & 1ull) && rlen[r] >= d;
-        int w = 0;
-        if (node) w = next_set(bm, r + 1) - r;
+        const int w = node ? node_weight(bm[wi], lane, r, after[(d - 1) * words + wi]) : 0;
         bool keep = node && (take_all || w > w_star || (w == w_star && d < d_star));
         if (!take_all && d == d_star) {
             const uint64_t e = __ballot(node && w == w_star);
@@ -690,6 +711,7 @@ extern "C" __attribute__((visibility("default"))) rest_status rest_retrieve(cons
     p.off_part = (int32_t)off; off = align16(off + (size_t)(128 + p.words + 64) * 4);
     p.off_sel = (int32_t)off;  off = align16(off + (size_t)REST_MAX_NODES * 5 * 4);
     p.off_pos = (int32_t)off;  off = align16(off + (size_t)p.K * 4);
+    p.off_after = (int32_t)off; off = align16(off + (size_t)p.m * p.words * 4);
     p.off_misc = (int32_t)off;
     size_t lds_bytes = off;
     const size_t top_bytes = (size_t)table_words(index->top_count) * 4;
