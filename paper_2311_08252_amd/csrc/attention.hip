@@ -3,17 +3,18 @@
 // its ancestors only.
 //
 // bf16 kernel design (HBM-bound: ~T flop per KV byte, far below the chip's balance point):
-//  * the work is the flat sequence of 32-key blocks of all (batch, head, query-group) units; it is cut into
-//    equal contiguous spans, one per wavefront (stream-K style).  A wavefront is a fully independent stream
-//    for up to 64 queries: no workgroup barrier anywhere.  A span that covers a whole unit writes the final
-//    output; the at most two partially covered units at its ends leave (reference, sum, O) partials that a
-//    small second kernel merges;
+//  * a unit is one (batch, head, group of 64 queries); its keys are cut into blocks of 32.  W streams share the
+//    work, a stream being a workgroup of two wavefronts (wavefront w owns queries 32w .. 32w+31 of the unit).
+//    Stream s first takes whole units s, s + W, ... and writes their output directly; the blocks of the units
+//    that are left over (fewer than W) are cut into equal contiguous spans, one per stream (stream-K), so every
+//    stream gets the same number of blocks whatever the number of units.  Only a span that starts or ends inside
+//    a unit leaves an fp32 partial (reference, sum, O), and a small second kernel merges those;
 //  * a block's K and V (8 KB each) are fetched with coalesced 16-byte non-temporal loads one block ahead of the
-//    arithmetic, wait in registers while in flight, and are then parked in a wave-private LDS tile; the XOR
+//    arithmetic -- each wavefront fetches half of the tile --, wait in registers while in flight, and are then
+//    parked in one of two LDS tiles shared by the two wavefronts (one workgroup barrier per block); the XOR
 //    swizzle that keeps the LDS reads conflict free is applied by choosing which 16-byte piece of a row each
 //    lane fetches, so the parking stores are plain lane-linear 16-byte writes;
-//  * the query rows sit in wave-private LDS as well (same swizzle) and are re-read as MFMA B operands per block,
-//    which keeps the register file for the O accumulators and the in-flight K/V;
+//  * the query fragments stay in registers for a whole unit;
 //  * S^T = K Q^T and O^T += V^T P^T run on v_mfma_f32_32x32x16_bf16.  With keys on the MFMA row axis a
 //    lane owns one query column, so the softmax statistics are per lane; V^T fragments come out of LDS
 //    through ds_read_b64_tr_b16; the probabilities go from the S accumulator straight into the B
@@ -21,7 +22,7 @@
 //  * the softmax reference is only moved when a block's maximum exceeds it by more than 2^8, so the O
 //    accumulators are rescaled a handful of times per unit instead of once per block (the result does not
 //    depend on the reference);
-//  * tree-mask bit rows are held in wave-private LDS and only consulted for blocks that reach past the prefix.
+//  * tree-mask bit rows are held in LDS and only consulted for blocks that reach past the prefix.
 #include "common.h"
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -53,7 +54,10 @@ struct AttnParams {
     int32_t mask_rows;   // rows of one mask: query row i uses mask row i % mask_rows
     int32_t nblk;     // ceil(Lk / 32)
     int32_t units;    // Nb * H * qgroups
-    int32_t n_streams;  // W: wavefronts that share the work
+    int32_t n_streams;  // W: streams (workgroups) that share the work
+    // Work of stream w: whole units w, w + W, ... (dp_rounds of them), then its span of the tail, i.e. of the
+    // blocks of the last tail_units units, which are cut into tail_streams contiguous spans (stream-K).
+    int32_t dp_rounds, tail_units, tail_streams;
     float c;          // scale * log2(e)
     int64_t qs[3], ks[3], vs[3], os[3];
 };
@@ -80,10 +84,64 @@ __global__ __launch_bounds__(128, 2) void tree_attn_bf16_kernel(AttnParams p) {
     const int col = lane & 31;     // MFMA column = query within this wave's 32-query tile
     const int lrow = lane >> 4, lpc = lane & 15;
 
-    const int64_t total = (int64_t)p.units * p.nblk;
     const int gw = blockIdx.x;     // stream index
-    const int64_t g_begin = span_begin(total, p.n_streams, gw), g_end = span_begin(total, p.n_streams, gw + 1);
-    if (g_begin >= g_end) return;
+    // this stream's span [tb, te) of the tail blocks (< 2^31 of them; tail coordinates count from the first tail
+    // unit).  Recomputed where needed rather than kept: the block loop is short of scalar registers.
+    auto tail_span = [&](int& tb, int& te) {
+        const int64_t t_total = (int64_t)p.tail_units * p.nblk;
+        tb = te = 0;
+        if (gw < p.tail_streams) {
+            tb = (int)span_begin(t_total, p.tail_streams, gw);
+            te = (int)span_begin(t_total, p.tail_streams, gw + 1);
+        }
+    };
+    int blocks_left;                                            // blocks still to be requested
+    {
+        int tb, te;
+        tail_span(tb, te);
+        blocks_left = p.dp_rounds * p.nblk + (te - tb);
+    }
+    if (blocks_left == 0) return;
+
+    // The stream's segments, in order: blocks [0, nblk) of units gw, gw + W, ... (dp_rounds of them), then the pieces
+    // of its tail span [tb, te), one per tail unit it touches.  Two cursors walk them, one for the loads and, one
+    // block behind, one for the arithmetic; each is a handful of scalars (kept out of structs so that they stay in
+    // registers: a cursor in scratch memory would tie every step to the outstanding K/V loads).
+#define REST_SEGMENT_FIRST(unit, j, je, round, tail)                                  \
+    do {                                                                              \
+        round = 0;                                                                    \
+        if (p.dp_rounds > 0) {                                                        \
+            tail = false; unit = gw; j = 0; je = p.nblk;                              \
+        } else {                                                                      \
+            tail = true;                                                              \
+            int tb_, te_;                                                             \
+            tail_span(tb_, te_);                                                      \
+            const int ut_ = tb_ / p.nblk;                                             \
+            unit = p.dp_rounds * p.n_streams + ut_; j = tb_ - ut_ * p.nblk;           \
+            const int rest_ = te_ - ut_ * p.nblk;                                     \
+            je = rest_ < p.nblk ? rest_ : p.nblk;                                     \
+        }                                                                             \
+    } while (0)
+    // to the next segment; the caller knows from its block count that there is one
+#define REST_SEGMENT_NEXT(unit, j, je, round, tail)                                   \
+    do {                                                                              \
+        if (!tail && ++round < p.dp_rounds) {                                         \
+            unit += p.n_streams; j = 0;                                               \
+        } else {                                                                      \
+            int tb_, te_;                                                             \
+            tail_span(tb_, te_);                                                      \
+            const int u0_ = p.dp_rounds * p.n_streams;                                \
+            if (!tail) {                                                              \
+                tail = true;                                                          \
+                const int ut_ = tb_ / p.nblk;                                         \
+                unit = u0_ + ut_; j = tb_ - ut_ * p.nblk;                             \
+            } else {                                                                  \
+                unit++; j = 0;                                                        \
+            }                                                                         \
+            const int rest_ = te_ - (unit - u0_) * p.nblk;                            \
+            je = rest_ < p.nblk ? rest_ : p.nblk;                                     \
+        }                                                                             \
+    } while (0)
 
     uint64_t* const my_mask = lds_mask + wave * (32 * 4);
     const int64_t k_row_bytes = p.ks[2] * 2, v_row_bytes = p.vs[2] * 2;
@@ -106,7 +164,9 @@ __global__ __launch_bounds__(128, 2) void tree_attn_bf16_kernel(AttnParams p) {
     };
 
     // ---- load side: a cursor one block ahead of the arithmetic
-    int ld_unit = (int)(g_begin / p.nblk), ld_j = (int)(g_begin % p.nblk);
+    int ld_unit, ld_j, ld_je, ld_round;
+    bool ld_tail;
+    REST_SEGMENT_FIRST(ld_unit, ld_j, ld_je, ld_round, ld_tail);
     const char *ld_kp, *ld_vp;
     unit_bases(ld_unit, ld_kp, ld_vp);
     i32x4 kr[4], vr[4];
@@ -130,10 +190,10 @@ __global__ __launch_bounds__(128, 2) void tree_attn_bf16_kernel(AttnParams p) {
                 vr[i] = __builtin_nontemporal_load((const i32x4*)(ld_vp + row * v_row_bytes + sw_v));
             }
         }
-        if (++ld_j == p.nblk) {
-            ld_j = 0;
-            ld_unit++;
-            if (ld_unit < p.units) unit_bases(ld_unit, ld_kp, ld_vp);
+        blocks_left--;
+        if (++ld_j == ld_je && blocks_left > 0) {
+            REST_SEGMENT_NEXT(ld_unit, ld_j, ld_je, ld_round, ld_tail);
+            unit_bases(ld_unit, ld_kp, ld_vp);
         }
     };
     auto park = [&](unsigned char* tile) {
@@ -151,15 +211,21 @@ __global__ __launch_bounds__(128, 2) void tree_attn_bf16_kernel(AttnParams p) {
     const uint32_t vsw = (uint32_t)vq << 2;                                          // V swizzle of that row
 
     int buf = 0;
-    int64_t g = g_begin;
+    int unit, seg_j, seg_je, seg_round;
+    bool seg_tail;
+    REST_SEGMENT_FIRST(unit, seg_j, seg_je, seg_round, seg_tail);
+    int todo = blocks_left;          // blocks still to be computed
     issue();
-    while (g < g_end) {
-        // ================= one segment: the part of unit `unit` inside this span
-        const int unit = (int)(g / p.nblk);
-        const int64_t unit_begin = (int64_t)unit * p.nblk;
-        const int64_t seg_end = g_end < unit_begin + p.nblk ? g_end : unit_begin + p.nblk;
-        const bool whole = g == unit_begin && seg_end == unit_begin + p.nblk;
-        const bool first_seg = g_begin >= unit_begin;
+    while (true) {
+        // ================= one segment: blocks [seg_j, seg_je) of `unit`
+        const bool whole = seg_j == 0 && seg_je == p.nblk;
+        // a partial segment is the first of this stream's tail span (slot 0) or its last (slot 1)
+        bool first_seg = false;
+        if (seg_tail) {
+            int tb, te;
+            tail_span(tb, te);
+            first_seg = (unit - p.dp_rounds * p.n_streams) * p.nblk + seg_j == tb;
+        }
         const int qg = unit % p.qgroups, slab = unit / p.qgroups;
         const int h = slab % p.H, nb = slab / p.H;
         const int qi = qg * 64 + wave * 32 + col;        // this lane's query row
@@ -184,6 +250,10 @@ __global__ __launch_bounds__(128, 2) void tree_attn_bf16_kernel(AttnParams p) {
                 qf[ks] = z;
             }
         }
+        // The query fragments (and the mask words) must have arrived before the block loop: inside it the only
+        // outstanding vector loads are to be the K/V of the next block, which the arithmetic must not wait for.
+        // s_waitcnt vmcnt(0), other counters untouched.
+        __builtin_amdgcn_s_waitcnt(0x0F70);
 
         f32x16 o[4];
         float m_ref = kNegBig, l_run = 0.f;     // m_ref in log2 units (logit * c)
@@ -192,16 +262,15 @@ __global__ __launch_bounds__(128, 2) void tree_attn_bf16_kernel(AttnParams p) {
 #pragma unroll
             for (int r = 0; r < 16; r++) o[dt][r] = 0.f;
 
-        for (; g < seg_end; g++, buf ^= 1) {
-            // my half of block g moves from the staging registers to tile `buf`, my half of block g+1 (possibly
+        for (int j = seg_j; j < seg_je; j++, buf ^= 1) {
+            // my half of this block moves from the staging registers to tile `buf`, my half of the next one (possibly
             // of the next unit) is requested, and after the barrier the whole tile is visible to both waves.
-            // Tile buf^1 may still be read by the other wave (block g-1); tile `buf` was last read for block
-            // g-2, which both waves finished before the previous barrier.
+            // Tile buf^1 may still be read by the other wave (previous block); tile `buf` was last read two
+            // blocks ago, which both waves finished before the previous barrier.
             unsigned char* tile = lds_tile[buf];
             park(tile);
-            if (g + 1 < g_end) issue();
+            if (blocks_left > 0) issue();
             __syncthreads();
-            const int j = (int)(g - unit_begin);
             const unsigned char* ldsK = tile;
             const unsigned char* ldsV = tile + kTileBytes;
 
@@ -317,55 +386,52 @@ __global__ __launch_bounds__(128, 2) void tree_attn_bf16_kernel(AttnParams p) {
                 }
             }
         }
+        todo -= seg_je - seg_j;
+        if (todo == 0) break;
+        REST_SEGMENT_NEXT(unit, seg_j, seg_je, seg_round, seg_tail);
     }
+#undef REST_SEGMENT_FIRST
+#undef REST_SEGMENT_NEXT
 }
 
-// Merges the partials of every unit that was cut between streams: one 256-thread block per (unit, query);
-// the four wavefronts take every fourth stream (a lane owns two of the 128 output columns), then combine in LDS.
-__global__ __launch_bounds__(256) void tree_attn_streamk_merge_kernel(AttnParams p) {
-    __shared__ float red_m[4], red_l[4];
-    __shared__ float red_o[4][kD];
-    const int unit = blockIdx.x / 64, ql = blockIdx.x % 64;
+// Merges the partials of every tail unit that was cut between streams.  A 256-thread block takes `rows` query rows
+// of one tail unit, a wavefront one row at a time (a lane owns two of the 128 output columns) and walks the
+// streams that hold a piece of the unit.
+__global__ __launch_bounds__(256) void tree_attn_streamk_merge_kernel(AttnParams p, int rows) {
+    const int per_unit = 64 / rows;
+    const int ut = blockIdx.x / per_unit;                   // unit in tail coordinates
+    const int row0 = (blockIdx.x % per_unit) * rows;
+    const int unit = p.dp_rounds * p.n_streams + ut;
     const int qg = unit % p.qgroups, slab = unit / p.qgroups;
-    const int qi = qg * 64 + ql;
-    if (qi >= p.Tq) return;
-    const int64_t total = (int64_t)p.units * p.nblk;
-    const int64_t ub = (int64_t)unit * p.nblk, ue = ub + p.nblk;
-    const int w0 = span_owner(total, p.n_streams, ub), w1 = span_owner(total, p.n_streams, ue - 1);
+    const int64_t t_total = (int64_t)p.tail_units * p.nblk;
+    const int64_t ub = (int64_t)ut * p.nblk, ue = ub + p.nblk;
+    const int w0 = span_owner(t_total, p.tail_streams, ub), w1 = span_owner(t_total, p.tail_streams, ue - 1);
     if (w0 == w1) return;     // one stream covered the whole unit and wrote the output itself
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     // Only the first stream can have started before this unit (its partial sits in slot 1); every later stream
-    // starts inside the unit, so this is its first segment (slot 0).  Streams are never empty (W <= blocks).
-    const int slot0 = span_begin(total, p.n_streams, w0) >= ub ? 0 : 1;
-    float m = kNegBig, l = 0.f, a0 = 0.f, a1 = 0.f;
+    // starts inside the unit, so this is its first segment (slot 0).  Streams are never empty.
+    const int slot0 = span_begin(t_total, p.tail_streams, w0) >= ub ? 0 : 1;
+    const int h = slab % p.H, nb = slab / p.H;
+    for (int ql = row0 + wv; ql < row0 + rows; ql += 4) {
+        const int qi = qg * 64 + ql;
+        if (qi >= p.Tq) break;
+        float m = kNegBig, l = 0.f, a0 = 0.f, a1 = 0.f;
 #pragma unroll 4
-    for (int w = w0 + wv; w <= w1; w += 4) {
-        const int64_t row = ((int64_t)w * 2 + (w == w0 ? slot0 : 0)) * 64 + ql;
-        const float mi = p.ws_ml[row * 2], li = p.ws_ml[row * 2 + 1];
-        const float2 oi = *(const float2*)(p.ws_o + row * kD + 2 * lane);
-        const float m_new = fmaxf(m, mi);
-        const float sa = __builtin_amdgcn_exp2f(m - m_new), sb = __builtin_amdgcn_exp2f(mi - m_new);
-        l = l * sa + li * sb;
-        a0 = a0 * sa + oi.x * sb;
-        a1 = a1 * sa + oi.y * sb;
-        m = m_new;
-    }
-    if (lane == 0) { red_m[wv] = m; red_l[wv] = l; }
-    red_o[wv][2 * lane] = a0;
-    red_o[wv][2 * lane + 1] = a1;
-    __syncthreads();
-    if (threadIdx.x < kD) {
-        const int d = threadIdx.x;
-        float mm = fmaxf(fmaxf(red_m[0], red_m[1]), fmaxf(red_m[2], red_m[3]));
-        float ll = 0.f, acc = 0.f;
-#pragma unroll
-        for (int i = 0; i < 4; i++) {
-            const float sc = __builtin_amdgcn_exp2f(red_m[i] - mm);
-            ll += red_l[i] * sc;
-            acc += red_o[i][d] * sc;
+        for (int w = w0; w <= w1; w++) {
+            const int64_t row = ((int64_t)w * 2 + (w == w0 ? slot0 : 0)) * 64 + ql;
+            const float mi = p.ws_ml[row * 2], li = p.ws_ml[row * 2 + 1];
+            const float2 oi = *(const float2*)(p.ws_o + row * kD + 2 * lane);
+            const float m_new = fmaxf(m, mi);
+            const float sa = __builtin_amdgcn_exp2f(m - m_new), sb = __builtin_amdgcn_exp2f(mi - m_new);
+            l = l * sa + li * sb;
+            a0 = a0 * sa + oi.x * sb;
+            a1 = a1 * sa + oi.y * sb;
+            m = m_new;
         }
-        const int h = slab % p.H, nb = slab / p.H;
-        p.out[nb * p.os[0] + h * p.os[1] + qi * p.os[2] + d] = (__bf16)(ll > 0.f ? acc / ll : 0.f);
+        typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+        const float inv = l > 0.f ? 1.0f / l : 0.f;
+        const bf16x2 o2 = {(__bf16)(a0 * inv), (__bf16)(a1 * inv)};
+        *(bf16x2*)(p.out + nb * p.os[0] + h * p.os[1] + qi * p.os[2] + 2 * lane) = o2;
     }
 }
 
@@ -467,6 +533,7 @@ __global__ __launch_bounds__(128) void tree_attn_f32_merge_kernel(const float* w
 // ---------------------------------------------------------------------------------------------------------
 struct Plan {
     int qt, qgroups, nblk, units, n_streams, nsplit_f32;
+    int dp_rounds, tail_units, tail_streams, merge_rows;
     bool need_merge;
 };
 
@@ -494,11 +561,23 @@ Plan make_plan(const rest_attn_desc* d) {
     if (w > total) w = total;
     if (w < 1) w = 1;
     pl.n_streams = (int)w;
+    // every stream takes dp_rounds whole units; the blocks of the units left over are cut into spans
+    pl.dp_rounds = pl.units / pl.n_streams;
+    pl.tail_units = pl.units - pl.dp_rounds * pl.n_streams;
+    const int64_t t_total = (int64_t)pl.tail_units * pl.nblk;
+    int64_t ts = d->num_splits > 0 ? w : t_total / 4;      // at least four blocks per tail span
+    if (ts > w) ts = w;
+    if (ts > t_total) ts = t_total;
+    if (ts < 1 && t_total > 0) ts = 1;
+    pl.tail_streams = (int)ts;
     pl.need_merge = false;
-    for (int u = 0; u < pl.units && !pl.need_merge; u++) {
+    for (int u = 0; u < pl.tail_units && !pl.need_merge; u++) {
         const int64_t ub = (int64_t)u * pl.nblk;
-        if (span_owner(total, pl.n_streams, ub) != span_owner(total, pl.n_streams, ub + pl.nblk - 1)) pl.need_merge = true;
+        if (span_owner(t_total, pl.tail_streams, ub) != span_owner(t_total, pl.tail_streams, ub + pl.nblk - 1)) pl.need_merge = true;
     }
+    // rows of a unit per merge block: about a thousand blocks in all, a multiple of the four wavefronts
+    pl.merge_rows = 64;
+    while (pl.merge_rows > 4 && (int64_t)pl.tail_units * (64 / pl.merge_rows) < 1024) pl.merge_rows /= 2;
     return pl;
 }
 
@@ -511,6 +590,8 @@ bool desc_ok(const rest_attn_desc* d) {
     if (d->num_splits < 0 || d->num_splits > 64) return false;
     if (d->mask_rows < 0 || d->mask_rows > d->Tq) return false;
     if ((int64_t)d->Nb * d->H * 64 > 0x7fffffff) return false;
+    // block counts are kept in 32 bits
+    if (((int64_t)d->Nb * d->H * ((d->Tq + 63) / 64) + 1) * ((d->P + d->Tk + kBlk - 1) / kBlk) > 0x7fffffff) return false;
     for (int i = 0; i < 3; i++)
         if (d->q_stride[i] < 0 || d->k_stride[i] < 0 || d->v_stride[i] < 0 || d->o_stride[i] < 0) return false;
     // rows are read with 16-byte vector loads
@@ -533,7 +614,7 @@ extern "C" __attribute__((visibility("default"))) size_t rest_tree_attention_wor
         return (size_t)d->Nb * d->H * pl.nsplit_f32 * d->Tq * (kD + 2) * sizeof(float);
     }
     if (!pl.need_merge) return 0;
-    return (size_t)pl.n_streams * 2 * (pl.qt * 32) * (kD + 2) * sizeof(float);
+    return (size_t)pl.tail_streams * 2 * (pl.qt * 32) * (kD + 2) * sizeof(float);
 }
 
 extern "C" __attribute__((visibility("default"))) rest_status rest_tree_attention(const void* d_q, const void* d_k, const void* d_v, const uint64_t* d_mask,
@@ -568,12 +649,16 @@ extern "C" __attribute__((visibility("default"))) rest_status rest_tree_attentio
         p.qgroups = pl.qgroups;
         p.units = pl.units;
         p.n_streams = pl.n_streams;
-        const size_t rows = (size_t)pl.n_streams * 2 * (pl.qt * 32);
+        p.dp_rounds = pl.dp_rounds;
+        p.tail_units = pl.tail_units;
+        p.tail_streams = pl.tail_streams;
+        const size_t rows = (size_t)pl.tail_streams * 2 * (pl.qt * 32);
         p.ws_ml = p.ws_o ? p.ws_o + rows * kD : nullptr;
         hipLaunchKernelGGL(tree_attn_bf16_kernel, dim3(pl.n_streams), dim3(128), 0, stream, p);
         REST_HIP_TRY(hipGetLastError());
         if (pl.need_merge) {
-            hipLaunchKernelGGL(tree_attn_streamk_merge_kernel, dim3(pl.units * 64), dim3(256), 0, stream, p);
+            hipLaunchKernelGGL(tree_attn_streamk_merge_kernel, dim3(pl.tail_units * (64 / pl.merge_rows)), dim3(256), 0, stream, p,
+                               pl.merge_rows);
             REST_HIP_TRY(hipGetLastError());
         }
     } else {
