@@ -36,10 +36,10 @@ namespace {
 
 constexpr int kD = 128;            // head dim
 constexpr int kBlk = 32;           // keys per block
-constexpr int kTileBytes = kBlk * kD * 2;   // 8 KB: one K or V block in bf16
+constexpr int kSubBytes = kBlk * kD * 2;    // 8 KB: K or V of one 32-key block in bf16
 constexpr float kNegBig = -1.0e30f;
 constexpr float kLazy = 8.0f;      // log2 units the running maximum may exceed the softmax reference
-constexpr int kMaxWaves = 1024;    // default number of streams: four two-wave streams on each of 256 CUs
+constexpr int kMaxWaves = 2048;    // wavefronts in flight: eight on each of 256 compute units
 
 struct AttnParams {
     const __bf16* q;
@@ -52,7 +52,7 @@ struct AttnParams {
     int32_t Nb, H, Tq, Tk, P, Lk;
     int32_t nsplit, qgroups, mask_words, mask_per_batch;
     int32_t mask_rows;   // rows of one mask: query row i uses mask row i % mask_rows
-    int32_t nblk;     // ceil(Lk / 32)
+    int32_t nblk;     // tiles per unit: ceil(Lk / (16 * wavefronts per stream))
     int32_t units;    // Nb * H * qgroups
     int32_t n_streams;  // W: streams (workgroups) that share the work
     // Work of stream w: whole units w, w + W, ... (dp_rounds of them), then its span of the tail, i.e. of the
@@ -71,12 +71,17 @@ __host__ __device__ inline int32_t span_owner(int64_t total, int32_t n, int64_t 
     return (int32_t)(((b + 1) * n - 1) / total);
 }
 
-// One stream = one workgroup of two wavefronts.  Both see the same K/V tile in LDS (each loads half of it);
-// wavefront w owns queries [32w, 32w+32) of the unit's 64.  Four streams fit a compute unit (2 waves per SIMD),
-// so one wave's MFMA, exponentials, LDS latency and load waits overlap the other's.
-__global__ __launch_bounds__(128, 2) void tree_attn_bf16_kernel(AttnParams p) {
-    __shared__ __attribute__((aligned(1024))) unsigned char lds_tile[2][2 * kTileBytes];   // [buffer][K | V], 32 KB
-    __shared__ uint64_t lds_mask[64 * 4];                                                   // 64 query rows x 4 words
+// One stream = one workgroup of NW wavefronts (2, 4 or 8) for a unit of 32 NW queries: wavefront w owns queries
+// [32w, 32w+32).  All see the same K/V tile in LDS, NW/2 blocks = 16 NW keys long, of which each wavefront fetches
+// its 1/NW: eight 16-byte pieces per lane and tile whatever NW is, so the bytes in flight per compute unit (eight
+// wavefronts: 2 per SIMD) do not depend on the number of queries, and every K/V byte is read once per unit.
+template <int NW>
+__global__ __launch_bounds__(64 * NW, 2) void tree_attn_bf16_kernel(AttnParams p) {
+    constexpr int kSub = NW / 2;                       // 32-key blocks per tile
+    constexpr int kTileKeys = kSub * kBlk;
+    constexpr int kTileBytes = kSub * kSubBytes;       // K (or V) part of a tile
+    __shared__ __attribute__((aligned(1024))) unsigned char lds_tile[2][2 * kTileBytes];   // [buffer][K | V]
+    __shared__ uint64_t lds_mask[NW * 32 * 4];                                              // query rows x 4 words
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -145,7 +150,6 @@ __global__ __launch_bounds__(128, 2) void tree_attn_bf16_kernel(AttnParams p) {
 
     uint64_t* const my_mask = lds_mask + wave * (32 * 4);
     const int64_t k_row_bytes = p.ks[2] * 2, v_row_bytes = p.vs[2] * 2;
-    const int plain_end = p.P / kBlk;   // blocks below this hold prefix keys only
 
     // Global -> registers -> LDS.  Chunk i of a tile is 4 rows x 256 B = 64 lanes x 16 B and is parked at
     // tile + i*1024 + lane*16, i.e. row i*4 + (lane >> 4), piece slot lane & 15.  The slot holds row piece
@@ -172,18 +176,18 @@ __global__ __launch_bounds__(128, 2) void tree_attn_bf16_kernel(AttnParams p) {
     i32x4 kr[4], vr[4];
     auto issue = [&]() {
         const int j = ld_j;
-        if ((j + 1) * kBlk <= p.Lk) {
+        if ((j + 1) * kTileKeys <= p.Lk) {
 #pragma unroll
             for (int i = 0; i < 4; i++) {
-                const int64_t row = (int64_t)j * kBlk + (4 * wave + i) * 4;
+                const int64_t row = (int64_t)j * kTileKeys + (4 * wave + i) * 4;
                 kr[i] = __builtin_nontemporal_load((const i32x4*)(ld_kp + row * k_row_bytes + k_off[i]));
                 vr[i] = __builtin_nontemporal_load((const i32x4*)(ld_vp + row * v_row_bytes + v_off));
             }
         } else {
-            // last, partial block of a unit: rows past the end re-read the last row; those keys are never visible
+            // last, partial tile of a unit: rows past the end re-read the last row; those keys are never visible
 #pragma unroll
             for (int i = 0; i < 4; i++) {
-                int64_t row = (int64_t)j * kBlk + (4 * wave + i) * 4 + lrow;
+                int64_t row = (int64_t)j * kTileKeys + (4 * wave + i) * 4 + lrow;
                 row = row < p.Lk ? row : p.Lk - 1;
                 const int sw_k = (lpc ^ (i * 4 + lrow)) << 4, sw_v = (lpc ^ (lrow << 2)) << 4;
                 kr[i] = __builtin_nontemporal_load((const i32x4*)(ld_kp + row * k_row_bytes + sw_k));
@@ -228,7 +232,7 @@ __global__ __launch_bounds__(128, 2) void tree_attn_bf16_kernel(AttnParams p) {
         }
         const int qg = unit % p.qgroups, slab = unit / p.qgroups;
         const int h = slab % p.H, nb = slab / p.H;
-        const int qi = qg * 64 + wave * 32 + col;        // this lane's query row
+        const int qi = qg * (32 * NW) + wave * 32 + col;        // this lane's query row
 
         // mask row of this lane's query -> LDS (the halves write words 0,1 / 2,3); only this wave reads it back
         {
@@ -271,8 +275,13 @@ __global__ __launch_bounds__(128, 2) void tree_attn_bf16_kernel(AttnParams p) {
             park(tile);
             if (blocks_left > 0) issue();
             __syncthreads();
-            const unsigned char* ldsK = tile;
-            const unsigned char* ldsV = tile + kTileBytes;
+            // the tile's 32-key blocks, one after the other
+#pragma unroll
+            for (int sb = 0; sb < kSub; sb++) {
+            const int key0 = j * kTileKeys + sb * kBlk;        // first key of the block
+            if (sb > 0 && key0 >= p.Lk) break;                 // the last tile of a unit may hold fewer blocks
+            const unsigned char* ldsK = tile + sb * kSubBytes;
+            const unsigned char* ldsV = tile + kTileBytes + sb * kSubBytes;
 
             // ---- S^T[key][query] = K Q^T
             f32x16 s;
@@ -286,8 +295,8 @@ __global__ __launch_bounds__(128, 2) void tree_attn_bf16_kernel(AttnParams p) {
 
             // ---- visibility (only blocks that reach past the prefix): one 32-bit word per lane says which of
             // the block's 32 keys its query sees; bit i <-> key j*32 + i
-            if (j >= plain_end) {
-                const int kb = j * kBlk - p.P;          // draft-token index of the block's first key (may be < 0)
+            if (key0 + kBlk > p.P) {
+                const int kb = key0 - p.P;              // draft-token index of the block's first key (may be < 0)
                 const int end = p.Tk - kb;              // keys at block offset >= end are past the last key
                 const uint32_t in_range = end >= 32 ? 0xffffffffu : (end > 0 ? (1u << end) - 1u : 0u);
                 const uint64_t* mw = &my_mask[col * 4];
@@ -351,6 +360,7 @@ __global__ __launch_bounds__(128, 2) void tree_attn_bf16_kernel(AttnParams p) {
                     o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(u.v, pf[ss], o[dt], 0, 0, 0);
                 }
             }
+            }   // blocks of the tile
         }
 
         // ================= end of segment: the two key halves of the wave hold disjoint keys
@@ -369,7 +379,7 @@ __global__ __launch_bounds__(128, 2) void tree_attn_bf16_kernel(AttnParams p) {
                         *(bf16x4*)(op + dt * 32 + 8 * gq + 4 * hh) = w;
                     }
             } else {
-                const int64_t row = ((int64_t)gw * 2 + (first_seg ? 0 : 1)) * 64 + wave * 32 + col;
+                const int64_t row = ((int64_t)gw * 2 + (first_seg ? 0 : 1)) * (32 * NW) + wave * 32 + col;
                 float* wo = p.ws_o + row * kD;
 #pragma unroll
                 for (int dt = 0; dt < 4; dt++)
@@ -397,8 +407,8 @@ __global__ __launch_bounds__(128, 2) void tree_attn_bf16_kernel(AttnParams p) {
 // Merges the partials of every tail unit that was cut between streams.  A 256-thread block takes `rows` query rows
 // of one tail unit, a wavefront one row at a time (a lane owns two of the 128 output columns) and walks the
 // streams that hold a piece of the unit.
-__global__ __launch_bounds__(256) void tree_attn_streamk_merge_kernel(AttnParams p, int rows) {
-    const int per_unit = 64 / rows;
+__global__ __launch_bounds__(256) void tree_attn_streamk_merge_kernel(AttnParams p, int rows, int unit_rows) {
+    const int per_unit = unit_rows / rows;
     const int ut = blockIdx.x / per_unit;                   // unit in tail coordinates
     const int row0 = (blockIdx.x % per_unit) * rows;
     const int unit = p.dp_rounds * p.n_streams + ut;
@@ -413,12 +423,12 @@ __global__ __launch_bounds__(256) void tree_attn_streamk_merge_kernel(AttnParams
     const int slot0 = span_begin(t_total, p.tail_streams, w0) >= ub ? 0 : 1;
     const int h = slab % p.H, nb = slab / p.H;
     for (int ql = row0 + wv; ql < row0 + rows; ql += 4) {
-        const int qi = qg * 64 + ql;
+        const int qi = qg * unit_rows + ql;
         if (qi >= p.Tq) break;
         float m = kNegBig, l = 0.f, a0 = 0.f, a1 = 0.f;
 #pragma unroll 4
         for (int w = w0; w <= w1; w++) {
-            const int64_t row = ((int64_t)w * 2 + (w == w0 ? slot0 : 0)) * 64 + ql;
+            const int64_t row = ((int64_t)w * 2 + (w == w0 ? slot0 : 0)) * unit_rows + ql;
             const float mi = p.ws_ml[row * 2], li = p.ws_ml[row * 2 + 1];
             const float2 oi = *(const float2*)(p.ws_o + row * kD + 2 * lane);
             const float m_new = fmaxf(m, mi);
@@ -545,8 +555,10 @@ Plan make_plan(const rest_attn_desc* d) {
         pl.nsplit_f32 = d->num_splits > 0 ? d->num_splits : 1;
         return pl;
     }
-    pl.qt = 2;                                   // a stream (two wavefronts) covers 64 queries
-    pl.qgroups = (d->Tq + 63) / 64;
+    // a stream of qt wavefronts covers 32 qt queries and moves tiles of 16 qt keys
+    pl.qt = d->Tq <= 64 ? 2 : (d->Tq <= 128 ? 4 : 8);
+    pl.qgroups = (d->Tq + 32 * pl.qt - 1) / (32 * pl.qt);
+    pl.nblk = (Lk + 16 * pl.qt - 1) / (16 * pl.qt);
     pl.units = d->Nb * d->H * pl.qgroups;
     const int64_t total = (int64_t)pl.units * pl.nblk;
     int64_t w;
@@ -554,9 +566,9 @@ Plan make_plan(const rest_attn_desc* d) {
         w = (int64_t)pl.units * d->num_splits;       // explicit request: num_splits streams per unit
         if (w > 16384) w = 16384;
     } else {
-        // four streams (eight wavefronts) per compute unit, but at least four key blocks per stream
+        // eight wavefronts per compute unit, but at least four tiles per stream
         w = total / 4;
-        if (w > kMaxWaves) w = kMaxWaves;
+        if (w > kMaxWaves / pl.qt) w = kMaxWaves / pl.qt;
     }
     if (w > total) w = total;
     if (w < 1) w = 1;
@@ -576,8 +588,8 @@ Plan make_plan(const rest_attn_desc* d) {
         if (span_owner(t_total, pl.tail_streams, ub) != span_owner(t_total, pl.tail_streams, ub + pl.nblk - 1)) pl.need_merge = true;
     }
     // rows of a unit per merge block: about a thousand blocks in all, a multiple of the four wavefronts
-    pl.merge_rows = 64;
-    while (pl.merge_rows > 4 && (int64_t)pl.tail_units * (64 / pl.merge_rows) < 1024) pl.merge_rows /= 2;
+    pl.merge_rows = 32 * pl.qt;
+    while (pl.merge_rows > 4 && (int64_t)pl.tail_units * (32 * pl.qt / pl.merge_rows) < 1024) pl.merge_rows /= 2;
     return pl;
 }
 
@@ -591,7 +603,7 @@ bool desc_ok(const rest_attn_desc* d) {
     if (d->mask_rows < 0 || d->mask_rows > d->Tq) return false;
     if ((int64_t)d->Nb * d->H * 64 > 0x7fffffff) return false;
     // block counts are kept in 32 bits
-    if (((int64_t)d->Nb * d->H * ((d->Tq + 63) / 64) + 1) * ((d->P + d->Tk + kBlk - 1) / kBlk) > 0x7fffffff) return false;
+    if (((int64_t)d->Nb * d->H + 1) * ((d->P + d->Tk + kBlk - 1) / kBlk) > 0x7fffffff) return false;
     for (int i = 0; i < 3; i++)
         if (d->q_stride[i] < 0 || d->k_stride[i] < 0 || d->v_stride[i] < 0 || d->o_stride[i] < 0) return false;
     // rows are read with 16-byte vector loads
@@ -654,11 +666,16 @@ extern "C" __attribute__((visibility("default"))) rest_status rest_tree_attentio
         p.tail_streams = pl.tail_streams;
         const size_t rows = (size_t)pl.tail_streams * 2 * (pl.qt * 32);
         p.ws_ml = p.ws_o ? p.ws_o + rows * kD : nullptr;
-        hipLaunchKernelGGL(tree_attn_bf16_kernel, dim3(pl.n_streams), dim3(128), 0, stream, p);
+        if (pl.qt == 2)
+            hipLaunchKernelGGL(tree_attn_bf16_kernel<2>, dim3(pl.n_streams), dim3(128), 0, stream, p);
+        else if (pl.qt == 4)
+            hipLaunchKernelGGL(tree_attn_bf16_kernel<4>, dim3(pl.n_streams), dim3(256), 0, stream, p);
+        else
+            hipLaunchKernelGGL(tree_attn_bf16_kernel<8>, dim3(pl.n_streams), dim3(512), 0, stream, p);
         REST_HIP_TRY(hipGetLastError());
         if (pl.need_merge) {
-            hipLaunchKernelGGL(tree_attn_streamk_merge_kernel, dim3(pl.tail_units * (64 / pl.merge_rows)), dim3(256), 0, stream, p,
-                               pl.merge_rows);
+            hipLaunchKernelGGL(tree_attn_streamk_merge_kernel, dim3(pl.tail_units * (32 * pl.qt / pl.merge_rows)), dim3(256), 0,
+                               stream, p, pl.merge_rows, 32 * pl.qt);
             REST_HIP_TRY(hipGetLastError());
         }
     } else {
