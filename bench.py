@@ -162,7 +162,7 @@ def main() -> int:
                                f"(rotating over {n_ctx}), K={w.max_matches}, m={w.cont_len}, c={c}, tree attention "
                                f"{Nb} layers x {H} heads x {D}, KV length {P}+{c}, one launch over all layers",
                    "global_batch": 1, "kv_len": P, "tree_nodes": c},
-        "roofline": {"bound": "hbm", "kernel": "tree_attn_bf16_kernel", "achieved": round(achieved, 1),
+        "roofline": {"bound": "hbm", "kernel": "tree_attn_bf16_kernel<2>", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "traffic": traffic, "algorithmic_bytes_per_launch": alg_bytes,
                      "avg_launch_us": round(attn_ms * 1e3, 2), "launches_timed": len(attn_samples),
