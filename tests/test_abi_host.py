@@ -72,6 +72,12 @@ def test_attention_workspace_sizing_is_host_only(rest):
     assert rest.rest_tree_attention_workspace_bytes(one_layer) == 528 * 2 * 64 * (128 + 2) * 4
     forced = make_desc(rest, Nb=1, num_splits=4)
     assert rest.rest_tree_attention_workspace_bytes(forced) == 32 * 4 * 2 * 64 * 130 * 4
+    # 128 queries: streams of four wavefronts on 64-key tiles: 32 units x 33 tiles over 264 streams, 128 rows per slot
+    wide = make_desc(rest, Nb=1, Tq=128, Tk=128, P=1984)
+    assert rest.rest_tree_attention_workspace_bytes(wide) == 264 * 2 * 128 * (128 + 2) * 4
+    # 13B shape: 1600 units, 1024 streams: one whole unit each, the other 576 units cut into 1024 spans
+    big = make_desc(rest, Nb=40, H=40, P=4096)
+    assert rest.rest_tree_attention_workspace_bytes(big) == 1024 * 2 * 64 * 130 * 4
     fp32 = make_desc(rest, Nb=1, dtype=rest.REST_FP32, num_splits=3)
     assert rest.rest_tree_attention_workspace_bytes(fp32) == 32 * 3 * 64 * 130 * 4
     for bad in [dict(D=64), dict(Tq=0), dict(Tq=257), dict(Tk=257), dict(scale=0.0), dict(dtype=7), dict(num_splits=65),

@@ -209,6 +209,14 @@ def test_tree_attention_bf16_split_counts(ns):
     attention_case(1, 2, 40, 3, seed=6, num_splits=ns)      # more waves than key blocks
 
 
+@pytest.mark.parametrize("T,P,ns", [(128, 700, 3), (100, 31, 1), (256, 300, 5), (200, 1, 64), (130, 2050, 2)])
+def test_tree_attention_bf16_wide_units_split(T, P, ns):
+    """More than 64 queries: streams of four or eight wavefronts on tiles of 64 or 128 keys, with the unit cut
+    between streams and merged."""
+    attention_case(1, 2, T, P, seed=300 + T, num_splits=ns)
+    attention_case(3, 1, T, P, seed=301 + T, num_splits=ns, per_batch=True)
+
+
 def test_tree_attention_bf16_variants():
     attention_case(3, 2, 64, 200, seed=7, per_batch=True)
     attention_case(2, 2, 64, 200, seed=8, Tq_extra=1)        # extra root query row seeing the prefix only
