@@ -255,6 +255,25 @@ def side_measurements(rest, torch, synth, corp, index, w, q, k, v, out, tree, P,
     sid = torch.empty(1 + T, dtype=torch.int32, device=dev)
     ms = timed(lambda: rest.rest_sample_ids(logits, u, 0.8, 0.95, out=sid), 20)
     res["sample_ids_65x32000_us"] = round(ms * 1e3, 1)
+
+    # the step with its cache steps: retrieve -> embed + append -> attention -> accept -> compact (greedy ids)
+    ctx1, len1 = d_ctx[:1], d_len[:1]
+    ids = torch.zeros((1, 1 + T), dtype=torch.int32, device=dev)
+    al = torch.empty(1, dtype=torch.int32, device=dev)
+    ap = torch.empty((1, w.cont_len), dtype=torch.int32, device=dev)
+    nx = torch.empty(1, dtype=torch.int32, device=dev)
+    desc = rest.make_attn_desc(q2, k, v, out, P, scale, False)
+    ws = torch.empty(max(rest.rest_tree_attention_workspace_bytes(desc), 16), dtype=torch.uint8, device=dev)
+
+    def full_step():
+        rest.rest_retrieve(index, ctx1, len1, out=one, **prm)
+        rest.rest_rope_append(q2, kn, vn, k, v, one.pos_ids[0], P)
+        rest.rest_tree_attention(q2, k, v, one.tree_mask[0], P, scale, out=out, workspace=ws)
+        rest.rest_accept(ids, one, w.cont_len, al, ap, nx)
+        rest.rest_kv_compact(k, v, ap, al, T, P)
+
+    ms = timed(full_step, 50)
+    res["step_with_cache_steps_us"] = round(ms * 1e3, 1)
     return res
 
 

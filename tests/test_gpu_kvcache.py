@@ -173,3 +173,64 @@ def test_layer_step_on_the_gpu_equals_plain_decoding_of_the_accepted_tokens():
             assert np.abs(to_np(out)[0, :, node] - o[:, 0]).max() <= 2e-2
         done += A > 0
     assert done >= 2
+
+
+def test_whole_step_replays_as_a_hip_graph():
+    """The per-step calls only enqueue kernels on the given stream (no allocation, no synchronisation, no memset), so
+    a step can be captured once and replayed: every replay, with eager work and synchronisations in between, must
+    reproduce the eager results bit for bit."""
+    w = synth.WORKLOADS["tiny"]
+    corp = synth.make_corpus(w.n_tokens, w.corpus_seed, w.n_motifs)
+    ctx, lens = synth.make_contexts(corp, 8, w.ctx_len, w.query_seed)
+    index = rest.rest_build_index(torch.from_numpy(corp.tokens).cuda(), 4)
+    c, m, H, P, V = w.max_nodes, w.cont_len, 4, 96, 4000
+    d_ctx, d_len = torch.from_numpy(ctx).cuda(), torch.from_numpy(lens).cuda()
+    tree = rest.Tree.empty(8, c)
+    q0, _ = bf16_tensor((8, H, c, 128), 70)
+    kn, _ = bf16_tensor((8, H, c, 128), 71)
+    vn, _ = bf16_tensor((8, H, c, 128), 72)
+    kc0, _ = bf16_tensor((8, H, P + c, 128), 73)
+    vc0, _ = bf16_tensor((8, H, P + c, 128), 74)
+    q, kc, vc = q0.clone(), kc0.clone(), vc0.clone()
+    out = torch.empty_like(q)
+    g = torch.Generator(device="cuda")
+    g.manual_seed(5)
+    logits = torch.randn((8 * (1 + c), V), generator=g, device="cuda") * 3
+    u = torch.rand(8 * (1 + c), generator=g, device="cuda")
+    ids = torch.empty(8 * (1 + c), dtype=torch.int32, device="cuda")
+    alen = torch.empty(8, dtype=torch.int32, device="cuda")
+    apath = torch.empty((8, m), dtype=torch.int32, device="cuda")
+    nxt = torch.empty(8, dtype=torch.int32, device="cuda")
+    desc = rest.make_attn_desc(q, kc, vc, out, P, 0.088, True)
+    ws = torch.empty(max(rest.rest_tree_attention_workspace_bytes(desc), 16), dtype=torch.uint8, device="cuda")
+
+    def step():
+        q.copy_(q0)
+        kc.copy_(kc0)
+        vc.copy_(vc0)
+        rest.rest_retrieve(index, d_ctx, d_len, out=tree, n_max=w.n_max, n_min=w.n_min, max_matches=w.max_matches,
+                           cont_len=m, max_nodes=c)
+        rest.rest_rope_append(q, kn, vn, kc, vc, tree.pos_ids, P)
+        rest.rest_tree_attention(q, kc, vc, tree.tree_mask, P, 0.088, out=out, workspace=ws)
+        rest.rest_sample_ids(logits, u, 0.8, 0.95, out=ids)
+        rest.rest_accept(ids.view(8, 1 + c), tree, m, alen, apath, nxt)
+        rest.rest_kv_compact(kc, vc, apath, alen, c, P)
+
+    step()                       # eager: also raises the kernels' LDS limits, which cannot be done under capture
+    torch.cuda.synchronize()
+    want = [t.clone() for t in (tree.draft_tokens, tree.tree_mask, out, ids, alen, apath, nxt, kc, vc)]
+    s = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(s):
+        with torch.cuda.graph(graph, stream=s):
+            step()
+    torch.cuda.synchronize()
+    for replay in range(3):
+        for t in (tree.draft_tokens, out, ids, alen, kc):
+            t.zero_()                       # eager work between replays; also proves the replay rewrites everything
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = (tree.draft_tokens, tree.tree_mask, out, ids, alen, apath, nxt, kc, vc)
+        for a, b in zip(got, want):
+            assert torch.equal(a, b), replay
