@@ -24,12 +24,17 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 
 
+def note(msg: str) -> None:
+    """progress lines go to stderr; stdout carries the one JSON line"""
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="llama7b", choices=["llama7b", "llama13b", "tiny"])
+    ap.add_argument("--workload", default="llama7b", choices=["llama7b", "llama13b", "batched2b", "tiny"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the per-layer and batched-retrieval side measurements")
     ap.add_argument("--sweep", action="store_true",
@@ -64,13 +69,16 @@ def main() -> int:
         print(json.dumps({"ablation": ablation(rest, torch, synth, np, dev)}))
         return 0
     w = synth.WORKLOADS[args.workload]
-    n_ctx = 16          # the timed steps rotate over these contexts (half copied from the stream, half i.i.d.)
+    B = w.batch         # contexts per step: 1, or 32 for the batched workload (one layer, per-context masks)
+    n_ctx = 16 if B == 1 else 2     # the timed steps rotate over this many context sets (half copied, half i.i.d.)
 
     # ---------------- inputs, resident in HBM
     t0 = time.time()
-    corp = synth.make_corpus(w.n_tokens, w.corpus_seed, w.n_motifs, dtype=w.token_dtype)
-    ctx_np, len_np = synth.make_contexts(corp, n_ctx, w.ctx_len, w.query_seed)
+    corp = synth.make_corpus(w.n_tokens, w.corpus_seed, w.n_motifs, dtype=w.token_dtype,
+                             workers=16 if w.n_tokens > 600_000_000 else 8)
+    ctx_np, len_np = synth.make_contexts(corp, n_ctx * B, w.ctx_len, w.query_seed)
     t_gen = time.time() - t0
+    note(f"datastore generated in {t_gen:.1f} s")
     d_corpus = torch.from_numpy(corp.tokens).to(dev)
     d_ctx = torch.from_numpy(ctx_np).to(dev)
     d_len = torch.from_numpy(len_np).to(dev)
@@ -79,8 +87,9 @@ def main() -> int:
     index = rest.rest_build_index(d_corpus, w.sa_bytes)
     torch.cuda.synchronize()
     t_build = time.time() - t0
+    note(f"index built in {t_build:.2f} s")
 
-    Nb, H, D, P, c = w.layers, w.heads, w.head_dim, w.kv_len, w.max_nodes
+    Nb, H, D, P, c = (w.layers if B == 1 else B), w.heads, w.head_dim, w.kv_len, w.max_nodes
     Lk = P + c
     gen = torch.Generator(device=dev)
     gen.manual_seed(w.qkv_seed)
@@ -91,24 +100,26 @@ def main() -> int:
     scale = 1.0 / float(np.sqrt(D))
     prm = dict(n_max=w.n_max, n_min=w.n_min, max_matches=w.max_matches, cont_len=w.cont_len, max_nodes=c)
 
-    trees = [rest.Tree.empty(1, c, dev) for _ in range(n_ctx)]
+    trees = [rest.Tree.empty(B, c, dev) for _ in range(n_ctx)]
     ids = []
     for i in range(n_ctx):      # model token ids per position (inputs of rest_accept), derived once from the trees
-        rest.rest_retrieve(index, d_ctx[i:i + 1], d_len[i:i + 1], out=trees[i], **prm)
+        rest.rest_retrieve(index, d_ctx[i * B:(i + 1) * B], d_len[i * B:(i + 1) * B], out=trees[i], **prm)
         torch.cuda.synchronize()
-        ids_np = synth.sampled_ids(w.qkv_seed + 100 + i, trees[i].draft_tokens[0].cpu().numpy(),
-                                   trees[i].parent_idx[0].cpu().numpy(), int(trees[i].n_nodes[0]))
-        ids.append(torch.from_numpy(ids_np[None]).to(dev))
-    alen = torch.empty(1, dtype=torch.int32, device=dev)
-    apath = torch.empty((1, w.cont_len), dtype=torch.int32, device=dev)
-    nxt = torch.empty(1, dtype=torch.int32, device=dev)
-    desc = rest.make_attn_desc(q, k, v, out, P, scale, False)
+        ids_np = np.stack([synth.sampled_ids(w.qkv_seed + 100 + i * B + b, trees[i].draft_tokens[b].cpu().numpy(),
+                                             trees[i].parent_idx[b].cpu().numpy(), int(trees[i].n_nodes[b]))
+                           for b in range(B)])
+        ids.append(torch.from_numpy(ids_np).to(dev))
+    alen = torch.empty(B, dtype=torch.int32, device=dev)
+    apath = torch.empty((B, w.cont_len), dtype=torch.int32, device=dev)
+    nxt = torch.empty(B, dtype=torch.int32, device=dev)
+    desc = rest.make_attn_desc(q, k, v, out, P, scale, B > 1)
     ws_bytes = rest.rest_tree_attention_workspace_bytes(desc)
     ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=dev)
 
-    ctx_rows = [d_ctx[i:i + 1] for i in range(n_ctx)]
-    len_rows = [d_len[i:i + 1] for i in range(n_ctx)]
-    masks = [t.tree_mask[0] for t in trees]      # [c, words] views: one mask shared by all layers
+    ctx_rows = [d_ctx[i * B:(i + 1) * B] for i in range(n_ctx)]
+    len_rows = [d_len[i * B:(i + 1) * B] for i in range(n_ctx)]
+    # [c, words] views: one mask shared by all layers; batched: [B, c, words], one mask per context
+    masks = [t.tree_mask[0] if B == 1 else t.tree_mask for t in trees]
 
     def step(i, ev=None):
         j = i % n_ctx
@@ -121,6 +132,7 @@ def main() -> int:
             ev[1].record()
         rest.rest_accept(ids[j], tree, w.cont_len, alen, apath, nxt)
 
+    note("inputs resident, timing")
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -140,7 +152,7 @@ def main() -> int:
     attn_ms = sum(attn_samples) / len(attn_samples)
 
     slabs = Nb * H
-    alg_bytes = slabs * (2 * Lk * D * 2 + 2 * c * D * 2) + c * ((c + 63) // 64) * 8
+    alg_bytes = slabs * (2 * Lk * D * 2 + 2 * c * D * 2) + B * c * ((c + 63) // 64) * 8
     achieved = alg_bytes / (attn_ms * 1e-3) / 1e9
 
     traffic = None
@@ -153,32 +165,36 @@ def main() -> int:
 
     result = {
         "metric": {"llama7b": "draft-verify steps/s (retrieve+tree-attn+accept) at 7B shape",
+                   "batched2b": "draft-verify steps/s (retrieve+tree-attn+accept), 32 contexts per step, 2B-token datastore",
                    "llama13b": "draft-verify steps/s (retrieve+tree-attn+accept) at 13B shape",
                    "tiny": "draft-verify steps/s (retrieve+tree-attn+accept), tiny config"}[args.workload],
         "value": round(1e3 / ms_per_step, 2), "unit": "steps/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"{w.name}: {w.n_tokens}-token Zipf(1.1)+motif datastore, 1 context x {w.ctx_len} per step "
-                               f"(rotating over {n_ctx}), K={w.max_matches}, m={w.cont_len}, c={c}, tree attention "
-                               f"{Nb} layers x {H} heads x {D}, KV length {P}+{c}, one launch over all layers",
-                   "global_batch": 1, "kv_len": P, "tree_nodes": c},
+        "config": {"workload": f"{w.name}: {w.n_tokens}-token Zipf(1.1)+motif datastore, {B} context(s) x {w.ctx_len} per step "
+                               f"(rotating over {n_ctx} sets), K={w.max_matches}, m={w.cont_len}, c={c}, tree attention "
+                               + (f"{Nb} layers x {H} heads x {D}, KV length {P}+{c}, one launch over all layers" if B == 1 else
+                                  f"{B} contexts x {H} heads x {D} (one layer, per-context masks), KV length {P}+{c}"),
+                   "global_batch": B, "kv_len": P, "tree_nodes": c},
         "roofline": {"bound": "hbm", "kernel": "tree_attn_bf16_kernel<2>", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "traffic": traffic, "algorithmic_bytes_per_launch": alg_bytes,
                      "avg_launch_us": round(attn_ms * 1e3, 2), "launches_timed": len(attn_samples),
                      "p10_p50_p90_us": [round(attn_samples[int(len(attn_samples) * f)] * 1e3, 1) for f in (0.1, 0.5, 0.9)]},
         "extra": {"index_build_s": round(t_build, 3), "corpus_gen_s": round(t_gen, 2),
-                  "tree_nodes_per_context": [int(t.n_nodes[0]) for t in trees],
-                  "matched_len_per_context": [int(t.matched_len[0]) for t in trees]},
+                  "contexts_per_s": round(B * 1e3 / ms_per_step, 1),
+                  "tree_nodes_per_context": [int(x) for t in trees for x in t.n_nodes.tolist()][:32],
+                  "matched_len_per_context": [int(x) for t in trees for x in t.matched_len.tolist()][:32]},
     }
 
-    if not args.no_extras:
+    if not args.no_extras and B == 1:
         result["extra"].update(side_measurements(rest, torch, synth, corp, index, w, q, k, v, out, trees[0], P, scale, prm))
     if args.sweep:
         result["extra"]["attention_sweep"] = attention_sweep(rest, torch, synth, np, dev)
     if not args.no_cpu_baseline:
+        note("timing the CPU oracle on a sample")
         result["cpu_baseline"], result["extra"]["parity_sample_max_abs_err"] = cpu_baseline(
-            np, torch, corp, ctx_np, w, q, k, v, out, trees, ids, P, scale, step)
+            np, torch, corp, ctx_np, w, q, k, v, out, trees, ids, P, scale, step, B)
     print(json.dumps(result))
     return 0
 
@@ -385,7 +401,7 @@ def ablation(rest, torch, synth, np, dev):
     return res
 
 
-def cpu_baseline(np, torch, corp, ctx_np, w, q, k, v, out, trees, ids, P, scale, step):
+def cpu_baseline(np, torch, corp, ctx_np, w, q, k, v, out, trees, ids, P, scale, step, B=1):
     """The plain CPU oracle on a bounded sample of the same workload, on this machine's host cores."""
     import oracle
     try:
@@ -395,9 +411,10 @@ def cpu_baseline(np, torch, corp, ctx_np, w, q, k, v, out, trees, ids, P, scale,
         threads = os.cpu_count() or 1
     n_ret = 3
     t0 = time.perf_counter()
-    cpu_trees = [oracle.draft_tree(corp.tokens, ctx_np[i], w.n_max, w.n_min, w.max_matches, w.cont_len, w.max_nodes)
+    cpu_trees = [oracle.draft_tree(corp.tokens, ctx_np[i], w.n_max, w.n_min, w.max_matches, w.cont_len, w.max_nodes,
+                                   one_pass=corp.tokens.size > 600_000_000)
                  for i in range(n_ret)]
-    t_ret = (time.perf_counter() - t0) / n_ret
+    t_ret = (time.perf_counter() - t0) / n_ret * B
     # attention: a seeded sample of (layer, head) slabs incl. the first and the last
     step(0)
     torch.cuda.synchronize()
@@ -407,19 +424,21 @@ def cpu_baseline(np, torch, corp, ctx_np, w, q, k, v, out, trees, ids, P, scale,
     while len(picks) < 48:
         picks.add((int(rng.integers(Nb)), int(rng.integers(H))))
     picks = sorted(picks)
-    mask = trees[0].tree_mask[0].cpu().numpy().view(np.uint64)
+    all_masks = trees[0].tree_mask.cpu().numpy().view(np.uint64)          # [B, c, words]
+    slab_mask = [all_masks[a if B > 1 else 0] for a, _ in picks]
     slabs = [(q[a, b].float().cpu().numpy(), k[a, b].float().cpu().numpy(), v[a, b].float().cpu().numpy()) for a, b in picks]
     t0 = time.perf_counter()
-    refs = [oracle.tree_attention(qq, kk, vv, mask, P, scale) for qq, kk, vv in slabs]
+    refs = [oracle.tree_attention(qq, kk, vv, mm, P, scale) for (qq, kk, vv), mm in zip(slabs, slab_mask)]
     t_attn = (time.perf_counter() - t0) * (Nb * H) / len(picks)
     err = max(float(np.abs(out[a, b].float().cpu().numpy() - r).max()) for (a, b), r in zip(picks, refs))
     t0 = time.perf_counter()
     for i in range(n_ret):
-        oracle.accept(ids[i][0].cpu().numpy(), cpu_trees[i].draft_tokens, cpu_trees[i].parent_idx, cpu_trees[i].n_nodes, w.cont_len)
-    t_acc = (time.perf_counter() - t0) / n_ret
+        oracle.accept(ids[0][i].cpu().numpy() if B > 1 else ids[i][0].cpu().numpy(), cpu_trees[i].draft_tokens,
+                      cpu_trees[i].parent_idx, cpu_trees[i].n_nodes, w.cont_len)
+    t_acc = (time.perf_counter() - t0) / n_ret * B
     total = t_ret + t_attn + t_acc
     base = {"value": round(1.0 / total, 4), "unit": "steps/s", "cores": int(threads), "kind": "oracle",
-            "sample": f"retrieval+Trie: {n_ret} of the rotating contexts, mean {t_ret:.3f} s; attention: {len(picks)} of "
+            "sample": f"retrieval+Trie: {n_ret} of the contexts, scaled to the {B} of a step: {t_ret:.3f} s; attention: {len(picks)} of "
                       f"{Nb * H} (layer, head) slabs in float64, scaled to all: {t_attn:.3f} s; accept {t_acc * 1e6:.0f} us"}
     return base, err
 
