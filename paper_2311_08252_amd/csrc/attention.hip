@@ -292,6 +292,15 @@ __global__ __launch_bounds__(64 * NW, 2) void tree_attn_bf16_kernel(AttnParams p
                 const bf16x8 a = *(const bf16x8*)(ldsK + (ka0 ^ (ks << 5)));
                 s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], s, 0, 0, 0);
             }
+            // keep two K fragments in flight: read, read, then (multiply, read) ..., so that an LDS read's latency
+            // hides behind the previous matrix instruction
+            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+#pragma unroll
+            for (int ks = 0; ks < 6; ks++) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            }
+            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
 
             // ---- visibility (only blocks that reach past the prefix): one 32-bit word per lane says which of
             // the block's 32 keys its query sees; bit i <-> key j*32 + i
@@ -360,6 +369,13 @@ __global__ __launch_bounds__(64 * NW, 2) void tree_attn_bf16_kernel(AttnParams p
                     o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(u.v, pf[ss], o[dt], 0, 0, 0);
                 }
             }
+            __builtin_amdgcn_sched_group_barrier(0x100, 4, 1);
+#pragma unroll
+            for (int i = 0; i < 6; i++) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 1);
+                __builtin_amdgcn_sched_group_barrier(0x100, 2, 1);
+            }
+            __builtin_amdgcn_sched_group_barrier(0x008, 2, 1);
             }   // blocks of the tile
         }
 
