@@ -223,6 +223,9 @@ def test_tree_attention_bf16_variants():
     attention_case(1, 1, 64, 300, seed=9, tree="chain")      # chain tree = plain causal attention
     attention_case(1, 2, 0, 129, seed=10, Tq_extra=3)        # no draft keys at all
     attention_case(9, 5, 64, 64, seed=11)                    # streams not a multiple of 8
+    attention_case(2, 2, 128, 200, seed=12, Tq_extra=1)      # 129 query rows: eight-wavefront streams, mostly idle rows
+    attention_case(1, 3, 0, 300, seed=13, Tq_extra=100)      # 100 query rows and no draft keys
+    attention_case(5, 7, 96, 1000, seed=14, tree="chain")    # 96 rows: four-wavefront streams with an idle wavefront
 
 
 def test_tree_attention_bf16_tiny_config():
