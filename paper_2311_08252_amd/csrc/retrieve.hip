@@ -18,7 +18,9 @@
 // Phase B, Trie without a Trie.  The kept occurrences are consecutive suffix-array ranks, hence already in
 // lexicographic order, so the Trie is implicit in the longest-common-prefix array of adjacent candidates:
 // a node at depth d starts at row r iff lcp[r] < d <= len[r], and its weight is the distance to the next row
-// with lcp < d.  Per-depth segment-start bitmaps are built with wavefront ballots; weights are bit scans.
+// with lcp < d.  Per-depth segment-start bitmaps are built with wavefront ballots; everything after that works on
+// the bitmaps 64 rows at a time with plain 64-bit logic (eight threads per word): nodes of weight 1 -- nearly all of
+// them deep in the Trie -- are counted with a popcount, only heavier nodes are visited one by one.
 // Top-c is a three-level counting select on the order (weight desc, depth asc, row asc): weight histogram,
 // depth histogram inside the boundary weight, row rank inside the boundary depth.
 #include "common.h"
@@ -54,7 +56,7 @@ struct RetrieveParams {
     rest_tree out;
     // LDS layout of phase B (byte offsets into dynamic LDS)
     int32_t words;        // bitmap words per depth = K/64 + 1
-    int32_t off_seg, off_lcp, off_len, off_hist, off_part, off_sel, off_pos, off_after, off_misc;
+    int32_t off_seg, off_lcp, off_len, off_hist, off_part, off_sel, off_pos, off_after, off_short, off_misc;
 };
 
 template <typename TokT>
@@ -203,12 +205,39 @@ __device__ void wave_search(const RetrieveParams& p, const int32_t* lds_tab, con
     out_hi = hi.a > lo.a ? hi.a : lo.a;
 }
 
-// Weight of the Trie node that starts at row r = 64 wi + lane of a depth's segment-start bitmap: the distance to
-// the next set bit, which lies in the same word or, for the last node of a word, at after[wi] (the first set bit of
-// any later word, tabulated once per depth).
-__device__ inline int node_weight(uint64_t word, int lane, int r, int32_t after) {
-    const uint64_t later = lane < 63 ? word & (~0ull << (lane + 1)) : 0ull;
-    return later ? __builtin_ctzll(later) - lane : after - r;
+// One item = the 64 rows of word wi at depth d, handled by ONE thread with 64-bit bit operations: `node` = rows that
+// start a Trie node (a segment start on a row long enough), `ones` = the nodes of weight 1 (the next row starts a
+// segment too), `big` = the others.  Deep in the Trie nearly every node has weight 1, so an item is mostly a few
+// logic operations and a popcount; only the `big` nodes are visited one by one.
+struct Item {
+    uint64_t word, node, ones, big;
+    int32_t after;      // first segment start in any later word
+};
+__device__ inline Item classify(const uint64_t* seg, const int32_t* after, const uint64_t* shortbm, const uint8_t* rlen,
+                                int words, int row_words, int d, int wi, int R) {
+    Item it;
+    it.word = seg[(d - 1) * words + wi];
+    it.after = after[(d - 1) * words + wi];
+    const int left = R - wi * 64;                                   // valid rows in this word
+    const uint64_t vmask = left >= 64 ? ~0ull : (left > 0 ? (1ull << left) - 1ull : 0ull);
+    it.node = it.word & vmask;
+    uint64_t cut = shortbm[wi] & it.node;                           // rows cut short by the end of the stream: rare
+    while (cut) {
+        const int b = __builtin_ctzll(cut);
+        cut &= cut - 1;
+        if (rlen[wi * 64 + b] < d) it.node &= ~(1ull << b);
+    }
+    // a valid row is never the last bit that matters: the terminator rows follow it, in this word or the next
+    const uint64_t next0 = wi + 1 < row_words ? seg[(d - 1) * words + wi + 1] & 1ull : 0ull;
+    const uint64_t follows = (it.word >> 1) | (next0 << 63);
+    it.ones = it.node & follows;
+    it.big = it.node & ~follows;
+    return it;
+}
+// weight of the node at bit b of an item: distance to the next segment start
+__device__ inline int bit_weight(const Item& it, int wi, int b) {
+    const uint64_t later = b < 63 ? it.word & (~0ull << (b + 1)) : 0ull;
+    return later ? __builtin_ctzll(later) - b : it.after - (wi * 64 + b);
 }
 
 // position of the highest set bit at or before `from` (bit 0 is always set)
@@ -330,6 +359,7 @@ __global__ __launch_bounds__(kThreads) void retrieve_kernel(RetrieveParams p) {
     int32_t* srt_par = (int32_t*)(srt_wgt + REST_MAX_NODES);  // [c]
     uint32_t* rowpos = (uint32_t*)(lds + p.off_pos);     // [K] suffix-array entry of each kept row
     int32_t* after = (int32_t*)(lds + p.off_after);      // [m][words] first set bit of seg[d] in any word after this one
+    uint64_t* shortbm = (uint64_t*)(lds + p.off_short);  // [words] rows cut short by the end of the stream
 
     for (int i = tid; i <= p.K; i += kThreads) hist[i] = 0;
     if (tid < 16) s_misc[tid] = 0;
@@ -378,6 +408,10 @@ __global__ __launch_bounds__(kThreads) void retrieve_kernel(RetrieveParams p) {
         }
         if (r == 0) l = 0;
         if (r < R) { lcp[r] = (uint8_t)l; rlen[r] = (uint8_t)len; }
+        {
+            const uint64_t cut = __ballot(r < R && len < m);
+            if (lane == 0) shortbm[base >> 6] = cut;
+        }
         for (int d = 1; d <= m; d++) {
             const uint64_t bits = __ballot(r >= R || l < d);
             if (lane == 0) seg[(d - 1) * words + (base >> 6)] = bits;
@@ -406,16 +440,21 @@ __global__ __launch_bounds__(kThreads) void retrieve_kernel(RetrieveParams p) {
 
     // ---- B2: weight histogram over all Trie nodes (node (d, r): segment start at depth d with len >= d)
     const int items = m * row_words;   // one item = (depth, 64-row word)
-    // items (depth, word) are dealt to the wavefronts round robin; (d, wi) advance without divisions
-    for (int it = wave, d = 1, wi = wave; it < items; it += kWavesPerWG, wi += kWavesPerWG) {
-        while (wi >= row_words) { wi -= row_words; d++; }
-        const int r = wi * 64 + lane;
-        const uint64_t* bm = seg + (d - 1) * words;
-        const bool node = r < R && ((bm[wi] >> lane) & 1ull) && rlen[r] >= d;
-        const int w = node ? node_weight(bm[wi], lane, r, after[(d - 1) * words + wi]) : 0;
-        const uint64_t ones = __ballot(node && w == 1);
-        if (lane == 0 && ones) atomicAdd(&hist[1], (uint32_t)popc64(ones));
-        if (node && w > 1) atomicAdd(&hist[w], 1u);
+    // eight threads per item, each with eight of its rows; weight-1 nodes are by far the most frequent and are
+    // summed over the wavefront before they touch the histogram
+    for (int u0 = wave * 64; u0 < items * 8; u0 += kThreads) {
+        const int u = u0 + lane;
+        uint32_t n_ones = 0;
+        if (u < items * 8) {
+            const int it = u >> 3, d = it / row_words + 1, wi = it % row_words;
+            const uint64_t mine = 0xffull << (8 * (u & 7));
+            const Item x = classify(seg, after, shortbm, rlen, words, row_words, d, wi, R);
+            n_ones = (uint32_t)popc64(x.ones & mine);
+            for (uint64_t rest = x.big & mine; rest; rest &= rest - 1)
+                atomicAdd(&hist[bit_weight(x, wi, __builtin_ctzll(rest))], 1u);
+        }
+        for (int off = 32; off > 0; off >>= 1) n_ones += __shfl_xor(n_ones, off, 64);
+        if (lane == 0 && n_ones) atomicAdd(&hist[1], n_ones);
     }
     __syncthreads();
 
@@ -460,15 +499,18 @@ __global__ __launch_bounds__(kThreads) void retrieve_kernel(RetrieveParams p) {
     if (tid <= m) dcount[tid] = 0;
     __syncthreads();
     if (!take_all) {
-        // items (depth, word) are dealt to the wavefronts round robin; (d, wi) advance without divisions
-        for (int it = wave, d = 1, wi = wave; it < items; it += kWavesPerWG, wi += kWavesPerWG) {
-            while (wi >= row_words) { wi -= row_words; d++; }
-            const int r = wi * 64 + lane;
-            const uint64_t* bm = seg + (d - 1) * words;
-            const bool node = r < R && ((bm[wi] >> lane) & 1ull) && rlen[r] >= d;
-            const bool eq = node && node_weight(bm[wi], lane, r, after[(d - 1) * words + wi]) == w_star;
-            const uint64_t e = __ballot(eq);
-            if (lane == 0 && e) atomicAdd(&dcount[d], (uint32_t)popc64(e));
+        for (int u = tid; u < items * 8; u += kThreads) {
+            const int it = u >> 3, d = it / row_words + 1, wi = it % row_words;
+            const uint64_t mine = 0xffull << (8 * (u & 7));
+            const Item x = classify(seg, after, shortbm, rlen, words, row_words, d, wi, R);
+            uint32_t n = 0;
+            if (w_star == 1) {
+                n = (uint32_t)popc64(x.ones & mine);
+            } else {
+                for (uint64_t rest = x.big & mine; rest; rest &= rest - 1)
+                    n += bit_weight(x, wi, __builtin_ctzll(rest)) == w_star;
+            }
+            if (n) atomicAdd(&dcount[d], n);
         }
     }
     __syncthreads();
@@ -490,13 +532,15 @@ __global__ __launch_bounds__(kThreads) void retrieve_kernel(RetrieveParams p) {
     // ---- B5: inside (w*, d*), rank by row: per-word counts and their exclusive prefix (one wavefront)
     uint32_t* wpre = part + 128;       // [row_words]
     if (!take_all && d_star <= m) {
-        const uint64_t* bm = seg + (d_star - 1) * words;
-        for (int wi = wave; wi < row_words; wi += kWavesPerWG) {
-            const int r = wi * 64 + lane;
-            const bool node = r < R && ((bm[wi] >> lane) & 1ull) && rlen[r] >= d_star;
-            const bool eq = node && node_weight(bm[wi], lane, r, after[(d_star - 1) * words + wi]) == w_star;
-            const uint64_t e = __ballot(eq);
-            if (lane == 0) wpre[wi] = (uint32_t)popc64(e);
+        for (int wi = tid; wi < row_words; wi += kThreads) {
+            const Item x = classify(seg, after, shortbm, rlen, words, row_words, d_star, wi, R);
+            uint32_t n = 0;
+            if (w_star == 1) {
+                n = (uint32_t)popc64(x.ones);
+            } else {
+                for (uint64_t rest = x.big; rest; rest &= rest - 1) n += bit_weight(x, wi, __builtin_ctzll(rest)) == w_star;
+            }
+            wpre[wi] = n;
         }
         __syncthreads();
         if (wave == 0) {
@@ -517,27 +561,45 @@ __global__ __launch_bounds__(kThreads) void retrieve_kernel(RetrieveParams p) {
     __syncthreads();
 
     // ---- B6: select
-    // items (depth, word) are dealt to the wavefronts round robin; (d, wi) advance without divisions
-    for (int it = wave, d = 1, wi = wave; it < items; it += kWavesPerWG, wi += kWavesPerWG) {
-        while (wi >= row_words) { wi -= row_words; d++; }
-        const int r = wi * 64 + lane;
-        const uint64_t* bm = seg + (d - 1) * words;
-        const bool node = r < R && ((bm[wi] >> lane) & 1ull) && rlen[r] >= d;
-        const int w = node ? node_weight(bm[wi], lane, r, after[(d - 1) * words + wi]) : 0;
-        bool keep = node && (take_all || w > w_star || (w == w_star && d < d_star));
-        if (!take_all && d == d_star) {
-            const uint64_t e = __ballot(node && w == w_star);
-            const int rank = (int)wpre[wi] + popc64(e & ((1ull << lane) - 1ull));
-            keep = keep || (node && w == w_star && rank < need_d);
+    // eight threads per item, each with eight of its rows; the kept nodes of a thread take consecutive free slots
+    // (the slots are ordered afterwards)
+    for (int u = tid; u < items * 8; u += kThreads) {
+        const int it = u >> 3, d = it / row_words + 1, wi = it % row_words;
+        const uint64_t mine = 0xffull << (8 * (u & 7));
+        const Item x = classify(seg, after, shortbm, rlen, words, row_words, d, wi, R);
+        // weight-1 nodes are kept only if everything is, or if the boundary weight is 1 and the depth allows it
+        const bool ones_matter = take_all || (w_star == 1 && d <= d_star);
+        uint64_t keep = (x.big | (ones_matter ? x.ones : 0ull)) & mine;
+        if (!take_all) {
+            // drop what is too light; at the boundary depth, nodes of the boundary weight are taken in row order
+            const bool ranked = d == d_star;
+            int rank = 0;
+            if (ranked) {
+                rank = (int)wpre[wi];
+                const uint64_t below = x.node & ~(~0ull << (8 * (u & 7)));
+                if (w_star == 1) {
+                    rank += popc64(x.ones & below);
+                } else {
+                    for (uint64_t rest = x.big & below; rest; rest &= rest - 1)
+                        rank += bit_weight(x, wi, __builtin_ctzll(rest)) == w_star;
+                }
+            }
+            for (uint64_t rest = keep; rest; rest &= rest - 1) {
+                const int b = __builtin_ctzll(rest);
+                const int w = ((x.ones >> b) & 1ull) ? 1 : bit_weight(x, wi, b);
+                bool ok = w > w_star || (w == w_star && d < d_star);
+                if (ranked && w == w_star) ok = rank++ < need_d;
+                if (!ok) keep &= ~(1ull << b);
+            }
         }
-        const uint64_t km = __ballot(keep);
-        if (km) {
-            int basei = 0;
-            if (lane == 0) basei = atomicAdd(&s_misc[4], popc64(km));
-            basei = __shfl(basei, 0, 64);
-            if (keep) {
-                const int idx = basei + popc64(km & ((1ull << lane) - 1ull));
-                if (idx < c) { sel_key[idx] = ((uint32_t)d << 16) | (uint32_t)r; sel_wgt[idx] = (uint32_t)w; }
+        if (keep) {
+            int idx = atomicAdd(&s_misc[4], popc64(keep));
+            for (; keep; keep &= keep - 1, idx++) {
+                const int b = __builtin_ctzll(keep);
+                if (idx < c) {
+                    sel_key[idx] = ((uint32_t)d << 16) | (uint32_t)(wi * 64 + b);
+                    sel_wgt[idx] = ((x.ones >> b) & 1ull) ? 1u : (uint32_t)bit_weight(x, wi, b);
+                }
             }
         }
     }
@@ -712,6 +774,7 @@ extern "C" __attribute__((visibility("default"))) rest_status rest_retrieve(cons
     p.off_sel = (int32_t)off;  off = align16(off + (size_t)REST_MAX_NODES * 5 * 4);
     p.off_pos = (int32_t)off;  off = align16(off + (size_t)p.K * 4);
     p.off_after = (int32_t)off; off = align16(off + (size_t)p.m * p.words * 4);
+    p.off_short = (int32_t)off; off = align16(off + (size_t)p.words * 8);
     p.off_misc = (int32_t)off;
     size_t lds_bytes = off;
     const size_t top_bytes = (size_t)table_words(index->top_count) * 4;
