@@ -104,7 +104,20 @@ class Retrieved:
 
 
 def retrieve(corpus: np.ndarray, context: np.ndarray, n_max: int = 16, n_min: int = 2,
-             max_matches: int = 5000, cont_len: int = 10, one_pass: bool = False) -> Retrieved:
+             max_matches: int = 5000, cont_len: int = 10, one_pass: bool = False,
+             strided: bool = False) -> Retrieved:
+    """Algorithm 1.  The paper only says that the set S of matches can be large; which max_matches of
+    them are kept is a choice of this implementation: the first max_matches in suffix order, or, with
+    strided=True, an evenly spaced sample of the whole sorted range: of S occurrences in suffix order,
+    number i of the K kept ones is occurrence floor(i * S / K) (all of them if S <= K)."""
+    if strided:
+        count = retrieve(corpus, context, n_max, n_min, 0, cont_len, one_pass).match_count
+        full = retrieve(corpus, context, n_max, n_min, max(count, 1), cont_len, one_pass)
+        S, K = full.rows.shape[0], int(max_matches)
+        if S <= K:
+            return full
+        pick = np.array([(i * S) // K for i in range(K)], dtype=np.int64)
+        return Retrieved(full.matched_len, full.match_count, full.row_pos[pick], full.rows[pick], full.row_len[pick])
     corpus = np.ascontiguousarray(corpus)
     s = np.ascontiguousarray(context, dtype=np.int32)
     K, m = int(max_matches), int(cont_len)
@@ -197,12 +210,13 @@ def random_rows(n_rows: int, n_seq: int, seed: int, ctx_index: int) -> np.ndarra
 
 def draft_tree(corpus: np.ndarray, context: np.ndarray, n_max: int = 16, n_min: int = 2,
                max_matches: int = 5000, cont_len: int = 10, max_nodes: int = 64,
-               one_pass: bool = False, random_seqs: int = 0, seed: int = 0, ctx_index: int = 0) -> DraftTree:
+               one_pass: bool = False, random_seqs: int = 0, seed: int = 0, ctx_index: int = 0,
+               strided: bool = False) -> DraftTree:
     """One context -> draft tree: Algorithm 1, then Algorithm 2 with the
     candidates inserted in stream-position order, then the layout.
     random_seqs > 0: the ablation's strategy instead -- only random_seqs randomly drawn
     candidates (each already cut to cont_len tokens) go into the Trie."""
-    got = retrieve(corpus, context, n_max, n_min, max_matches, cont_len, one_pass)
+    got = retrieve(corpus, context, n_max, n_min, max_matches, cont_len, one_pass, strided)
     if random_seqs > 0:
         sel = random_rows(got.rows.shape[0], random_seqs, seed, ctx_index)
         got = Retrieved(got.matched_len, got.match_count, got.row_pos[sel], got.rows[sel], got.row_len[sel])

@@ -437,3 +437,49 @@ def test_random_selection_strategy():
             assert counts[tuple(path[::-1])] == tree.node_weight[i]
         some += tree.n_nodes > 8
     assert some >= 2
+
+
+def test_strided_match_sampling():
+    """Which occurrences are kept when there are more than max_matches: an evenly spaced sample of the sorted range
+    instead of its head."""
+    # brute force: every occurrence sorted by its whole suffix in Python, then ranks floor(i*S/K)
+    for n, vocab, seed in [(2000, 2, 31), (3000, 3, 32), (1500, 5, 33)]:
+        corpus = small_corpus(n, vocab, seed)
+        toks = [int(x) for x in corpus]
+        capped = 0
+        for qi in range(10):
+            ctx = small_corpus([2, 3, 4, 6, 17][qi % 5], vocab, seed * 10 + qi).astype(np.int32)
+            for K, m in [(7, 4), (64, 10), (1000, 3)]:
+                n_star, cnt, occ, _ = py_retrieve(corpus, ctx, 16, 2, 10 ** 9, m)
+                pick = occ if cnt <= K else [occ[(i * cnt) // K] for i in range(K)]
+                got = oracle.retrieve(corpus, ctx, 16, 2, K, m, strided=True)
+                assert (got.matched_len, got.match_count) == (n_star, cnt)
+                assert got.row_pos.tolist() == pick
+                for r, p in enumerate(pick):
+                    row = toks[p + n_star:p + n_star + m]
+                    assert got.rows[r, :len(row)].tolist() == row and got.row_len[r] == len(row)
+                    assert (got.rows[r, len(row):] == -1).all()
+                if cnt <= K:      # nothing to drop: the same rows as the head rule
+                    head = oracle.retrieve(corpus, ctx, 16, 2, K, m)
+                    np.testing.assert_array_equal(head.row_pos, got.row_pos)
+                capped += cnt > K
+        assert capped >= 3
+    # closed form: the pair (5, 6) is followed 700 times by 1 and 300 times by 2 (separators 9 keep longer matches
+    # away).  Sorted, the 700 come first, so the head rule with K = 100 sees only token 1; the evenly spaced sample
+    # takes ranks 0, 10, ..., 990: exactly 70 and 30.
+    order = np.array([1] * 700 + [2] * 300)
+    order = order[np.argsort(synth.randint(77, [0], 1000, 1 << 30), kind="stable")]
+    corpus = np.concatenate([[5, 6, int(a), 9] for a in order]).astype(np.int32)
+    ctx = np.array([3, 5, 6], dtype=np.int32)
+    head = oracle.draft_tree(corpus, ctx, max_matches=100, cont_len=1, max_nodes=8)
+    even = oracle.draft_tree(corpus, ctx, max_matches=100, cont_len=1, max_nodes=8, strided=True)
+    assert head.match_count == even.match_count == 1000 and head.matched_len == 2
+    assert head.draft_tokens[:head.n_nodes].tolist() == [1] and head.node_weight[0] == 100
+    assert even.draft_tokens[:even.n_nodes].tolist() == [1, 2] and even.node_weight[:2].tolist() == [70, 30]
+    # with random selection on top, the draws index the strided sample
+    got = oracle.retrieve(corpus, ctx, max_matches=100, cont_len=1, strided=True)
+    sel = oracle.random_rows(100, 8, 5, 3)
+    tree = oracle.draft_tree(corpus, ctx, max_matches=100, cont_len=1, max_nodes=8, strided=True, random_seqs=8, seed=5,
+                             ctx_index=3)
+    want = Counter(int(got.rows[r, 0]) for r in sel)
+    assert {int(t): int(w) for t, w in zip(tree.draft_tokens[:tree.n_nodes], tree.node_weight)} == dict(want)
