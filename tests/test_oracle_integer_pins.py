@@ -468,7 +468,7 @@ def test_strided_match_sampling():
     # away).  Sorted, the 700 come first, so the head rule with K = 100 sees only token 1; the evenly spaced sample
     # takes ranks 0, 10, ..., 990: exactly 70 and 30.
     order = np.array([1] * 700 + [2] * 300)
-    order = order[np.argsort(synth.randint(77, [0], 1000, 1 << 30), kind="stable")]
+    order = order[np.argsort(synth.randint(77, np.arange(1000), 0, 1 << 30), kind="stable")]
     corpus = np.concatenate([[5, 6, int(a), 9] for a in order]).astype(np.int32)
     ctx = np.array([3, 5, 6], dtype=np.int32)
     head = oracle.draft_tree(corpus, ctx, max_matches=100, cont_len=1, max_nodes=8)
