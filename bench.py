@@ -366,7 +366,7 @@ def ablation(rest, torch, synth, np, dev):
     index = rest.rest_build_index(torch.from_numpy(corp.tokens).to(dev), 4)
     prompts = [corp.tokens[s:s + 48].astype(np.int32) for s in (1000, 250_000, 500_000, 750_000)]
 
-    def run(n_max, c, random_seqs, cont_len, n_new=160):
+    def run(n_max, c, random_seqs, cont_len, n_new=160, max_matches=None, strided=False):
         gen, steps = 0, 0
         for pi, prompt in enumerate(prompts):
             seq = [int(x) for x in prompt]
@@ -374,8 +374,9 @@ def ablation(rest, torch, synth, np, dev):
             while made < n_new:
                 ctx = torch.tensor([seq[-64:]], dtype=torch.int32, device=dev)
                 ln = torch.tensor([ctx.shape[1]], dtype=torch.int32, device=dev)
-                tree = rest.rest_retrieve(index, ctx, ln, n_max=n_max, n_min=min(2, n_max), max_matches=w.max_matches,
-                                          cont_len=cont_len, max_nodes=c, random_seqs=random_seqs, seed=1000 * pi + steps)
+                tree = rest.rest_retrieve(index, ctx, ln, n_max=n_max, n_min=min(2, n_max),
+                                          max_matches=max_matches or w.max_matches, cont_len=cont_len, max_nodes=c,
+                                          random_seqs=random_seqs, seed=1000 * pi + steps, strided=strided)
                 n = int(tree.n_nodes[0])
                 t_tok = tree.draft_tokens[0, :n].cpu().tolist()
                 t_par = tree.parent_idx[0, :n].cpu().tolist()
@@ -397,7 +398,10 @@ def ablation(rest, torch, synth, np, dev):
     res = {"datastore_tokens": w.n_tokens, "prompts": len(prompts), "tokens_per_prompt": 160,
            "M_trie_c64_nmax16": run(16, 64, 0, 10), "M_random_8x8_nmax16": run(16, 64, 8, 8),
            "M_by_n_max_trie_c64": {n: run(n, 64, 0, 10) for n in (2, 4, 8, 16)},
-           "M_by_c_trie_nmax16": {c: run(16, c, 0, 10) for c in (4, 16, 64, 256)}}
+           "M_by_c_trie_nmax16": {c: run(16, c, 0, 10) for c in (4, 16, 64, 256)},
+           # which occurrences a small cap keeps (short suffixes, so that match sets are large)
+           "M_nmax2_by_max_matches_head_vs_evenly_spaced": {
+               K: [run(2, 64, 0, 10, max_matches=K), run(2, 64, 0, 10, max_matches=K, strided=True)] for K in (8, 32, 128)}}
     return res
 
 

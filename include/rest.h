@@ -121,9 +121,10 @@ void rest_index_destroy(rest_index* index);
  *     of s; the first n for which q occurs in the stream is matched_len and
  *     match_count its number of occurrences (0 / 0 if none, or if len < n_min).
  *     The paper's loop has no lower bound; n_min >= 1 supplies one.
- *  2. Of the occurrences, the first max_matches in suffix-array order are kept;
- *     the candidate of an occurrence is the cont_len tokens following it, cut
- *     at the end of the stream ("Hyperparameters": m).
+ *  2. Of the occurrences, the first max_matches in suffix-array order are kept
+ *     (the paper gives no rule for a large match set; see `strided` below for
+ *     the other rule offered); the candidate of an occurrence is the cont_len
+ *     tokens following it, cut at the end of the stream ("Hyperparameters": m).
  *  3. Algorithm 2: the Trie of all non-empty candidate prefixes, node weight =
  *     number of candidates with that prefix; the max_nodes heaviest nodes are
  *     kept, ties broken by (depth ascending, prefix lexicographically
@@ -151,6 +152,12 @@ typedef struct {
      * finaliser; equal draws collapse. */
     int32_t random_seqs;
     uint64_t seed;
+    /* 0: keep the first max_matches occurrences in suffix-array order.  1: of S > max_matches
+     * occurrences keep an evenly spaced sample of the sorted range, number i (0-based) of the K kept
+     * being occurrence floor(i*S/K), so that node weights estimate the frequencies over all
+     * occurrences and not over the lexicographically smallest ones.  No difference when S <= K. */
+    int32_t strided;
+    int32_t reserved_;    /* set to 0 */
 } rest_retrieve_params;
 
 typedef struct {

@@ -54,7 +54,7 @@ class RestError(RuntimeError):
 class rest_retrieve_params(ctypes.Structure):
     _fields_ = [("n_max", ctypes.c_int32), ("n_min", ctypes.c_int32), ("max_matches", ctypes.c_int32),
                 ("cont_len", ctypes.c_int32), ("max_nodes", ctypes.c_int32), ("random_seqs", ctypes.c_int32),
-                ("seed", ctypes.c_uint64)]
+                ("seed", ctypes.c_uint64), ("strided", ctypes.c_int32), ("reserved_", ctypes.c_int32)]
 
 
 class rest_tree(ctypes.Structure):
@@ -267,14 +267,15 @@ def rest_retrieve_workspace_bytes(B: int, n_max=16, n_min=2, max_matches=5000, c
 
 def rest_retrieve(index: RestIndex, contexts: torch.Tensor, ctx_len: torch.Tensor, out: Tree | None = None,
                   n_max=16, n_min=2, max_matches=5000, cont_len=10, max_nodes=64,
-                  workspace: torch.Tensor | None = None, random_seqs: int = 0, seed: int = 0) -> Tree:
+                  workspace: torch.Tensor | None = None, random_seqs: int = 0, seed: int = 0,
+                  strided: bool = False) -> Tree:
     """contexts [B, ctx_stride] int32, ctx_len [B] int32 (device).  Enqueues on the current stream.
     random_seqs > 0: the ablation's strategy (that many randomly drawn candidates instead of the whole Trie)."""
     assert contexts.dim() == 2 and contexts.is_contiguous() and ctx_len.is_contiguous()
     B, stride = contexts.shape
     if out is None:
         out = Tree.empty(B, max_nodes, contexts.device)
-    prm = rest_retrieve_params(n_max, n_min, max_matches, cont_len, max_nodes, random_seqs, seed)
+    prm = rest_retrieve_params(n_max, n_min, max_matches, cont_len, max_nodes, random_seqs, seed, int(strided), 0)
     tree = out.as_struct()
     ws_ptr = workspace.data_ptr() if workspace is not None else None
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0

@@ -53,6 +53,7 @@ struct RetrieveParams {
     int32_t n_max, n_min, K, m, c, mask_words;
     int32_t random_seqs;  // 0, or the number of randomly drawn candidates that replace the kept ones
     uint64_t seed;
+    int32_t strided;      // more occurrences than K: keep an evenly spaced sample of the range instead of its head
     rest_tree out;
     // LDS layout of phase B (byte offsets into dynamic LDS)
     int32_t words;        // bitmap words per depth = K/64 + 1
@@ -345,6 +346,15 @@ __global__ __launch_bounds__(kThreads) void retrieve_kernel(RetrieveParams p) {
     }
     const int m = p.m;
     const int words = p.words;
+    // Kept candidate i is entry lo + i of the suffix array, or, sampling S > K occurrences evenly, entry
+    // lo + floor(i*S/K) = lo + i*(S/K) + floor(i*(S%K)/K); i and S%K are below K <= 8192, so 32 bits hold the product.
+    const uint32_t S = hi - lo;
+    const bool spaced = p.strided != 0 && S > (uint32_t)p.K;
+    const uint32_t step_q = spaced ? S / (uint32_t)p.K : 1u, step_r = spaced ? S % (uint32_t)p.K : 0u;
+    auto kept_entry = [&](int r) -> uint32_t {
+        const uint32_t i = drawn ? (uint32_t)s_pick[r] : (uint32_t)r;
+        return spaced ? lo + i * step_q + (i * step_r) / (uint32_t)p.K : lo + i;
+    };
 
     // ---------------- phase B LDS (aliases the key table, which is dead now)
     uint64_t* seg = (uint64_t*)(lds + p.off_seg);        // [m][words] segment-start bits per depth
@@ -371,7 +381,7 @@ __global__ __launch_bounds__(kThreads) void retrieve_kernel(RetrieveParams p) {
         int32_t tok[REST_MAX_CONT_LEN];
         int len = 0;
         if (r < R) {
-            const uint32_t start = load_sa<SaT>(p.sa, lo + (drawn ? (uint32_t)s_pick[r] : (uint32_t)r));
+            const uint32_t start = load_sa<SaT>(p.sa, kept_entry(r));
             rowpos[r] = start;
             const uint64_t pos = (uint64_t)start + n_star;
             const uint64_t left = p.n_tokens > pos ? p.n_tokens - pos : 0;
@@ -393,7 +403,7 @@ __global__ __launch_bounds__(kThreads) void retrieve_kernel(RetrieveParams p) {
         bool run = true;
         uint64_t ppos = 0;
         if (lane == 0 && r > 0 && r < R) {
-            ppos = (uint64_t)load_sa<SaT>(p.sa, lo + (drawn ? (uint32_t)s_pick[r - 1] : (uint32_t)(r - 1))) + n_star;
+            ppos = (uint64_t)load_sa<SaT>(p.sa, kept_entry(r - 1)) + n_star;
             const uint64_t left = p.n_tokens > ppos ? p.n_tokens - ppos : 0;
             plen = left < (uint64_t)m ? (int)left : m;
         }
@@ -681,6 +691,7 @@ bool params_ok(const rest_retrieve_params* q) {
     if (q->cont_len < 1 || q->cont_len > REST_MAX_CONT_LEN) return false;
     if (q->max_nodes < 1 || q->max_nodes > REST_MAX_NODES) return false;
     if (q->random_seqs < 0 || q->random_seqs > 64) return false;
+    if (q->strided != 0 && q->strided != 1) return false;
     return true;
 }
 
@@ -763,6 +774,7 @@ extern "C" __attribute__((visibility("default"))) rest_status rest_retrieve(cons
     p.mask_words = (q->max_nodes + 63) / 64;
     p.random_seqs = q->random_seqs;
     p.seed = q->seed;
+    p.strided = q->strided;
     p.out = *out;
     p.words = p.K / 64 + 1;
     size_t off = 0;

@@ -97,7 +97,7 @@ def test_calls_reject_null_and_bad_arguments_before_touching_the_gpu(rest):
     assert lib.rest_index_from_sa(ctypes.c_void_p(16), None, 10, 4, 4, None, ctypes.byref(h)) == rest.REST_INVALID_ARG
     assert lib.rest_index_view(None, None, None, None, None, None) == rest.REST_INVALID_ARG
     lib.rest_index_destroy(None)
-    prm = rest.rest_retrieve_params(16, 2, 100, 10, 64, 0, 0)
+    prm = rest.rest_retrieve_params(16, 2, 100, 10, 64, 0, 0, 0, 0)
     tree = rest.rest_tree()
     assert lib.rest_retrieve(None, None, None, 1, 8, ctypes.byref(prm), ctypes.byref(tree), None, 0, None) == rest.REST_INVALID_ARG
     assert lib.rest_accept(None, ctypes.byref(tree), 1, 64, 10, None, None, None, None) == rest.REST_INVALID_ARG

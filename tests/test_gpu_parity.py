@@ -315,6 +315,45 @@ def test_random_selection_strategy_matches_oracle(n_seq, m, c, seed):
     assert rich >= 3 or n_seq == 1
 
 
+@pytest.mark.parametrize("K,m,c,n_seq,sa_bytes", [(1, 10, 64, 0, 4), (7, 10, 64, 0, 4), (64, 10, 64, 0, 8), (300, 16, 256, 0, 4),
+                                                  (100, 8, 64, 8, 4), (8192, 10, 64, 0, 4)])
+def test_evenly_spaced_match_sample_matches_oracle(K, m, c, n_seq, sa_bytes):
+    """More occurrences than max_matches: the kept ones are spread over the whole sorted range."""
+    corp = synth.make_corpus(200_000, 8, 40)
+    ctx, lens = synth.make_contexts(corp, 24, 64, 23)
+    t = corp.tokens.astype(np.int64)      # eight contexts end in the most frequent pairs: hundreds to thousands of occurrences
+    pairs, cnt = np.unique(t[:-1] * 65536 + t[1:], return_counts=True)
+    top = pairs[np.argsort(-cnt, kind="stable")[:8]]
+    ctx[:8, -2] = top >> 16
+    ctx[:8, -1] = top & 65535
+    ctx[:8, -3] = 31_999
+    index = rest.rest_build_index(dev(corp.tokens), sa_bytes)
+    out = rest.rest_retrieve(index, dev(ctx), dev(lens), max_matches=K, cont_len=m, max_nodes=c, random_seqs=n_seq, seed=9,
+                             strided=True)
+    head = rest.rest_retrieve(index, dev(ctx), dev(lens), max_matches=K, cont_len=m, max_nodes=c, random_seqs=n_seq, seed=9)
+    torch.cuda.synchronize()
+    words = (c + 63) // 64
+    capped = differs = 0
+    for b in range(24):
+        want = oracle.draft_tree(corp.tokens, ctx[b], 16, 2, K, m, c, random_seqs=n_seq, seed=9, ctx_index=b, strided=True)
+        assert (int(out.matched_len[b]), int(out.match_count[b]), int(out.n_nodes[b])) == \
+            (want.matched_len, want.match_count, want.n_nodes), b
+        np.testing.assert_array_equal(out.draft_tokens[b].cpu().numpy(), want.draft_tokens)
+        np.testing.assert_array_equal(out.parent_idx[b].cpu().numpy(), want.parent_idx)
+        np.testing.assert_array_equal(out.pos_ids[b].cpu().numpy(), want.pos_ids)
+        np.testing.assert_array_equal(out.node_weight[b].cpu().numpy(), want.node_weight)
+        np.testing.assert_array_equal(out.tree_mask[b].cpu().numpy().view(np.uint64).reshape(c, words), want.tree_mask)
+        if want.match_count > K:
+            capped += 1
+            differs += not torch.equal(out.node_weight[b], head.node_weight[b]) or \
+                not torch.equal(out.draft_tokens[b], head.draft_tokens[b])
+        else:                               # nothing dropped: the option changes nothing
+            assert torch.equal(out.draft_tokens[b], head.draft_tokens[b])
+            assert torch.equal(out.node_weight[b], head.node_weight[b])
+    if K < 8192:
+        assert capped >= 6 and (differs >= 3 or K == 1), (capped, differs)
+
+
 def test_index_file_round_trip_and_exchange_with_the_oracle(tmp_path):
     corp = synth.make_corpus(300_000, 4, 30)
     d_corpus = dev(corp.tokens)
