@@ -81,6 +81,20 @@ def suffix_array(corpus: np.ndarray) -> np.ndarray:
     return sa
 
 
+def prefix_sorted_array(corpus: np.ndarray, depth: int) -> np.ndarray:
+    """The depth-limited index: all positions ordered by their first `depth` tokens only (the end of the
+    stream smaller than every token), positions with equal such prefixes in ascending position order.
+    Algorithm 1 looks at no more than n_max tokens of a suffix and Algorithm 2 at the cont_len after
+    them, so for depth >= n_max + cont_len this array serves every retrieval exactly as the suffix array
+    does ("Retrieving from the datastore")."""
+    corpus = np.ascontiguousarray(corpus)
+    n, depth = corpus.shape[0], int(depth)
+    assert depth >= 1
+    tok = np.concatenate([corpus.astype(np.int64) + 1, np.zeros(depth, dtype=np.int64)])
+    columns = [tok[j:j + n] for j in range(depth)]
+    return np.lexsort(columns[::-1]).astype(np.int64)      # stable: the last key given is the primary one
+
+
 def check_suffix_array(corpus: np.ndarray, sa: np.ndarray) -> int:
     """-1 if `sa` is the suffix array of `corpus` by definition (a permutation
     whose adjacent suffixes strictly increase), else the first bad rank."""
@@ -244,7 +258,8 @@ def mask_from_parents(parent_idx: np.ndarray, n_nodes: int, words: int | None = 
 # ---------------------------------------------------------------------------
 # The index file ("Datastore construction": built once, reused): a 64-byte
 # little-endian header -- "RESTSA01", n_tokens u64, token_bytes i32, sa_bytes
-# i32, fingerprint u64, zeros -- then the suffix array.  The fingerprint ties
+# i32, fingerprint u64, sort depth i32 (0 = a full suffix array, else the number
+# of tokens the positions are ordered by), zeros -- then the array.  The fingerprint ties
 # the array to its token stream: the sum over i of
 # splitmix64-finaliser(token_i + (i+1) * 0x9E3779B97F4A7C15) modulo 2^64.
 # ---------------------------------------------------------------------------
@@ -262,25 +277,25 @@ def corpus_fingerprint(corpus: np.ndarray) -> int:
     return int(total)
 
 
-def write_index_file(path: str, corpus: np.ndarray, sa: np.ndarray) -> None:
+def write_index_file(path: str, corpus: np.ndarray, sa: np.ndarray, sort_depth: int = 0) -> None:
     import struct
     assert sa.dtype in (np.int32, np.int64) and sa.size == corpus.size
     with open(path, "wb") as f:
-        f.write(b"RESTSA01" + struct.pack("<QiiQ", corpus.size, _token_bytes(corpus), sa.dtype.itemsize,
-                                          corpus_fingerprint(corpus)) + bytes(32))
+        f.write(b"RESTSA01" + struct.pack("<QiiQi", corpus.size, _token_bytes(corpus), sa.dtype.itemsize,
+                                          corpus_fingerprint(corpus), sort_depth) + bytes(28))
         f.write(np.ascontiguousarray(sa).tobytes())
 
 
 def read_index_file(path: str):
-    """Returns (n_tokens, token_bytes, sa_bytes, fingerprint, suffix array)."""
+    """Returns (n_tokens, token_bytes, sa_bytes, fingerprint, array, sort depth)."""
     import struct
     with open(path, "rb") as f:
         head = f.read(64)
-        assert len(head) == 64 and head[:8] == b"RESTSA01" and head[32:] == bytes(32)
-        n, tb, sb, fp = struct.unpack("<QiiQ", head[8:32])
+        assert len(head) == 64 and head[:8] == b"RESTSA01" and head[36:] == bytes(28)
+        n, tb, sb, fp, depth = struct.unpack("<QiiQi", head[8:36])
         sa = np.frombuffer(f.read(), dtype=np.int32 if sb == 4 else np.int64)
-    assert sa.size == n
-    return n, tb, sb, fp, sa
+    assert sa.size == n and depth >= 0
+    return n, tb, sb, fp, sa, depth
 
 
 # ---------------------------------------------------------------------------

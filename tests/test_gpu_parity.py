@@ -361,7 +361,7 @@ def test_index_file_round_trip_and_exchange_with_the_oracle(tmp_path):
     p = str(tmp_path / "a.restsa")
     rest.rest_index_save(index, p)
     # the oracle reads what the library wrote: header, fingerprint, and the array is the suffix array by definition
-    n, tb, sb, fp, sa = oracle.read_index_file(p)
+    n, tb, sb, fp, sa, depth = oracle.read_index_file(p)
     assert (n, tb, sb) == (300_000, 4, 4) and fp == oracle.corpus_fingerprint(corp.tokens)
     assert oracle.check_suffix_array(corp.tokens, sa) == -1
     # the library reads its own file back: same array, same retrieval results

@@ -385,9 +385,13 @@ def test_index_file_fingerprint_and_round_trip(tmp_path):
     raw = open(p, "rb").read()
     assert len(raw) == 64 + 6 * 4 and raw[:8] == b"RESTSA01" and raw[8:16] == (6).to_bytes(8, "little")
     assert raw[16:20] == (4).to_bytes(4, "little") and raw[20:24] == (4).to_bytes(4, "little")
-    n, tb, sb, fp, back = oracle.read_index_file(p)
-    assert (n, tb, sb, fp) == (6, 4, 4, oracle.corpus_fingerprint(corpus))
+    n, tb, sb, fp, back, depth = oracle.read_index_file(p)
+    assert (n, tb, sb, fp, depth) == (6, 4, 4, oracle.corpus_fingerprint(corpus), 0) and raw[32:64] == bytes(32)
     np.testing.assert_array_equal(back, sa)
+    oracle.write_index_file(p, corpus, oracle.prefix_sorted_array(corpus, 2), sort_depth=2)
+    raw = open(p, "rb").read()
+    assert raw[32:36] == (2).to_bytes(4, "little") and raw[36:64] == bytes(28)
+    assert oracle.read_index_file(p)[5] == 2 and oracle.read_index_file(p)[4].tolist() == [1, 4, 0, 3, 2, 5]
 
 
 def test_random_selection_strategy():
@@ -483,3 +487,64 @@ def test_strided_match_sampling():
                              ctx_index=3)
     want = Counter(int(got.rows[r, 0]) for r in sel)
     assert {int(t): int(w) for t, w in zip(tree.draft_tokens[:tree.n_nodes], tree.node_weight)} == dict(want)
+
+
+def test_depth_limited_order():
+    """Positions ordered by their first `depth` tokens only, equal prefixes by position."""
+    # by hand: stream 1 0 1 1 0 2, depth 2: prefixes (1,0)@0 (0,1)@1 (1,1)@2 (1,0)@3 (0,2)@4 (2)@5
+    corpus = np.array([1, 0, 1, 1, 0, 2], np.int32)
+    assert oracle.prefix_sorted_array(corpus, 2).tolist() == [1, 4, 0, 3, 2, 5]
+    assert oracle.prefix_sorted_array(corpus, 1).tolist() == [1, 4, 0, 2, 3, 5]
+    for n, vocab, seed, dtype in [(500, 2, 41, np.int32), (2000, 3, 42, np.uint16), (1500, 30, 43, np.int32)]:
+        corpus = small_corpus(n, vocab, seed, dtype)
+        toks = [int(x) for x in corpus]
+        # depth 1 is a stable sort of the tokens; a depth no repeat reaches gives the suffix array itself
+        np.testing.assert_array_equal(oracle.prefix_sorted_array(corpus, 1), np.argsort(corpus, kind="stable"))
+        np.testing.assert_array_equal(oracle.prefix_sorted_array(corpus, n), oracle.suffix_array(corpus))
+        for depth in (2, 5, 26):
+            arr = oracle.prefix_sorted_array(corpus, depth)
+            assert arr.tolist() == sorted(range(n), key=lambda p: (tuple(toks[p:p + depth]), p))
+            # against the suffix array: same multiset, and position i's rank can only move within the run of
+            # suffixes sharing its first `depth` tokens
+            sa = oracle.suffix_array(corpus)
+            assert [tuple(toks[p:p + depth]) for p in arr] == [tuple(toks[p:p + depth]) for p in sa]
+
+
+def test_depth_limited_order_serves_retrieval_like_the_suffix_array():
+    """Algorithm 1 + 2 evaluated on an explicit ordering of the positions (a range of occurrences, its first K
+    members, their continuations): with the depth-limited order of depth n_max + cont_len the drafts equal those of
+    the definition, which orders occurrences by their whole suffixes; with a smaller depth they need not."""
+    def drafts_on(order, corpus, ctx, n_max, n_min, K, m, c):
+        toks = corpus.tolist()
+        for n in range(min(n_max, len(ctx)), n_min - 1, -1):
+            q = ctx[len(ctx) - n:].tolist()
+            occ = [p for p in order.tolist() if toks[p:p + n] == q][:K]
+            if occ:
+                rows = np.full((len(occ), m), -1, np.int32)
+                lens = np.zeros(len(occ), np.int32)
+                for r, p in enumerate(occ):
+                    cont = toks[p + n:p + n + m]
+                    rows[r, :len(cont)] = cont
+                    lens[r] = len(cont)
+                return oracle.select_drafts(rows, lens, c, np.argsort(np.array(occ), kind="stable"))
+        return None
+    n_max, m, K, c = 6, 4, 5, 12
+    differs_when_too_shallow = 0
+    for n, vocab, seed in [(1500, 2, 51), (2500, 3, 52)]:
+        corpus = small_corpus(n, vocab, seed)
+        full = oracle.prefix_sorted_array(corpus, n_max + m)
+        shallow = oracle.prefix_sorted_array(corpus, 3)
+        for qi in range(16):
+            ctx = small_corpus(3 + qi % 6, vocab, seed * 10 + qi).astype(np.int32)
+            want = oracle.draft_tree(corpus, ctx, n_max, 2, K, m, c)
+            got = drafts_on(full, corpus, ctx, n_max, 2, K, m, c)
+            if got is None:
+                assert want.n_nodes == 0
+                continue
+            assert got.n_nodes == want.n_nodes
+            for name in ("draft_tokens", "parent_idx", "pos_ids", "node_weight", "tree_mask"):
+                np.testing.assert_array_equal(getattr(got, name), getattr(want, name), err_msg=name)
+            bad = drafts_on(shallow, corpus, ctx, n_max, 2, K, m, c)
+            differs_when_too_shallow += not (np.array_equal(bad.draft_tokens, want.draft_tokens) and
+                                             np.array_equal(bad.node_weight, want.node_weight))
+    assert differs_when_too_shallow >= 3
