@@ -88,6 +88,14 @@ def main() -> int:
     torch.cuda.synchronize()
     t_build = time.time() - t0
     note(f"index built in {t_build:.2f} s")
+    t_build32 = None
+    if not args.no_extras:      # the depth-limited build of the same stream (enough for n_max + cont_len <= 32)
+        t0 = time.time()
+        lim = rest.rest_build_index_prefix(d_corpus, w.sa_bytes, 32)
+        torch.cuda.synchronize()
+        t_build32 = time.time() - t0
+        note(f"depth-32 index built in {t_build32:.2f} s (ordered by {lim.sort_depth or 'all'} tokens)")
+        del lim
 
     Nb, H, D, P, c = (w.layers if B == 1 else B), w.heads, w.head_dim, w.kv_len, w.max_nodes
     Lk = P + c
@@ -181,7 +189,8 @@ def main() -> int:
                      "traffic": traffic, "algorithmic_bytes_per_launch": alg_bytes,
                      "avg_launch_us": round(attn_ms * 1e3, 2), "launches_timed": len(attn_samples),
                      "p10_p50_p90_us": [round(attn_samples[int(len(attn_samples) * f)] * 1e3, 1) for f in (0.1, 0.5, 0.9)]},
-        "extra": {"index_build_s": round(t_build, 3), "corpus_gen_s": round(t_gen, 2),
+        "extra": {"index_build_s": round(t_build, 3),
+                  "index_build_depth32_s": None if t_build32 is None else round(t_build32, 3), "corpus_gen_s": round(t_gen, 2),
                   "contexts_per_s": round(B * 1e3 / ms_per_step, 1),
                   "tree_nodes_per_context": [int(x) for t in trees for x in t.n_nodes.tolist()][:32],
                   "matched_len_per_context": [int(x) for t in trees for x in t.matched_len.tolist()][:32]},

@@ -88,6 +88,22 @@ typedef struct rest_index rest_index;
 rest_status rest_build_index(const void* d_corpus, uint64_t n_tokens, int32_t token_bytes,
                              int32_t sa_bytes, void* stream, rest_index** out);
 
+/* The same with a depth limit: positions are ordered by their first `depth`
+ * tokens only (depth is rounded up to a power of two >= 2; 0 = no limit), and
+ * positions whose prefixes of that length are equal stay in ascending position
+ * order.  Algorithm 1 reads at most n_max tokens of a suffix and Algorithm 2
+ * the cont_len after them, so every call of rest_retrieve with
+ * n_max + cont_len <= depth returns what it returns on the full suffix array
+ * (others are refused with REST_UNSUPPORTED), while streams with long repeats
+ * (duplicated documents) need far fewer doubling rounds.  If the rounds leave
+ * no two equal prefixes the result is the suffix array and is marked so. */
+rest_status rest_build_index_prefix(const void* d_corpus, uint64_t n_tokens, int32_t token_bytes,
+                                    int32_t sa_bytes, int32_t depth, void* stream, rest_index** out);
+
+/* Number of tokens the handle's array is ordered by; 0 = a full suffix array;
+ * -1 for a NULL handle. */
+int32_t rest_index_sort_depth(const rest_index* index);
+
 /* Wraps a caller-supplied suffix array (e.g. one built elsewhere or loaded
  * from disk); both arrays are borrowed.  The array is trusted, not checked.
  * Only the small search table is computed (synchronises `stream`). */
@@ -101,7 +117,7 @@ rest_status rest_index_view(const rest_index* index, const void** d_corpus, cons
 /* Datastore persistence ("Datastore construction": the index is built once and
  * reused).  rest_index_save writes the suffix array behind a 64-byte header
  * ("RESTSA01", n_tokens u64, token_bytes i32, sa_bytes i32, a 64-bit
- * fingerprint of the token stream, zero padding; little endian) to the host
+ * fingerprint of the token stream, the sort depth i32, zero padding; little endian) to the host
  * file `path`.  rest_index_load reads such a file for the stream at d_corpus
  * (borrowed, as in rest_build_index): length, token width and fingerprint
  * must agree with the file's, else REST_BAD_FILE; the handle owns the array.

@@ -42,6 +42,7 @@ EXPORTS = [
     "rest_index_destroy", "rest_retrieve_workspace_bytes", "rest_retrieve",
     "rest_tree_attention_workspace_bytes", "rest_tree_attention", "rest_accept",
     "rest_rope_append", "rest_kv_compact", "rest_sample_ids", "rest_index_save", "rest_index_load",
+    "rest_build_index_prefix", "rest_index_sort_depth",
 ]
 
 
@@ -85,6 +86,11 @@ _lib.rest_version.restype = ctypes.c_char_p
 _lib.rest_build_index.restype = ctypes.c_int32
 _lib.rest_build_index.argtypes = [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p,
                                   ctypes.POINTER(ctypes.c_void_p)]
+_lib.rest_build_index_prefix.restype = ctypes.c_int32
+_lib.rest_build_index_prefix.argtypes = [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                         ctypes.c_void_p, ctypes.POINTER(ctypes.c_void_p)]
+_lib.rest_index_sort_depth.restype = ctypes.c_int32
+_lib.rest_index_sort_depth.argtypes = [ctypes.c_void_p]
 _lib.rest_index_from_sa.restype = ctypes.c_int32
 _lib.rest_index_from_sa.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint64, ctypes.c_int32, ctypes.c_int32,
                                     ctypes.c_void_p, ctypes.POINTER(ctypes.c_void_p)]
@@ -165,6 +171,10 @@ class RestIndex:
             raise RestError(st, "rest_index_view")
         return c.value, s.value, n.value, tb.value, sb.value
 
+    @property
+    def sort_depth(self) -> int:
+        return int(_lib.rest_index_sort_depth(self.handle))
+
     def suffix_array(self) -> torch.Tensor:
         """Device copy of the suffix array held by the handle (int32 or int64)."""
         _, s, n, _, sb = self.view()
@@ -202,6 +212,17 @@ def rest_build_index(corpus: torch.Tensor, sa_bytes: int = 4) -> RestIndex:
     st = _lib.rest_build_index(_dev(corpus), corpus.numel(), _token_bytes(corpus), sa_bytes, _stream(), ctypes.byref(h))
     if st != REST_OK:
         raise RestError(st, "rest_build_index")
+    return RestIndex(h.value, corpus, None)
+
+
+def rest_build_index_prefix(corpus: torch.Tensor, sa_bytes: int = 4, depth: int = 32) -> RestIndex:
+    """Positions ordered by their first `depth` tokens only (enough for n_max + cont_len <= depth)."""
+    assert corpus.is_contiguous() and corpus.dim() == 1
+    h = ctypes.c_void_p()
+    st = _lib.rest_build_index_prefix(_dev(corpus), corpus.numel(), _token_bytes(corpus), sa_bytes, depth, _stream(),
+                                      ctypes.byref(h))
+    if st != REST_OK:
+        raise RestError(st, "rest_build_index_prefix")
     return RestIndex(h.value, corpus, None)
 
 

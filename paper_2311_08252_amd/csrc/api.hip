@@ -35,6 +35,7 @@ extern "C" __attribute__((visibility("default"))) rest_status rest_index_from_sa
     idx->sa_bytes = sa_bytes;
     idx->top_count = 0;
     idx->owns_sa = 0;
+    idx->sort_depth = 0;
     rest_status st = rest_internal_make_top_table(idx, (hipStream_t)stream);
     if (st != REST_OK) {
         rest_index_destroy(idx);
@@ -53,6 +54,10 @@ extern "C" __attribute__((visibility("default"))) rest_status rest_index_view(co
     if (token_bytes) *token_bytes = index->token_bytes;
     if (sa_bytes) *sa_bytes = index->sa_bytes;
     return REST_OK;
+}
+
+extern "C" __attribute__((visibility("default"))) int32_t rest_index_sort_depth(const rest_index* index) {
+    return index ? index->sort_depth : -1;
 }
 
 extern "C" __attribute__((visibility("default"))) void rest_index_destroy(rest_index* index) {

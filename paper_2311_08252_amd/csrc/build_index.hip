@@ -267,7 +267,15 @@ struct Scratch {
 
 extern "C" __attribute__((visibility("default"))) rest_status rest_build_index(const void* d_corpus, uint64_t n, int32_t token_bytes, int32_t sa_bytes,
                                         void* stream_, rest_index** out) {
+    return rest_build_index_prefix(d_corpus, n, token_bytes, sa_bytes, 0, stream_, out);
+}
+
+// depth > 0: doubling stops once the positions are ordered by their first 2h >= depth tokens; every round sorts
+// (position order, key) pairs stably from scratch, so positions with equal prefixes stay in ascending order.
+extern "C" __attribute__((visibility("default"))) rest_status rest_build_index_prefix(const void* d_corpus, uint64_t n, int32_t token_bytes, int32_t sa_bytes,
+                                               int32_t depth, void* stream_, rest_index** out) {
     if (!d_corpus || !out) return REST_INVALID_ARG;
+    if (depth < 0 || depth > (1 << 30)) return REST_INVALID_ARG;
     if (token_bytes != 2 && token_bytes != 4) return REST_INVALID_ARG;
     if (sa_bytes != 4 && sa_bytes != 8) return REST_INVALID_ARG;
     if (n < 1 || n > 0xFFFFFFFEull) return REST_INVALID_ARG;
@@ -303,6 +311,7 @@ extern "C" __attribute__((visibility("default"))) rest_status rest_build_index(c
     REST_HIP_TRY(hipStreamSynchronize(st));
 
     int cur = 0;
+    int32_t sorted_by = 0;   // tokens the final order looks at; 0 = all of them
     for (uint64_t h = 1;; h *= 2) {
         const int bits = bit_length(max_rank);
         const int passes_half = (bits + 7) / 8;
@@ -330,7 +339,8 @@ extern "C" __attribute__((visibility("default"))) rest_status rest_build_index(c
         unsigned long long runs = 0;
         REST_HIP_TRY(hipMemcpyAsync(&runs, s.counters, 8, hipMemcpyDeviceToHost, st));
         REST_HIP_TRY(hipStreamSynchronize(st));
-        if (runs == n || h >= n) break;
+        if (runs == n || h >= n) break;                    // every suffix distinct: the suffix array
+        if (depth > 0 && 2 * h >= (uint64_t)depth) { sorted_by = (int32_t)(2 * h); break; }
         rest_status rs = scan_u32<true>(grp, n, s.sums, st);
         if (rs != REST_OK) return rs;
         hipLaunchKernelGGL(assign_rank_kernel, dim3(gs), dim3(256), 0, st, s.val[cur], grp, n, s.rank);
@@ -347,6 +357,7 @@ extern "C" __attribute__((visibility("default"))) rest_status rest_build_index(c
     rest_status rs = rest_index_from_sa(d_corpus, s.sa, n, token_bytes, sa_bytes, stream_, &idx);
     if (rs != REST_OK) return rs;
     idx->owns_sa = 1;
+    idx->sort_depth = sorted_by;
     s.sa = nullptr;   // ownership moved to the handle
     *out = idx;
     return REST_OK;

@@ -25,6 +25,7 @@ struct rest_index {
     int32_t sa_bytes;
     int32_t top_count;      // number of sampled suffix-array ranks in d_top_keys
     int32_t owns_sa;
+    int32_t sort_depth;     // 0: d_sa is the suffix array; else positions are ordered by their first sort_depth tokens only
 };
 
 // Rank of the i-th sampled suffix (i in [0, top_count)): the ranks split [0, n) into top_count + 1 near-equal parts.

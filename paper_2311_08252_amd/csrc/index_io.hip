@@ -7,7 +7,8 @@
 //     bytes 16..19  token_bytes     int32 (2 or 4)
 //     bytes 20..23  sa_bytes        int32 (4 or 8)
 //     bytes 24..31  fingerprint     uint64 of the token stream the array belongs to
-//     bytes 32..63  zero
+//     bytes 32..35  sort depth      int32: 0 = a suffix array, else the positions are ordered by that many tokens
+//     bytes 36..63  zero
 // followed by n_tokens suffix-array entries of sa_bytes each.
 // fingerprint = sum over i of mix(token_i + (i + 1) * 0x9E3779B97F4A7C15) modulo 2^64, mix = the splitmix64 finaliser;
 // a sum, so it can be formed in any order.  The array moves through a pinned 64 MB staging buffer.
@@ -95,6 +96,7 @@ extern "C" __attribute__((visibility("default"))) rest_status rest_index_save(co
     memcpy(header + 16, &index->token_bytes, 4);
     memcpy(header + 20, &index->sa_bytes, 4);
     memcpy(header + 24, &fp, 8);
+    memcpy(header + 32, &index->sort_depth, 4);
     if (fwrite(header, 1, kHeader, file.f) != kHeader) return REST_IO_ERROR;
     Stage stage;
     if (!stage.alloc()) return REST_OUT_OF_MEMORY;
@@ -121,13 +123,14 @@ extern "C" __attribute__((visibility("default"))) rest_status rest_index_load(co
     unsigned char header[kHeader];
     if (fread(header, 1, kHeader, file.f) != kHeader) return REST_IO_ERROR;
     uint64_t n = 0, fp_file = 0;
-    int32_t tb = 0, sb = 0;
+    int32_t tb = 0, sb = 0, depth = 0;
     memcpy(&n, header + 8, 8);
     memcpy(&tb, header + 16, 4);
     memcpy(&sb, header + 20, 4);
     memcpy(&fp_file, header + 24, 8);
+    memcpy(&depth, header + 32, 4);
     if (memcmp(header, kMagic, 8) != 0 || (sb != 4 && sb != 8) || (sb == 4 && n >= (1ull << 31))) return REST_BAD_FILE;
-    if (n != n_tokens || tb != token_bytes) return REST_BAD_FILE;
+    if (n != n_tokens || tb != token_bytes || depth < 0) return REST_BAD_FILE;
     uint64_t fp = 0;
     rest_status st = fingerprint(d_corpus, n_tokens, token_bytes, stream, &fp);
     if (st != REST_OK) return st;
@@ -156,6 +159,7 @@ extern "C" __attribute__((visibility("default"))) rest_status rest_index_load(co
         return st;
     }
     idx->owns_sa = 1;
+    idx->sort_depth = depth;
     *out = idx;
     return REST_OK;
 }

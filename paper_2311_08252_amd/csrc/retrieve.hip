@@ -755,6 +755,9 @@ extern "C" __attribute__((visibility("default"))) rest_status rest_retrieve(cons
     (void)workspace_bytes;
     if (!index || !params_ok(q) || !out) return REST_INVALID_ARG;
     if (B < 0 || ctx_stride < 0) return REST_INVALID_ARG;
+    // a depth-limited index orders positions by sort_depth tokens only; the search reads n_max of them and the
+    // adjacent-row comparison cont_len more
+    if (index->sort_depth > 0 && q->n_max + q->cont_len > index->sort_depth) return REST_UNSUPPORTED;
     if (B == 0) return REST_OK;
     if (!d_contexts || !d_ctx_len) return REST_INVALID_ARG;
     if (!out->draft_tokens || !out->parent_idx || !out->pos_ids || !out->node_weight || !out->tree_mask ||

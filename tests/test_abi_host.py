@@ -28,7 +28,7 @@ def declared_functions():
 
 def test_header_functions_are_exported(rest):
     names = declared_functions()
-    assert len(names) == 16 and "rest_retrieve" in names and "rest_tree_attention" in names
+    assert len(names) == 18 and "rest_retrieve" in names and "rest_tree_attention" in names
     lib = ctypes.CDLL(LIB)
     for n in names:
         assert getattr(lib, n) is not None
@@ -95,6 +95,9 @@ def test_calls_reject_null_and_bad_arguments_before_touching_the_gpu(rest):
     assert lib.rest_build_index(ctypes.c_void_p(16), 1 << 31, 4, 4, None, ctypes.byref(h)) == rest.REST_INVALID_ARG
     assert lib.rest_build_index(ctypes.c_void_p(16), 0, 4, 8, None, ctypes.byref(h)) == rest.REST_INVALID_ARG
     assert lib.rest_index_from_sa(ctypes.c_void_p(16), None, 10, 4, 4, None, ctypes.byref(h)) == rest.REST_INVALID_ARG
+    assert lib.rest_build_index_prefix(ctypes.c_void_p(16), 10, 4, 4, -1, None, ctypes.byref(h)) == rest.REST_INVALID_ARG
+    assert lib.rest_build_index_prefix(None, 10, 4, 4, 32, None, ctypes.byref(h)) == rest.REST_INVALID_ARG
+    assert lib.rest_index_sort_depth(None) == -1
     assert lib.rest_index_view(None, None, None, None, None, None) == rest.REST_INVALID_ARG
     lib.rest_index_destroy(None)
     prm = rest.rest_retrieve_params(16, 2, 100, 10, 64, 0, 0, 0, 0)

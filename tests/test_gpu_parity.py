@@ -354,6 +354,67 @@ def test_evenly_spaced_match_sample_matches_oracle(K, m, c, n_seq, sa_bytes):
         assert capped >= 6 and (differs >= 3 or K == 1), (capped, differs)
 
 
+@pytest.mark.parametrize("n,dtype,sa_bytes,depth", [(5_000, np.int32, 4, 2), (40_000, np.uint16, 4, 8), (150_000, np.int32, 8, 32),
+                                                     (150_000, np.int32, 4, 26), (70_001, np.int32, 4, 1)])
+def test_depth_limited_index_matches_oracle_order(n, dtype, sa_bytes, depth):
+    """Few distinct tokens and planted repeats, so that many positions share their first `depth` tokens."""
+    rng_tokens = synth.randint(61, np.arange(n), 0, 3).astype(dtype)
+    rng_tokens[n // 2:n // 2 + n // 5] = rng_tokens[:n // 5]          # a long repeat: full doubling would need many rounds
+    index = rest.rest_build_index_prefix(dev(rng_tokens), sa_bytes, depth)
+    used = index.sort_depth
+    assert used >= max(depth, 2) and used < 2 * max(depth, 2) and used & (used - 1) == 0
+    got = index.suffix_array().cpu().numpy()
+    np.testing.assert_array_equal(got, oracle.prefix_sorted_array(rng_tokens, used))
+    assert got.dtype == (np.int32 if sa_bytes == 4 else np.int64)
+    # a depth the repeats do not reach: the suffix array itself, marked as such
+    plain = synth.randint(62, np.arange(3000), 0, 30_000).astype(np.int32)
+    full = rest.rest_build_index_prefix(dev(plain), 4, 16)
+    assert full.sort_depth == 0 and oracle.check_suffix_array(plain, full.suffix_array().cpu().numpy()) == -1
+
+
+def test_depth_limited_index_serves_retrieval_like_the_suffix_array(tmp_path):
+    corp = synth.make_corpus(300_000, 12, 30)
+    toks = corp.tokens.copy()
+    toks[200_000:260_000] = toks[10_000:70_000]                         # duplicated "document"
+    d_corpus = dev(toks)
+    full = rest.rest_build_index(d_corpus, 4)
+    lim = rest.rest_build_index_prefix(d_corpus, 4, 32)
+    assert full.sort_depth == 0 and lim.sort_depth == 32
+    assert not torch.equal(full.suffix_array(), lim.suffix_array())
+    ctx, lens = synth.make_contexts(corp, 32, 64, 13)
+    ctx[:8, :] = toks[30_000 - 64 + np.arange(8)[:, None] * 500 + np.arange(64)[None, :]]   # contexts inside the duplicate
+    for kw in (dict(max_matches=5000, cont_len=16, max_nodes=64), dict(max_matches=7, cont_len=10, max_nodes=64, strided=True),
+               dict(max_matches=300, cont_len=8, max_nodes=256, random_seqs=8, seed=4)):
+        a = rest.rest_retrieve(full, dev(ctx), dev(lens), **kw)
+        b = rest.rest_retrieve(lim, dev(ctx), dev(lens), **kw)
+        torch.cuda.synchronize()
+        for name in ("draft_tokens", "parent_idx", "pos_ids", "node_weight", "tree_mask", "n_nodes", "matched_len", "match_count"):
+            assert torch.equal(getattr(a, name), getattr(b, name)), (name, kw)
+        assert int(a.n_nodes.sum()) > 100
+    for bi in range(0, 32, 5):                                           # and the oracle's definition directly
+        want = oracle.draft_tree(toks, ctx[bi], 16, 2, 5000, 16, 64)
+        got = rest.rest_retrieve(lim, dev(ctx[bi:bi + 1]), dev(lens[bi:bi + 1]), max_matches=5000, cont_len=16, max_nodes=64)
+        np.testing.assert_array_equal(got.draft_tokens[0].cpu().numpy(), want.draft_tokens)
+        np.testing.assert_array_equal(got.node_weight[0].cpu().numpy(), want.node_weight)
+    # the limit is enforced: a 16-token index cannot serve n_max + cont_len = 26
+    short = rest.rest_build_index_prefix(d_corpus, 4, 16)
+    assert short.sort_depth == 16
+    with pytest.raises(rest.RestError) as e:
+        rest.rest_retrieve(short, dev(ctx), dev(lens), max_matches=100, cont_len=10, max_nodes=64)
+    assert e.value.status == rest.REST_UNSUPPORTED
+    rest.rest_retrieve(short, dev(ctx), dev(lens), n_max=8, max_matches=100, cont_len=8, max_nodes=64)
+    # the file keeps the depth
+    p = str(tmp_path / "lim.restsa")
+    rest.rest_index_save(lim, p)
+    assert oracle.read_index_file(p)[5] == 32
+    back = rest.rest_index_load(p, d_corpus)
+    assert back.sort_depth == 32 and torch.equal(back.suffix_array(), lim.suffix_array())
+    oracle.write_index_file(p, toks, oracle.prefix_sorted_array(toks, 32).astype(np.int32), sort_depth=32)
+    theirs = rest.rest_index_load(p, d_corpus)
+    assert theirs.sort_depth == 32 and torch.equal(theirs.suffix_array(), lim.suffix_array())
+    torch.cuda.synchronize()
+
+
 def test_index_file_round_trip_and_exchange_with_the_oracle(tmp_path):
     corp = synth.make_corpus(300_000, 4, 30)
     d_corpus = dev(corp.tokens)
