@@ -331,6 +331,44 @@ def tree_attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, mask: np.ndarray
     return np.matmul(p, v)
 
 
+# ---------------------------------------------------------------------------
+# 8-bit KV cache.  Not in the paper: the cache may hold K and V in the OCP 8-bit
+# floating point format E4M3 (1 sign bit, 4 exponent bits with bias 7, 3 mantissa
+# bits; exponent field 0 = subnormals m * 2^-9; no infinities; S.1111.111 = NaN;
+# largest finite value 448), each (batch, head) slab with one float scale:
+# k = k_scale * decode(k8), v = v_scale * decode(v8).  Attention on such a cache
+# is, by definition, the attention above on those decoded values.
+# ---------------------------------------------------------------------------
+def fp8_e4m3_decode(codes: np.ndarray) -> np.ndarray:
+    codes = np.asarray(codes, dtype=np.uint8).astype(np.int64)
+    sign = np.where(codes & 0x80, -1.0, 1.0)
+    e, m = (codes >> 3) & 15, codes & 7
+    val = np.where(e == 0, m * 2.0 ** -9, (1.0 + m / 8.0) * 2.0 ** (e.astype(np.float64) - 7))
+    val = np.where((e == 15) & (m == 7), np.nan, val)
+    return sign * val
+
+
+def fp8_e4m3_encode(x: np.ndarray) -> np.ndarray:
+    """Nearest E4M3 value, ties to the even mantissa, magnitudes beyond 448 saturate to 448, NaN -> 0x7f."""
+    x = np.asarray(x, dtype=np.float64)
+    grid = fp8_e4m3_decode(np.arange(0x7f))                       # the 127 finite magnitudes, ascending with the code
+    a = np.abs(np.nan_to_num(x, nan=0.0))
+    hi = np.clip(np.searchsorted(grid, a, side="left"), 1, 0x7e)  # grid[hi-1] <= a <= grid[hi] (or a beyond the ends)
+    lo = hi - 1
+    d_lo, d_hi = a - grid[lo], grid[hi] - a
+    code = np.where(d_lo < d_hi, lo, np.where(d_hi < d_lo, hi, np.where(lo % 2 == 0, lo, hi)))
+    code = np.where(np.signbit(x), code | 0x80, code)
+    return np.where(np.isnan(x), 0x7f, code).astype(np.uint8)
+
+
+def tree_attention_fp8kv(q: np.ndarray, k8: np.ndarray, v8: np.ndarray, k_scale, v_scale, mask: np.ndarray,
+                         prefix_len: int, scale: float) -> np.ndarray:
+    """q [Nb, H, Tq, D] (any float dtype); k8, v8 [Nb, H, P+Tk, D] uint8 E4M3 codes; k_scale, v_scale [Nb, H]."""
+    k = fp8_e4m3_decode(k8) * np.asarray(k_scale, dtype=np.float64)[..., None, None]
+    v = fp8_e4m3_decode(v8) * np.asarray(v_scale, dtype=np.float64)[..., None, None]
+    return tree_attention(q, k, v, mask, prefix_len, scale)
+
+
 def tree_attention_loops(q, k, v, mask, prefix_len: int, scale: float) -> np.ndarray:
     """The same definition as explicit Python loops for one [Tq, D] / [Lk, D]
     slab (small cases only)."""
