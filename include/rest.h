@@ -217,8 +217,19 @@ rest_status rest_retrieve(const rest_index* index, const int32_t* d_contexts, co
  * dtype: REST_BF16 (bf16 in/out, fp32 accumulation and softmax, probabilities
  * rounded to bf16 for the second product) or REST_FP32 (fp32 in/out and math).
  * D must be 128.  Tq, Tk <= REST_MAX_NODES (Tk may be 0).
+ *
+ * 8-bit cache (an extension; the paper's models keep a 16-bit cache): with
+ * kv_dtype = REST_KV_FP8_E4M3 (dtype must be REST_BF16) d_k and d_v hold one
+ * byte per element in the OCP 8-bit floating point format E4M3 (1 sign,
+ * 4 exponent bits with bias 7, 3 mantissa bits, no infinities), strides in
+ * elements = bytes and multiples of 16, and the attention is, by definition,
+ * the one above on k = d_k_scale[nb*H + h] * decode(d_k), v = d_v_scale[nb*H + h]
+ * * decode(d_v) (device arrays of Nb*H floats; NULL = all ones).  Decoding is
+ * exact, so q.k and the result differ from that definition only as the bf16
+ * path's do.  A NaN code poisons its row as a NaN in a 16-bit cache would.
  * ---------------------------------------------------------------------- */
 enum { REST_BF16 = 0, REST_FP32 = 1 };
+enum { REST_KV_AS_DTYPE = 0, REST_KV_FP8_E4M3 = 1 };
 
 typedef struct {
     int32_t Nb, H, Tq, Tk, P, D;
@@ -231,6 +242,9 @@ typedef struct {
     int32_t mask_per_batch;
     int32_t num_splits;      /* 0 = let the library choose; else KV splits per (Nb, H) */
     int32_t mask_rows;       /* 0 = Tq; else rows of one mask: query row i uses mask row i % mask_rows */
+    int32_t kv_dtype;        /* REST_KV_AS_DTYPE: K, V have `dtype`; REST_KV_FP8_E4M3: one E4M3 byte per element */
+    const float* d_k_scale;  /* 8-bit cache: [Nb*H] device floats, NULL = 1 */
+    const float* d_v_scale;
 } rest_attn_desc;
 
 /* Bytes of device workspace (partial results of the KV splits). */

@@ -32,6 +32,8 @@ REST_IO_ERROR = -6
 REST_BAD_FILE = -7
 REST_BF16 = 0
 REST_FP32 = 1
+REST_KV_AS_DTYPE = 0
+REST_KV_FP8_E4M3 = 1
 REST_MAX_SUFFIX_LEN = 16
 REST_MAX_CONT_LEN = 32
 REST_MAX_MATCHES = 8192
@@ -69,7 +71,8 @@ class rest_attn_desc(ctypes.Structure):
                 ("P", ctypes.c_int32), ("D", ctypes.c_int32), ("dtype", ctypes.c_int32), ("scale", ctypes.c_float),
                 ("q_stride", ctypes.c_int64 * 3), ("k_stride", ctypes.c_int64 * 3), ("v_stride", ctypes.c_int64 * 3),
                 ("o_stride", ctypes.c_int64 * 3), ("mask_per_batch", ctypes.c_int32), ("num_splits", ctypes.c_int32),
-                ("mask_rows", ctypes.c_int32)]
+                ("mask_rows", ctypes.c_int32), ("kv_dtype", ctypes.c_int32), ("d_k_scale", ctypes.c_void_p),
+                ("d_v_scale", ctypes.c_void_p)]
 
 
 class rest_kv_desc(ctypes.Structure):
@@ -308,7 +311,8 @@ def rest_retrieve(index: RestIndex, contexts: torch.Tensor, ctx_len: torch.Tenso
 
 
 def make_attn_desc(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, out: torch.Tensor, prefix_len: int,
-                   scale: float, mask_per_batch: bool, num_splits: int = 0, mask_rows: int = 0) -> rest_attn_desc:
+                   scale: float, mask_per_batch: bool, num_splits: int = 0, mask_rows: int = 0,
+                   k_scale: torch.Tensor | None = None, v_scale: torch.Tensor | None = None) -> rest_attn_desc:
     Nb, H, Tq, D = q.shape
     Lk = k.shape[2]
     dt = {torch.bfloat16: REST_BF16, torch.float32: REST_FP32}[q.dtype]
@@ -322,6 +326,16 @@ def make_attn_desc(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, out: torch
     d.mask_per_batch = 1 if mask_per_batch else 0
     d.num_splits = num_splits
     d.mask_rows = mask_rows
+    if k.dtype == torch.uint8:          # one OCP E4M3 byte per cached element
+        assert v.dtype == torch.uint8 and q.dtype == torch.bfloat16
+        d.kv_dtype = REST_KV_FP8_E4M3
+        for name, t in (("d_k_scale", k_scale), ("d_v_scale", v_scale)):
+            if t is not None:
+                assert t.dtype == torch.float32 and t.is_contiguous() and t.numel() == Nb * H
+                setattr(d, name, t.data_ptr())
+    else:
+        assert k_scale is None and v_scale is None and k.dtype == q.dtype and v.dtype == q.dtype
+        d.kv_dtype = REST_KV_AS_DTYPE
     return d
 
 
@@ -331,14 +345,16 @@ def rest_tree_attention_workspace_bytes(desc: rest_attn_desc) -> int:
 
 def rest_tree_attention(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, mask: torch.Tensor, prefix_len: int,
                         scale: float, out: torch.Tensor | None = None, num_splits: int = 0,
-                        workspace: torch.Tensor | None = None, mask_rows: int = 0) -> torch.Tensor:
+                        workspace: torch.Tensor | None = None, mask_rows: int = 0,
+                        k_scale: torch.Tensor | None = None, v_scale: torch.Tensor | None = None) -> torch.Tensor:
     """q [Nb,H,Tq,128]; k, v [Nb,H,P+Tk,128] (bf16 or fp32, device); mask [Tq,words] or [Nb,Tq,words] int64/uint64.
+    k, v of dtype uint8: an 8-bit (OCP E4M3) cache with optional per-(Nb, H) float32 scales.
     Enqueues on the current stream."""
     assert q.dim() == 4 and k.dim() == 4 and v.dim() == 4 and k.shape == v.shape
     if out is None:
         out = torch.empty_like(q)
     per_batch = mask.dim() == 3
-    desc = make_attn_desc(q, k, v, out, prefix_len, scale, per_batch, num_splits, mask_rows)
+    desc = make_attn_desc(q, k, v, out, prefix_len, scale, per_batch, num_splits, mask_rows, k_scale, v_scale)
     need = rest_tree_attention_workspace_bytes(desc)
     if workspace is None and need:
         workspace = torch.empty(need, dtype=torch.uint8, device=q.device)

@@ -49,6 +49,8 @@ struct AttnParams {
     __bf16* out;
     float* ws_o;      // bf16 path: [W][2][QT*32][128] partial O; fp32 path: [rows][128]
     float* ws_ml;     // bf16 path: [W][2][QT*32][2] (reference in log2 units, sum); fp32 path: [rows][2]
+    const float* k_scale;   // 8-bit cache only: [Nb*H] factors of the decoded K and V values, or null for 1
+    const float* v_scale;
     int32_t Nb, H, Tq, Tk, P, Lk;
     int32_t nsplit, qgroups, mask_words, mask_per_batch;
     int32_t mask_rows;   // rows of one mask: query row i uses mask row i % mask_rows
@@ -75,8 +77,15 @@ __host__ __device__ inline int32_t span_owner(int64_t total, int32_t n, int64_t 
 // [32w, 32w+32).  All see the same K/V tile in LDS, NW/2 blocks = 16 NW keys long, of which each wavefront fetches
 // its 1/NW: eight 16-byte pieces per lane and tile whatever NW is, so the bytes in flight per compute unit (eight
 // wavefronts: 2 per SIMD) do not depend on the number of queries, and every K/V byte is read once per unit.
-template <int NW>
+//
+// KV8: the cache holds OCP E4M3 bytes (128-byte rows).  A lane still fetches 16-byte pieces -- half as many per
+// tile --, and turns each into two pieces of bf16 (exact: every E4M3 value is a bf16 value) on the way into the
+// same LDS layout, so everything after the parking store is the bf16 kernel; the per-(batch, head) scales are
+// folded into the softmax scale and into the final division.
+template <int NW, bool KV8>
 __global__ __launch_bounds__(64 * NW, 2) void tree_attn_bf16_kernel(AttnParams p) {
+    constexpr int kElt = KV8 ? 1 : 2;                  // bytes per cached element
+    constexpr int kFetch = KV8 ? 2 : 4;                // 16-byte pieces of K (and of V) a lane fetches per tile
     constexpr int kSub = NW / 2;                       // 32-key blocks per tile
     constexpr int kTileKeys = kSub * kBlk;
     constexpr int kTileBytes = kSub * kSubBytes;       // K (or V) part of a tile
@@ -149,22 +158,27 @@ __global__ __launch_bounds__(64 * NW, 2) void tree_attn_bf16_kernel(AttnParams p
     } while (0)
 
     uint64_t* const my_mask = lds_mask + wave * (32 * 4);
-    const int64_t k_row_bytes = p.ks[2] * 2, v_row_bytes = p.vs[2] * 2;
+    const int64_t k_row_bytes = p.ks[2] * kElt, v_row_bytes = p.vs[2] * kElt;
 
     // Global -> registers -> LDS.  Chunk i of a tile is 4 rows x 256 B = 64 lanes x 16 B and is parked at
     // tile + i*1024 + lane*16, i.e. row i*4 + (lane >> 4), piece slot lane & 15.  The slot holds row piece
     // (slot ^ swizzle(row)), so that is the piece this lane fetches.  K: swizzle = row & 15; V: (row & 3) << 2.
     // Wavefront w moves chunks 4w .. 4w+3 of K and of V.
+    // KV8: chunk i is 8 rows x 128 B; the lane fetches piece lane & 7 of row i*8 + (lane >> 3) as it lies in memory
+    // and applies the swizzle when it parks the two bf16 pieces made from it.  Wavefront w moves chunks 2w, 2w+1.
     uint32_t k_off[4];
 #pragma unroll
-    for (int x = 0; x < 4; x++) k_off[x] = (uint32_t)(lrow * k_row_bytes) + ((lpc ^ (x * 4 + lrow)) << 4);
-    const uint32_t v_off = (uint32_t)(lrow * v_row_bytes) + ((lpc ^ (lrow << 2)) << 4);
+    for (int x = 0; x < 4; x++)
+        k_off[x] = KV8 ? (uint32_t)((lane >> 3) * k_row_bytes) + ((lane & 7) << 4)
+                       : (uint32_t)(lrow * k_row_bytes) + ((lpc ^ (x * 4 + lrow)) << 4);
+    const uint32_t v_off = KV8 ? (uint32_t)((lane >> 3) * v_row_bytes) + ((lane & 7) << 4)
+                               : (uint32_t)(lrow * v_row_bytes) + ((lpc ^ (lrow << 2)) << 4);
 
     auto unit_bases = [&](int unit, const char*& kp, const char*& vp) {
         const int slab = unit / p.qgroups;
         const int h = slab % p.H, nb = slab / p.H;
-        kp = (const char*)(p.k + nb * p.ks[0] + h * p.ks[1]);
-        vp = (const char*)(p.v + nb * p.vs[0] + h * p.vs[1]);
+        kp = (const char*)p.k + (nb * p.ks[0] + h * p.ks[1]) * kElt;
+        vp = (const char*)p.v + (nb * p.vs[0] + h * p.vs[1]) * kElt;
     };
 
     // ---- load side: a cursor one block ahead of the arithmetic
@@ -173,23 +187,25 @@ __global__ __launch_bounds__(64 * NW, 2) void tree_attn_bf16_kernel(AttnParams p
     REST_SEGMENT_FIRST(ld_unit, ld_j, ld_je, ld_round, ld_tail);
     const char *ld_kp, *ld_vp;
     unit_bases(ld_unit, ld_kp, ld_vp);
-    i32x4 kr[4], vr[4];
+    i32x4 kr[kFetch], vr[kFetch];
+    constexpr int kChunkRows = KV8 ? 8 : 4;            // rows of a 1 KB chunk
     auto issue = [&]() {
         const int j = ld_j;
         if ((j + 1) * kTileKeys <= p.Lk) {
 #pragma unroll
-            for (int i = 0; i < 4; i++) {
-                const int64_t row = (int64_t)j * kTileKeys + (4 * wave + i) * 4;
+            for (int i = 0; i < kFetch; i++) {
+                const int64_t row = (int64_t)j * kTileKeys + (kFetch * wave + i) * kChunkRows;
                 kr[i] = __builtin_nontemporal_load((const i32x4*)(ld_kp + row * k_row_bytes + k_off[i]));
                 vr[i] = __builtin_nontemporal_load((const i32x4*)(ld_vp + row * v_row_bytes + v_off));
             }
         } else {
             // last, partial tile of a unit: rows past the end re-read the last row; those keys are never visible
 #pragma unroll
-            for (int i = 0; i < 4; i++) {
-                int64_t row = (int64_t)j * kTileKeys + (4 * wave + i) * 4 + lrow;
+            for (int i = 0; i < kFetch; i++) {
+                int64_t row = (int64_t)j * kTileKeys + (kFetch * wave + i) * kChunkRows + (KV8 ? lane >> 3 : lrow);
                 row = row < p.Lk ? row : p.Lk - 1;
-                const int sw_k = (lpc ^ (i * 4 + lrow)) << 4, sw_v = (lpc ^ (lrow << 2)) << 4;
+                const int sw_k = KV8 ? (lane & 7) << 4 : (lpc ^ (i * 4 + lrow)) << 4;
+                const int sw_v = KV8 ? (lane & 7) << 4 : (lpc ^ (lrow << 2)) << 4;
                 kr[i] = __builtin_nontemporal_load((const i32x4*)(ld_kp + row * k_row_bytes + sw_k));
                 vr[i] = __builtin_nontemporal_load((const i32x4*)(ld_vp + row * v_row_bytes + sw_v));
             }
@@ -200,11 +216,36 @@ __global__ __launch_bounds__(64 * NW, 2) void tree_attn_bf16_kernel(AttnParams p
             unit_bases(ld_unit, ld_kp, ld_vp);
         }
     };
+    // eight E4M3 bytes (two dwords) -> one 16-byte piece of bf16
+    auto widen = [](int lo, int hi) -> i32x4 {
+        typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+        union { bf16x2 h[4]; i32x4 v; } u;
+        u.h[0] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(lo, 1.0f, false);
+        u.h[1] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(lo, 1.0f, true);
+        u.h[2] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(hi, 1.0f, false);
+        u.h[3] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(hi, 1.0f, true);
+        return u.v;
+    };
     auto park = [&](unsigned char* tile) {
+        if constexpr (KV8) {
 #pragma unroll
-        for (int i = 0; i < 4; i++) {
-            *(i32x4*)(tile + (4 * wave + i) * 1024 + lane * 16) = kr[i];
-            *(i32x4*)(tile + kTileBytes + (4 * wave + i) * 1024 + lane * 16) = vr[i];
+            for (int i = 0; i < 2; i++) {
+                // fetched piece g of tile row `row` becomes bf16 pieces 2g and 2g+1, parked in their swizzled slots
+                const int row = (2 * wave + i) * 8 + (lane >> 3), pc = 2 * (lane & 7);
+                unsigned char* krow = tile + row * 256;
+                unsigned char* vrow = tile + kTileBytes + row * 256;
+                const int swk = row & 15, swv = (row & 3) << 2;
+                *(i32x4*)(krow + ((pc ^ swk) << 4)) = widen(kr[i][0], kr[i][1]);
+                *(i32x4*)(krow + (((pc + 1) ^ swk) << 4)) = widen(kr[i][2], kr[i][3]);
+                *(i32x4*)(vrow + ((pc ^ swv) << 4)) = widen(vr[i][0], vr[i][1]);
+                *(i32x4*)(vrow + (((pc + 1) ^ swv) << 4)) = widen(vr[i][2], vr[i][3]);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; i++) {
+                *(i32x4*)(tile + (4 * wave + i) * 1024 + lane * 16) = kr[i];
+                *(i32x4*)(tile + kTileBytes + (4 * wave + i) * 1024 + lane * 16) = vr[i];
+            }
         }
     };
 
@@ -233,6 +274,9 @@ __global__ __launch_bounds__(64 * NW, 2) void tree_attn_bf16_kernel(AttnParams p
         const int qg = unit % p.qgroups, slab = unit / p.qgroups;
         const int h = slab % p.H, nb = slab / p.H;
         const int qi = qg * (32 * NW) + wave * 32 + col;        // this lane's query row
+        // scale of the logits in log2 units, and of the output: the slab's K and V factors folded in
+        const float cu = KV8 && p.k_scale ? p.c * p.k_scale[slab] : p.c;
+        const float vu = KV8 && p.v_scale ? p.v_scale[slab] : 1.0f;
 
         // mask row of this lane's query -> LDS (the halves write words 0,1 / 2,3); only this wave reads it back
         {
@@ -334,7 +378,7 @@ __global__ __launch_bounds__(64 * NW, 2) void tree_attn_bf16_kernel(AttnParams p
                 float mx = s[0];
 #pragma unroll
                 for (int r = 1; r < 16; r++) mx = fmaxf(mx, s[r]);
-                mx = fmaxf(mx, wave_xor32(mx)) * p.c;
+                mx = fmaxf(mx, wave_xor32(mx)) * cu;
                 if (__any(mx > m_ref + kLazy)) {
                     const float m_new = fmaxf(m_ref, mx);
                     const float alpha = __builtin_amdgcn_exp2f(m_ref - m_new);
@@ -348,7 +392,7 @@ __global__ __launch_bounds__(64 * NW, 2) void tree_attn_bf16_kernel(AttnParams p
                 float sum = 0.f;
 #pragma unroll
                 for (int r = 0; r < 16; r++) {
-                    const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], p.c, -m_ref));
+                    const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], cu, -m_ref));
                     sum += e;
                     pf[r >> 3][r & 7] = (__bf16)e;
                 }
@@ -383,7 +427,7 @@ __global__ __launch_bounds__(64 * NW, 2) void tree_attn_bf16_kernel(AttnParams p
         l_run += wave_xor32(l_run);
         if (qi < p.Tq) {
             if (whole) {
-                const float inv = l_run > 0.f ? 1.0f / l_run : 0.f;
+                const float inv = l_run > 0.f ? vu / l_run : 0.f;
                 __bf16* op = p.out + nb * p.os[0] + h * p.os[1] + qi * p.os[2];
 #pragma unroll
                 for (int dt = 0; dt < 4; dt++)
@@ -403,7 +447,7 @@ __global__ __launch_bounds__(64 * NW, 2) void tree_attn_bf16_kernel(AttnParams p
                     for (int gq = 0; gq < 4; gq++) {
                         f32x4 w;
 #pragma unroll
-                        for (int e = 0; e < 4; e++) w[e] = o[dt][4 * gq + e];
+                        for (int e = 0; e < 4; e++) w[e] = o[dt][4 * gq + e] * vu;
                         *(f32x4*)(wo + dt * 32 + 8 * gq + 4 * hh) = w;
                     }
                 if (hh == 0) {
@@ -614,6 +658,8 @@ bool desc_ok(const rest_attn_desc* d) {
     if (d->Nb < 1 || d->H < 1 || d->Tq < 1 || d->Tq > REST_MAX_NODES || d->Tk < 0 || d->Tk > REST_MAX_NODES) return false;
     if (d->P < 0 || d->P + d->Tk < 1 || d->D != kD) return false;
     if (d->dtype != REST_BF16 && d->dtype != REST_FP32) return false;
+    if (d->kv_dtype != REST_KV_AS_DTYPE && d->kv_dtype != REST_KV_FP8_E4M3) return false;
+    if (d->kv_dtype == REST_KV_FP8_E4M3 && d->dtype != REST_BF16) return false;
     if (!(d->scale > 0.f) || !(d->scale < 1e30f)) return false;
     if (d->num_splits < 0 || d->num_splits > 64) return false;
     if (d->mask_rows < 0 || d->mask_rows > d->Tq) return false;
@@ -624,8 +670,9 @@ bool desc_ok(const rest_attn_desc* d) {
         if (d->q_stride[i] < 0 || d->k_stride[i] < 0 || d->v_stride[i] < 0 || d->o_stride[i] < 0) return false;
     // rows are read with 16-byte vector loads
     const int64_t al = d->dtype == REST_BF16 ? 8 : 4;
+    const int64_t al_kv = d->kv_dtype == REST_KV_FP8_E4M3 ? 16 : al;
     for (int i = 0; i < 3; i++)
-        if (d->q_stride[i] % al || d->k_stride[i] % al || d->v_stride[i] % al || d->o_stride[i] % 4) return false;
+        if (d->q_stride[i] % al || d->k_stride[i] % al_kv || d->v_stride[i] % al_kv || d->o_stride[i] % 4) return false;
     if (d->q_stride[2] < kD || d->k_stride[2] < kD || d->v_stride[2] < kD || d->o_stride[2] < kD) return false;
     // four consecutive rows are addressed with a 32-bit byte offset
     if (d->k_stride[2] > (1 << 26) || d->v_stride[2] > (1 << 26)) return false;
@@ -671,6 +718,9 @@ extern "C" __attribute__((visibility("default"))) rest_status rest_tree_attentio
     p.c = d->scale * 1.4426950408889634f;
     for (int i = 0; i < 3; i++) { p.qs[i] = d->q_stride[i]; p.ks[i] = d->k_stride[i]; p.vs[i] = d->v_stride[i]; p.os[i] = d->o_stride[i]; }
     p.ws_o = (float*)d_workspace;
+    const bool kv8 = d->kv_dtype == REST_KV_FP8_E4M3;
+    p.k_scale = kv8 ? d->d_k_scale : nullptr;
+    p.v_scale = kv8 ? d->d_v_scale : nullptr;
 
     if (d->dtype == REST_BF16) {
         p.nsplit = 1;
@@ -682,12 +732,18 @@ extern "C" __attribute__((visibility("default"))) rest_status rest_tree_attentio
         p.tail_streams = pl.tail_streams;
         const size_t rows = (size_t)pl.tail_streams * 2 * (pl.qt * 32);
         p.ws_ml = p.ws_o ? p.ws_o + rows * kD : nullptr;
-        if (pl.qt == 2)
-            hipLaunchKernelGGL(tree_attn_bf16_kernel<2>, dim3(pl.n_streams), dim3(128), 0, stream, p);
+        if (pl.qt == 2 && !kv8)
+            hipLaunchKernelGGL((tree_attn_bf16_kernel<2, false>), dim3(pl.n_streams), dim3(128), 0, stream, p);
+        else if (pl.qt == 4 && !kv8)
+            hipLaunchKernelGGL((tree_attn_bf16_kernel<4, false>), dim3(pl.n_streams), dim3(256), 0, stream, p);
+        else if (!kv8)
+            hipLaunchKernelGGL((tree_attn_bf16_kernel<8, false>), dim3(pl.n_streams), dim3(512), 0, stream, p);
+        else if (pl.qt == 2)
+            hipLaunchKernelGGL((tree_attn_bf16_kernel<2, true>), dim3(pl.n_streams), dim3(128), 0, stream, p);
         else if (pl.qt == 4)
-            hipLaunchKernelGGL(tree_attn_bf16_kernel<4>, dim3(pl.n_streams), dim3(256), 0, stream, p);
+            hipLaunchKernelGGL((tree_attn_bf16_kernel<4, true>), dim3(pl.n_streams), dim3(256), 0, stream, p);
         else
-            hipLaunchKernelGGL(tree_attn_bf16_kernel<8>, dim3(pl.n_streams), dim3(512), 0, stream, p);
+            hipLaunchKernelGGL((tree_attn_bf16_kernel<8, true>), dim3(pl.n_streams), dim3(512), 0, stream, p);
         REST_HIP_TRY(hipGetLastError());
         if (pl.need_merge) {
             hipLaunchKernelGGL(tree_attn_streamk_merge_kernel, dim3(pl.tail_units * (32 * pl.qt / pl.merge_rows)), dim3(256), 0,

@@ -1,5 +1,7 @@
 """GPU parity tests: the HIP path (through the C ABI binding) against the CPU oracle, element by element,
 on the same seeded inputs.  Integer outputs must be bit-exact; attention within the stated tolerances."""
+import ctypes
+
 import numpy as np
 import pytest
 import torch
@@ -148,7 +150,7 @@ def test_retrieve_tiny_config_with_gpu_built_index():
 
 
 # ------------------------------------------------------------------ tree attention
-def attention_case(Nb, H, T, P, seed, dtype="bf16", per_batch=False, num_splits=0, Tq_extra=0, tree="random"):
+def attention_case(Nb, H, T, P, seed, dtype="bf16", per_batch=False, num_splits=0, Tq_extra=0, tree="random", scales=True):
     Tq = T + Tq_extra
     if tree == "chain":
         par = np.arange(-1, T - 1, dtype=np.int32)
@@ -173,6 +175,18 @@ def attention_case(Nb, H, T, P, seed, dtype="bf16", per_batch=False, num_splits=
         vb = synth.normal_bf16_bits(seed + 2, (Nb, H, P + T, 128))
         q, k, v = (synth.bf16_bits_to_f32(x) for x in (qb, kb, vb))
         dq, dk, dv = (dev(x.view(np.int16)).view(torch.bfloat16) for x in (qb, kb, vb))
+    elif dtype == "fp8kv":
+        # bf16 queries on an 8-bit cache: normal values divided by the slab's scale, then encoded by the oracle
+        qb = synth.normal_bf16_bits(seed, (Nb, H, Tq, 128))
+        q = synth.bf16_bits_to_f32(qb)
+        dq = dev(qb.view(np.int16)).view(torch.bfloat16)
+        k_scale = (0.25 + 2 * synth.uniform01(seed + 3, np.arange(Nb * H))).reshape(Nb, H).astype(np.float32)
+        v_scale = (0.25 + 2 * synth.uniform01(seed + 4, np.arange(Nb * H))).reshape(Nb, H).astype(np.float32)
+        if not scales:
+            k_scale[:], v_scale[:] = 1.0, 1.0
+        k8 = oracle.fp8_e4m3_encode(synth.normal_f32(seed + 1, (Nb, H, P + T, 128)) / k_scale[..., None, None])
+        v8 = oracle.fp8_e4m3_encode(synth.normal_f32(seed + 2, (Nb, H, P + T, 128)) / v_scale[..., None, None])
+        dk, dv = dev(k8), dev(v8)
     else:
         q = synth.normal_f32(seed, (Nb, H, Tq, 128))
         k = synth.normal_f32(seed + 1, (Nb, H, P + T, 128))
@@ -180,14 +194,19 @@ def attention_case(Nb, H, T, P, seed, dtype="bf16", per_batch=False, num_splits=
         dq, dk, dv = dev(q), dev(k), dev(v)
     scale = 1.0 / np.sqrt(128.0)
     omask = mask[:, None] if per_batch else mask
-    want = oracle.tree_attention(q, k, v, omask, P, scale)
     dmask = dev(mask.view(np.int64)) if T > 0 else torch.zeros((Tq, 1), dtype=torch.int64, device="cuda")
     out = torch.full_like(dq, float("nan"))
-    rest.rest_tree_attention(dq, dk, dv, dmask, P, float(scale), out=out, num_splits=num_splits)
+    if dtype == "fp8kv":
+        want = oracle.tree_attention_fp8kv(q, k8, v8, k_scale, v_scale, omask, P, scale)
+        rest.rest_tree_attention(dq, dk, dv, dmask, P, float(scale), out=out, num_splits=num_splits,
+                                 k_scale=dev(k_scale) if scales else None, v_scale=dev(v_scale) if scales else None)
+    else:
+        want = oracle.tree_attention(q, k, v, omask, P, scale)
+        rest.rest_tree_attention(dq, dk, dv, dmask, P, float(scale), out=out, num_splits=num_splits)
     torch.cuda.synchronize()
     got = out.float().cpu().numpy().astype(np.float64)
     assert np.isfinite(got).all()
-    if dtype == "bf16":
+    if dtype in ("bf16", "fp8kv"):
         assert np.abs(got - want).max() <= 2e-2, np.abs(got - want).max()
     else:
         for nb in range(Nb):
@@ -231,6 +250,52 @@ def test_tree_attention_bf16_variants():
 def test_tree_attention_bf16_tiny_config():
     """Config 'tiny': 1 layer x 32 heads x 128, KV length 256, the 32-node cap."""
     attention_case(1, 32, 32, 256, seed=22)
+
+
+@pytest.mark.parametrize("T,P,ns", [(1, 1, 0), (16, 100, 0), (33, 64, 0), (64, 256, 0), (64, 1000, 3), (64, 2048, 0), (100, 77, 0),
+                                     (128, 700, 3), (256, 300, 5), (200, 1, 64), (130, 2050, 2), (64, 0, 0), (40, 3, 8)])
+def test_tree_attention_on_8bit_cache(T, P, ns):
+    """K and V as E4M3 bytes with per-(batch, head) scales: two-, four- and eight-wavefront streams, whole units and
+    units cut between streams, ragged last tiles."""
+    attention_case(2, 3, T, P, seed=500 + T + P, dtype="fp8kv", num_splits=ns)
+
+
+def test_tree_attention_on_8bit_cache_variants():
+    attention_case(3, 2, 64, 200, seed=507, dtype="fp8kv", per_batch=True)
+    attention_case(2, 2, 64, 200, seed=508, dtype="fp8kv", Tq_extra=1, scales=False)
+    attention_case(1, 2, 0, 129, seed=510, dtype="fp8kv", Tq_extra=3)            # no draft keys
+    attention_case(9, 5, 64, 64, seed=511, dtype="fp8kv")                         # streams not a multiple of 8
+    attention_case(5, 7, 96, 1000, seed=514, dtype="fp8kv", tree="chain")
+    attention_case(1, 32, 32, 256, seed=522, dtype="fp8kv")
+    # token-major cache [Nb, L, H, D] viewed as [Nb, H, L, D], every code (NaN excepted) present, extreme magnitudes
+    Nb, H, T, P = 2, 4, 64, 300
+    qb = synth.normal_bf16_bits(1, (Nb, H, T, 128))
+    codes = synth.randint(31, np.arange(2 * Nb * (P + T) * H * 128), 0, 256).astype(np.uint8).reshape(2, Nb, P + T, H, 128)
+    codes[(codes & 0x7F) == 0x7F] = 0x38
+    codes[0] = np.where((codes[0] & 0x78) > 0x48, codes[0] & 0xC7 | 0x30, codes[0])    # keys: |k| < 4 keeps the softmax soft
+    k_scale = np.full((Nb, H), 0.5, np.float32)
+    v_scale = np.full((Nb, H), 2.0 ** -6, np.float32)
+    mask = synth.random_tree(T, 5)[3]
+    dq = dev(qb.view(np.int16)).view(torch.bfloat16)
+    dk, dv = dev(codes[0]).permute(0, 2, 1, 3), dev(codes[1]).permute(0, 2, 1, 3)
+    out = rest.rest_tree_attention(dq, dk, dv, dev(mask.view(np.int64)), P, 0.088, k_scale=dev(k_scale), v_scale=dev(v_scale))
+    torch.cuda.synchronize()
+    want = oracle.tree_attention_fp8kv(synth.bf16_bits_to_f32(qb), codes[0].transpose(0, 2, 1, 3), codes[1].transpose(0, 2, 1, 3),
+                                       k_scale, v_scale, mask, P, 0.088)
+    err = np.abs(out.float().cpu().numpy() - want)
+    assert (err <= 2e-2 * np.maximum(1.0, np.abs(want))).all(), err.max()
+    # refused before anything is launched: fp32 queries on an 8-bit cache; cache strides that are not multiples of 16
+    d = rest.make_attn_desc(dq, dk, dv, out, P, 0.088, False)
+    args = (dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), dev(mask.view(np.int64)).data_ptr(), out.data_ptr())
+    ws = torch.empty(max(rest.rest_tree_attention_workspace_bytes(d), 16), dtype=torch.uint8, device="cuda")
+    tail = (ctypes.byref(d), ws.data_ptr(), ws.numel(), None)
+    assert rest._lib.rest_tree_attention(*args, *tail) == rest.REST_OK
+    d.dtype = rest.REST_FP32
+    assert rest._lib.rest_tree_attention(*args, *tail) == rest.REST_INVALID_ARG
+    d.dtype = rest.REST_BF16
+    d.k_stride[2] = H * 128 + 8
+    assert rest._lib.rest_tree_attention(*args, *tail) == rest.REST_INVALID_ARG
+    torch.cuda.synchronize()
 
 
 @pytest.mark.parametrize("T,P,ns", [(1, 3, 1), (64, 256, 1), (33, 200, 4), (130, 77, 2)])
