@@ -435,6 +435,26 @@ def rope_append(q, k_new, v_new, k_cache, v_cache, pos_ids, pos_offset: int, pre
     return qr, kc, vc
 
 
+def rope_append_fp8kv(q, k_new, v_new, k_cache8, v_cache8, k_scale, v_scale, pos_ids, pos_offset: int,
+                      prefix_len: int, theta: float = 10000.0):
+    """The same step on an 8-bit cache: the embedded key divided by its slab's k_scale, and the value
+    divided by v_scale, are stored as the nearest E4M3 codes (saturating).  q, k_new, v_new [Nb, H, T, D];
+    caches [Nb, H, L, D] uint8; scales [Nb, H].  Returns (q embedded float64, k cache, v cache, and the two
+    exact quotients [Nb, H, T, D] the new codes were rounded from)."""
+    pos = np.asarray(pos_ids, dtype=np.int64) + int(pos_offset)
+    if pos.ndim == 2:
+        pos = pos[:, None, :]                       # [Nb, T]: shared by the heads
+    T = np.asarray(q).shape[-2]
+    P = int(prefix_len)
+    kx = rope(k_new, pos, theta) / np.asarray(k_scale, dtype=np.float64)[..., None, None]
+    vx = np.asarray(v_new, dtype=np.float64) / np.asarray(v_scale, dtype=np.float64)[..., None, None]
+    kc = np.array(k_cache8, dtype=np.uint8, copy=True)
+    vc = np.array(v_cache8, dtype=np.uint8, copy=True)
+    kc[..., P:P + T, :] = fp8_e4m3_encode(kx)
+    vc[..., P:P + T, :] = fp8_e4m3_encode(vx)
+    return rope(q, pos, theta), kc, vc, kx, vx
+
+
 def kv_compact(cache: np.ndarray, prefix_len: int, accept_path: np.ndarray, accept_len: int) -> np.ndarray:
     """After acceptance: row prefix_len + i of the result is row prefix_len +
     accept_path[i] of the input for i < accept_len; every other row is

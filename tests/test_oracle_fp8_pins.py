@@ -65,3 +65,45 @@ def test_attention_on_an_8bit_cache_is_plain_attention_on_the_decoded_values():
             ref = oracle.tree_attention_loops(q[nb, h], oracle.fp8_e4m3_decode(k8[nb, h]), oracle.fp8_e4m3_decode(v8[nb, h]),
                                               mask, P, 0.3 * ks[nb, h]) * vs[nb, h]
             np.testing.assert_allclose(got[nb, h], ref, rtol=1e-12, atol=1e-14)
+
+
+def test_append_to_an_8bit_cache():
+    Nb, H, T, P, L, D = 2, 3, 6, 5, 14, 16
+    q = synth.normal_f32(21, (Nb, H, T, D)).astype(np.float64)
+    kn = synth.normal_f32(22, (Nb, H, T, D)).astype(np.float64)
+    vn = synth.normal_f32(23, (Nb, H, T, D)).astype(np.float64)
+    kc = synth.randint(24, np.arange(Nb * H * L * D), 0, 0x7F).astype(np.uint8).reshape(Nb, H, L, D)
+    vc = synth.randint(25, np.arange(Nb * H * L * D), 0, 0x7F).astype(np.uint8).reshape(Nb, H, L, D)
+    ks = 0.25 + synth.uniform01(26, np.arange(Nb * H)).reshape(Nb, H)
+    vs = 0.25 + synth.uniform01(27, np.arange(Nb * H)).reshape(Nb, H)
+    pos = np.array([1, 1, 2, 2, 3, 4])
+    qr, k8, v8, kx, vx = oracle.rope_append_fp8kv(q, kn, vn, kc, vc, ks, vs, pos, P - 1, P, 10000.0)
+    # the 16-bit definition gives the values that are quantised; q is embedded as there
+    q_ref, k_ref, v_ref = oracle.rope_append(q, kn, vn, np.zeros((Nb, H, L, D)), np.zeros((Nb, H, L, D)), pos, P - 1, P, 10000.0)
+    np.testing.assert_array_equal(qr, q_ref)
+    np.testing.assert_allclose(kx * ks[..., None, None], k_ref[:, :, P:P + T], rtol=1e-15, atol=0)
+    np.testing.assert_allclose(vx * vs[..., None, None], v_ref[:, :, P:P + T], rtol=1e-15, atol=0)
+    # stored codes are within half a grid step of the quotient (grid step = 2^(exponent - 3), 2^-9 below 2^-6)
+    for x, c8 in ((kx, k8), (vx, v8)):
+        new = oracle.fp8_e4m3_decode(c8[:, :, P:P + T])
+        step = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(x), 2.0 ** -6))) - 3)
+        assert (np.abs(new - x) <= step / 2).all() and (np.sign(new) * np.sign(x) >= 0).all()
+    # rows outside P .. P+T-1 keep their codes
+    for old, c8 in ((kc, k8), (vc, v8)):
+        np.testing.assert_array_equal(c8[:, :, :P], old[:, :, :P])
+        np.testing.assert_array_equal(c8[:, :, P + T:], old[:, :, P + T:])
+    # representable values at position 0 (no rotation) and unit scales come back as their own codes; a per-batch
+    # position array gives every batch entry its own angles
+    codes = synth.randint(28, np.arange(Nb * H * T * D), 0, 0x7F).astype(np.uint8).reshape(Nb, H, T, D)
+    one = np.ones((Nb, H))
+    _, k8, v8, _, _ = oracle.rope_append_fp8kv(q, oracle.fp8_e4m3_decode(codes), -oracle.fp8_e4m3_decode(codes), kc, vc, one, one,
+                                               np.zeros(T, np.int64), 0, P)
+    np.testing.assert_array_equal(k8[:, :, P:P + T], codes)
+    np.testing.assert_array_equal(v8[:, :, P:P + T] & 0x7F, codes & 0x7F)
+    pos2 = np.stack([pos, pos[::-1]])
+    _, k8b, _, _, _ = oracle.rope_append_fp8kv(q, kn, vn, kc, vc, ks, vs, pos2, P - 1, P)
+    _, k8r, _, _, _ = oracle.rope_append_fp8kv(q[1:], kn[1:], vn[1:], kc[1:], vc[1:], ks[1:], vs[1:], pos[::-1], P - 1, P)
+    np.testing.assert_array_equal(k8b[1], k8r[0])
+    # saturation: a scale far too small stores the largest magnitude
+    _, ksat, _, _, _ = oracle.rope_append_fp8kv(q, kn * 1e12, vn, kc, vc, one, one, pos, P - 1, P)
+    assert set(np.unique(ksat[:, :, P:P + T] & 0x7F)) == {0x7E}
