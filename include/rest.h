@@ -317,6 +317,13 @@ rest_status rest_sample_ids(const float* d_logits, int64_t row_stride, const flo
  *
  * D must be 128; strides are in elements for the Nb, H and row axes, D
  * contiguous, rows 16-byte aligned.  Both calls only enqueue work on `stream`.
+ *
+ * 8-bit cache (cache_dtype = REST_KV_FP8_E4M3, see rest_tree_attention): the
+ * caches hold one E4M3 byte per element, strides in bytes and multiples of 16.
+ * rest_rope_append then stores, for slab (nb, h), the codes nearest to
+ * rotated key / d_k_scale[nb*H + h] and value / d_v_scale[nb*H + h] (ties to
+ * the even code, magnitudes beyond 448 saturate; the quotients are formed in
+ * fp32); d_q, d_k_new and d_v_new stay bf16.  rest_kv_compact moves bytes.
  * ---------------------------------------------------------------------- */
 typedef struct {
     int32_t Nb, H, T, D;
@@ -330,6 +337,10 @@ typedef struct {
     int64_t vn_stride[3];
     int64_t kc_stride[3];
     int64_t vc_stride[3];
+    int32_t cache_dtype;     /* REST_KV_AS_DTYPE or REST_KV_FP8_E4M3 */
+    int32_t reserved_;       /* set to 0 */
+    const float* d_k_scale;  /* 8-bit cache: [Nb*H] device floats, NULL = 1 */
+    const float* d_v_scale;
 } rest_kv_desc;
 
 rest_status rest_rope_append(void* d_q, const void* d_k_new, const void* d_v_new, void* d_k_cache, void* d_v_cache,

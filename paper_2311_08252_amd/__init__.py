@@ -80,7 +80,9 @@ class rest_kv_desc(ctypes.Structure):
                 ("P", ctypes.c_int32), ("pos_offset", ctypes.c_int32), ("per_batch", ctypes.c_int32),
                 ("dtype", ctypes.c_int32), ("theta", ctypes.c_double),
                 ("q_stride", ctypes.c_int64 * 3), ("kn_stride", ctypes.c_int64 * 3), ("vn_stride", ctypes.c_int64 * 3),
-                ("kc_stride", ctypes.c_int64 * 3), ("vc_stride", ctypes.c_int64 * 3)]
+                ("kc_stride", ctypes.c_int64 * 3), ("vc_stride", ctypes.c_int64 * 3),
+                ("cache_dtype", ctypes.c_int32), ("reserved_", ctypes.c_int32), ("d_k_scale", ctypes.c_void_p),
+                ("d_v_scale", ctypes.c_void_p)]
 
 
 _lib.rest_status_string.restype = ctypes.c_char_p
@@ -387,13 +389,24 @@ def rest_accept(ids: torch.Tensor, tree: Tree, path_cap: int,
 
 def make_kv_desc(k_cache: torch.Tensor, v_cache: torch.Tensor, T: int, prefix_len: int, pos_offset: int | None = None,
                  theta: float = 10000.0, per_batch: bool = False, q: torch.Tensor | None = None,
-                 k_new: torch.Tensor | None = None, v_new: torch.Tensor | None = None) -> rest_kv_desc:
+                 k_new: torch.Tensor | None = None, v_new: torch.Tensor | None = None,
+                 k_scale: torch.Tensor | None = None, v_scale: torch.Tensor | None = None) -> rest_kv_desc:
     Nb, H, _, D = k_cache.shape
     d = rest_kv_desc()
     d.Nb, d.H, d.T, d.D, d.P = Nb, H, T, D, prefix_len
     d.pos_offset = prefix_len - 1 if pos_offset is None else pos_offset
     d.per_batch = 1 if per_batch else 0
-    d.dtype = {torch.bfloat16: REST_BF16, torch.float32: REST_FP32}[k_cache.dtype]
+    if k_cache.dtype == torch.uint8:          # one OCP E4M3 byte per cached element; the new rows arrive as bf16
+        assert v_cache.dtype == torch.uint8
+        d.dtype, d.cache_dtype = REST_BF16, REST_KV_FP8_E4M3
+        for name, t in (("d_k_scale", k_scale), ("d_v_scale", v_scale)):
+            if t is not None:
+                assert t.dtype == torch.float32 and t.is_contiguous() and t.numel() == Nb * H
+                setattr(d, name, t.data_ptr())
+    else:
+        assert k_scale is None and v_scale is None
+        d.dtype = {torch.bfloat16: REST_BF16, torch.float32: REST_FP32}[k_cache.dtype]
+        d.cache_dtype = REST_KV_AS_DTYPE
     d.theta = theta
     for name, t in (("q_stride", q), ("kn_stride", k_new), ("vn_stride", v_new), ("kc_stride", k_cache),
                     ("vc_stride", v_cache)):
@@ -405,14 +418,16 @@ def make_kv_desc(k_cache: torch.Tensor, v_cache: torch.Tensor, T: int, prefix_le
 
 def rest_rope_append(q: torch.Tensor, k_new: torch.Tensor, v_new: torch.Tensor, k_cache: torch.Tensor,
                      v_cache: torch.Tensor, pos_ids: torch.Tensor, prefix_len: int, pos_offset: int | None = None,
-                     theta: float = 10000.0) -> None:
+                     theta: float = 10000.0, k_scale: torch.Tensor | None = None,
+                     v_scale: torch.Tensor | None = None) -> None:
     """q, k_new, v_new [Nb,H,T,128]; caches [Nb,H,>=P+T,128] (bf16, device); pos_ids [T] or [Nb,T] int32.
     Rotates q in place and writes the rotated keys and the values to cache rows P .. P+T-1.  Enqueues on the
     current stream."""
     assert q.dim() == 4 and q.shape == k_new.shape == v_new.shape and k_cache.shape == v_cache.shape
     T = q.shape[2]
     assert k_cache.shape[2] >= prefix_len + T and pos_ids.shape[-1] == T and pos_ids.is_contiguous()
-    desc = make_kv_desc(k_cache, v_cache, T, prefix_len, pos_offset, theta, pos_ids.dim() == 2, q, k_new, v_new)
+    desc = make_kv_desc(k_cache, v_cache, T, prefix_len, pos_offset, theta, pos_ids.dim() == 2, q, k_new, v_new,
+                        k_scale, v_scale)
     st = _lib.rest_rope_append(_dev(q), _dev(k_new), _dev(v_new), _dev(k_cache), _dev(v_cache),
                                _dev(pos_ids, torch.int32), ctypes.byref(desc), _stream())
     if st != REST_OK:

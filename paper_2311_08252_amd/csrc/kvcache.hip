@@ -24,6 +24,8 @@ struct KvParams {
     const int32_t* pos_ids;
     const int32_t* path;
     const int32_t* path_len;
+    const float* k_scale;   // 8-bit cache: [Nb*H] factors (stored code = value / factor), or null for 1
+    const float* v_scale;
     int32_t Nb, H, T, P, pos_offset, per_batch, path_cap;
     double log2_theta;
     int64_t qs[3], kns[3], vns[3], kcs[3], vcs[3];
@@ -50,6 +52,37 @@ __device__ inline void rotate8(i32x4& a, i32x4& b, const float (&c)[8], const fl
     }
 }
 
+// rotated plane vectors as floats: ra[e], rb[e] from the bf16 groups a, b
+__device__ inline void rotate8f(const i32x4& a, const i32x4& b, const float (&c)[8], const float (&s)[8], float (&ra)[8], float (&rb)[8]) {
+#pragma unroll
+    for (int w = 0; w < 4; w++) {
+        const float a0 = bf16_lo(a[w]), a1 = bf16_hi(a[w]), b0 = bf16_lo(b[w]), b1 = bf16_hi(b[w]);
+        ra[2 * w] = a0 * c[2 * w] - b0 * s[2 * w];
+        rb[2 * w] = a0 * s[2 * w] + b0 * c[2 * w];
+        ra[2 * w + 1] = a1 * c[2 * w + 1] - b1 * s[2 * w + 1];
+        rb[2 * w + 1] = a1 * s[2 * w + 1] + b1 * c[2 * w + 1];
+    }
+}
+
+// eight floats divided by `scale` -> eight E4M3 codes (nearest even, magnitudes beyond 448 saturate) in two dwords
+typedef int32_t i32x2 __attribute__((ext_vector_type(2)));
+__device__ inline i32x2 to_e4m3(const float (&x)[8], float scale) {
+    int32_t w0, w1;
+    float y[8];
+#pragma unroll
+    for (int e = 0; e < 8; e++) {
+        const float q = x[e] / scale;
+        y[e] = q == q ? fminf(fmaxf(q, -448.f), 448.f) : q;     // a NaN stays a NaN (code 0x7f)
+    }
+    w0 = __builtin_amdgcn_cvt_pk_fp8_f32(y[0], y[1], 0, false);
+    w0 = __builtin_amdgcn_cvt_pk_fp8_f32(y[2], y[3], w0, true);
+    w1 = __builtin_amdgcn_cvt_pk_fp8_f32(y[4], y[5], 0, false);
+    w1 = __builtin_amdgcn_cvt_pk_fp8_f32(y[6], y[7], w1, true);
+    return i32x2{w0, w1};
+}
+
+// C8: the caches hold one E4M3 byte per element (128-byte rows); q, k_new, v_new are bf16 either way
+template <bool C8>
 __global__ __launch_bounds__(256) void rope_append_kernel(KvParams p) {
     __shared__ float lds_c[4][64], lds_s[4][64];
     const int tid = threadIdx.x;
@@ -85,18 +118,38 @@ __global__ __launch_bounds__(256) void rope_append_kernel(KvParams p) {
         i32x4 ka = *(const i32x4*)kp, kb = *(const i32x4*)(kp + 64);
         const i32x4 va = *(const i32x4*)vp, vb = *(const i32x4*)(vp + 64);
         rotate8(qa, qb, c, s);
-        rotate8(ka, kb, c, s);
         *(i32x4*)qp = qa;
         *(i32x4*)(qp + 64) = qb;
-        __bf16* kd = p.kc + nb * p.kcs[0] + h * p.kcs[1] + (int64_t)(p.P + t) * p.kcs[2] + 8 * o;
-        __bf16* vd = p.vc + nb * p.vcs[0] + h * p.vcs[1] + (int64_t)(p.P + t) * p.vcs[2] + 8 * o;
-        *(i32x4*)kd = ka;
-        *(i32x4*)(kd + 64) = kb;
-        *(i32x4*)vd = va;
-        *(i32x4*)(vd + 64) = vb;
+        if constexpr (!C8) {
+            rotate8(ka, kb, c, s);
+            __bf16* kd = p.kc + nb * p.kcs[0] + h * p.kcs[1] + (int64_t)(p.P + t) * p.kcs[2] + 8 * o;
+            __bf16* vd = p.vc + nb * p.vcs[0] + h * p.vcs[1] + (int64_t)(p.P + t) * p.vcs[2] + 8 * o;
+            *(i32x4*)kd = ka;
+            *(i32x4*)(kd + 64) = kb;
+            *(i32x4*)vd = va;
+            *(i32x4*)(vd + 64) = vb;
+        } else {
+            const float ksc = p.k_scale ? p.k_scale[nb * p.H + h] : 1.f, vsc = p.v_scale ? p.v_scale[nb * p.H + h] : 1.f;
+            float ra[8], rb[8], fa[8], fb[8];
+            rotate8f(ka, kb, c, s, ra, rb);
+#pragma unroll
+            for (int w = 0; w < 4; w++) {
+                fa[2 * w] = bf16_lo(va[w]); fa[2 * w + 1] = bf16_hi(va[w]);
+                fb[2 * w] = bf16_lo(vb[w]); fb[2 * w + 1] = bf16_hi(vb[w]);
+            }
+            const i32x2 ka8 = to_e4m3(ra, ksc), kb8 = to_e4m3(rb, ksc), va8 = to_e4m3(fa, vsc), vb8 = to_e4m3(fb, vsc);
+            unsigned char* kd = (unsigned char*)p.kc + nb * p.kcs[0] + h * p.kcs[1] + (int64_t)(p.P + t) * p.kcs[2] + 8 * o;
+            unsigned char* vd = (unsigned char*)p.vc + nb * p.vcs[0] + h * p.vcs[1] + (int64_t)(p.P + t) * p.vcs[2] + 8 * o;
+            *(i32x2*)kd = ka8;
+            *(i32x2*)(kd + 64) = kb8;
+            *(i32x2*)vd = va8;
+            *(i32x2*)(vd + 64) = vb8;
+        }
     }
 }
 
+// ELT: bytes per cached element (2: bf16, 1: E4M3); a row is 16 or 8 pieces of 16 bytes
+template <int ELT>
 __global__ __launch_bounds__(512) void kv_compact_kernel(KvParams p) {
     const int h = blockIdx.x, nb = blockIdx.y;
     const int i = threadIdx.x >> 4, piece = threadIdx.x & 15;
@@ -116,24 +169,24 @@ __global__ __launch_bounds__(512) void kv_compact_kernel(KvParams p) {
     __syncthreads();
     if (i < n && !live && piece == 0) atomicMin(&first_bad, i);
     __syncthreads();
-    live = live && i < first_bad;
-    __bf16* kbase = p.kc + nb * p.kcs[0] + h * p.kcs[1] + 8 * piece;
-    __bf16* vbase = p.vc + nb * p.vcs[0] + h * p.vcs[1] + 8 * piece;
+    live = live && i < first_bad && piece * 16 < kD * ELT;
+    unsigned char* kbase = (unsigned char*)p.kc + (nb * p.kcs[0] + h * p.kcs[1]) * ELT + 16 * piece;
+    unsigned char* vbase = (unsigned char*)p.vc + (nb * p.vcs[0] + h * p.vcs[1]) * ELT + 16 * piece;
     i32x4 kv = {0, 0, 0, 0}, vv = {0, 0, 0, 0};
     if (live) {
-        kv = *(const i32x4*)(kbase + (int64_t)(p.P + src) * p.kcs[2]);
-        vv = *(const i32x4*)(vbase + (int64_t)(p.P + src) * p.vcs[2]);
+        kv = *(const i32x4*)(kbase + (int64_t)(p.P + src) * p.kcs[2] * ELT);
+        vv = *(const i32x4*)(vbase + (int64_t)(p.P + src) * p.vcs[2] * ELT);
     }
     __syncthreads();
     if (live) {
-        *(i32x4*)(kbase + (int64_t)(p.P + i) * p.kcs[2]) = kv;
-        *(i32x4*)(vbase + (int64_t)(p.P + i) * p.vcs[2]) = vv;
+        *(i32x4*)(kbase + (int64_t)(p.P + i) * p.kcs[2] * ELT) = kv;
+        *(i32x4*)(vbase + (int64_t)(p.P + i) * p.vcs[2] * ELT) = vv;
     }
 }
 
-bool strides_ok(const int64_t (&s)[3]) {
+bool strides_ok(const int64_t (&s)[3], int64_t multiple = 8) {
     for (int i = 0; i < 3; i++)
-        if (s[i] < 0 || s[i] % 8) return false;
+        if (s[i] < 0 || s[i] % multiple) return false;
     return s[2] >= kD;
 }
 
@@ -143,13 +196,19 @@ bool desc_ok(const rest_kv_desc* d) {
     if (d->Nb > 65535) return false;                 // grid y
     if (!(d->theta > 1.0) || !(d->theta < 1e30)) return false;
     if ((int64_t)d->P + d->T > 0x7fffffff) return false;
-    return strides_ok(d->kc_stride) && strides_ok(d->vc_stride);
+    if (d->cache_dtype != REST_KV_AS_DTYPE && d->cache_dtype != REST_KV_FP8_E4M3) return false;
+    // rows are moved in 16-byte pieces
+    const int64_t mult = d->cache_dtype == REST_KV_FP8_E4M3 ? 16 : 8;
+    return strides_ok(d->kc_stride, mult) && strides_ok(d->vc_stride, mult);
 }
 
 void fill(KvParams& p, const rest_kv_desc* d) {
     p.Nb = d->Nb; p.H = d->H; p.T = d->T; p.P = d->P; p.pos_offset = d->pos_offset;
     p.per_batch = d->per_batch ? 1 : 0;
     p.log2_theta = log2(d->theta);
+    const bool c8 = d->cache_dtype == REST_KV_FP8_E4M3;
+    p.k_scale = c8 ? d->d_k_scale : nullptr;
+    p.v_scale = c8 ? d->d_v_scale : nullptr;
     for (int i = 0; i < 3; i++) {
         p.qs[i] = d->q_stride[i]; p.kns[i] = d->kn_stride[i]; p.vns[i] = d->vn_stride[i];
         p.kcs[i] = d->kc_stride[i]; p.vcs[i] = d->vc_stride[i];
@@ -174,7 +233,10 @@ extern "C" __attribute__((visibility("default"))) rest_status rest_rope_append(v
     // enough workgroups to fill the chip, at most one per eight heads
     int gz = (int)((2048 + (int64_t)tg * d->Nb - 1) / ((int64_t)tg * d->Nb));
     gz = gz < 1 ? 1 : (gz > hg ? hg : gz);
-    hipLaunchKernelGGL(rope_append_kernel, dim3(tg, d->Nb, gz), dim3(256), 0, (hipStream_t)stream, p);
+    if (d->cache_dtype == REST_KV_FP8_E4M3)
+        hipLaunchKernelGGL(rope_append_kernel<true>, dim3(tg, d->Nb, gz), dim3(256), 0, (hipStream_t)stream, p);
+    else
+        hipLaunchKernelGGL(rope_append_kernel<false>, dim3(tg, d->Nb, gz), dim3(256), 0, (hipStream_t)stream, p);
     REST_HIP_TRY(hipGetLastError());
     return REST_OK;
 }
@@ -191,7 +253,10 @@ extern "C" __attribute__((visibility("default"))) rest_status rest_kv_compact(vo
     p.path = d_accept_path;
     p.path_len = d_accept_len;
     p.path_cap = path_cap;
-    hipLaunchKernelGGL(kv_compact_kernel, dim3(d->H, d->Nb), dim3(512), 0, (hipStream_t)stream, p);
+    if (d->cache_dtype == REST_KV_FP8_E4M3)
+        hipLaunchKernelGGL(kv_compact_kernel<1>, dim3(d->H, d->Nb), dim3(512), 0, (hipStream_t)stream, p);
+    else
+        hipLaunchKernelGGL(kv_compact_kernel<2>, dim3(d->H, d->Nb), dim3(512), 0, (hipStream_t)stream, p);
     REST_HIP_TRY(hipGetLastError());
     return REST_OK;
 }

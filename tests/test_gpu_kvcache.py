@@ -125,6 +125,111 @@ def test_kv_compact_stops_at_an_entry_that_is_no_draft_row():
     np.testing.assert_array_equal(to_np(vc)[0], oracle.kv_compact(vc_np[0], P, path[0], 1))
 
 
+def codes(shape, seed):
+    """seeded E4M3 bytes (every finite code) as a device tensor and a numpy array"""
+    c = synth.randint(seed, np.arange(int(np.prod(shape))), 0, 256).astype(np.uint8).reshape(shape)
+    c[(c & 0x7F) == 0x7F] = 0x3A
+    return torch.from_numpy(c).cuda(), c
+
+
+def assert_codes(got, want, exact):
+    """E4M3 codes written by the library against the oracle's.  The library forms rotation and quotient in fp32, so
+    where the exact quotient lies within 2^-16 (relative) of the midpoint of two neighbouring values either neighbour
+    is right; everywhere else the codes are equal."""
+    diff = got != want
+    if diff.any():
+        g, w, x = oracle.fp8_e4m3_decode(got[diff]), oracle.fp8_e4m3_decode(want[diff]), exact[diff]
+        mid = 0.5 * (g + w)
+        step = np.abs(g - w)
+        assert (step <= 2.0 ** (np.floor(np.log2(np.maximum(np.abs(x), 2.0 ** -6))) - 3) * 1.001).all()    # neighbours
+        assert (np.abs(x - mid) <= 2.0 ** -16 * np.maximum(np.abs(x), 2.0 ** -9)).all(), float(np.abs(x - mid).max())
+    return int(diff.sum())
+
+
+@pytest.mark.parametrize("Nb,H,T,P,extra,per_batch,scales", [
+    (2, 3, 5, 7, 0, False, True), (1, 8, 64, 200, 3, False, True), (3, 5, 33, 100, 9, True, True),
+    (4, 32, 64, 4096, 0, True, False), (1, 1, 1, 0, 0, False, True), (2, 9, 256, 17, 5, False, True)])
+def test_rope_append_on_8bit_cache(Nb, H, T, P, extra, per_batch, scales):
+    L = P + T + extra
+    q, q_np = bf16_tensor((Nb, H, T, 128), 1)
+    kn, kn_np = bf16_tensor((Nb, H, T, 128), 2)
+    vn, vn_np = bf16_tensor((Nb, H, T, 128), 3)
+    kc, kc_np = codes((Nb, H, L, 128), 4)
+    vc, vc_np = codes((Nb, H, L, 128), 5)
+    ks = (0.05 + 0.5 * synth.uniform01(6, np.arange(Nb * H))).reshape(Nb, H).astype(np.float32)
+    vs = (0.05 + 0.5 * synth.uniform01(7, np.arange(Nb * H))).reshape(Nb, H).astype(np.float32)
+    vs.flat[0] = 0.002                                                   # most values of this slab saturate
+    if not scales:
+        ks[:], vs[:] = 1.0, 1.0
+    rng = np.random.default_rng(T + P)
+    pos_np = rng.integers(0, 17, size=(Nb, T) if per_batch else (T,)).astype(np.int32)
+    off = P - 1 if P else 41
+    q_ref, k_ref, v_ref, kx, vx = oracle.rope_append_fp8kv(q_np, kn_np, vn_np, kc_np, vc_np, ks, vs, pos_np, off, P, 10000.0)
+    rest.rest_rope_append(q, kn, vn, kc, vc, torch.from_numpy(pos_np).cuda(), P, off, 10000.0,
+                          k_scale=torch.from_numpy(ks).cuda() if scales else None,
+                          v_scale=torch.from_numpy(vs).cuda() if scales else None)
+    torch.cuda.synchronize()
+    assert_rotated(to_np(q), q_ref, q_np)
+    got_k, got_v = kc.cpu().numpy(), vc.cpu().numpy()
+    flips = assert_codes(got_k[:, :, P:P + T], k_ref[:, :, P:P + T], kx)
+    assert flips <= 1 + kx.size // 20000, flips
+    # a value is a bf16 number divided once: only the fp32 quotient can differ from the exact one
+    assert_codes(got_v[:, :, P:P + T], v_ref[:, :, P:P + T], vx)
+    if scales:
+        assert ((v_ref[0, 0, P:P + T] & 0x7F) == 0x7E).mean() > 0.2     # saturated values were among the cases
+    for got, old in ((got_k, kc_np), (got_v, vc_np)):                   # rows outside P .. P+T-1 keep their bytes
+        np.testing.assert_array_equal(got[:, :, :P], old[:, :, :P])
+        np.testing.assert_array_equal(got[:, :, P + T:], old[:, :, P + T:])
+
+
+def test_kv_compact_on_8bit_cache_is_bit_exact():
+    for Nb, H, T, P, paths in [(2, 3, 8, 5, [[1, 2, 5, -1, -1]]), (3, 4, 16, 9, [[2, 5, 9, 15, -1, -1], [-1] * 6, [0, 3, 4, 7, 8, 11]]),
+                               (1, 32, 64, 2048, [[0, 2, 7, 12, 20, 33, 41, 63] + [-1] * 8])]:
+        big_k, big_k_np = codes((Nb, H, P + T + 2, 256), 11)             # caches as halves of wider rows
+        big_v, big_v_np = codes((Nb, H, P + T + 2, 256), 12)
+        kc, vc = big_k[..., :128], big_v[..., 128:]
+        path = np.array(paths, dtype=np.int32)
+        lens = np.array([sum(1 for x in row if x >= 0) for row in paths], dtype=np.int32)
+        k_ref, v_ref = big_k_np.copy(), big_v_np.copy()
+        for nb in range(Nb):
+            row = nb if len(paths) > 1 else 0
+            k_ref[nb, ..., :128] = oracle.kv_compact(big_k_np[nb, ..., :128], P, path[row], lens[row])
+            v_ref[nb, ..., 128:] = oracle.kv_compact(big_v_np[nb, ..., 128:], P, path[row], lens[row])
+        rest.rest_kv_compact(kc, vc, torch.from_numpy(path).cuda(), torch.from_numpy(lens).cuda(), T, P)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(big_k.cpu().numpy(), k_ref)
+        np.testing.assert_array_equal(big_v.cpu().numpy(), v_ref)
+
+
+def test_layer_step_on_an_8bit_cache():
+    """append (quantising) -> tree attention on the 8-bit cache -> compact, against the oracle's chain of the same
+    steps; a code that differs at a rounding boundary moves one key element by one grid step, far inside the
+    attention tolerance."""
+    Nb, H, T, P = 2, 4, 48, 333
+    par, dep, tok, mask = synth.random_tree(T, 9)
+    q, q_np = bf16_tensor((Nb, H, T, 128), 31)
+    kn, kn_np = bf16_tensor((Nb, H, T, 128), 32)
+    vn, vn_np = bf16_tensor((Nb, H, T, 128), 33)
+    ks = (0.2 + 0.3 * synth.uniform01(34, np.arange(Nb * H))).reshape(Nb, H).astype(np.float32)
+    vs = (0.2 + 0.3 * synth.uniform01(35, np.arange(Nb * H))).reshape(Nb, H).astype(np.float32)
+    k8 = oracle.fp8_e4m3_encode(synth.normal_f32(36, (Nb, H, P + T, 128)) / ks[..., None, None])
+    v8 = oracle.fp8_e4m3_encode(synth.normal_f32(37, (Nb, H, P + T, 128)) / vs[..., None, None])
+    kc, vc = torch.from_numpy(k8).cuda(), torch.from_numpy(v8).cuda()
+    d_ks, d_vs = torch.from_numpy(ks).cuda(), torch.from_numpy(vs).cuda()
+    pos = dep.astype(np.int32)
+    rest.rest_rope_append(q, kn, vn, kc, vc, torch.from_numpy(pos).cuda(), P, k_scale=d_ks, v_scale=d_vs)
+    out = rest.rest_tree_attention(q, kc, vc, torch.from_numpy(mask.view(np.int64)).cuda(), P, 0.088, k_scale=d_ks, v_scale=d_vs)
+    path = np.array([[0, 1, 2, 3, -1, -1]], dtype=np.int32)
+    rest.rest_kv_compact(kc, vc, torch.from_numpy(path).cuda(), torch.tensor([4], dtype=torch.int32).cuda(), T, P)
+    torch.cuda.synchronize()
+    q_ref, k_ref, v_ref, _, _ = oracle.rope_append_fp8kv(q_np, kn_np, vn_np, k8, v8, ks, vs, pos, P - 1, P)
+    want = oracle.tree_attention_fp8kv(q_ref, k_ref, v_ref, ks, vs, mask, P, 0.088)
+    assert np.abs(to_np(out) - want).max() <= 2e-2
+    k_fin = oracle.kv_compact(k_ref, P, path[0], 4)
+    assert (kc.cpu().numpy() != k_fin).sum() <= 2
+    np.testing.assert_array_equal(vc.cpu().numpy()[:, :, :P], v8[:, :, :P])
+
+
 def test_layer_step_on_the_gpu_equals_plain_decoding_of_the_accepted_tokens():
     """retrieve -> rope_append -> tree attention -> accept -> compact, all on the GPU, against the oracle's
     token-by-token decoding of the accepted path (positions P, P+1, ...; causal attention)."""
