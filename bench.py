@@ -299,6 +299,27 @@ def side_measurements(rest, torch, synth, corp, index, w, q, k, v, out, tree, P,
 
     ms = timed(full_step, 50)
     res["step_with_cache_steps_us"] = round(ms * 1e3, 1)
+
+    # the same on an 8-bit (E4M3) cache with per-(layer, head) scales: half the cache bytes per step
+    sc_k = torch.full((Nb * H,), 0.5, dtype=torch.float32, device=dev)
+    sc_v = torch.full((Nb * H,), 0.5, dtype=torch.float32, device=dev)
+    k8 = (k.float() / 0.5).to(torch.float8_e4m3fn).view(torch.uint8)
+    v8 = (v.float() / 0.5).to(torch.float8_e4m3fn).view(torch.uint8)
+    ms = timed(lambda: rest.rest_tree_attention(q, k8, v8, mask, P, scale, out=out, k_scale=sc_k, v_scale=sc_v), 20)
+    res["attn_8bit_cache_single_launch_us"] = round(ms * 1e3, 1)
+    res["attn_8bit_cache_GBps"] = round(Nb * H * (2 * (P + T) * 128 + 2 * T * 128 * 2) / (ms * 1e-3) / 1e9, 1)
+    desc8 = rest.make_attn_desc(q2, k8, v8, out, P, scale, False, k_scale=sc_k, v_scale=sc_v)
+    ws8 = torch.empty(max(rest.rest_tree_attention_workspace_bytes(desc8), 16), dtype=torch.uint8, device=dev)
+
+    def full_step_8bit():
+        rest.rest_retrieve(index, ctx1, len1, out=one, **prm)
+        rest.rest_rope_append(q2, kn, vn, k8, v8, one.pos_ids[0], P, k_scale=sc_k, v_scale=sc_v)
+        rest.rest_tree_attention(q2, k8, v8, one.tree_mask[0], P, scale, out=out, workspace=ws8, k_scale=sc_k, v_scale=sc_v)
+        rest.rest_accept(ids, one, w.cont_len, al, ap, nx)
+        rest.rest_kv_compact(k8, v8, ap, al, T, P)
+
+    ms = timed(full_step_8bit, 50)
+    res["step_with_cache_steps_8bit_cache_us"] = round(ms * 1e3, 1)
     return res
 
 

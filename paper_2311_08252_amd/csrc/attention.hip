@@ -86,6 +86,7 @@ template <int NW, bool KV8>
 __global__ __launch_bounds__(64 * NW, 2) void tree_attn_bf16_kernel(AttnParams p) {
     constexpr int kElt = KV8 ? 1 : 2;                  // bytes per cached element
     constexpr int kFetch = KV8 ? 2 : 4;                // 16-byte pieces of K (and of V) a lane fetches per tile
+    constexpr bool kPairSwap = KV8;                    // LDS rows hold pieces 8..15 with the slots of each pair swapped
     constexpr int kSub = NW / 2;                       // 32-key blocks per tile
     constexpr int kTileKeys = kSub * kBlk;
     constexpr int kTileBytes = kSub * kSubBytes;       // K (or V) part of a tile
@@ -230,15 +231,18 @@ __global__ __launch_bounds__(64 * NW, 2) void tree_attn_bf16_kernel(AttnParams p
         if constexpr (KV8) {
 #pragma unroll
             for (int i = 0; i < 2; i++) {
-                // fetched piece g of tile row `row` becomes bf16 pieces 2g and 2g+1, parked in their swizzled slots
-                const int row = (2 * wave + i) * 8 + (lane >> 3), pc = 2 * (lane & 7);
+                // fetched piece g of tile row `row` becomes bf16 pieces 2g and 2g+1, parked in their swizzled slots.
+                // The eight lanes of a row store eight pieces of one parity at a time, which would hit each bank
+                // twice; swapping the slots of a pair in the upper half of the row (pieces 8..15) spreads one store
+                // over all banks.  The operand reads below undo the swap (kPairSwap).
+                const int row = (2 * wave + i) * 8 + (lane >> 3), pc = (2 * (lane & 7)) ^ ((lane & 7) >> 2);
                 unsigned char* krow = tile + row * 256;
                 unsigned char* vrow = tile + kTileBytes + row * 256;
                 const int swk = row & 15, swv = (row & 3) << 2;
                 *(i32x4*)(krow + ((pc ^ swk) << 4)) = widen(kr[i][0], kr[i][1]);
-                *(i32x4*)(krow + (((pc + 1) ^ swk) << 4)) = widen(kr[i][2], kr[i][3]);
+                *(i32x4*)(krow + (((pc ^ 1) ^ swk) << 4)) = widen(kr[i][2], kr[i][3]);
                 *(i32x4*)(vrow + ((pc ^ swv) << 4)) = widen(vr[i][0], vr[i][1]);
-                *(i32x4*)(vrow + (((pc + 1) ^ swv) << 4)) = widen(vr[i][2], vr[i][3]);
+                *(i32x4*)(vrow + (((pc ^ 1) ^ swv) << 4)) = widen(vr[i][2], vr[i][3]);
             }
         } else {
 #pragma unroll
@@ -333,7 +337,7 @@ __global__ __launch_bounds__(64 * NW, 2) void tree_attn_bf16_kernel(AttnParams p
             for (int r = 0; r < 16; r++) s[r] = 0.f;
 #pragma unroll
             for (int ks = 0; ks < 8; ks++) {
-                const bf16x8 a = *(const bf16x8*)(ldsK + (ka0 ^ (ks << 5)));
+                const bf16x8 a = *(const bf16x8*)(ldsK + (ka0 ^ (ks << 5) ^ (kPairSwap ? (ks >> 2) << 4 : 0)));
                 s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], s, 0, 0, 0);
             }
             // keep two K fragments in flight: read, read, then (multiply, read) ..., so that an LDS read's latency
@@ -404,7 +408,7 @@ __global__ __launch_bounds__(64 * NW, 2) void tree_attn_bf16_kernel(AttnParams p
             for (int ss = 0; ss < 2; ss++) {
 #pragma unroll
                 for (int dt = 0; dt < 4; dt++) {
-                    const unsigned char* a0 = ldsV + va0 + ss * 4096 + ((((uint32_t)dt << 2) ^ vsw) << 4);
+                    const unsigned char* a0 = ldsV + ((va0 + ss * 4096 + ((((uint32_t)dt << 2) ^ vsw) << 4)) ^ (kPairSwap ? (dt >> 1) << 4 : 0));
                     s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)a0);
                     s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(a0 + 8 * 256));
                     union { struct { s16x4 lo, hi; } sp; bf16x8 v; } u;

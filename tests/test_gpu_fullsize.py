@@ -136,6 +136,37 @@ def test_llama7b_cache_steps_at_benchmark_shape():
         np.testing.assert_array_equal(f64(vc[a, b]), oracle.kv_compact(f64(vc1[a, b]), P, path, A))
 
 
+def test_llama7b_attention_on_8bit_cache_at_benchmark_shape():
+    """The 8-bit cache in the benchmark's launch configuration (32 layers x 32 heads in one call, 2048 + 64 keys):
+    sampled (layer, head) slabs against the oracle."""
+    w = synth.WORKLOADS["llama7b"]
+    Nb, H, T, P = w.layers, w.heads, w.max_nodes, w.kv_len
+    g = torch.Generator(device="cuda")
+    g.manual_seed(w.qkv_seed + 11)
+    q = torch.randn((Nb, H, T, 128), generator=g, device="cuda").to(torch.bfloat16)
+    ks = 0.25 + torch.rand((Nb, H), generator=g, device="cuda")
+    vs = 0.25 + torch.rand((Nb, H), generator=g, device="cuda")
+    k8 = (torch.randn((Nb, H, P + T, 128), generator=g, device="cuda") / ks[..., None, None]).to(torch.float8_e4m3fn).view(torch.uint8)
+    v8 = (torch.randn((Nb, H, P + T, 128), generator=g, device="cuda") / vs[..., None, None]).to(torch.float8_e4m3fn).view(torch.uint8)
+    mask = synth.random_tree(T, 78)[3]
+    out = torch.full_like(q, float("nan"))
+    scale = 1.0 / np.sqrt(128.0)
+    rest.rest_tree_attention(q, k8, v8, dev(mask.view(np.int64)), P, float(scale), out=out, k_scale=ks, v_scale=vs)
+    torch.cuda.synchronize()
+    assert torch.isfinite(out.float()).all()
+    rng = np.random.default_rng(6)
+    picks = {(0, 0), (Nb - 1, H - 1)}
+    while len(picks) < 24:
+        picks.add((int(rng.integers(Nb)), int(rng.integers(H))))
+    worst = 0.0
+    for a, b in sorted(picks):
+        ref = oracle.tree_attention_fp8kv(q[a, b].float().cpu().numpy()[None, None], k8[a, b].cpu().numpy()[None, None],
+                                          v8[a, b].cpu().numpy()[None, None], ks[a, b].cpu().numpy().reshape(1, 1),
+                                          vs[a, b].cpu().numpy().reshape(1, 1), mask, P, scale)[0, 0]
+        worst = max(worst, float(np.abs(out[a, b].float().cpu().numpy() - ref).max()))
+    assert worst <= 2e-2, worst
+
+
 @pytest.mark.parametrize("T,P", [(16, 1024), (64, 8192), (128, 4096), (256, 1024), (256, 8192)])
 def test_sweep_shapes_random_trees(T, P):
     """Tree-size / KV-length sweep at the 7B head shape with random tries (branching <= 8, depth <= 16)."""
