@@ -44,6 +44,9 @@ def main() -> int:
                          "synthetic datastore and print the mean generated length per step")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device-to-device copy five times (reference for rocprofv3 --pmc byte counters)")
+    ap.add_argument("--attention-8bit-only", action="store_true",
+                    help="only run the tree attention on an 8-bit (E4M3) cache at the llama7b shape a few times "
+                         "(for rocprofv3 counter runs of that kernel)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -67,6 +70,29 @@ def main() -> int:
         return 0
     if args.ablation:
         print(json.dumps({"ablation": ablation(rest, torch, synth, np, dev)}))
+        return 0
+    if args.attention_8bit_only:
+        w = synth.WORKLOADS["llama7b"]
+        Nb, H, T, P = w.layers, w.heads, w.max_nodes, w.kv_len
+        g = torch.Generator(device=dev)
+        g.manual_seed(w.qkv_seed)
+        q = torch.randn((Nb, H, T, 128), generator=g, device=dev).to(torch.bfloat16)
+        k8, v8 = (torch.randn((Nb, H, P + T, 128), generator=g, device=dev).to(torch.float8_e4m3fn).view(torch.uint8)
+                  for _ in range(2))
+        sc = torch.full((Nb * H,), 1.0, dtype=torch.float32, device=dev)
+        mask = torch.from_numpy(synth.random_tree(T, 5)[3].view(np.int64)).to(dev)
+        out = torch.empty_like(q)
+        for _ in range(3):
+            rest.rest_tree_attention(q, k8, v8, mask, P, 1.0 / float(np.sqrt(128.0)), out=out, k_scale=sc, v_scale=sc)
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(10):
+            rest.rest_tree_attention(q, k8, v8, mask, P, 1.0 / float(np.sqrt(128.0)), out=out, k_scale=sc, v_scale=sc)
+        b.record()
+        torch.cuda.synchronize()
+        print(json.dumps({"attention_8bit_cache_us": round(a.elapsed_time(b) / 10 * 1e3, 1),
+                          "bytes_per_launch": Nb * H * (2 * (P + T) * 128 + 2 * T * 128 * 2)}))
         return 0
     w = synth.WORKLOADS[args.workload]
     B = w.batch         # contexts per step: 1, or 32 for the batched workload (one layer, per-context masks)
