@@ -210,7 +210,7 @@ def main() -> int:
                                + (f"{Nb} layers x {H} heads x {D}, KV length {P}+{c}, one launch over all layers" if B == 1 else
                                   f"{B} contexts x {H} heads x {D} (one layer, per-context masks), KV length {P}+{c}"),
                    "global_batch": B, "kv_len": P, "tree_nodes": c},
-        "roofline": {"bound": "hbm", "kernel": "tree_attn_bf16_kernel<2>", "achieved": round(achieved, 1),
+        "roofline": {"bound": "hbm", "kernel": "tree_attn_bf16_kernel<2, false>", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "traffic": traffic, "algorithmic_bytes_per_launch": alg_bytes,
                      "avg_launch_us": round(attn_ms * 1e3, 2), "launches_timed": len(attn_samples),
