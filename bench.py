@@ -6,7 +6,7 @@ from the retrieve output in HBM) -> rest_accept, on the Llama-2-7B-shaped synthe
 100M-token Zipf(1.1) datastore with planted motifs, contexts of 512 tokens, K=5000, m=16, c=64,
 32 layers x 32 heads x 128, KV length 2048, bf16.  All inputs are resident in HBM before timing starts.
 
-Prints ONE JSON line (see README for the fields).  The CPU oracle is used only for the
+Prints ONE JSON line (metric, value, roofline, cpu_baseline, extra side measurements).  The CPU oracle is used only for the
 `cpu_baseline` leg and a sampled parity check, never inside the timed region.
 """
 from __future__ import annotations
