@@ -263,6 +263,21 @@ def side_measurements(rest, torch, synth, corp, index, w, q, k, v, out, tree, P,
         lat.append(timed(lambda: rest.rest_retrieve(index, d_ctx[j:j + 1], d_len[j:j + 1], out=one, **prm), 20))
     res["retrieve_batch1_us"] = [round(x * 1e3, 1) for x in lat]
 
+    # the same datastore left in pinned host memory (what one larger than the GPU's memory would need): the kernels
+    # read it in place over the host link
+    if corp.tokens.size <= 200_000_000:
+        h_corpus = torch.empty(corp.tokens.shape, dtype=torch.from_numpy(corp.tokens[:1]).dtype, pin_memory=True)
+        h_corpus.copy_(torch.from_numpy(corp.tokens))
+        sa_dev = index.suffix_array()
+        h_sa = torch.empty(sa_dev.shape, dtype=sa_dev.dtype, pin_memory=True)
+        h_sa.copy_(sa_dev)
+        del sa_dev
+        torch.cuda.synchronize()
+        hidx = rest.rest_index_from_sa(h_corpus, h_sa)
+        lat = [timed(lambda: rest.rest_retrieve(hidx, d_ctx[j:j + 1], d_len[j:j + 1], out=one, **prm), 20) for j in range(8)]
+        res["retrieve_batch1_host_resident_datastore_us"] = [round(x * 1e3, 1) for x in lat]
+        del hidx, h_corpus, h_sa
+
     Nb = q.shape[0]
     mask = tree.tree_mask[0]
 

@@ -106,7 +106,11 @@ int32_t rest_index_sort_depth(const rest_index* index);
 
 /* Wraps a caller-supplied suffix array (e.g. one built elsewhere or loaded
  * from disk); both arrays are borrowed.  The array is trusted, not checked.
- * Only the small search table is computed (synchronises `stream`). */
+ * Only the small search table is computed (synchronises `stream`).
+ * Here d_corpus and d_sa may also be host memory that the device addresses
+ * directly (hipHostMalloc): a datastore larger than the GPU's memory stays on
+ * the host and rest_retrieve reads it over the host link (a few hundred small
+ * reads per context; same results, about twice the latency of one context). */
 rest_status rest_index_from_sa(const void* d_corpus, const void* d_sa, uint64_t n_tokens,
                                int32_t token_bytes, int32_t sa_bytes, void* stream, rest_index** out);
 

@@ -147,9 +147,27 @@ def _stream() -> int:
     return torch.cuda.current_stream().cuda_stream
 
 
-def _dev(t: torch.Tensor, dtype=None) -> int:
+class _hipPointerAttribute(ctypes.Structure):
+    _fields_ = [("type", ctypes.c_int), ("device", ctypes.c_int), ("devicePointer", ctypes.c_void_p),
+                ("hostPointer", ctypes.c_void_p), ("isManaged", ctypes.c_int), ("allocationFlags", ctypes.c_uint)]
+
+
+def _pinned_is_mapped(t: torch.Tensor) -> bool:
+    """True if the GPU reads this pinned host tensor at its host address (asked of the HIP runtime, so that a
+    pointer the device cannot follow is never handed to a kernel)."""
+    try:
+        hip = ctypes.CDLL("libamdhip64.so")
+    except OSError:
+        return False
+    a = _hipPointerAttribute()
+    rc = hip.hipPointerGetAttributes(ctypes.byref(a), ctypes.c_void_p(t.data_ptr()))
+    return rc == 0 and a.devicePointer == t.data_ptr()
+
+
+def _dev(t: torch.Tensor, dtype=None, pinned_ok: bool = False) -> int:
     if not t.is_cuda:
-        raise TypeError("expected a device tensor")
+        if not (pinned_ok and t.is_pinned() and _pinned_is_mapped(t)):
+            raise TypeError("expected a device tensor" + (" or a pinned host tensor the device can address" if pinned_ok else ""))
     if dtype is not None and t.dtype != dtype:
         raise TypeError(f"expected {dtype}, got {t.dtype}")
     return t.data_ptr()
@@ -232,10 +250,12 @@ def rest_build_index_prefix(corpus: torch.Tensor, sa_bytes: int = 4, depth: int 
 
 
 def rest_index_from_sa(corpus: torch.Tensor, sa: torch.Tensor) -> RestIndex:
+    """Wraps a token stream and its suffix array.  Both may also live in pinned host memory (a datastore larger than
+    the GPU's memory): the kernels then read them over the host link, a few hundred small reads per context."""
     assert corpus.is_contiguous() and sa.is_contiguous() and corpus.numel() == sa.numel()
     sa_bytes = {torch.int32: 4, torch.int64: 8}[sa.dtype]
     h = ctypes.c_void_p()
-    st = _lib.rest_index_from_sa(_dev(corpus), _dev(sa), corpus.numel(), _token_bytes(corpus), sa_bytes, _stream(),
+    st = _lib.rest_index_from_sa(_dev(corpus, pinned_ok=True), _dev(sa, pinned_ok=True), corpus.numel(), _token_bytes(corpus), sa_bytes, _stream(),
                                  ctypes.byref(h))
     if st != REST_OK:
         raise RestError(st, "rest_index_from_sa")

@@ -480,6 +480,28 @@ def test_depth_limited_index_serves_retrieval_like_the_suffix_array(tmp_path):
     torch.cuda.synchronize()
 
 
+def test_datastore_in_pinned_host_memory():
+    """A datastore that does not fit the GPU stays in pinned host memory; retrieval reads it in place."""
+    corp = synth.make_corpus(400_000, 14, 40)
+    ctx, lens = synth.make_contexts(corp, 16, 64, 29)
+    sa = oracle.suffix_array(corp.tokens).astype(np.int32)
+    h_corpus = torch.empty(corp.tokens.shape, dtype=torch.int32, pin_memory=True)
+    h_corpus.copy_(torch.from_numpy(corp.tokens))
+    h_sa = torch.empty(sa.shape, dtype=torch.int32, pin_memory=True)
+    h_sa.copy_(torch.from_numpy(sa))
+    index = rest.rest_index_from_sa(h_corpus, h_sa)        # refuses memory the device cannot address
+    out = rest.rest_retrieve(index, dev(ctx), dev(lens), max_matches=1000, cont_len=10, max_nodes=64)
+    torch.cuda.synchronize()
+    some = 0
+    for b in range(16):
+        want = oracle.draft_tree(corp.tokens, ctx[b], 16, 2, 1000, 10, 64)
+        assert_tree_equal(tree_to_numpy(out, b), want, f"context {b}")
+        some += want.n_nodes > 0
+    assert some >= 6
+    with pytest.raises(TypeError):                         # ordinary host memory is not accepted
+        rest.rest_index_from_sa(torch.from_numpy(corp.tokens), torch.from_numpy(sa))
+
+
 def test_index_file_round_trip_and_exchange_with_the_oracle(tmp_path):
     corp = synth.make_corpus(300_000, 4, 30)
     d_corpus = dev(corp.tokens)
