@@ -60,6 +60,7 @@ enum {
 #define REST_MAX_CONT_LEN 32        /* m */
 #define REST_MAX_MATCHES 8192       /* K */
 #define REST_MAX_NODES 256          /* c */
+#define REST_MAX_QUERY_ROWS 1024    /* query rows of one rest_tree_attention slab (grouped heads stacked) */
 
 const char* rest_status_string(rest_status s);
 /* Library version string, e.g. "rest-gfx950 0.1". */
@@ -220,7 +221,9 @@ rest_status rest_retrieve(const rest_index* index, const int32_t* d_contexts, co
  * per group.
  * dtype: REST_BF16 (bf16 in/out, fp32 accumulation and softmax, probabilities
  * rounded to bf16 for the second product) or REST_FP32 (fp32 in/out and math).
- * D must be 128.  Tq, Tk <= REST_MAX_NODES (Tk may be 0).
+ * D must be 128.  Tk <= REST_MAX_NODES (Tk may be 0); Tq <= REST_MAX_QUERY_ROWS, so that up to 16
+ * grouped query heads of 64 draft tokens fit one call.  Query rows are worked on in groups of at most 256,
+ * each of which reads the slab's K and V once.
  *
  * 8-bit cache (an extension; the paper's models keep a 16-bit cache): with
  * kv_dtype = REST_KV_FP8_E4M3 (dtype must be REST_BF16) d_k and d_v hold one

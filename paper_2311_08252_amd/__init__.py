@@ -38,6 +38,7 @@ REST_MAX_SUFFIX_LEN = 16
 REST_MAX_CONT_LEN = 32
 REST_MAX_MATCHES = 8192
 REST_MAX_NODES = 256
+REST_MAX_QUERY_ROWS = 1024
 
 EXPORTS = [
     "rest_status_string", "rest_version", "rest_build_index", "rest_index_from_sa", "rest_index_view",

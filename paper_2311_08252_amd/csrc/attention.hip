@@ -659,7 +659,7 @@ Plan make_plan(const rest_attn_desc* d) {
 
 bool desc_ok(const rest_attn_desc* d) {
     if (!d) return false;
-    if (d->Nb < 1 || d->H < 1 || d->Tq < 1 || d->Tq > REST_MAX_NODES || d->Tk < 0 || d->Tk > REST_MAX_NODES) return false;
+    if (d->Nb < 1 || d->H < 1 || d->Tq < 1 || d->Tq > REST_MAX_QUERY_ROWS || d->Tk < 0 || d->Tk > REST_MAX_NODES) return false;
     if (d->P < 0 || d->P + d->Tk < 1 || d->D != kD) return false;
     if (d->dtype != REST_BF16 && d->dtype != REST_FP32) return false;
     if (d->kv_dtype != REST_KV_AS_DTYPE && d->kv_dtype != REST_KV_FP8_E4M3) return false;
@@ -667,9 +667,10 @@ bool desc_ok(const rest_attn_desc* d) {
     if (!(d->scale > 0.f) || !(d->scale < 1e30f)) return false;
     if (d->num_splits < 0 || d->num_splits > 64) return false;
     if (d->mask_rows < 0 || d->mask_rows > d->Tq) return false;
-    if ((int64_t)d->Nb * d->H * 64 > 0x7fffffff) return false;
-    // block counts are kept in 32 bits
-    if (((int64_t)d->Nb * d->H + 1) * ((d->P + d->Tk + kBlk - 1) / kBlk) > 0x7fffffff) return false;
+    // units (a slab's query rows in groups of at most 256) and block counts are kept in 32 bits
+    const int64_t slabs_q = (int64_t)d->Nb * d->H * ((d->Tq + 255) / 256);
+    if (slabs_q * 64 > 0x7fffffff) return false;
+    if ((slabs_q + 1) * ((d->P + d->Tk + kBlk - 1) / kBlk) > 0x7fffffff) return false;
     for (int i = 0; i < 3; i++)
         if (d->q_stride[i] < 0 || d->k_stride[i] < 0 || d->v_stride[i] < 0 || d->o_stride[i] < 0) return false;
     // rows are read with 16-byte vector loads

@@ -45,7 +45,7 @@ def test_status_strings_and_version(rest):
 
 def test_limits_match_header(rest):
     text = open(os.path.join(ROOT, "include", "rest.h")).read()
-    for name in ["REST_MAX_SUFFIX_LEN", "REST_MAX_CONT_LEN", "REST_MAX_MATCHES", "REST_MAX_NODES"]:
+    for name in ["REST_MAX_SUFFIX_LEN", "REST_MAX_CONT_LEN", "REST_MAX_MATCHES", "REST_MAX_NODES", "REST_MAX_QUERY_ROWS"]:
         val = int(re.search(rf"#define {name} (\d+)", text).group(1))
         assert getattr(rest, name) == val
 
@@ -65,6 +65,16 @@ def make_desc(rest, **over):
 
 
 def test_attention_workspace_sizing_is_host_only(rest):
+    # sixteen grouped query heads of 64 draft tokens are the most one slab takes: four groups of 256 rows over 1024
+    # units, every stream a whole unit; one row more is refused (size 0 = invalid description)
+    wide = make_desc(rest, Nb=8, Tq=1024, mask_rows=64)
+    wide.q_stride[:] = [32 * 1024 * 128, 1024 * 128, 128]
+    wide.o_stride[:] = [32 * 1024 * 128, 1024 * 128, 128]
+    assert rest.rest_tree_attention_workspace_bytes(wide) == 0
+    lib = ctypes.CDLL(LIB)
+    p16 = ctypes.c_void_p(16)
+    wide.Tq = 1025
+    assert lib.rest_tree_attention(p16, p16, p16, p16, p16, ctypes.byref(wide), None, 0, None) == rest.REST_INVALID_ARG
     # 1024 (layer, head) units over 1024 streams: every stream owns whole units, no partial results
     assert rest.rest_tree_attention_workspace_bytes(make_desc(rest)) == 0
     # one layer: 32 units x 66 key blocks = 2112 blocks over 2112 / 4 = 528 streams, two partial slots each

@@ -326,7 +326,9 @@ def test_tree_attention_strided_layout_and_errors():
 
 
 @pytest.mark.parametrize("dtype,Hkv,g,T,P,per_batch", [("bf16", 2, 4, 16, 100, False), ("bf16", 3, 4, 64, 515, True),
-                                                       ("bf16", 8, 2, 33, 64, False), ("fp32", 2, 3, 20, 40, False)])
+                                                       ("bf16", 8, 2, 33, 64, False), ("fp32", 2, 3, 20, 40, False),
+                                                       ("bf16", 2, 8, 64, 300, False), ("bf16", 1, 16, 64, 100, True),
+                                                       ("bf16", 3, 6, 100, 77, False), ("fp32", 1, 8, 40, 50, False)])
 def test_grouped_query_attention_as_a_view(dtype, Hkv, g, T, P, per_batch):
     """g query heads per K/V head: the call sees H = Hkv heads with g*T query rows each and mask_rows = T."""
     Nb = 2
