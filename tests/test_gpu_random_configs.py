@@ -134,3 +134,35 @@ def test_attention_random_configuration(case):
             f"scale={scale} token_major={token_major}"
     assert np.isfinite(got).all(), where
     assert np.abs(got - want).max() <= 2e-2, (where, float(np.abs(got - want).max()))
+
+
+@pytest.mark.parametrize("case", range(30))
+def test_sampling_random_configuration(case):
+    """rest_sample_ids against the oracle's candidate sets (the tokens a perturbation of 1e-9 of the mass could draw)."""
+    s = 9800 + case
+    V = [1, 2, 63, 64, 65, 513, 1000, 4097, 32000, 32768][draw(s, 0, 0, 10)]
+    R = draw(s, 1, 1, 7)
+    temperature = [0.1, 0.7, 0.8, 1.0, 2.5][draw(s, 2, 0, 5)]
+    top_p = [0.05, 0.5, 0.8, 0.95, 1.0][draw(s, 3, 0, 5)]
+    kind = draw(s, 4, 0, 4)
+    x = synth.normal_f32(s, (R, V)) * 2.0
+    if kind == 1:                       # many exactly equal logits
+        x = np.round(x * 2.0) / 2.0
+    elif kind == 2:                     # a few dominant tokens
+        for r in range(R):
+            x[r, synth.randint(s + r, np.arange(min(V, 4)), 0, V)] += 9.0
+    elif kind == 3:                     # part of the vocabulary switched off
+        x[:, ::3] = -np.inf
+        x[:, 0] = 0.0
+    x = x.astype(np.float32)
+    u = synth.uniform01(s + 50, np.arange(R)).astype(np.float32)
+    stride = V + [0, 0, 3, 64][draw(s, 5, 0, 4)]
+    big = torch.full((R, stride), 5.0, dtype=torch.float32, device="cuda")
+    big[:, :V] = torch.from_numpy(x).cuda()
+    ids = rest.rest_sample_ids(big[:, :V], torch.from_numpy(u).cuda(), temperature, top_p)
+    torch.cuda.synchronize()
+    got = ids.cpu().numpy()
+    for r in range(R):
+        cands = oracle.nucleus_candidates(x[r], np.float32(temperature), np.float32(top_p), np.float32(u[r]))
+        assert int(got[r]) in cands, (case, r, V, temperature, top_p, kind, int(got[r]), cands)
+        assert len(cands) <= 3
