@@ -152,3 +152,28 @@ def test_calls_reject_null_and_bad_arguments_before_touching_the_gpu(rest):
     kd.kc_stride[2] = 128
     kd.dtype = rest.REST_FP32
     assert lib.rest_kv_compact(p16, p16, p16, p16, 10, ctypes.byref(kd), None) == rest.REST_UNSUPPORTED
+
+
+def test_header_is_plain_c_and_struct_layouts_match_the_binding(tmp_path, rest):
+    """include/rest.h compiles as C99 and as C++17 on its own, and the sizes / field offsets a C compiler gives the
+    parameter structs are the ones the ctypes binding marshals."""
+    import subprocess
+    structs = {"rest_retrieve_params": rest.rest_retrieve_params, "rest_attn_desc": rest.rest_attn_desc,
+               "rest_kv_desc": rest.rest_kv_desc, "rest_tree": rest.rest_tree}
+    lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "rest.h"', 'int main(void) {']
+    for name, cls in structs.items():
+        lines.append(f'  printf("{name} %zu\\n", sizeof({name}));')
+        for field, _ in cls._fields_:
+            lines.append(f'  printf("{name}.{field} %zu\\n", offsetof({name}, {field}));')
+    lines += ['  return 0;', '}']
+    src = tmp_path / "layout.c"
+    src.write_text("\n".join(lines))
+    inc = os.path.join(ROOT, "include")
+    subprocess.check_call(["g++", "-std=c++17", "-Wall", "-Wextra", "-Werror", "-fsyntax-only", "-x", "c++", "-I", inc, str(src)])
+    exe = tmp_path / "layout"
+    subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", inc, str(src), "-o", str(exe)])
+    out = dict(line.split() for line in subprocess.check_output([str(exe)], text=True).splitlines())
+    for name, cls in structs.items():
+        assert int(out[name]) == ctypes.sizeof(cls), name
+        for field, _ in cls._fields_:
+            assert int(out[f"{name}.{field}"]) == getattr(cls, field).offset, (name, field)
