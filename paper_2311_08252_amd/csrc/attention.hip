@@ -5,6 +5,8 @@
 // bf16 kernel design (HBM-bound: ~T flop per KV byte, far below the chip's balance point):
 //  * a unit is one (batch, head, group of 64 queries); its keys are cut into blocks of 32.  W streams share the
 //    work, a stream being a workgroup of two wavefronts (wavefront w owns queries 32w .. 32w+31 of the unit).
+//    (Described for up to 64 query rows; 128 / 256 rows per unit run on streams of four / eight wavefronts and
+//    tiles of two / four blocks, see the kernel's template comment.  An 8-bit cache changes the fetch only.)
 //    Stream s first takes whole units s, s + W, ... and writes their output directly; the blocks of the units
 //    that are left over (fewer than W) are cut into equal contiguous spans, one per stream (stream-K), so every
 //    stream gets the same number of blocks whatever the number of units.  Only a span that starts or ends inside
