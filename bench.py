@@ -278,6 +278,22 @@ def side_measurements(rest, torch, synth, corp, index, w, q, k, v, out, tree, P,
         res["retrieve_batch1_host_resident_datastore_us"] = [round(x * 1e3, 1) for x in lat]
         del hidx, h_corpus, h_sa
 
+    # the index as a file: suffix array through a pinned staging buffer to a temporary file and back (fingerprint of the
+    # stream computed on the GPU both ways)
+    if corp.tokens.size <= 200_000_000:
+        import tempfile
+        with tempfile.TemporaryDirectory() as td:
+            path = os.path.join(td, "bench.restsa")
+            t0 = time.time()
+            rest.rest_index_save(index, path)
+            res["index_save_s"] = round(time.time() - t0, 3)
+            t0 = time.time()
+            again = rest.rest_index_load(path, index._corpus)
+            torch.cuda.synchronize()
+            res["index_load_s"] = round(time.time() - t0, 3)
+            res["index_file_MB"] = round(os.path.getsize(path) / 1e6, 1)
+            del again
+
     Nb = q.shape[0]
     mask = tree.tree_mask[0]
 
