@@ -17,6 +17,8 @@
  * rest_sample_ids draws the model's token per position for nucleus sampling
  * ("Sampling strategies"); rest_rope_append and rest_kv_compact are the cache
  * steps before and after verification that "Draft acceptance" implies.
+ * rest_index_save / rest_index_load keep the index as a file and
+ * rest_build_index_prefix builds one ordered by a bounded number of tokens.
  *
  * Conventions
  *  - Every pointer whose name starts with d_ (and every pointer inside
