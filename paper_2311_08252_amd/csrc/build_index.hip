@@ -25,11 +25,17 @@ __global__ void init_rank_kernel(const TokT* corpus, uint64_t n, uint32_t* rank,
         rank[i] = r;
         mx = r > mx ? r : mx;
     }
+    __shared__ uint32_t part[4];
     for (int off = 32; off > 0; off >>= 1) {
         uint32_t y = __shfl_xor(mx, off, 64);
         mx = y > mx ? y : mx;
     }
-    if ((threadIdx.x & 63) == 0) atomicMax(max_out, mx);
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = mx;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < 4; w++) mx = part[w] > mx ? part[w] : mx;
+        atomicMax(max_out, mx);
+    }
 }
 
 __global__ void make_keys_kernel(const uint32_t* rank, uint64_t n, uint64_t h, uint64_t* key, uint32_t* val) {
@@ -60,12 +66,22 @@ __global__ __launch_bounds__(kSortThreads) void radix_hist_kernel(const uint64_t
     cnt[tid] = 0;
     __syncthreads();
     const uint64_t base = (uint64_t)blockIdx.x * tile;
-    for (uint32_t s = 0; s < tile; s += kSortThreads) {
-        const uint64_t i = base + s + tid;
-        const bool valid = i < n;
-        const uint32_t d = valid ? (uint32_t)(key[i] >> shift) & 255u : 0u;
-        const uint64_t m = match_digit(d, valid);
-        if (valid && (m & ((1ull << lane) - 1ull)) == 0) atomicAdd(&cnt[d], (uint32_t)__popcll(m));
+    // eight reads in flight per thread (tile is a multiple of 256, not of 2048: the last group may be ragged)
+    for (uint32_t s = 0; s < tile; s += 8 * kSortThreads) {
+        uint64_t k[8];
+#pragma unroll
+        for (int r = 0; r < 8; r++) {
+            const uint64_t i = base + s + r * kSortThreads + tid;
+            k[r] = (s + r * kSortThreads < tile && i < n) ? key[i] : 0ull;
+        }
+#pragma unroll
+        for (int r = 0; r < 8; r++) {
+            const uint64_t i = base + s + r * kSortThreads + tid;
+            const bool valid = s + r * kSortThreads < tile && i < n;
+            const uint32_t d = (uint32_t)(k[r] >> shift) & 255u;
+            const uint64_t m = match_digit(d, valid);
+            if (valid && (m & ((1ull << lane) - 1ull)) == 0) atomicAdd(&cnt[d], (uint32_t)__popcll(m));
+        }
     }
     __syncthreads();
     hist[(uint64_t)tid * ntiles + blockIdx.x] = cnt[tid];
@@ -158,42 +174,96 @@ __global__ __launch_bounds__(256) void scan_apply_kernel(uint32_t* x, uint64_t n
     }
 }
 
-// stable scatter of one tile by digit
+// Stable scatter of one tile by digit.  The tile goes through LDS in chunks of kChunk elements: a chunk is first put
+// in digit order inside LDS (wavefront w ranks elements [1024 w, 1024 w + 1024) of the chunk, 64 at a time, with a
+// running count per digit; a scan over (digit, wavefront) turns the ranks into LDS positions), then written out in
+// that order, so that the elements of one digit leave as one contiguous run instead of one 12-byte write each.
+constexpr int kChunk = 4096;
+constexpr int kPerLane = kChunk / kSortThreads;     // 16 elements per thread and chunk
+
 __global__ __launch_bounds__(kSortThreads) void radix_scatter_kernel(const uint64_t* key_in, const uint32_t* val_in,
                                                                       uint64_t* key_out, uint32_t* val_out, uint64_t n,
                                                                       int shift, uint32_t tile, uint32_t ntiles,
                                                                       const uint32_t* offsets) {
-    __shared__ uint32_t base[256];
-    __shared__ uint32_t wcount[4][256];
+    __shared__ uint64_t skey[kChunk];
+    __shared__ uint32_t sval[kChunk];
+    __shared__ uint32_t base[256];            // global position of the next element of each digit
+    __shared__ uint32_t wcnt[4][256];         // running count per (wavefront, digit), then its LDS start
+    __shared__ uint32_t dstart[256];          // LDS position of a digit's first element in the chunk
+    __shared__ uint32_t scan[256];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     base[tid] = offsets[(uint64_t)tid * ntiles + blockIdx.x];
-#pragma unroll
-    for (int w = 0; w < 4; w++) wcount[w][tid] = 0;
-    __syncthreads();
     const uint64_t tbase = (uint64_t)blockIdx.x * tile;
-    for (uint32_t s = 0; s < tile; s += kSortThreads) {
-        const uint64_t i = tbase + s + tid;
-        const bool valid = i < n;
-        uint64_t k = 0;
-        uint32_t v = 0;
-        if (valid) { k = key_in[i]; v = val_in[i]; }
-        const uint32_t d = (uint32_t)(k >> shift) & 255u;
-        const uint64_t m = match_digit(d, valid);
-        const uint32_t before = (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
-        if (valid && before == 0) wcount[wave][d] = (uint32_t)__popcll(m);
+    for (uint32_t c0 = 0; c0 < tile; c0 += kChunk) {
+#pragma unroll
+        for (int w = 0; w < 4; w++) wcnt[w][tid] = 0;
         __syncthreads();
-        if (valid) {
-            uint32_t pre = 0;
-            for (int w = 0; w < wave; w++) pre += wcount[w][d];
-            const uint32_t dst = base[d] + pre + before;
-            key_out[dst] = k;
-            val_out[dst] = v;
+        // ---- rank: element e of the chunk is handled by wavefront e / 1024, round (e % 1024) / 64, lane e % 64
+        uint64_t k[kPerLane];
+        uint32_t v[kPerLane];
+        uint32_t rank[kPerLane];              // rank among the wavefront's elements of the same digit
+        const uint32_t climit = tile - c0 < (uint32_t)kChunk ? tile - c0 : (uint32_t)kChunk;
+        // all of the chunk's reads are issued before the first is needed
+#pragma unroll
+        for (int r = 0; r < kPerLane; r++) {
+            const uint32_t e = (uint32_t)wave * (kChunk / 4) + r * 64 + lane;
+            const uint64_t i = tbase + c0 + e;
+            k[r] = 0;
+            v[r] = 0;
+            if (e < climit && i < n) { k[r] = key_in[i]; v[r] = val_in[i]; }
+        }
+#pragma unroll
+        for (int r = 0; r < kPerLane; r++) {
+            const uint32_t e = (uint32_t)wave * (kChunk / 4) + r * 64 + lane;
+            const bool valid = e < climit && tbase + c0 + e < n;
+            const uint32_t d = (uint32_t)(k[r] >> shift) & 255u;
+            const uint64_t m = match_digit(d, valid);
+            const uint32_t before = (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
+            // all lanes of a digit read the running count, then the first of them moves it on
+            const uint32_t old = valid ? wcnt[wave][d] : 0u;
+            rank[r] = valid ? old + before : 0xffffffffu;
+            if (valid && before == 0) wcnt[wave][d] = old + (uint32_t)__popcll(m);
         }
         __syncthreads();
-        uint32_t add = 0;
+        // ---- LDS start of every (digit, wavefront) group: digits ascending, wavefronts ascending within a digit
+        uint32_t c[4], tot = 0;
 #pragma unroll
-        for (int w = 0; w < 4; w++) { add += wcount[w][tid]; wcount[w][tid] = 0; }
-        base[tid] += add;
+        for (int w = 0; w < 4; w++) { c[w] = wcnt[w][tid]; tot += c[w]; }
+        scan[tid] = tot;
+        __syncthreads();
+        for (int off = 1; off < 256; off <<= 1) {
+            const uint32_t y = tid >= off ? scan[tid - off] : 0u;
+            __syncthreads();
+            scan[tid] += y;
+            __syncthreads();
+        }
+        uint32_t run = scan[tid] - tot;       // exclusive
+        dstart[tid] = run;
+#pragma unroll
+        for (int w = 0; w < 4; w++) { wcnt[w][tid] = run; run += c[w]; }
+        __syncthreads();
+        // ---- place
+#pragma unroll
+        for (int r = 0; r < kPerLane; r++) {
+            if (rank[r] != 0xffffffffu) {
+                const uint32_t d = (uint32_t)(k[r] >> shift) & 255u;
+                const uint32_t pos = wcnt[wave][d] + rank[r];
+                skey[pos] = k[r];
+                sval[pos] = v[r];
+            }
+        }
+        __syncthreads();
+        // ---- write out in LDS order: position p of digit d goes to base[d] + (p - dstart[d])
+        const uint32_t count = scan[255];
+        for (uint32_t pp = tid; pp < count; pp += kSortThreads) {
+            const uint64_t kk = skey[pp];
+            const uint32_t d = (uint32_t)(kk >> shift) & 255u;
+            const uint32_t dst = base[d] + (pp - dstart[d]);
+            key_out[dst] = kk;
+            val_out[dst] = sval[pp];
+        }
+        __syncthreads();
+        base[tid] += tot;
         __syncthreads();
     }
 }
@@ -206,8 +276,15 @@ __global__ __launch_bounds__(256) void heads_kernel(const uint64_t* key, uint64_
         grp[j] = head ? (uint32_t)j : 0u;
         local += head ? 1u : 0u;
     }
+    // one atomic per workgroup: a quarter of a million of them on one address would take longer than the pass itself
+    __shared__ uint32_t part[4];
     for (int off = 32; off > 0; off >>= 1) local += __shfl_xor(local, off, 64);
-    if ((threadIdx.x & 63) == 0 && local) atomicAdd(n_runs, (unsigned long long)local);
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = local;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const uint32_t sum = part[0] + part[1] + part[2] + part[3];
+        if (sum) atomicAdd(n_runs, (unsigned long long)sum);
+    }
 }
 
 __global__ void assign_rank_kernel(const uint32_t* val, const uint32_t* grp, uint64_t n, uint32_t* rank) {
@@ -300,11 +377,12 @@ extern "C" __attribute__((visibility("default"))) rest_status rest_build_index_p
     REST_ALLOC(s.sa, n * (uint64_t)sa_bytes);
 
     const unsigned gs = (unsigned)((n + 255) / 256 < 65536 ? (n + 255) / 256 : 65536);
+    const unsigned gs_reduce = gs < 4096 ? gs : 4096;      // kernels that end in one atomic per workgroup
     REST_HIP_TRY(hipMemsetAsync(s.counters, 0, 16, st));
     if (token_bytes == 2)
-        hipLaunchKernelGGL(init_rank_kernel<uint16_t>, dim3(gs), dim3(256), 0, st, (const uint16_t*)d_corpus, n, s.rank, (uint32_t*)s.counters);
+        hipLaunchKernelGGL(init_rank_kernel<uint16_t>, dim3(gs_reduce), dim3(256), 0, st, (const uint16_t*)d_corpus, n, s.rank, (uint32_t*)s.counters);
     else
-        hipLaunchKernelGGL(init_rank_kernel<int32_t>, dim3(gs), dim3(256), 0, st, (const int32_t*)d_corpus, n, s.rank, (uint32_t*)s.counters);
+        hipLaunchKernelGGL(init_rank_kernel<int32_t>, dim3(gs_reduce), dim3(256), 0, st, (const int32_t*)d_corpus, n, s.rank, (uint32_t*)s.counters);
     REST_HIP_TRY(hipGetLastError());
     uint32_t max_rank = 0;
     REST_HIP_TRY(hipMemcpyAsync(&max_rank, s.counters, 4, hipMemcpyDeviceToHost, st));
@@ -334,7 +412,7 @@ extern "C" __attribute__((visibility("default"))) rest_status rest_build_index_p
         // runs of equal keys -> new ranks
         uint32_t* grp = s.val[cur ^ 1];
         REST_HIP_TRY(hipMemsetAsync(s.counters, 0, 16, st));
-        hipLaunchKernelGGL(heads_kernel, dim3(gs), dim3(256), 0, st, s.key[cur], n, grp, s.counters);
+        hipLaunchKernelGGL(heads_kernel, dim3(gs_reduce), dim3(256), 0, st, s.key[cur], n, grp, s.counters);
         REST_HIP_TRY(hipGetLastError());
         unsigned long long runs = 0;
         REST_HIP_TRY(hipMemcpyAsync(&runs, s.counters, 8, hipMemcpyDeviceToHost, st));
