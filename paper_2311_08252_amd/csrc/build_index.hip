@@ -5,7 +5,11 @@
 // Round with step h: rank[i] orders suffix i by its first h tokens (0 = past the end of the stream, which
 // makes the end smaller than every token).  Sorting positions by the 64-bit key (rank[i], rank[i+h])
 // orders them by their first 2h tokens; new ranks are the index of the first member of each run of equal
-// keys.  The first round uses token + 1 as rank.  Rounds stop when every key is distinct.
+// keys.  The first round uses token + 1 as rank.  A suffix whose key is unique has its final rank; only the
+// others (kept as a list, in sorted order) go into the next round, where the first key half -- the rank of
+// their group, i.e. one plus the group's first place in the final array -- keeps the groups apart and in
+// place.  On text, and on the synthetic streams, four fifths of the suffixes remain after the first round,
+// an eighth after the second, under one per cent after the third.  Rounds stop when no suffix is left.
 //
 // Radix sort: 8-bit digits, three kernels per digit (per-tile digit histogram, exclusive scan over
 // (digit, tile), stable scatter).  Inside a wavefront, lanes holding the same digit find each other with
@@ -38,11 +42,14 @@ __global__ void init_rank_kernel(const TokT* corpus, uint64_t n, uint32_t* rank,
     }
 }
 
-__global__ void make_keys_kernel(const uint32_t* rank, uint64_t n, uint64_t h, uint64_t* key, uint32_t* val) {
-    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (uint64_t)gridDim.x * blockDim.x) {
+// keys of the m suffixes still in play: list[j] (or j itself in the first round, list == null)
+__global__ void make_keys_kernel(const uint32_t* rank, uint64_t n, uint64_t h, const uint32_t* list, uint64_t m,
+                                 uint64_t* key, uint32_t* val) {
+    for (uint64_t j = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; j < m; j += (uint64_t)gridDim.x * blockDim.x) {
+        const uint64_t i = list ? (uint64_t)list[j] : j;
         const uint32_t second = i + h < n ? rank[i + h] : 0u;
-        key[i] = ((uint64_t)rank[i] << 32) | second;
-        val[i] = (uint32_t)i;
+        key[j] = ((uint64_t)rank[i] << 32) | second;
+        val[j] = (uint32_t)i;
     }
 }
 
@@ -268,12 +275,19 @@ __global__ __launch_bounds__(kSortThreads) void radix_scatter_kernel(const uint6
     }
 }
 
-// grp[j] = j if sorted key j starts a new run else 0; counts the runs
-__global__ __launch_bounds__(256) void heads_kernel(const uint64_t* key, uint64_t n, uint32_t* grp, unsigned long long* n_runs) {
+// Sorted keys of the suffixes in play: run[j] = j where a run of equal keys starts, grp[j] = j where a group (equal
+// first half, i.e. one group of the previous round) starts, else 0; an inclusive max-scan turns both into "start of
+// my run / of my group".  In the first round the first halves are tokens, not ranks: everything is one group.
+// Counts the runs.
+__global__ __launch_bounds__(256) void marks_kernel(const uint64_t* key, uint64_t m, int first_round, uint32_t* run, uint32_t* grp,
+                                                    unsigned long long* n_runs) {
     uint32_t local = 0;
-    for (uint64_t j = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; j < n; j += (uint64_t)gridDim.x * blockDim.x) {
-        const bool head = j == 0 || key[j] != key[j - 1];
-        grp[j] = head ? (uint32_t)j : 0u;
+    for (uint64_t j = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; j < m; j += (uint64_t)gridDim.x * blockDim.x) {
+        const uint64_t k = key[j], prev = j ? key[j - 1] : 0ull;
+        const bool head = j == 0 || k != prev;
+        const bool ghead = j > 0 && !first_round && (k >> 32) != (prev >> 32);
+        run[j] = head ? (uint32_t)j : 0u;
+        grp[j] = ghead ? (uint32_t)j : 0u;
         local += head ? 1u : 0u;
     }
     // one atomic per workgroup: a quarter of a million of them on one address would take longer than the pass itself
@@ -287,15 +301,51 @@ __global__ __launch_bounds__(256) void heads_kernel(const uint64_t* key, uint64_
     }
 }
 
-__global__ void assign_rank_kernel(const uint32_t* val, const uint32_t* grp, uint64_t n, uint32_t* rank) {
-    for (uint64_t j = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; j < n; j += (uint64_t)gridDim.x * blockDim.x)
-        rank[val[j]] = grp[j] + 1u;
+// New rank of suffix val[j]: the rank of its group (first key half; 1 in the first round) plus the offset of its run
+// inside the group.  In the last round of a depth-limited build every suffix gets its own place instead (offset of j
+// itself): equal keys then stay in the order they have, which is ascending position.
+__global__ void assign_rank_kernel(const uint64_t* key, const uint32_t* val, const uint32_t* run_start, const uint32_t* grp_start,
+                                   uint64_t m, int first_round, int spread, uint32_t* rank) {
+    for (uint64_t j = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; j < m; j += (uint64_t)gridDim.x * blockDim.x) {
+        const uint32_t base = first_round ? 1u : (uint32_t)(key[j] >> 32);
+        const uint32_t at = spread ? (uint32_t)j : run_start[j];
+        rank[val[j]] = base + (at - grp_start[j]);
+    }
 }
 
+// flag[j] = 1 if suffix j of the sorted list shares its key with a neighbour (it stays in play), else 0; counts them
+__global__ __launch_bounds__(256) void unsettled_kernel(const uint32_t* run_start, uint64_t m, uint32_t* flag, unsigned long long* count) {
+    uint32_t local = 0;
+    for (uint64_t j = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; j < m; j += (uint64_t)gridDim.x * blockDim.x) {
+        const bool alone = run_start[j] == (uint32_t)j && (j + 1 == m || run_start[j + 1] == (uint32_t)(j + 1));
+        flag[j] = alone ? 0u : 1u;
+        local += alone ? 0u : 1u;
+    }
+    __shared__ uint32_t part[4];
+    for (int off = 32; off > 0; off >>= 1) local += __shfl_xor(local, off, 64);
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = local;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const uint32_t sum = part[0] + part[1] + part[2] + part[3];
+        if (sum) atomicAdd(count, (unsigned long long)sum);
+    }
+}
+
+// the suffixes that stay in play, in their sorted order: pos = exclusive prefix sum of the flags
+__global__ void compact_kernel(const uint32_t* val, const uint32_t* run_start, const uint32_t* pos, uint64_t m, uint32_t* list) {
+    for (uint64_t j = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; j < m; j += (uint64_t)gridDim.x * blockDim.x) {
+        const bool alone = run_start[j] == (uint32_t)j && (j + 1 == m || run_start[j + 1] == (uint32_t)(j + 1));
+        if (!alone) list[pos[j]] = val[j];
+    }
+}
+
+// final ranks are a permutation of 1..n: the suffix array is its inverse
 template <typename SaT>
-__global__ void write_sa_kernel(const uint32_t* val, uint64_t n, SaT* sa) {
-    for (uint64_t j = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; j < n; j += (uint64_t)gridDim.x * blockDim.x)
-        sa[j] = (SaT)val[j];
+__global__ void invert_kernel(const uint32_t* rank, uint64_t n, SaT* sa) {
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (uint64_t)gridDim.x * blockDim.x) {
+        const uint32_t r = rank[i];
+        if (r >= 1u && (uint64_t)r <= n) sa[r - 1u] = (SaT)i;
+    }
 }
 
 template <bool IS_MAX>
@@ -318,6 +368,7 @@ struct Scratch {
     uint64_t* key[2] = {nullptr, nullptr};
     uint32_t* val[2] = {nullptr, nullptr};
     uint32_t* rank = nullptr;
+    uint32_t* list = nullptr;
     uint32_t* hist = nullptr;
     uint32_t* sums = nullptr;
     unsigned long long* counters = nullptr;
@@ -325,6 +376,7 @@ struct Scratch {
     ~Scratch() {
         for (int i = 0; i < 2; i++) { if (key[i]) (void)hipFree(key[i]); if (val[i]) (void)hipFree(val[i]); }
         if (rank) (void)hipFree(rank);
+        if (list) (void)hipFree(list);
         if (hist) (void)hipFree(hist);
         if (sums) (void)hipFree(sums);
         if (counters) (void)hipFree(counters);
@@ -359,75 +411,105 @@ extern "C" __attribute__((visibility("default"))) rest_status rest_build_index_p
     if (sa_bytes == 4 && n >= (1ull << 31)) return REST_INVALID_ARG;
     hipStream_t st = (hipStream_t)stream_;
 
-    // tiles: multiples of 256 elements, at most 32768 tiles
-    uint64_t tile64 = (n + 32767) / 32768;
-    tile64 = ((tile64 + kSortThreads - 1) / kSortThreads) * kSortThreads;
-    if (tile64 < 4096) tile64 = 4096;
-    const uint32_t tile = (uint32_t)tile64;
-    const uint32_t ntiles = (uint32_t)((n + tile - 1) / tile);
-    const uint64_t hist_n = (uint64_t)256 * ntiles;
-    const uint64_t sums_n = ((n > hist_n ? n : hist_n) + kScanChunk - 1) / kScanChunk;
+    // tiles of the radix passes: multiples of 256 elements, at most 32768 of them; sized per round for the m suffixes
+    // still in play, so the buffers sized here for m = n hold every round
+    auto tile_of = [](uint64_t m) {
+        uint64_t t = (m + 32767) / 32768;
+        t = ((t + kSortThreads - 1) / kSortThreads) * kSortThreads;
+        return (uint32_t)(t < 4096 ? 4096 : t);
+    };
+    // a round with m <= n suffixes uses ceil(m / tile_of(m)) tiles: never more than 32768, nor than ceil(n / 4096)
+    const uint64_t max_tiles = (n + 4095) / 4096 < 32768 ? (n + 4095) / 4096 : 32768;
+    const uint64_t hist_cap = (uint64_t)256 * max_tiles;
+    const uint64_t sums_n = ((n > hist_cap ? n : hist_cap) + kScanChunk - 1) / kScanChunk;
 
     Scratch s;
     for (int i = 0; i < 2; i++) { REST_ALLOC(s.key[i], n * 8); REST_ALLOC(s.val[i], n * 4); }
     REST_ALLOC(s.rank, n * 4);
-    REST_ALLOC(s.hist, hist_n * 4);
+    REST_ALLOC(s.list, n * 4);
+    REST_ALLOC(s.hist, hist_cap * 4);
     REST_ALLOC(s.sums, sums_n * 4);
     REST_ALLOC(s.counters, 16);
     REST_ALLOC(s.sa, n * (uint64_t)sa_bytes);
 
-    const unsigned gs = (unsigned)((n + 255) / 256 < 65536 ? (n + 255) / 256 : 65536);
-    const unsigned gs_reduce = gs < 4096 ? gs : 4096;      // kernels that end in one atomic per workgroup
+    auto blocks_for = [](uint64_t m, unsigned cap) { return (unsigned)((m + 255) / 256 < cap ? (m + 255) / 256 : cap); };
     REST_HIP_TRY(hipMemsetAsync(s.counters, 0, 16, st));
     if (token_bytes == 2)
-        hipLaunchKernelGGL(init_rank_kernel<uint16_t>, dim3(gs_reduce), dim3(256), 0, st, (const uint16_t*)d_corpus, n, s.rank, (uint32_t*)s.counters);
+        hipLaunchKernelGGL(init_rank_kernel<uint16_t>, dim3(blocks_for(n, 4096)), dim3(256), 0, st, (const uint16_t*)d_corpus, n, s.rank, (uint32_t*)s.counters);
     else
-        hipLaunchKernelGGL(init_rank_kernel<int32_t>, dim3(gs_reduce), dim3(256), 0, st, (const int32_t*)d_corpus, n, s.rank, (uint32_t*)s.counters);
+        hipLaunchKernelGGL(init_rank_kernel<int32_t>, dim3(blocks_for(n, 4096)), dim3(256), 0, st, (const int32_t*)d_corpus, n, s.rank, (uint32_t*)s.counters);
     REST_HIP_TRY(hipGetLastError());
     uint32_t max_rank = 0;
     REST_HIP_TRY(hipMemcpyAsync(&max_rank, s.counters, 4, hipMemcpyDeviceToHost, st));
     REST_HIP_TRY(hipStreamSynchronize(st));
 
-    int cur = 0;
     int32_t sorted_by = 0;   // tokens the final order looks at; 0 = all of them
+    uint64_t m = n;          // suffixes still in play, listed in s.list in sorted order (first round: all, no list)
     for (uint64_t h = 1;; h *= 2) {
-        const int bits = bit_length(max_rank);
-        const int passes_half = (bits + 7) / 8;
-        hipLaunchKernelGGL(make_keys_kernel, dim3(gs), dim3(256), 0, st, s.rank, n, h, s.key[0], s.val[0]);
+        const bool first_round = h == 1;
+        const unsigned gs = blocks_for(m, 65536), gs_reduce = blocks_for(m, 4096);
+        const uint32_t tile = tile_of(m);
+        const uint32_t ntiles = (uint32_t)((m + tile - 1) / tile);
+        const uint64_t hist_n = (uint64_t)256 * ntiles;
+        const int passes_half = (bit_length(max_rank) + 7) / 8;
+        hipLaunchKernelGGL(make_keys_kernel, dim3(gs), dim3(256), 0, st, s.rank, n, h, first_round ? nullptr : s.list, m, s.key[0], s.val[0]);
         REST_HIP_TRY(hipGetLastError());
-        cur = 0;
+        int cur = 0;
         for (int half = 0; half < 2; half++) {
             for (int ps = 0; ps < passes_half; ps++) {
                 const int shift = half * 32 + ps * 8;
-                hipLaunchKernelGGL(radix_hist_kernel, dim3(ntiles), dim3(kSortThreads), 0, st, s.key[cur], n, shift, tile, ntiles, s.hist);
+                hipLaunchKernelGGL(radix_hist_kernel, dim3(ntiles), dim3(kSortThreads), 0, st, s.key[cur], m, shift, tile, ntiles, s.hist);
                 REST_HIP_TRY(hipGetLastError());
                 rest_status rs = scan_u32<false>(s.hist, hist_n, s.sums, st);
                 if (rs != REST_OK) return rs;
                 hipLaunchKernelGGL(radix_scatter_kernel, dim3(ntiles), dim3(kSortThreads), 0, st, s.key[cur], s.val[cur],
-                                   s.key[cur ^ 1], s.val[cur ^ 1], n, shift, tile, ntiles, s.hist);
+                                   s.key[cur ^ 1], s.val[cur ^ 1], m, shift, tile, ntiles, s.hist);
                 REST_HIP_TRY(hipGetLastError());
                 cur ^= 1;
             }
         }
-        // runs of equal keys -> new ranks
-        uint32_t* grp = s.val[cur ^ 1];
+        // runs of equal keys and groups of equal first halves -> new ranks.  The other key and value buffers are free now.
+        uint32_t* run = s.val[cur ^ 1];
+        uint32_t* grp = (uint32_t*)s.key[cur ^ 1];
+        uint32_t* flag = grp + m;
         REST_HIP_TRY(hipMemsetAsync(s.counters, 0, 16, st));
-        hipLaunchKernelGGL(heads_kernel, dim3(gs_reduce), dim3(256), 0, st, s.key[cur], n, grp, s.counters);
+        hipLaunchKernelGGL(marks_kernel, dim3(gs_reduce), dim3(256), 0, st, s.key[cur], m, first_round ? 1 : 0, run, grp, s.counters);
         REST_HIP_TRY(hipGetLastError());
         unsigned long long runs = 0;
         REST_HIP_TRY(hipMemcpyAsync(&runs, s.counters, 8, hipMemcpyDeviceToHost, st));
-        REST_HIP_TRY(hipStreamSynchronize(st));
-        if (runs == n || h >= n) break;                    // every suffix distinct: the suffix array
-        if (depth > 0 && 2 * h >= (uint64_t)depth) { sorted_by = (int32_t)(2 * h); break; }
-        rest_status rs = scan_u32<true>(grp, n, s.sums, st);
+        rest_status rs = scan_u32<true>(run, m, s.sums, st);
         if (rs != REST_OK) return rs;
-        hipLaunchKernelGGL(assign_rank_kernel, dim3(gs), dim3(256), 0, st, s.val[cur], grp, n, s.rank);
+        rs = scan_u32<true>(grp, m, s.sums, st);
+        if (rs != REST_OK) return rs;
+        REST_HIP_TRY(hipStreamSynchronize(st));
+        // the last round of a depth-limited build (or, as a guard, a step that already spans the stream) gives every
+        // suffix a place of its own
+        const bool limit = depth > 0 && 2 * h >= (uint64_t)depth;
+        const bool spread = runs < m && (limit || h >= n);
+        hipLaunchKernelGGL(assign_rank_kernel, dim3(gs), dim3(256), 0, st, s.key[cur], s.val[cur], run, grp, m, first_round ? 1 : 0,
+                           spread ? 1 : 0, s.rank);
         REST_HIP_TRY(hipGetLastError());
+        if (runs == m) break;                               // every suffix distinct: the suffix array
+        if (spread) { sorted_by = limit ? (int32_t)(2 * h) : 0; break; }
+        // the suffixes that still share a key go on
+        REST_HIP_TRY(hipMemsetAsync(s.counters, 0, 16, st));
+        hipLaunchKernelGGL(unsettled_kernel, dim3(gs_reduce), dim3(256), 0, st, run, m, flag, s.counters);
+        REST_HIP_TRY(hipGetLastError());
+        unsigned long long left = 0;
+        REST_HIP_TRY(hipMemcpyAsync(&left, s.counters, 8, hipMemcpyDeviceToHost, st));
+        rs = scan_u32<false>(flag, m, s.sums, st);
+        if (rs != REST_OK) return rs;
+        hipLaunchKernelGGL(compact_kernel, dim3(gs), dim3(256), 0, st, s.val[cur], run, flag, m, s.list);
+        REST_HIP_TRY(hipGetLastError());
+        REST_HIP_TRY(hipStreamSynchronize(st));
+        if (left == 0) break;                               // cannot happen while runs < m; a guard
+        m = left;
         max_rank = (uint32_t)n;
     }
 
-    if (sa_bytes == 4) hipLaunchKernelGGL(write_sa_kernel<int32_t>, dim3(gs), dim3(256), 0, st, s.val[cur], n, (int32_t*)s.sa);
-    else hipLaunchKernelGGL(write_sa_kernel<int64_t>, dim3(gs), dim3(256), 0, st, s.val[cur], n, (int64_t*)s.sa);
+    const unsigned gn = blocks_for(n, 65536);
+    if (sa_bytes == 4) hipLaunchKernelGGL(invert_kernel<int32_t>, dim3(gn), dim3(256), 0, st, s.rank, n, (int32_t*)s.sa);
+    else hipLaunchKernelGGL(invert_kernel<int64_t>, dim3(gn), dim3(256), 0, st, s.rank, n, (int64_t*)s.sa);
     REST_HIP_TRY(hipGetLastError());
     REST_HIP_TRY(hipStreamSynchronize(st));
 
