@@ -67,6 +67,31 @@ def test_build_index_closed_forms_and_motifs():
     np.testing.assert_array_equal(sa.astype(np.int64), oracle.suffix_array(c.tokens))
 
 
+@pytest.mark.parametrize("sa_bytes", [4, 8])
+def test_build_index_streams_that_need_many_rounds(sa_bytes):
+    """Streams whose suffixes stay tied for long, so that nearly every suffix is still in play in every doubling round
+    (closed forms; the quadratic oracle sort would take hours on them)."""
+    n = 300_001
+    # one token throughout: the shorter suffix is the smaller one; 19 rounds
+    idx = rest.rest_build_index(dev(np.full(n, 5, np.uint16)), sa_bytes)
+    np.testing.assert_array_equal(idx.suffix_array().cpu().numpy(), np.arange(n - 1, -1, -1))
+    # period two, "1 0 1 0 ... 1": suffixes starting with 0 (odd positions) come first, among the suffixes of one parity
+    # the shorter is a prefix of the longer, hence smaller
+    t = (1 - np.arange(n) % 2).astype(np.int32)
+    idx = rest.rest_build_index(dev(t), sa_bytes)
+    want = np.concatenate([np.arange(n - 2, 0, -2), np.arange(n - 1, -1, -2)])
+    assert want.size == n and t[want[0]] == 0
+    np.testing.assert_array_equal(idx.suffix_array().cpu().numpy(), want)
+    m = 201                                            # the same closed form against the oracle's sort where that is quick
+    np.testing.assert_array_equal(oracle.suffix_array(t[:m]), np.concatenate([np.arange(m - 2, 0, -2), np.arange(m - 1, -1, -2)]))
+    # the depth-limited build of the constant stream: suffixes with at least 32 tokens left tie and stay in position
+    # order, behind the 31 shorter ones
+    lim = rest.rest_build_index_prefix(dev(np.full(n, 5, np.uint16)), sa_bytes, 32)
+    assert lim.sort_depth == 32
+    np.testing.assert_array_equal(lim.suffix_array().cpu().numpy(),
+                                  np.concatenate([np.arange(n - 1, n - 32, -1), np.arange(0, n - 31)]))
+
+
 # ------------------------------------------------------------------ retrieval
 def run_retrieve_case(corpus, contexts, lens, prm, index=None):
     idx = index or rest.rest_index_from_sa(dev(corpus), dev(oracle.suffix_array(corpus).astype(np.int32)))
