@@ -250,6 +250,8 @@ def test_trie_invariants(seed):
             path.append(int(big.draft_tokens[v]))
             v = int(par[v])
         assert child_sum[i] == w[i] - ends_at.get(tuple(path[::-1]), 0)
+    # a shared prefix appears once: no two nodes have the same (parent, token)
+    assert len({(int(par[i]), int(big.draft_tokens[i])) for i in range(T)}) == T
     roots = w[par == -1].sum()
     assert roots == int((lens > 0).sum())            # depth-1 weights sum to the candidates
     # result for c is a prefix (in weight order) of the result for c+1, and closed under parents
