@@ -550,3 +550,19 @@ def test_depth_limited_order_serves_retrieval_like_the_suffix_array():
             differs_when_too_shallow += not (np.array_equal(bad.draft_tokens, want.draft_tokens) and
                                              np.array_equal(bad.node_weight, want.node_weight))
     assert differs_when_too_shallow >= 3
+
+
+def test_c_oracle_under_address_and_undefined_behaviour_sanitizers(tmp_path):
+    """The C half of the oracle, driven over 400 small irregular inputs (tests/oracle_sanitize_driver.c) in a build with
+    -fsanitize=address,undefined: no out-of-bounds access, overflow or leak."""
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    exe = str(tmp_path / "oracle_san")
+    cmd = ["gcc", "-std=c99", "-g", "-O1", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined",
+           "-static-libasan", "-static-libubsan", os.path.join(root, "oracle", "rest_oracle.c"),
+           os.path.join(root, "tests", "oracle_sanitize_driver.c"), "-o", exe]
+    built = subprocess.run(cmd, capture_output=True, text=True)
+    if built.returncode != 0:
+        pytest.skip("no sanitizer runtime for gcc here: " + built.stderr[-200:])
+    run = subprocess.run([exe], capture_output=True, text=True, timeout=300)
+    assert run.returncode == 0 and "ok" in run.stdout, run.stderr[-2000:]
