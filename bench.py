@@ -410,6 +410,40 @@ def attention_sweep(rest, torch, synth, np, dev):
             rows.append({"T": T, "P": P, "us": round(us, 1), "GB/s": round(alg / us / 1e3, 1),
                          "frac_of_8TB/s": round(alg / us / 1e3 / HBM_PEAK_GBS, 3)})
             del q, k, v, out, ws
+    # grouped-query attention as a view: 32 layers x 8 K/V heads, g query heads of 64 draft tokens stacked along the
+    # row axis of each (Tq = 64 g rows, mask_rows = 64); 8-bit cache as a second variant
+    mask = torch.from_numpy(synth.random_tree(64, 78)[3].view(np.int64)).to(dev)
+    for g_heads in (4, 8):
+        for P in (2048, 8192):
+            for kv8 in (False, True):
+                g = torch.Generator(device=dev)
+                g.manual_seed(7000 + g_heads * 100 + P)
+                Tq = 64 * g_heads
+                q = torch.randn((32, 8, Tq, 128), generator=g, device=dev).to(torch.bfloat16)
+                k, v = (torch.randn((32, 8, P + 64, 128), generator=g, device=dev) for _ in range(2))
+                if kv8:
+                    k, v = (x.to(torch.float8_e4m3fn).view(torch.uint8) for x in (k, v))
+                else:
+                    k, v = (x.to(torch.bfloat16) for x in (k, v))
+                out = torch.empty_like(q)
+                scale = 1.0 / float(np.sqrt(128.0))
+                desc = rest.make_attn_desc(q, k, v, out, P, scale, False, 0, 64)
+                ws = torch.empty(max(rest.rest_tree_attention_workspace_bytes(desc), 16), dtype=torch.uint8, device=dev)
+                for _ in range(3):
+                    rest.rest_tree_attention(q, k, v, mask, P, scale, out=out, workspace=ws, mask_rows=64)
+                torch.cuda.synchronize()
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+                for _ in range(10):
+                    rest.rest_tree_attention(q, k, v, mask, P, scale, out=out, workspace=ws, mask_rows=64)
+                b.record()
+                torch.cuda.synchronize()
+                us = a.elapsed_time(b) / 10 * 1e3
+                alg = 256 * (2 * (P + 64) * 128 * (1 if kv8 else 2) + 2 * Tq * 128 * 2)
+                rows.append({"grouped_query_heads": g_heads, "kv_heads": 8, "T": 64, "P": P, "cache": "e4m3" if kv8 else "bf16",
+                             "us": round(us, 1), "GB/s": round(alg / us / 1e3, 1),
+                             "TFLOP/s": round(256 * 4.0 * Tq * (P + 64) * 128 / us / 1e6, 1)})
+                del q, k, v, out, ws
     return rows
 
 
