@@ -10,7 +10,7 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
-    config.addinivalue_line("markers", "big: full-size 13B / 2B-token workloads (set REST_BIG=1)")
+    config.addinivalue_line("markers", "big: the 2-billion-token datastore (set REST_BIG=1)")
 
 
 def pytest_collection_modifyitems(config, items):

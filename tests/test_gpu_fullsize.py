@@ -1,6 +1,6 @@
 """Full-size GPU parity: the benchmark's own shapes and launch configuration, checked on sampled outputs the
 oracle can compute one by one (whole contexts for retrieval, whole (layer, head) slabs for attention) and on
-the suffix array's defining property.  The 13B-shaped and 2-billion-token workloads are marked `big`."""
+the suffix array's defining property.  The 2-billion-token datastore is marked `big` (a tenth of it runs by default)."""
 import os
 
 import numpy as np
@@ -174,7 +174,6 @@ def test_sweep_shapes_random_trees(T, P):
     sampled_attention_check(32, 32, T, P, 100 + T + P, 6, mask)
 
 
-@pytest.mark.big
 def test_llama13b_shape():
     w = synth.WORKLOADS["llama13b"]
     corp = synth.make_corpus(w.n_tokens, w.corpus_seed, w.n_motifs)
@@ -187,18 +186,19 @@ def test_llama13b_shape():
     sampled_attention_check(w.layers, w.heads, w.max_nodes, w.kv_len, w.qkv_seed, 12, mask)
 
 
-@pytest.mark.big
-def test_batched_2b_uint16_int64():
+def batched_uint16_int64(n_tokens, n_motifs, sample):
+    """The batched workload's step on a datastore of n_tokens 16-bit tokens with 64-bit suffix-array entries: index
+    by its definition, 32 contexts of 1024 tokens in one retrieval launch, one layer of attention over the 32
+    contexts with a mask per context."""
     w = synth.WORKLOADS["batched2b"]
-    corp = synth.make_corpus(w.n_tokens, w.corpus_seed, w.n_motifs, dtype=np.uint16, workers=16)
+    corp = synth.make_corpus(n_tokens, w.corpus_seed, n_motifs, dtype=np.uint16, workers=16)
     index = rest.rest_build_index(dev(corp.tokens), 8)
     if os.environ.get("REST_BIG_CHECK_SA", "1") == "1":
         sa = index.suffix_array().cpu().numpy()
         assert sa.dtype == np.int64
         assert oracle.check_suffix_array(corp.tokens, sa) == -1
         del sa
-    check_retrieval(corp, index, w, w.batch, w.query_seed, [0, 1, 2, 3, 30, 31])
-    # 32 contexts, one layer, per-context masks
+    check_retrieval(corp, index, w, w.batch, w.query_seed, sample)
     g = torch.Generator(device="cuda")
     g.manual_seed(w.qkv_seed)
     Nb, H, T, P = w.batch, w.heads, w.max_nodes, w.kv_len
@@ -212,3 +212,14 @@ def test_batched_2b_uint16_int64():
         ref = oracle.tree_attention(q[a, b].float().cpu().numpy(), k[a, b].float().cpu().numpy(),
                                     v[a, b].float().cpu().numpy(), masks[a], P, 1 / np.sqrt(128.0))
         assert np.abs(out[a, b].float().cpu().numpy() - ref).max() <= 2e-2
+
+
+def test_batched_uint16_int64_on_a_tenth_of_the_datastore():
+    w = synth.WORKLOADS["batched2b"]
+    batched_uint16_int64(w.n_tokens // 10, w.n_motifs // 10, range(w.batch))
+
+
+@pytest.mark.big
+def test_batched_2b_uint16_int64():
+    w = synth.WORKLOADS["batched2b"]
+    batched_uint16_int64(w.n_tokens, w.n_motifs, [0, 1, 2, 3, 30, 31])
