@@ -85,9 +85,12 @@ def test_attention_workspace_sizing_is_host_only(rest):
     # 128 queries: streams of four wavefronts on 64-key tiles: 32 units x 33 tiles over 264 streams, 128 rows per slot
     wide = make_desc(rest, Nb=1, Tq=128, Tk=128, P=1984)
     assert rest.rest_tree_attention_workspace_bytes(wide) == 264 * 2 * 128 * (128 + 2) * 4
-    # 13B shape: 1600 units, 1024 streams: one whole unit each, the other 576 units cut into 1024 spans
+    # 13B shape: 1600 units, 1024 streams: one whole unit each, and 576 >= 512 of them a second one: nothing is cut
     big = make_desc(rest, Nb=40, H=40, P=4096)
-    assert rest.rest_tree_attention_workspace_bytes(big) == 1024 * 2 * 64 * 130 * 4
+    assert rest.rest_tree_attention_workspace_bytes(big) == 0
+    # 1280 units: the 256 < 512 left over after the whole round are cut into 1024 spans
+    cut = make_desc(rest, Nb=40, H=32, P=4096)
+    assert rest.rest_tree_attention_workspace_bytes(cut) == 1024 * 2 * 64 * 130 * 4
     fp32 = make_desc(rest, Nb=1, dtype=rest.REST_FP32, num_splits=3)
     assert rest.rest_tree_attention_workspace_bytes(fp32) == 32 * 3 * 64 * 130 * 4
     for bad in [dict(D=64), dict(Tq=0), dict(Tq=257), dict(Tk=257), dict(scale=0.0), dict(dtype=7), dict(num_splits=65),

@@ -272,6 +272,18 @@ def test_tree_attention_bf16_variants():
     attention_case(5, 7, 96, 1000, seed=14, tree="chain")    # 96 rows: four-wavefront streams with an idle wavefront
 
 
+@pytest.mark.parametrize("Nb,H,T,P,dtype", [(22, 50, 64, 100, "bf16"), (35, 41, 64, 36, "bf16"), (42, 50, 64, 70, "bf16"),
+                                            (7, 150, 33, 300, "fp8kv"), (20, 30, 128, 300, "bf16"), (10, 30, 256, 200, "bf16"),
+                                            (40, 40, 64, 50, "bf16"), (31, 50, 40, 64, "fp8kv"), (30, 28, 128, 200, "bf16"),
+                                            (7, 100, 256, 100, "bf16"), (45, 57, 64, 8, "bf16")])
+def test_tree_attention_more_units_than_streams(Nb, H, T, P, dtype):
+    """More units than the streams one launch runs (1024, 512 or 256 by the width of a unit) and not a multiple of
+    them: one or two whole rounds, then either the remaining units cut into spans and merged, or -- half a round or
+    more of them, 64 queries at most, 16-bit cache -- one more whole unit for that many streams; every slab is
+    compared."""
+    attention_case(Nb, H, T, P, seed=Nb * 100 + H, dtype=dtype, per_batch=True)
+
+
 def test_tree_attention_bf16_tiny_config():
     """Config 'tiny': 1 layer x 32 heads x 128, KV length 256, the 32-node cap."""
     attention_case(1, 32, 32, 256, seed=22)
