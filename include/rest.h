@@ -32,6 +32,10 @@
  *    may synchronise.
  *  - All calls return a rest_status; no call aborts, throws or prints.  On an
  *    error nothing has been enqueued and output buffers are untouched.
+ *  - The library keeps no state between calls apart from the rest_index
+ *    handles: calls may come from several host threads and on several streams at
+ *    once as long as they share no output buffer and no workspace; any number
+ *    of rest_retrieve calls may read one index concurrently.
  *  - Tokens are non-negative.  A corpus stores them as int32 (token_bytes 4)
  *    or uint16 (token_bytes 2); contexts and draft tokens are always int32.
  */

@@ -23,6 +23,8 @@
 // them deep in the Trie -- are counted with a popcount, only heavier nodes are visited one by one.
 // Top-c is a three-level counting select on the order (weight desc, depth asc, row asc): weight histogram,
 // depth histogram inside the boundary weight, row rank inside the boundary depth.
+#include <mutex>
+
 #include "common.h"
 
 namespace {
@@ -702,12 +704,16 @@ rest_status launch(const RetrieveParams& p, int B, size_t lds_bytes, hipStream_t
     auto kern = retrieve_kernel<TokT, SaT>;
     // raise the kernel's dynamic-LDS limit once per (instantiation, device) and only when a call needs more
     static size_t granted[64] = {0};
+    static std::mutex granted_lock;                 // host threads may call at once
     int dev = 0;
     REST_HIP_TRY(hipGetDevice(&dev));
     if (dev < 0 || dev >= 64) return REST_UNSUPPORTED;
-    if (lds_bytes > granted[dev]) {
-        REST_HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
-        granted[dev] = lds_bytes;
+    {
+        std::lock_guard<std::mutex> hold(granted_lock);
+        if (lds_bytes > granted[dev]) {
+            REST_HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
+            granted[dev] = lds_bytes;
+        }
     }
     hipLaunchKernelGGL(kern, dim3(B), dim3(kThreads), lds_bytes, stream, p);
     REST_HIP_TRY(hipGetLastError());

@@ -14,6 +14,8 @@
 // threads by one wavefront in a fixed order, and every thread walks the 16 bucket masses from the top.  Eight levels pin the key;
 // equal keys are then resolved arithmetically (their masses are equal) and by ascending token id through ballots.
 // All sums have a fixed order, so results repeat bit for bit from run to run.
+#include <mutex>
+
 #include "common.h"
 
 namespace {
@@ -228,12 +230,16 @@ extern "C" __attribute__((visibility("default"))) rest_status rest_sample_ids(co
     if (R == 0) return REST_OK;
     const size_t lds = (size_t)16 * kThreads * sizeof(double);
     static bool granted[64] = {false};
+    static std::mutex granted_lock;                 // host threads may call at once
     int dev = 0;
     REST_HIP_TRY(hipGetDevice(&dev));
     if (dev < 0 || dev >= 64) return REST_UNSUPPORTED;
-    if (!granted[dev]) {
-        REST_HIP_TRY(hipFuncSetAttribute((const void*)sample_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        granted[dev] = true;
+    {
+        std::lock_guard<std::mutex> hold(granted_lock);
+        if (!granted[dev]) {
+            REST_HIP_TRY(hipFuncSetAttribute((const void*)sample_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+            granted[dev] = true;
+        }
     }
     hipLaunchKernelGGL(sample_kernel, dim3(R), dim3(kThreads), lds, (hipStream_t)stream, d_logits, row_stride, d_u, V,
                        (double)temperature, (double)top_p, d_ids);

@@ -590,6 +590,64 @@ def test_index_file_round_trip_and_exchange_with_the_oracle(tmp_path):
 
 
 # ------------------------------------------------------------------ acceptance
+def test_calls_from_several_host_threads():
+    """Four host threads, each on its own stream with its own outputs and workspaces, drive retrieval (with
+    parameters of different LDS needs), attention and acceptance at once; every result equals the one a single
+    thread got before."""
+    import threading
+    corp = synth.make_corpus(200_000, seed=31, n_motifs=40, copies=50)
+    ctx, lens = synth.make_contexts(corp, 8, 64, 9)
+    d_ctx, d_lens = dev(ctx), dev(lens)
+    index = rest.rest_build_index(dev(corp.tokens), 4)
+    prms = [dict(n_max=16, n_min=2, max_matches=K, cont_len=m, max_nodes=c)
+            for K, m, c in [(100, 4, 16), (1000, 10, 64), (5000, 16, 64), (8192, 32, 256)]]
+    H, P = 4, 300
+    g = torch.Generator(device="cuda")
+    g.manual_seed(3)
+    scale = float(1 / np.sqrt(128.0))
+
+    def one_pass(prm, seed):
+        c = prm["max_nodes"]
+        tree = rest.rest_retrieve(index, d_ctx, d_lens, **prm)
+        gg = torch.Generator(device="cuda")
+        gg.manual_seed(seed)
+        q = torch.randn((8, H, c, 128), generator=gg, device="cuda").to(torch.bfloat16)
+        k = torch.randn((8, H, P + c, 128), generator=gg, device="cuda").to(torch.bfloat16)
+        v = torch.randn((8, H, P + c, 128), generator=gg, device="cuda").to(torch.bfloat16)
+        out = rest.rest_tree_attention(q, k, v, tree.tree_mask, P, scale)
+        ids = torch.randint(0, 32000, (8, 1 + c), generator=gg, device="cuda", dtype=torch.int32)
+        ids[:, 0] = tree.draft_tokens[:, 0]                      # the first draft token is accepted where there is one
+        alen, apath, nxt = rest.rest_accept(ids, tree, prm["cont_len"])
+        return [tree.draft_tokens, tree.parent_idx, tree.tree_mask, tree.n_nodes, out, alen, apath, nxt]
+
+    want = []
+    for i, prm in enumerate(prms):
+        want.append([t.clone() for t in one_pass(prm, 100 + i)])
+    torch.cuda.synchronize()
+    failures = []
+
+    def worker(i):
+        try:
+            with torch.cuda.stream(torch.cuda.Stream()):
+                for rep in range(10):
+                    j = (i + rep) % len(prms)
+                    got = one_pass(prms[j], 100 + j)
+                    torch.cuda.current_stream().synchronize()
+                    for a, b in zip(got, want[j]):
+                        if not torch.equal(a, b):
+                            failures.append((i, rep, j))
+        except Exception as e:                                   # noqa: BLE001 - reported below
+            failures.append((i, repr(e)))
+
+    threads = [threading.Thread(target=worker, args=(i,)) for i in range(4)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not failures, failures[:5]
+    assert int(want[1][3].max()) > 8 and int(want[1][5].max()) >= 1
+
+
 def test_accept_matches_oracle_on_random_trees():
     B, c, cap = 40, 64, 16
     tree = rest.Tree.empty(B, c, fill=0)
