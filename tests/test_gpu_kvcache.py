@@ -97,6 +97,7 @@ def test_rope_append_strided_inputs_from_a_fused_projection():
     (3, 4, 16, 9, 6, [[2, 5, 9, 15, -1, -1], [-1] * 6, [0, 3, 4, 7, 8, 11]]),     # per batch, one empty
     (1, 32, 64, 2048, 16, [[0, 2, 7, 12, 20, 33, 41, 63] + [-1] * 8]),
     (1, 1, 40, 0, 32, [list(range(8, 40))]),             # the longest path the call takes
+    (2, 2, 8, 3, 4, [[2, 0, 1, -1]]),                    # not increasing (no tree gives this): old rows move all the same
 ])
 def test_kv_compact_matches_oracle_bit_for_bit(Nb, H, T, P, cap, paths):
     kc, kc_np = bf16_tensor((Nb, H, P + T + 2, 128), 11)

@@ -96,6 +96,10 @@ def test_compact_hand_case_and_identity():
     # a source row may be another move's destination (path [1, 2]: row P+1 is read by move 0 and written by move 1)
     out = oracle.kv_compact(cache, P, np.array([1, 2]), 2)
     np.testing.assert_array_equal(out[:, 0], [0, 1, 3, 4, 4, 5, 6])
+    # the definition reads the cache as it was: a path that is not increasing (no tree produces one) still moves the
+    # old rows -- new P+0 = old P+2, new P+1 = old P+0, new P+2 = old P+1 --, not rows an earlier move has written
+    out = oracle.kv_compact(cache, P, np.array([2, 0, 1]), 3)
+    np.testing.assert_array_equal(out[:, 0], [0, 1, 4, 2, 3, 5, 6])
 
 
 @pytest.mark.parametrize("seed", [0, 1, 2])

@@ -34,6 +34,21 @@ def test_hand_distribution_boundaries():
     assert oracle.nucleus_sample(lg, 0.5, 1.0, 336.1 / 344)[0] == 1
 
 
+def test_boundaries_hit_exactly():
+    """Four equal logits: every probability is exactly 1/4 and every cumulative sum exact, so both inequalities of the
+    definition show: the nucleus is the shortest prefix whose mass is >= top_p (not >), and the draw is the first
+    token whose cumulative mass exceeds (not reaches) u times the nucleus mass."""
+    lg = np.full(4, 1.5, dtype=np.float32)
+    # top_p = 1/2 is reached by two tokens: nucleus {0, 1}, mass 1/2.  A nucleus of three would give token 2 at u = 0.7.
+    assert oracle.nucleus_sample(lg, 1.0, 0.5, 0.7)[0] == 1
+    assert {oracle.nucleus_sample(lg, 1.0, 0.5, u)[0] for u in np.linspace(0, 0.999, 40)} == {0, 1}
+    # u = 1/2: the target 1/4 equals the first cumulative sum, which does not exceed it: token 1
+    assert oracle.nucleus_sample(lg, 1.0, 0.5, 0.5)[0] == 1
+    assert oracle.nucleus_sample(lg, 1.0, 0.5, 0.4999)[0] == 0
+    # top_p = 1: all four; targets on the cumulative sums go to the next token
+    assert [oracle.nucleus_sample(lg, 1.0, 1.0, u)[0] for u in (0.0, 0.25, 0.5, 0.75)] == [0, 1, 2, 3]
+
+
 def test_limits_are_argmax_with_lowest_id_on_ties():
     rng = np.random.default_rng(0)
     for _ in range(20):
