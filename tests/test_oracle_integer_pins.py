@@ -337,6 +337,19 @@ def test_accept_hand_cases():
         assert n == 1 and path[0] == chain[0] and nxt == -7
 
 
+def test_rest_loop_on_a_fully_predictable_stream_emits_the_whole_draft_and_one_more_token_per_step():
+    """A periodic stream and a model that continues the period: every draft token is accepted, and each verification
+    step also yields the model's own token after the last accepted one ("Draft acceptance"), so a step emits
+    cont_len + 1 tokens."""
+    period, m = 50, 8
+    corpus = np.tile(np.arange(period, dtype=np.int32), 40)
+    model = lambda seq: (seq[-1] + 1) % period          # noqa: E731
+    prompt = list(range(20))
+    got, steps = oracle.rest_decode(model, prompt, 60, corpus, max_matches=200, cont_len=m, max_nodes=24)
+    assert got == [(20 + i) % period for i in range(60)]
+    assert steps == -(-60 // (m + 1))                    # 7 steps of 9 tokens, not 8 of 8
+
+
 @pytest.mark.parametrize("seed", [1, 2, 3])
 def test_rest_loop_reproduces_greedy_decoding(seed):
     corp = synth.make_corpus(30000, seed=seed, n_motifs=40, copies=20, vocab=500)
@@ -401,6 +414,11 @@ def test_random_selection_strategy():
     # the generator: published first outputs of splitmix64 seeded with 0 are its finaliser at G and 2G
     G = 0x9E3779B97F4A7C15
     assert oracle._mix64(G) == 0xE220A8397B1DCDAF and oracle._mix64(2 * G) == 0x6E789E6AA1B965F4
+    # with seed = -G (mod 2^64) and context 0 the inner state is mix(0) = 0, so draw j uses the published output
+    # number 1 + j of that generator (0xE220..., 0x6E78..., 0x06C4...) and takes its leading bits: floor(U * n / 2^64)
+    assert oracle._mix64(0) == 0 and oracle._mix64(3 * G) == 0x06C45D188009454F
+    np.testing.assert_array_equal(oracle.random_rows(16, 2, (1 << 64) - G, 0), [0x6, 0xE])
+    np.testing.assert_array_equal(oracle.random_rows(256, 3, (1 << 64) - G, 0), [0x06, 0x6E, 0xE2])
     # one candidate: every draw is that candidate; no candidates: nothing
     np.testing.assert_array_equal(oracle.random_rows(1, 8, 3, 0), [0])
     assert oracle.random_rows(0, 8, 3, 0).size == 0

@@ -84,6 +84,26 @@ EDITS = {
     "sampling: u not scaled by the nucleus mass": ("sampling", "nucleus_sample", "target = float(u) * mass", "target = float(u)"),
     "mask: a node does not see itself": ("integer", "mask_from_parents", "        v = i\n", "        v = int(parent_idx[i])\n"),
     "mask: parent only, no further ancestors": ("integer", "mask_from_parents", "while v != -1:", "for _ in range(2 if v != -1 else 0):\n            if v == -1:\n                break"),
+    "attention: only the first mask word read": ("attention", "tree_attention", "mask[..., j // 64]", "mask[..., 0]"),
+    "attention: 8-bit cache, V scaled by the K scale": ("fp8", "tree_attention_fp8kv", "fp8_e4m3_decode(v8) * np.asarray(v_scale,",
+                                                       "fp8_e4m3_decode(v8) * np.asarray(k_scale,"),
+    "append: queries not rotated": ("kv", "rope_append", "qr = rope(q, pos, theta)", "qr = np.asarray(q, dtype=np.float64)"),
+    "append: 8-bit cache, multiplied by the scale": ("fp8", "rope_append_fp8kv", "kx = rope(k_new, pos, theta) / np.asarray(",
+                                                    "kx = rope(k_new, pos, theta) * np.asarray("),
+    "compact: last accepted row not moved": ("kv", "kv_compact", "for i in range(int(accept_len)):", "for i in range(int(accept_len) - 1):"),
+    "sampling: candidates without the tolerance at the nucleus end": ("sampling", "nucleus_candidates",
+                                                                     "if cum[k] >= top_p - tol and (k == 0 or cum[k - 1] < top_p + tol)]",
+                                                                     "if cum[k] >= top_p and (k == 0 or cum[k - 1] < top_p)][:1]"),
+    "retrieve: evenly spaced sample rounded up": ("integer", "retrieve", "pick = np.array([(i * S) // K for i in range(K)]",
+                                                  "pick = np.array([min((i * S + K - 1) // K, S - 1) for i in range(K)]"),
+    "random selection: draw by remainder": ("integer", "random_rows", "(_mix64(h + G * (1 + j)) * n_rows) >> 64", "_mix64(h + G * (1 + j)) % n_rows"),
+    "random selection: draws counted from zero": ("integer", "random_rows", "_mix64(h + G * (1 + j))", "_mix64(h + G * j)"),
+    "depth-limited order: equal prefixes by descending position": ("integer", "prefix_sorted_array", "return np.lexsort(columns[::-1])",
+                                                                   "return np.lexsort([-np.arange(n)] + columns[::-1])"),
+    "depth-limited order: end of the stream largest": ("integer", "prefix_sorted_array", "np.zeros(depth, dtype=np.int64)]",
+                                                       "np.full(depth, 1 << 40, dtype=np.int64)]"),
+    "index file: fingerprint without the position": ("integer", "corpus_fingerprint", "z = tok + (np.arange(", "z = tok + 0 * (np.arange("),
+    "decoding loop: bonus token left out": ("integer", "rest_decode", "        seq.append(int(nxt))\n", "        seq.append(int(nxt)) if n_acc == 0 else None\n"),
     "fp8: truncation instead of nearest": ("fp8", "fp8_e4m3_encode", "code = np.where(d_lo < d_hi, lo, np.where(d_hi < d_lo, hi, np.where(lo % 2 == 0, lo, hi)))",
                                            "code = lo + (d_hi == 0)"),
     "fp8: ties away from zero": ("fp8", "fp8_e4m3_encode", "np.where(lo % 2 == 0, lo, hi)", "hi"),
