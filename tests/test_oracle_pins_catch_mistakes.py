@@ -130,6 +130,10 @@ def retrieve_with(change):
                 got.rows[r, :] = -1
                 got.rows[r, :seg.shape[0]] = seg
                 got.row_len[r] = seg.shape[0]
+        elif change == "occurrences without a continuation dropped":
+            keep = got.row_len > 0
+            got = oracle.Retrieved(got.matched_len if keep.any() else 0, got.match_count - int((~keep).sum()),
+                                   got.row_pos[keep], got.rows[keep], got.row_len[keep])
         elif change == "keeps the last K of the range" and got.match_count > max_matches > 0 and not strided:
             full = orig(corpus, context, n_max, n_min, got.match_count, cont_len, one_pass, False)
             keep = slice(got.match_count - int(max_matches), got.match_count)
@@ -268,7 +272,8 @@ def suffix_array_with(change):
 
 WRAPS = {f"retrieve: {c}": ("integer", "retrieve", retrieve_with, c) for c in
          ["n_min ignored", "longest length never tried", "count capped at K",
-          "continuation starts at the last matched token", "keeps the last K of the range"]}
+          "continuation starts at the last matched token", "keeps the last K of the range",
+          "occurrences without a continuation dropped"]}
 WRAPS.update({f"select: {c}": ("integer", "select_drafts", select_with, c) for c in
               ["one node too few", "depths counted from zero", "weights one too high", "rows beyond their length counted",
                "siblings in descending token order"]})
