@@ -590,6 +590,42 @@ def test_index_file_round_trip_and_exchange_with_the_oracle(tmp_path):
 
 
 # ------------------------------------------------------------------ acceptance
+def test_results_repeat_bit_for_bit():
+    """The same call on the same inputs, many times: every output identical to the first run's (sums are taken in
+    a fixed order everywhere; nothing depends on which workgroup arrives first)."""
+    corp = synth.make_corpus(300_000, seed=17, n_motifs=60, copies=50)
+    d_corpus = dev(corp.tokens)
+    sa0 = rest.rest_build_index(d_corpus, 4).suffix_array().clone()
+    index = rest.rest_build_index(d_corpus, 4)
+    assert torch.equal(index.suffix_array(), sa0)
+    ctx, lens = synth.make_contexts(corp, 16, 64, 3)
+    d_ctx, d_lens = dev(ctx), dev(lens)
+    prm = dict(n_max=16, n_min=2, max_matches=5000, cont_len=16, max_nodes=64)
+    first = rest.rest_retrieve(index, d_ctx, d_lens, **prm)
+    fields = ("draft_tokens", "parent_idx", "pos_ids", "node_weight", "tree_mask", "n_nodes", "matched_len", "match_count")
+    keep = [getattr(first, f).clone() for f in fields]
+    for _ in range(50):
+        again = rest.rest_retrieve(index, d_ctx, d_lens, **prm)
+        for f, want in zip(fields, keep):
+            assert torch.equal(getattr(again, f), want), f
+    g = torch.Generator(device="cuda")
+    g.manual_seed(8)
+    mask = first.tree_mask[0]
+    # one layer cut into spans and merged; more units than streams with a cut remainder; with a whole extra round
+    for Nb, H, P in [(1, 32, 2048), (22, 50, 100), (40, 40, 50)]:
+        q = torch.randn((Nb, H, 64, 128), generator=g, device="cuda").to(torch.bfloat16)
+        k = torch.randn((Nb, H, P + 64, 128), generator=g, device="cuda").to(torch.bfloat16)
+        v = torch.randn((Nb, H, P + 64, 128), generator=g, device="cuda").to(torch.bfloat16)
+        want = rest.rest_tree_attention(q, k, v, mask, P, 0.0884).clone()
+        for _ in range(30):
+            assert torch.equal(rest.rest_tree_attention(q, k, v, mask, P, 0.0884), want), (Nb, H, P)
+    logits = torch.randn((65, 32000), generator=g, device="cuda") * 3
+    u = torch.rand(65, generator=g, device="cuda")
+    want = rest.rest_sample_ids(logits, u, 0.7, 0.95).clone()
+    for _ in range(20):
+        assert torch.equal(rest.rest_sample_ids(logits, u, 0.7, 0.95), want)
+
+
 def test_calls_from_several_host_threads():
     """Four host threads, each on its own stream with its own outputs and workspaces, drive retrieval (with
     parameters of different LDS needs), attention and acceptance at once; every result equals the one a single
