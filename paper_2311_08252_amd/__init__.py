@@ -165,6 +165,13 @@ def _pinned_is_mapped(t: torch.Tensor) -> bool:
     return rc == 0 and a.devicePointer == t.data_ptr()
 
 
+def _require(cond: bool, what: str) -> None:
+    """Shapes and dtypes are checked on the host before any pointer reaches a kernel: the kernels index the buffers
+    from the sizes in the call, so a buffer smaller than those sizes imply would be read or written out of bounds."""
+    if not cond:
+        raise ValueError(what)
+
+
 def _dev(t: torch.Tensor, dtype=None, pinned_ok: bool = False) -> int:
     if not t.is_cuda:
         if not (pinned_ok and t.is_pinned() and _pinned_is_mapped(t)):
@@ -301,6 +308,19 @@ class Tree:
         return Tree(mk((B, c), torch.int32), mk((B, c), torch.int32), mk((B, c), torch.int32), mk((B, c), torch.int32),
                     mk((B, c, words), torch.int64), mk((B,), torch.int32), mk((B,), torch.int32), mk((B,), torch.int64))
 
+    def check(self, B: int, c: int) -> None:
+        """Raises ValueError unless every buffer is a contiguous tensor of the shape and dtype rest_tree gives it for B
+        contexts with node capacity c."""
+        words = (c + 63) // 64
+        for name, shape, dts in (("draft_tokens", (B, c), (torch.int32,)), ("parent_idx", (B, c), (torch.int32,)),
+                                 ("pos_ids", (B, c), (torch.int32,)), ("node_weight", (B, c), (torch.int32,)),
+                                 ("tree_mask", (B, c, words), (torch.int64, torch.uint64)),
+                                 ("n_nodes", (B,), (torch.int32,)), ("matched_len", (B,), (torch.int32,)),
+                                 ("match_count", (B,), (torch.int64,))):
+            t = getattr(self, name)
+            _require(tuple(t.shape) == shape and t.dtype in dts and t.is_contiguous(),
+                     f"tree.{name}: expected contiguous {dts[0]} of shape {shape}, got {t.dtype} {tuple(t.shape)}")
+
     def as_struct(self) -> rest_tree:
         return rest_tree(self.draft_tokens.data_ptr(), self.parent_idx.data_ptr(), self.pos_ids.data_ptr(),
                          self.node_weight.data_ptr(), self.tree_mask.data_ptr(), self.n_nodes.data_ptr(),
@@ -318,10 +338,16 @@ def rest_retrieve(index: RestIndex, contexts: torch.Tensor, ctx_len: torch.Tenso
                   strided: bool = False) -> Tree:
     """contexts [B, ctx_stride] int32, ctx_len [B] int32 (device).  Enqueues on the current stream.
     random_seqs > 0: the ablation's strategy (that many randomly drawn candidates instead of the whole Trie)."""
-    assert contexts.dim() == 2 and contexts.is_contiguous() and ctx_len.is_contiguous()
+    _require(contexts.dim() == 2 and contexts.is_contiguous() and ctx_len.is_contiguous(), "contexts [B, stride], ctx_len [B], contiguous")
     B, stride = contexts.shape
+    _require(ctx_len.numel() == B, f"ctx_len holds {ctx_len.numel()} entries for {B} contexts")
+    in_range = 1 <= max_nodes <= REST_MAX_NODES        # the library refuses other values before it touches `out`
     if out is None:
-        out = Tree.empty(B, max_nodes, contexts.device)
+        out = Tree.empty(B, max_nodes if in_range else 1, contexts.device)
+    if in_range:
+        out.check(B, max_nodes)
+    if workspace is not None:
+        _require(workspace.is_contiguous(), "workspace must be contiguous")
     prm = rest_retrieve_params(n_max, n_min, max_matches, cont_len, max_nodes, random_seqs, seed, int(strided), 0)
     tree = out.as_struct()
     ws_ptr = workspace.data_ptr() if workspace is not None else None
@@ -336,30 +362,49 @@ def rest_retrieve(index: RestIndex, contexts: torch.Tensor, ctx_len: torch.Tenso
 def make_attn_desc(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, out: torch.Tensor, prefix_len: int,
                    scale: float, mask_per_batch: bool, num_splits: int = 0, mask_rows: int = 0,
                    k_scale: torch.Tensor | None = None, v_scale: torch.Tensor | None = None) -> rest_attn_desc:
+    _require(q.dim() == 4 and k.dim() == 4 and v.dim() == 4 and out.dim() == 4, "q, k, v, out must be [Nb, H, rows, D]")
     Nb, H, Tq, D = q.shape
     Lk = k.shape[2]
+    _require(tuple(k.shape) == (Nb, H, Lk, D) and tuple(v.shape) == (Nb, H, Lk, D),
+             f"k {tuple(k.shape)} and v {tuple(v.shape)} must be [Nb={Nb}, H={H}, P+Tk, D={D}]")
+    _require(tuple(out.shape) == (Nb, H, Tq, D) and out.dtype == q.dtype,
+             f"out must have q's shape {tuple(q.shape)} and dtype, got {out.dtype} {tuple(out.shape)}")
+    _require(0 <= prefix_len <= Lk, f"prefix_len {prefix_len} outside [0, {Lk}]")
+    _require(q.dtype in (torch.bfloat16, torch.float32), "q must be bfloat16 or float32")
     dt = {torch.bfloat16: REST_BF16, torch.float32: REST_FP32}[q.dtype]
     d = rest_attn_desc()
     d.Nb, d.H, d.Tq, d.Tk, d.P, d.D = Nb, H, Tq, Lk - prefix_len, prefix_len, D
     d.dtype = dt
     d.scale = scale
     for name, t in (("q_stride", q), ("k_stride", k), ("v_stride", v), ("o_stride", out)):
-        assert t.stride(3) == 1
+        _require(t.stride(3) == 1, f"{name}: the last axis must be contiguous")
         getattr(d, name)[:] = [t.stride(0), t.stride(1), t.stride(2)]
     d.mask_per_batch = 1 if mask_per_batch else 0
     d.num_splits = num_splits
     d.mask_rows = mask_rows
     if k.dtype == torch.uint8:          # one OCP E4M3 byte per cached element
-        assert v.dtype == torch.uint8 and q.dtype == torch.bfloat16
+        _require(v.dtype == torch.uint8 and q.dtype == torch.bfloat16, "an 8-bit cache needs uint8 k and v and bfloat16 q")
         d.kv_dtype = REST_KV_FP8_E4M3
         for name, t in (("d_k_scale", k_scale), ("d_v_scale", v_scale)):
             if t is not None:
-                assert t.dtype == torch.float32 and t.is_contiguous() and t.numel() == Nb * H
-                setattr(d, name, t.data_ptr())
+                _require(t.dtype == torch.float32 and t.is_contiguous() and t.numel() == Nb * H,
+                         f"{name}: expected {Nb * H} contiguous float32 scales")
+                setattr(d, name, _dev(t))
     else:
-        assert k_scale is None and v_scale is None and k.dtype == q.dtype and v.dtype == q.dtype
+        _require(k_scale is None and v_scale is None and k.dtype == q.dtype and v.dtype == q.dtype,
+                 "k and v must have q's dtype (scales belong to an 8-bit cache)")
         d.kv_dtype = REST_KV_AS_DTYPE
     return d
+
+
+def _check_mask(mask: torch.Tensor, desc: rest_attn_desc, per_batch: bool, mask_rows: int) -> None:
+    """The kernels read mask row (i % rows) of batch entry nb at [nb, i % rows, 0 .. words): the tensor must hold that."""
+    rows, words = (mask_rows if mask_rows > 0 else desc.Tq), (desc.Tk + 63) // 64
+    _require(0 <= mask_rows <= desc.Tq, f"mask_rows {mask_rows} outside [0, Tq]")
+    if desc.Tk > 0:
+        _require(mask.dtype in (torch.int64, torch.uint64) and mask.is_contiguous(), "mask must be contiguous int64/uint64 bit rows")
+        want = (desc.Nb, rows, words) if per_batch else (rows, words)
+        _require(tuple(mask.shape) == want, f"mask: expected shape {want} (one mask per batch entry if 3-D), got {tuple(mask.shape)}")
 
 
 def rest_tree_attention_workspace_bytes(desc: rest_attn_desc) -> int:
@@ -373,11 +418,14 @@ def rest_tree_attention(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, mask:
     """q [Nb,H,Tq,128]; k, v [Nb,H,P+Tk,128] (bf16 or fp32, device); mask [Tq,words] or [Nb,Tq,words] int64/uint64.
     k, v of dtype uint8: an 8-bit (OCP E4M3) cache with optional per-(Nb, H) float32 scales.
     Enqueues on the current stream."""
-    assert q.dim() == 4 and k.dim() == 4 and v.dim() == 4 and k.shape == v.shape
+    _require(q.dim() == 4, "q must be [Nb, H, Tq, D]")
     if out is None:
         out = torch.empty_like(q)
     per_batch = mask.dim() == 3
     desc = make_attn_desc(q, k, v, out, prefix_len, scale, per_batch, num_splits, mask_rows, k_scale, v_scale)
+    _check_mask(mask, desc, per_batch, mask_rows)
+    if workspace is not None:
+        _require(workspace.is_contiguous(), "workspace must be contiguous")
     need = rest_tree_attention_workspace_bytes(desc)
     if workspace is None and need:
         workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
@@ -394,12 +442,19 @@ def rest_accept(ids: torch.Tensor, tree: Tree, path_cap: int,
                 accept_len: torch.Tensor | None = None, accept_path: torch.Tensor | None = None,
                 next_token: torch.Tensor | None = None):
     """ids [B, 1+c] int32 (device).  Returns (accept_len [B], accept_path [B, path_cap], next_token [B])."""
+    _require(ids.dim() == 2 and ids.is_contiguous() and ids.shape[1] >= 2, "ids must be contiguous [B, 1 + c]")
     B, c1 = ids.shape
     c = c1 - 1
+    tree.check(B, c)
+    _require(1 <= path_cap <= REST_MAX_CONT_LEN, "path_cap out of range")
     dev = ids.device
     accept_len = accept_len if accept_len is not None else torch.empty(B, dtype=torch.int32, device=dev)
     accept_path = accept_path if accept_path is not None else torch.empty((B, path_cap), dtype=torch.int32, device=dev)
     next_token = next_token if next_token is not None else torch.empty(B, dtype=torch.int32, device=dev)
+    for name, t, shape in (("accept_len", accept_len, (B,)), ("accept_path", accept_path, (B, path_cap)),
+                           ("next_token", next_token, (B,))):
+        _require(tuple(t.shape) == shape and t.dtype == torch.int32 and t.is_contiguous(),
+                 f"{name}: expected contiguous int32 of shape {shape}, got {t.dtype} {tuple(t.shape)}")
     ts = tree.as_struct()
     st = _lib.rest_accept(_dev(ids, torch.int32), ctypes.byref(ts), B, c, path_cap, _dev(accept_len), _dev(accept_path),
                           _dev(next_token), _stream())

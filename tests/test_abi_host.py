@@ -180,3 +180,77 @@ def test_header_is_plain_c_and_struct_layouts_match_the_binding(tmp_path, rest):
         assert int(out[name]) == ctypes.sizeof(cls), name
         for field, _ in cls._fields_:
             assert int(out[f"{name}.{field}"]) == getattr(cls, field).offset, (name, field)
+
+
+def test_binding_rejects_buffers_that_do_not_fit_the_call(rest):
+    """The kernels index every buffer from the sizes in the call, so the binding compares shapes and dtypes with those
+    sizes before a pointer goes anywhere (host tensors suffice: the shape checks come first)."""
+    import torch
+    bf = torch.bfloat16
+    q, k, v = torch.zeros((4, 2, 8, 128), dtype=bf), torch.zeros((4, 2, 40, 128), dtype=bf), torch.zeros((4, 2, 40, 128), dtype=bf)
+    ok_mask = torch.zeros((8, 1), dtype=torch.int64)
+
+    def attn(**over):
+        a = dict(q=q, k=k, v=v, mask=ok_mask, prefix_len=32, scale=0.1)
+        a.update(over)
+        return rest.rest_tree_attention(**a)
+
+    # a single tree's [1, c, words] mask with four batch entries would be read as one mask per entry, three past its end
+    with pytest.raises(ValueError, match="mask"):
+        attn(mask=torch.zeros((1, 8, 1), dtype=torch.int64))
+    for bad in (torch.zeros((7, 1), dtype=torch.int64), torch.zeros((8, 2), dtype=torch.int64),
+                torch.zeros((8, 1), dtype=torch.int32), torch.zeros((8, 2), dtype=torch.int64)[:, :1]):
+        with pytest.raises(ValueError, match="mask"):
+            attn(mask=bad)
+    with pytest.raises(ValueError, match="mask_rows"):
+        attn(mask_rows=9)
+    with pytest.raises(ValueError, match="mask"):
+        attn(mask_rows=4)                                              # then the mask has four rows, not eight
+    with pytest.raises(ValueError):
+        attn(v=torch.zeros((4, 2, 39, 128), dtype=bf))
+    with pytest.raises(ValueError):
+        attn(k=torch.zeros((4, 3, 40, 128), dtype=bf), v=torch.zeros((4, 3, 40, 128), dtype=bf))
+    with pytest.raises(ValueError):
+        attn(k=k.float(), v=v.float())
+    with pytest.raises(ValueError, match="out"):
+        attn(out=torch.zeros((4, 2, 7, 128), dtype=bf))
+    with pytest.raises(ValueError, match="out"):
+        attn(out=torch.zeros((4, 2, 8, 128), dtype=torch.float32))
+    with pytest.raises(ValueError, match="prefix_len"):
+        attn(prefix_len=41)
+    with pytest.raises(ValueError):
+        attn(q=q.transpose(2, 3))
+    with pytest.raises(ValueError, match="scale"):
+        attn(k=k.view(torch.uint8)[..., :128].contiguous(), v=v.view(torch.uint8)[..., :128].contiguous(),
+             k_scale=torch.ones(7))
+    with pytest.raises(TypeError):                                     # shapes fit; host tensors are then refused as such
+        attn()
+
+    class FakeIndex:
+        handle = None
+
+    ctx, ln = torch.zeros((3, 16), dtype=torch.int32), torch.zeros(3, dtype=torch.int32)
+    with pytest.raises(ValueError, match="ctx_len"):
+        rest.rest_retrieve(FakeIndex(), ctx, ln[:2], max_nodes=8)
+    small = rest.Tree.empty(3, 4, device="cpu")                        # room for four nodes, eight asked for
+    with pytest.raises(ValueError, match="tree"):
+        rest.rest_retrieve(FakeIndex(), ctx, ln, out=small, max_nodes=8)
+    few = rest.Tree.empty(2, 8, device="cpu")
+    with pytest.raises(ValueError, match="tree"):
+        rest.rest_retrieve(FakeIndex(), ctx, ln, out=few, max_nodes=8)
+    wrong = rest.Tree.empty(3, 8, device="cpu")
+    wrong.match_count = wrong.match_count.to(torch.int32)
+    with pytest.raises(ValueError, match="match_count"):
+        rest.rest_retrieve(FakeIndex(), ctx, ln, out=wrong, max_nodes=8)
+
+    tree = rest.Tree.empty(3, 8, device="cpu")
+    with pytest.raises(ValueError, match="tree"):                      # ids for a capacity of 16 against a tree of 8
+        rest.rest_accept(torch.zeros((3, 17), dtype=torch.int32), tree, 10)
+    with pytest.raises(ValueError, match="tree"):
+        rest.rest_accept(torch.zeros((2, 9), dtype=torch.int32), tree, 10)
+    with pytest.raises(ValueError, match="accept_path"):
+        rest.rest_accept(torch.zeros((3, 9), dtype=torch.int32), tree, 10, accept_path=torch.zeros((3, 9), dtype=torch.int32))
+    with pytest.raises(ValueError, match="path_cap"):
+        rest.rest_accept(torch.zeros((3, 9), dtype=torch.int32), tree, 33)
+    with pytest.raises(TypeError):
+        rest.rest_accept(torch.zeros((3, 9), dtype=torch.int32), tree, 10)
