@@ -267,6 +267,21 @@ rest_status rest_tree_attention(const void* d_q, const void* d_k, const void* d_
                                 void* d_out, const rest_attn_desc* desc,
                                 void* d_workspace, size_t workspace_bytes, void* stream);
 
+/* rest_tree_attention for callers that cannot allocate device memory or bring a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments (minus the workspace), same
+ * kernels, same results bit for bit; the partial results of the KV splits go to a device array of
+ * REST_STATIC_SCRATCH_BYTES that is part of the library's image on each GPU (held until the process ends).  The
+ * call allocates nothing and frees nothing.  A description whose rest_tree_attention_workspace_bytes exceeds
+ * REST_STATIC_SCRATCH_BYTES is refused with REST_WORKSPACE_TOO_SMALL (64 MiB covers one layer of 32 heads at any
+ * KV length, i.e. single-context decoding; launches with many (batch, head) slabs need no partials at all unless
+ * num_splits forces them).  All calls on one GPU share that GPU's array: calls that overlap in time on one GPU
+ * (two streams, two host threads) race on it and must be serialised by the caller; calls in stream order on one
+ * stream are safe.  The first call on a device asks the runtime for the array's address there (do that call
+ * outside a graph capture). */
+#define REST_STATIC_SCRATCH_BYTES (64 * 1024 * 1024)
+rest_status rest_tree_attention_noalloc(const void* d_q, const void* d_k, const void* d_v, const uint64_t* d_mask,
+                                        void* d_out, const rest_attn_desc* desc, void* stream);
+
 /* ------------------------------------------------------------------------
  * rest_accept ("Draft acceptance"): d_ids[b, 0] is the model's token after the
  * context, d_ids[b, 1+i] its token after draft node i (greedy: the argmax).

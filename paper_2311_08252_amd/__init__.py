@@ -39,13 +39,14 @@ REST_MAX_CONT_LEN = 32
 REST_MAX_MATCHES = 8192
 REST_MAX_NODES = 256
 REST_MAX_QUERY_ROWS = 1024
+REST_STATIC_SCRATCH_BYTES = 64 * 1024 * 1024
 
 EXPORTS = [
     "rest_status_string", "rest_version", "rest_build_index", "rest_index_from_sa", "rest_index_view",
     "rest_index_destroy", "rest_retrieve_workspace_bytes", "rest_retrieve",
     "rest_tree_attention_workspace_bytes", "rest_tree_attention", "rest_accept",
     "rest_rope_append", "rest_kv_compact", "rest_sample_ids", "rest_index_save", "rest_index_load",
-    "rest_build_index_prefix", "rest_index_sort_depth",
+    "rest_build_index_prefix", "rest_index_sort_depth", "rest_tree_attention_noalloc",
 ]
 
 
@@ -122,6 +123,9 @@ _lib.rest_tree_attention_workspace_bytes.argtypes = [ctypes.POINTER(rest_attn_de
 _lib.rest_tree_attention.restype = ctypes.c_int32
 _lib.rest_tree_attention.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                      ctypes.POINTER(rest_attn_desc), ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+_lib.rest_tree_attention_noalloc.restype = ctypes.c_int32
+_lib.rest_tree_attention_noalloc.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                             ctypes.POINTER(rest_attn_desc), ctypes.c_void_p]
 _lib.rest_accept.restype = ctypes.c_int32
 _lib.rest_accept.argtypes = [ctypes.c_void_p, ctypes.POINTER(rest_tree), ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
                              ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
@@ -435,6 +439,22 @@ def rest_tree_attention(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, mask:
                                   ctypes.byref(desc), ws_ptr, ws_bytes, _stream())
     if st != REST_OK:
         raise RestError(st, "rest_tree_attention")
+    return out
+
+
+def rest_tree_attention_noalloc(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, mask: torch.Tensor, prefix_len: int,
+                                scale: float, out: torch.Tensor, num_splits: int = 0, mask_rows: int = 0,
+                                k_scale: torch.Tensor | None = None, v_scale: torch.Tensor | None = None) -> torch.Tensor:
+    """rest_tree_attention without a workspace and without any allocation (`out` is the caller's): partial results
+    go to the library's own fixed device array.  Raises RestError(REST_WORKSPACE_TOO_SMALL) when they would not fit."""
+    _require(q.dim() == 4, "q must be [Nb, H, Tq, D]")
+    per_batch = mask.dim() == 3
+    desc = make_attn_desc(q, k, v, out, prefix_len, scale, per_batch, num_splits, mask_rows, k_scale, v_scale)
+    _check_mask(mask, desc, per_batch, mask_rows)
+    st = _lib.rest_tree_attention_noalloc(_dev(q), _dev(k), _dev(v), _dev(mask) if mask.numel() else None, _dev(out),
+                                          ctypes.byref(desc), _stream())
+    if st != REST_OK:
+        raise RestError(st, "rest_tree_attention_noalloc")
     return out
 
 

@@ -28,6 +28,7 @@
 //    depend on the reference);
 //  * tree-mask bit rows are held in LDS and only consulted for blocks that reach past the prefix.
 #include "common.h"
+#include <mutex>
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
@@ -722,9 +723,10 @@ extern "C" __attribute__((visibility("default"))) size_t rest_tree_attention_wor
     return (size_t)pl.tail_streams * 2 * (pl.qt * 32) * (kD + 2) * sizeof(float);
 }
 
-extern "C" __attribute__((visibility("default"))) rest_status rest_tree_attention(const void* d_q, const void* d_k, const void* d_v, const uint64_t* d_mask,
-                                           void* d_out, const rest_attn_desc* d, void* d_workspace,
-                                           size_t workspace_bytes, void* stream_) {
+// Checks the call and enqueues its kernels; the partial results of cut units go to d_workspace.
+static rest_status enqueue_tree_attention(const void* d_q, const void* d_k, const void* d_v, const uint64_t* d_mask,
+                                          void* d_out, const rest_attn_desc* d, void* d_workspace,
+                                          size_t workspace_bytes, void* stream_) {
     if (!desc_ok(d) || !d_q || !d_k || !d_v || !d_out) return REST_INVALID_ARG;
     if (d->Tk > 0 && !d_mask) return REST_INVALID_ARG;
     if (((uintptr_t)d_q | (uintptr_t)d_k | (uintptr_t)d_v | (uintptr_t)d_out) & 15) return REST_INVALID_ARG;
@@ -800,4 +802,52 @@ extern "C" __attribute__((visibility("default"))) rest_status rest_tree_attentio
         }
     }
     return REST_OK;
+}
+
+extern "C" __attribute__((visibility("default"))) rest_status rest_tree_attention(const void* d_q, const void* d_k, const void* d_v, const uint64_t* d_mask,
+                                           void* d_out, const rest_attn_desc* d, void* d_workspace,
+                                           size_t workspace_bytes, void* stream_) {
+    return enqueue_tree_attention(d_q, d_k, d_v, d_mask, d_out, d, d_workspace, workspace_bytes, stream_);
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// rest_tree_attention for callers that cannot allocate: the partial results live in a device array that is part of
+// the library's code object.  Each GPU holds its own copy at its own address; the array's name is only a handle in
+// host code, so the address is asked of the runtime once per device and that pointer is what the kernels get.
+namespace {
+static __device__ __align__(256) unsigned char scratch[REST_STATIC_SCRATCH_BYTES];
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_lock;
+void* g_scratch_ptr[kMaxDevices];      // per device: where `scratch` lives there (null = not asked yet)
+
+rest_status static_scratch(void** out) {
+    int dev = -1;
+    REST_HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return REST_UNSUPPORTED;
+    std::lock_guard<std::mutex> hold(g_scratch_lock);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        REST_HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr) return REST_HIP_ERROR;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return REST_OK;
+}
+}  // namespace
+
+extern "C" __attribute__((visibility("default"))) rest_status rest_tree_attention_noalloc(const void* d_q, const void* d_k, const void* d_v,
+                                                   const uint64_t* d_mask, void* d_out, const rest_attn_desc* d,
+                                                   void* stream_) {
+    if (!desc_ok(d)) return REST_INVALID_ARG;
+    const size_t need = rest_tree_attention_workspace_bytes(d);
+    if (need > (size_t)REST_STATIC_SCRATCH_BYTES) return REST_WORKSPACE_TOO_SMALL;
+    void* ws = nullptr;
+    if (need) {
+        const rest_status st = static_scratch(&ws);
+        if (st != REST_OK) return st;
+    }
+    // Every partial that the merge reads was written earlier in the same call, so nothing in the array has to start
+    // at zero and what the last call left there is never seen.
+    return enqueue_tree_attention(d_q, d_k, d_v, d_mask, d_out, d, ws, need, stream_);
 }
