@@ -44,9 +44,10 @@ def main() -> int:
                          "synthetic datastore and print the mean generated length per step")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device-to-device copy five times (reference for rocprofv3 --pmc byte counters)")
-    ap.add_argument("--attention-8bit-only", action="store_true",
-                    help="only run the tree attention on an 8-bit (E4M3) cache at the llama7b shape a few times "
-                         "(for rocprofv3 counter runs of that kernel)")
+    ap.add_argument("--attention-only", metavar="NbxHxTxP[:kv8][:gqaG][:layers]", default=None,
+                    help="only run rest_tree_attention at that shape 3 + 10 times (for rocprofv3 runs of one kernel): Nb batch "
+                         "entries x H K/V heads, T draft tokens, P cached keys; kv8 = 8-bit (E4M3) cache; gqaG = G query heads "
+                         "per K/V head stacked along the row axis; layers = one launch per batch entry")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -71,28 +72,8 @@ def main() -> int:
     if args.ablation:
         print(json.dumps({"ablation": ablation(rest, torch, synth, np, dev)}))
         return 0
-    if args.attention_8bit_only:
-        w = synth.WORKLOADS["llama7b"]
-        Nb, H, T, P = w.layers, w.heads, w.max_nodes, w.kv_len
-        g = torch.Generator(device=dev)
-        g.manual_seed(w.qkv_seed)
-        q = torch.randn((Nb, H, T, 128), generator=g, device=dev).to(torch.bfloat16)
-        k8, v8 = (torch.randn((Nb, H, P + T, 128), generator=g, device=dev).to(torch.float8_e4m3fn).view(torch.uint8)
-                  for _ in range(2))
-        sc = torch.full((Nb * H,), 1.0, dtype=torch.float32, device=dev)
-        mask = torch.from_numpy(synth.random_tree(T, 5)[3].view(np.int64)).to(dev)
-        out = torch.empty_like(q)
-        for _ in range(3):
-            rest.rest_tree_attention(q, k8, v8, mask, P, 1.0 / float(np.sqrt(128.0)), out=out, k_scale=sc, v_scale=sc)
-        torch.cuda.synchronize()
-        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        a.record()
-        for _ in range(10):
-            rest.rest_tree_attention(q, k8, v8, mask, P, 1.0 / float(np.sqrt(128.0)), out=out, k_scale=sc, v_scale=sc)
-        b.record()
-        torch.cuda.synchronize()
-        print(json.dumps({"attention_8bit_cache_us": round(a.elapsed_time(b) / 10 * 1e3, 1),
-                          "bytes_per_launch": Nb * H * (2 * (P + T) * 128 + 2 * T * 128 * 2)}))
+    if args.attention_only:
+        print(json.dumps(attention_only(rest, torch, synth, np, dev, args.attention_only)))
         return 0
     w = synth.WORKLOADS[args.workload]
     B = w.batch         # contexts per step: 1, or 32 for the batched workload (one layer, per-context masks)
@@ -182,20 +163,33 @@ def main() -> int:
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed * 1e3 / args.steps
-    attn_samples = sorted(a.elapsed_time(b) for a, b in events.values())
-    attn_ms = sum(attn_samples) / len(attn_samples)
+    in_step = sorted(a.elapsed_time(b) for a, b in events.values())
 
+    # The roofline figure comes from a loop of its own, so that it does not depend on --steps: 20 warm launches of
+    # the attention call of the step, then 100 timed ones between two HIP events on the launch stream.
     slabs = Nb * H
     alg_bytes = slabs * (2 * Lk * D * 2 + 2 * c * D * 2) + B * c * ((c + 63) // 64) * 8
-    achieved = alg_bytes / (attn_ms * 1e-3) / 1e9
+    n_roof = 100
 
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", "tree_attn_bf16_llama7b_traffic.json")
-    if args.workload == "llama7b" and os.path.exists(tpath):
-        try:
-            traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
-        except Exception:
-            traffic = None
+    def attn_once(i=0):
+        rest.rest_tree_attention(q, k, v, masks[i % n_ctx], P, scale, out=out, workspace=ws)
+
+    for i in range(20):
+        attn_once(i)
+    torch.cuda.synchronize()
+    batches = []
+    for rep in range(3):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(n_roof):
+            attn_once(i)
+        e1.record()
+        torch.cuda.synchronize()
+        batches.append(e0.elapsed_time(e1) / n_roof)
+    attn_ms = sorted(batches)[1]                # median of three batches of 100
+    achieved = alg_bytes / (attn_ms * 1e-3) / 1e9
+    kernel_name = attention_kernel_name(Nb * H, c, False)
+    traffic, traffic_from = profiled_traffic(args.workload)
 
     result = {
         "metric": {"llama7b": "draft-verify steps/s (retrieve+tree-attn+accept) at 7B shape",
@@ -210,18 +204,81 @@ def main() -> int:
                                + (f"{Nb} layers x {H} heads x {D}, KV length {P}+{c}, one launch over all layers" if B == 1 else
                                   f"{B} contexts x {H} heads x {D} (one layer, per-context masks), KV length {P}+{c}"),
                    "global_batch": B, "kv_len": P, "tree_nodes": c},
-        "roofline": {"bound": "hbm", "kernel": "tree_attn_bf16_kernel<2, false>", "achieved": round(achieved, 1),
+        "roofline": {"bound": "hbm", "kernel": kernel_name, "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": traffic, "algorithmic_bytes_per_launch": alg_bytes,
-                     "avg_launch_us": round(attn_ms * 1e3, 2), "launches_timed": len(attn_samples),
-                     "p10_p50_p90_us": [round(attn_samples[int(len(attn_samples) * f)] * 1e3, 1) for f in (0.1, 0.5, 0.9)]},
-        "extra": {"index_build_s": round(t_build, 3),
+                     "traffic": traffic, "traffic_from": traffic_from, "algorithmic_bytes_per_launch": alg_bytes,
+                     "avg_launch_us": round(attn_ms * 1e3, 2), "launches_timed": 3 * n_roof,
+                     "batches_of_100_us": [round(x * 1e3, 2) for x in batches]},
+        "extra": {"attn_inside_step_us_p10_p50_p90": [round(in_step[int(len(in_step) * f)] * 1e3, 1) for f in (0.1, 0.5, 0.9)]
+                  if in_step else None,
+                  "index_build_s": round(t_build, 3),
                   "index_build_depth32_s": None if t_build32 is None else round(t_build32, 3), "corpus_gen_s": round(t_gen, 2),
                   "contexts_per_s": round(B * 1e3 / ms_per_step, 1),
                   "tree_nodes_per_context": [int(x) for t in trees for x in t.n_nodes.tolist()][:32],
                   "matched_len_per_context": [int(x) for t in trees for x in t.matched_len.tolist()][:32]},
     }
 
+    if B == 1 and Nb > 1:
+        # The same step as a model has to take it: layer l + 1 needs layer l's output, so the attention of the 32 layers is
+        # 32 launches in a row, one layer of H heads each.  Timed as the whole step (retrieve, the launches, accept),
+        # and the launches alone both from the host and replayed as one HIP graph (no host time between them).
+        views = [(q[nb:nb + 1], k[nb:nb + 1], v[nb:nb + 1], out[nb:nb + 1]) for nb in range(Nb)]
+        d1 = rest.make_attn_desc(*views[0], P, scale, False)
+        ws1 = torch.empty(max(rest.rest_tree_attention_workspace_bytes(d1), 16), dtype=torch.uint8, device=dev)
+
+        def layers(mask):
+            for qq, kk, vv, oo in views:
+                rest.rest_tree_attention(qq, kk, vv, mask, P, scale, out=oo, workspace=ws1)
+
+        def step_layers(i):
+            j = i % n_ctx
+            rest.rest_retrieve(index, ctx_rows[j], len_rows[j], out=trees[j], **prm)
+            layers(masks[j])
+            rest.rest_accept(ids[j], trees[j], w.cont_len, alen, apath, nxt)
+
+        for i in range(5):
+            step_layers(i)
+        torch.cuda.synchronize()
+        n_lay = 50
+        t0 = time.perf_counter()
+        for i in range(n_lay):
+            step_layers(i)
+        torch.cuda.synchronize()
+        ms_step_layers = (time.perf_counter() - t0) * 1e3 / n_lay
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            layers(masks[0])
+            torch.cuda.synchronize()
+            with torch.cuda.graph(graph, stream=side):
+                layers(masks[0])
+        torch.cuda.synchronize()
+        lay = {}
+        for name, fn in (("host_launches", lambda: layers(masks[0])), ("hip_graph_replay", graph.replay)):
+            for _ in range(5):
+                fn()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(20):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            lay[name] = e0.elapsed_time(e1) / 20
+        del graph
+        per_launch_ms = min(lay.values()) / Nb
+        bytes_layer = H * (2 * Lk * D * 2 + 2 * c * D * 2) + c * ((c + 63) // 64) * 8
+        result["value_layer_by_layer"] = round(1e3 / ms_step_layers, 2)
+        result["roofline_layer_by_layer"] = {
+            "bound": "hbm", "kernel": attention_kernel_name(H, c, False), "launches_per_step": Nb,
+            "achieved": round(bytes_layer / (per_launch_ms * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": round(bytes_layer / (per_launch_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+            "algorithmic_bytes_per_launch": bytes_layer, "avg_launch_us": round(per_launch_ms * 1e3, 2),
+            "all_layers_us": {kk: round(vv * 1e3, 1) for kk, vv in lay.items()},
+            "note": "launch-to-launch period of back-to-back launches on one stream (start-up and the gap between "
+                    "kernels included); `value` and `roofline` above are the one-launch form of the same work"}
+        result["extra"]["ms_per_step_layer_by_layer"] = round(ms_step_layers, 5)
+        result["extra"]["attn_per_layer_launches_us_total"] = round(lay["host_launches"] * 1e3, 1)
     if not args.no_extras and B == 1:
         result["extra"].update(side_measurements(rest, torch, synth, corp, index, w, q, k, v, out, trees[0], P, scale, prm))
     if args.sweep:
@@ -232,6 +289,83 @@ def main() -> int:
             np, torch, corp, ctx_np, w, q, k, v, out, trees, ids, P, scale, step, B)
     print(json.dumps(result))
     return 0
+
+
+def attention_only(rest, torch, synth, np, dev, spec):
+    """rest_tree_attention alone at one shape: 3 warm launches, then 10 between two HIP events."""
+    parts = spec.split(":")
+    Nb, H, T, P = (int(x) for x in parts[0].split("x"))
+    kv8 = "kv8" in parts[1:]
+    by_layer = "layers" in parts[1:]
+    g_heads = max([int(x[3:]) for x in parts[1:] if x.startswith("gqa")] + [1])
+    Tq = T * g_heads
+    g = torch.Generator(device=dev)
+    g.manual_seed(T * 100000 + P + g_heads)
+    q = torch.randn((Nb, H, Tq, 128), generator=g, device=dev).to(torch.bfloat16)
+    k, v = (torch.randn((Nb, H, P + T, 128), generator=g, device=dev) for _ in range(2))
+    sc = None
+    if kv8:
+        k, v = (x.to(torch.float8_e4m3fn).view(torch.uint8) for x in (k, v))
+        sc = torch.full((Nb * H,), 1.0, dtype=torch.float32, device=dev)
+    else:
+        k, v = (x.to(torch.bfloat16) for x in (k, v))
+    mask = torch.from_numpy(synth.random_tree(T, 14 + T)[3].view(np.int64)).to(dev)
+    out = torch.empty_like(q)
+    scale = 1.0 / float(np.sqrt(128.0))
+    mr = T if g_heads > 1 else 0
+    if by_layer:
+        views = [(q[i:i + 1], k[i:i + 1], v[i:i + 1], out[i:i + 1], None if sc is None else sc[i * H:(i + 1) * H]) for i in range(Nb)]
+    else:
+        views = [(q, k, v, out, sc)]
+    desc = rest.make_attn_desc(*views[0][:4], P, scale, False, 0, mr, views[0][4], views[0][4])
+    ws = torch.empty(max(rest.rest_tree_attention_workspace_bytes(desc), 16), dtype=torch.uint8, device=dev)
+
+    def run():
+        for qq, kk, vv, oo, ss in views:
+            rest.rest_tree_attention(qq, kk, vv, mask, P, scale, out=oo, workspace=ws, mask_rows=mr, k_scale=ss, v_scale=ss)
+
+    for _ in range(3):
+        run()
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(10):
+        run()
+    b.record()
+    torch.cuda.synchronize()
+    us = a.elapsed_time(b) / 10 * 1e3
+    alg = Nb * H * (2 * (P + T) * 128 * (1 if kv8 else 2) + 2 * Tq * 128 * 2) + T * ((T + 63) // 64) * 8
+    flops = Nb * H * 4.0 * Tq * (P + T) * 128
+    return {"attention_only": spec, "kernel": attention_kernel_name((H if by_layer else Nb * H) * ((Tq + 255) // 256), min(Tq, 256), kv8),
+            "launches_per_run": len(views), "us_per_run": round(us, 1), "algorithmic_bytes_per_run": alg,
+            "GB/s": round(alg / us / 1e3, 1), "frac_of_8TB/s": round(alg / us / 1e3 / HBM_PEAK_GBS, 3),
+            "TFLOP/s": round(flops / us / 1e6, 1)}
+
+
+def attention_kernel_name(units, Tq, kv8):
+    """The kernel rest_tree_attention launches for `units` (batch, head) slabs of Tq <= 256 query rows (the
+    library's plan: streams of 2, 4 or 8 wavefronts by the number of query rows; few units of at most 64 rows
+    take the split plan)."""
+    kv = "true" if kv8 else "false"
+    if Tq <= 64 and units <= 128:
+        return f"tree_attn_split_kernel<{kv}>"
+    return f"tree_attn_bf16_kernel<{2 if Tq <= 64 else 4 if Tq <= 128 else 8}, {kv}>"
+
+
+def profiled_traffic(workload):
+    """HBM bytes per attention launch of this workload as counted by rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE) and
+    kept under profiles/: a figure from a file, not from this run.  It is reported only while the kernel source it
+    was counted on is the one being benchmarked (the file records the source's SHA-256)."""
+    import hashlib
+    path = os.path.join(ROOT, "profiles", f"tree_attn_bf16_{workload}_traffic.json")
+    src = os.path.join(ROOT, "paper_2311_08252_amd", "csrc", "attention.hip")
+    try:
+        rec = json.load(open(path))
+        if rec.get("attention_hip_sha256") != hashlib.sha256(open(src, "rb").read()).hexdigest():
+            return None, f"profiles/{os.path.basename(path)} is for an older kernel source: not reported"
+        return rec.get("hbm_bytes_per_launch"), f"profiles/{os.path.basename(path)} (rocprofv3 --pmc, counted {rec.get('captured', '?')})"
+    except Exception:
+        return None, None
 
 
 def side_measurements(rest, torch, synth, corp, index, w, q, k, v, out, tree, P, scale, prm):
@@ -297,15 +431,6 @@ def side_measurements(rest, torch, synth, corp, index, w, q, k, v, out, tree, P,
     Nb = q.shape[0]
     mask = tree.tree_mask[0]
 
-    def per_layer():
-        for nb in range(Nb):
-            rest.rest_tree_attention(q[nb:nb + 1], k[nb:nb + 1], v[nb:nb + 1], mask, P, scale, out=out[nb:nb + 1],
-                                     workspace=ws_layer)
-
-    d1 = rest.make_attn_desc(q[:1], k[:1], v[:1], out[:1], P, scale, False)
-    ws_layer = torch.empty(max(rest.rest_tree_attention_workspace_bytes(d1), 16), dtype=torch.uint8, device=dev)
-    ms = timed(per_layer, 10)
-    res["attn_per_layer_launches_us_total"] = round(ms * 1e3, 1)
     ms = timed(lambda: rest.rest_tree_attention(q, k, v, mask, P, scale, out=out), 20)
     res["attn_single_launch_us"] = round(ms * 1e3, 1)
 

@@ -260,7 +260,8 @@ typedef struct {
     const float* d_v_scale;
 } rest_attn_desc;
 
-/* Bytes of device workspace (partial results of the KV splits). */
+/* Bytes of device workspace (partial results of the KV splits, 16-byte aligned; it needs no initialisation and its
+ * contents after a call mean nothing to the caller). */
 size_t rest_tree_attention_workspace_bytes(const rest_attn_desc* desc);
 
 rest_status rest_tree_attention(const void* d_q, const void* d_k, const void* d_v, const uint64_t* d_mask,

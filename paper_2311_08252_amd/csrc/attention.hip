@@ -70,6 +70,11 @@ struct AttnParams {
     int32_t extra_units;
     float c;          // scale * log2(e)
     int64_t qs[3], ks[3], vs[3], os[3];
+    // split plan (few units): every unit is shared by split_s workgroups of four key groups each
+    int32_t split_s;               // workgroups per unit
+    int32_t split_rounds;          // most blocks any key group gets: ceil(nblk / (4 split_s))
+    __bf16* ws_po;                 // [units][split_s][64][128] normalised partial outputs
+    unsigned long long* tickets;   // [units] arrival counters
 };
 
 __device__ inline float wave_xor32(float x) { return __shfl_xor(x, 32, 64); }
@@ -79,6 +84,110 @@ __host__ __device__ inline int64_t span_begin(int64_t total, int32_t n, int64_t 
 // the stream whose span contains block b
 __host__ __device__ inline int32_t span_owner(int64_t total, int32_t n, int64_t b) {
     return (int32_t)(((b + 1) * n - 1) / total);
+}
+
+// One block of 32 keys for the 32 queries of a wavefront: S^T = K Q^T, the tree mask for keys past the prefix,
+// softmax numerators against the lazily updated reference, O^T += V^T P^T.  ldsK / ldsV: the block's K and V rows in
+// LDS (256-byte rows, swizzled as the parking stores leave them); ka0, va0, vsw: the lane's operand read offsets;
+// qf: the query fragments; o, m_ref (log2 units), l_run: the running output, reference and sum of this lane's query
+// column; key0: index of the block's first key; mw: the four mask words of this lane's query row (in LDS).
+template <bool kPairSwap>
+__device__ __forceinline__ void attn_block(const unsigned char* ldsK, const unsigned char* ldsV, const uint32_t ka0,
+                                           const uint32_t va0, const uint32_t vsw, const int hh, const bf16x8 (&qf)[8],
+                                           f32x16 (&o)[4], float& m_ref, float& l_run, const float cu, const int key0,
+                                           const int P, const int Tk, const uint64_t* mw) {
+    // ---- S^T[key][query] = K Q^T
+    f32x16 s;
+#pragma unroll
+    for (int r = 0; r < 16; r++) s[r] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < 8; ks++) {
+        const bf16x8 a = *(const bf16x8*)(ldsK + (ka0 ^ (ks << 5) ^ (kPairSwap ? (ks >> 2) << 4 : 0)));
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], s, 0, 0, 0);
+    }
+    // keep two K fragments in flight: read, read, then (multiply, read) ..., so that an LDS read's latency
+    // hides behind the previous matrix instruction
+    __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+#pragma unroll
+    for (int ks = 0; ks < 6; ks++) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+
+    // ---- visibility (only blocks that reach past the prefix): one 32-bit word per lane says which of
+    // the block's 32 keys its query sees; bit i <-> key j*32 + i
+    if (key0 + kBlk > P) {
+        const int kb = key0 - P;              // draft-token index of the block's first key (may be < 0)
+        const int end = Tk - kb;              // keys at block offset >= end are past the last key
+        const uint32_t in_range = end >= 32 ? 0xffffffffu : (end > 0 ? (1u << end) - 1u : 0u);
+        uint32_t vbits;
+        if (kb < 0) {
+            vbits = ((1u << (-kb)) - 1u) | ((uint32_t)mw[0] << (-kb));
+        } else {
+            const int w = kb >> 6, sh = kb & 63;
+            const uint64_t lo = mw[w];
+            const uint64_t hi = (w + 1 < 4) ? mw[w + 1] : 0ull;
+            vbits = (uint32_t)(lo >> sh);
+            if (sh > 32) vbits |= (uint32_t)(hi << (64 - sh));
+        }
+        vbits &= in_range;
+        vbits >>= 4 * hh;
+#pragma unroll
+        for (int r = 0; r < 16; r++) {
+            const bool vis = (vbits >> (8 * (r >> 2) + (r & 3))) & 1u;
+            s[r] = vis ? s[r] : -INFINITY;
+        }
+    }
+
+    // ---- softmax numerators against a lazily updated reference, per lane = per query column
+    bf16x8 pf[2];
+    {
+        float mx = s[0];
+#pragma unroll
+        for (int r = 1; r < 16; r++) mx = fmaxf(mx, s[r]);
+        mx = fmaxf(mx, wave_xor32(mx)) * cu;
+        if (__any(mx > m_ref + kLazy)) {
+            const float m_new = fmaxf(m_ref, mx);
+            const float alpha = __builtin_amdgcn_exp2f(m_ref - m_new);
+            m_ref = m_new;
+            l_run *= alpha;
+#pragma unroll
+            for (int dt = 0; dt < 4; dt++)
+#pragma unroll
+                for (int r = 0; r < 16; r++) o[dt][r] *= alpha;
+        }
+        float sum = 0.f;
+#pragma unroll
+        for (int r = 0; r < 16; r++) {
+            const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], cu, -m_ref));
+            sum += e;
+            pf[r >> 3][r & 7] = (__bf16)e;
+        }
+        l_run += sum;
+    }
+
+    // ---- O^T[d][query] += V^T P^T
+#pragma unroll
+    for (int ss = 0; ss < 2; ss++) {
+#pragma unroll
+        for (int dt = 0; dt < 4; dt++) {
+            const unsigned char* a0 = ldsV + ((va0 + ss * 4096 + ((((uint32_t)dt << 2) ^ vsw) << 4)) ^ (kPairSwap ? (dt >> 1) << 4 : 0));
+            s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)a0);
+            s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(a0 + 8 * 256));
+            union { struct { s16x4 lo, hi; } sp; bf16x8 v; } u;
+            u.sp.lo = lo;
+            u.sp.hi = hi;
+            o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(u.v, pf[ss], o[dt], 0, 0, 0);
+        }
+    }
+    __builtin_amdgcn_sched_group_barrier(0x100, 4, 1);
+#pragma unroll
+    for (int i = 0; i < 6; i++) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 1);
+        __builtin_amdgcn_sched_group_barrier(0x100, 2, 1);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, 2, 1);
 }
 
 // One stream = one workgroup of NW wavefronts (2, 4 or 8) for a unit of 32 NW queries: wavefront w owns queries
@@ -344,99 +453,7 @@ __global__ __launch_bounds__(64 * NW, 2) void tree_attn_bf16_kernel(AttnParams p
             const unsigned char* ldsK = tile + sb * kSubBytes;
             const unsigned char* ldsV = tile + kTileBytes + sb * kSubBytes;
 
-            // ---- S^T[key][query] = K Q^T
-            f32x16 s;
-#pragma unroll
-            for (int r = 0; r < 16; r++) s[r] = 0.f;
-#pragma unroll
-            for (int ks = 0; ks < 8; ks++) {
-                const bf16x8 a = *(const bf16x8*)(ldsK + (ka0 ^ (ks << 5) ^ (kPairSwap ? (ks >> 2) << 4 : 0)));
-                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], s, 0, 0, 0);
-            }
-            // keep two K fragments in flight: read, read, then (multiply, read) ..., so that an LDS read's latency
-            // hides behind the previous matrix instruction
-            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-#pragma unroll
-            for (int ks = 0; ks < 6; ks++) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-            }
-            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
-
-            // ---- visibility (only blocks that reach past the prefix): one 32-bit word per lane says which of
-            // the block's 32 keys its query sees; bit i <-> key j*32 + i
-            if (key0 + kBlk > p.P) {
-                const int kb = key0 - p.P;              // draft-token index of the block's first key (may be < 0)
-                const int end = p.Tk - kb;              // keys at block offset >= end are past the last key
-                const uint32_t in_range = end >= 32 ? 0xffffffffu : (end > 0 ? (1u << end) - 1u : 0u);
-                const uint64_t* mw = &my_mask[col * 4];
-                uint32_t vbits;
-                if (kb < 0) {
-                    vbits = ((1u << (-kb)) - 1u) | ((uint32_t)mw[0] << (-kb));
-                } else {
-                    const int w = kb >> 6, sh = kb & 63;
-                    const uint64_t lo = mw[w];
-                    const uint64_t hi = (w + 1 < 4) ? mw[w + 1] : 0ull;
-                    vbits = (uint32_t)(lo >> sh);
-                    if (sh > 32) vbits |= (uint32_t)(hi << (64 - sh));
-                }
-                vbits &= in_range;
-                vbits >>= 4 * hh;
-#pragma unroll
-                for (int r = 0; r < 16; r++) {
-                    const bool vis = (vbits >> (8 * (r >> 2) + (r & 3))) & 1u;
-                    s[r] = vis ? s[r] : -INFINITY;
-                }
-            }
-
-            // ---- softmax numerators against a lazily updated reference, per lane = per query column
-            bf16x8 pf[2];
-            {
-                float mx = s[0];
-#pragma unroll
-                for (int r = 1; r < 16; r++) mx = fmaxf(mx, s[r]);
-                mx = fmaxf(mx, wave_xor32(mx)) * cu;
-                if (__any(mx > m_ref + kLazy)) {
-                    const float m_new = fmaxf(m_ref, mx);
-                    const float alpha = __builtin_amdgcn_exp2f(m_ref - m_new);
-                    m_ref = m_new;
-                    l_run *= alpha;
-#pragma unroll
-                    for (int dt = 0; dt < 4; dt++)
-#pragma unroll
-                        for (int r = 0; r < 16; r++) o[dt][r] *= alpha;
-                }
-                float sum = 0.f;
-#pragma unroll
-                for (int r = 0; r < 16; r++) {
-                    const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], cu, -m_ref));
-                    sum += e;
-                    pf[r >> 3][r & 7] = (__bf16)e;
-                }
-                l_run += sum;
-            }
-
-            // ---- O^T[d][query] += V^T P^T
-#pragma unroll
-            for (int ss = 0; ss < 2; ss++) {
-#pragma unroll
-                for (int dt = 0; dt < 4; dt++) {
-                    const unsigned char* a0 = ldsV + ((va0 + ss * 4096 + ((((uint32_t)dt << 2) ^ vsw) << 4)) ^ (kPairSwap ? (dt >> 1) << 4 : 0));
-                    s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)a0);
-                    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(a0 + 8 * 256));
-                    union { struct { s16x4 lo, hi; } sp; bf16x8 v; } u;
-                    u.sp.lo = lo;
-                    u.sp.hi = hi;
-                    o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(u.v, pf[ss], o[dt], 0, 0, 0);
-                }
-            }
-            __builtin_amdgcn_sched_group_barrier(0x100, 4, 1);
-#pragma unroll
-            for (int i = 0; i < 6; i++) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 1);
-                __builtin_amdgcn_sched_group_barrier(0x100, 2, 1);
-            }
-            __builtin_amdgcn_sched_group_barrier(0x008, 2, 1);
+            attn_block<kPairSwap>(ldsK, ldsV, ka0, va0, vsw, hh, qf, o, m_ref, l_run, cu, key0, p.P, p.Tk, &my_mask[col * 4]);
             }   // blocks of the tile
         }
 
@@ -479,6 +496,308 @@ __global__ __launch_bounds__(64 * NW, 2) void tree_attn_bf16_kernel(AttnParams p
     }
 #undef REST_SEGMENT_FIRST
 #undef REST_SEGMENT_NEXT
+}
+
+// Arrival of one workgroup at a unit's ticket; true for the one that completes the unit (the `need`-th arrival).
+// The ticket word is (kTicketMagic << 8) | arrivals; the completing workgroup puts it back to "no arrivals" when it is
+// done, so in the steady state an arrival is one fetch-and-add, a single trip to the memory side.  A word that
+// does not carry the magic number -- the caller's workspace as it was allocated -- counts as "no arrivals yet" and
+// is put right by compare-and-swap (an add that met such a word is thrown away with it), so the workspace needs no
+// initialisation: a wrong start would take uninitialised memory that holds exactly these 56 bits.  No workgroup waits
+// for another: every loop here ends as soon as no other arrival has changed the word in between.
+constexpr unsigned long long kTicketMagic = 0x52455354747265ull;       // 56 bits
+__device__ inline bool ticket_arrive(unsigned long long* t, int need) {
+    unsigned long long old = __hip_atomic_fetch_add(t, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if ((old >> 8) == kTicketMagic) return (int)(old & 0xffull) + 1 == need;
+    old = __hip_atomic_load(t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    unsigned long long want;
+    do {
+        want = (old >> 8) == kTicketMagic ? old + 1 : ((kTicketMagic << 8) | 1ull);
+    } while (!__hip_atomic_compare_exchange_strong(t, &old, want, __ATOMIC_RELAXED, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+    return (int)(want & 0xffull) == need;
+}
+
+// Split plan, for launches with so few units that whole units or long spans per stream would leave most of the chip
+// idle (one layer of a single context: 32 heads).  A workgroup is eight wavefronts = four key groups x two query
+// halves; split_s workgroups share a unit, so its key blocks are cut into 4 split_s contiguous runs, one per key
+// group.  A key group is a two-wavefront stream as in the kernel above (own pair of LDS tiles, same fetch, same
+// arithmetic).  The four partial results of a workgroup are combined through LDS (the tiles' space, free by then) into
+// one partial per workgroup: the output normalised by its own sum, in bf16 (one more rounding of the size the final
+// output has anyway), plus reference and sum in fp32.  The workgroup that arrives last at the unit's ticket combines
+// the split_s partials, always in the order 0 .. split_s-1, so the result does not depend on who that is.
+// Workgroup w works on unit w % units: workgroups are dealt to the eight XCDs in turn, so when the number of units is a
+// multiple of eight all workgroups of a unit sit on one XCD and its queries and partials stay in that XCD's L2.
+template <bool KV8>
+__global__ __launch_bounds__(512, 1) void tree_attn_split_kernel(AttnParams p) {
+    constexpr int G = 4;                               // key groups per workgroup
+    constexpr int kElt = KV8 ? 1 : 2;
+    constexpr int kFetch = KV8 ? 2 : 4;
+    constexpr int kChunkRows = KV8 ? 8 : 4;
+    constexpr int kTileBytes = kSubBytes;              // a tile is one block of 32 keys
+    // [group][buffer][K | V]; afterwards the groups' fp32 outputs [group][64 queries][128]
+    __shared__ __attribute__((aligned(1024))) unsigned char lds_tile[G * 2 * 2 * kTileBytes];
+    __shared__ uint64_t lds_mask[2 * G * 32 * 4];
+    __shared__ float lds_ml[G * 64 * 2];
+    __shared__ int lds_last;
+    static_assert(G * 2 * 2 * kTileBytes == G * 64 * kD * 4, "the outputs of the key groups reuse the tiles' space exactly");
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int g = wave >> 1, qw = wave & 1;            // key group; which 32 of the 64 queries
+    const int hh = lane >> 5, col = lane & 31, lrow = lane >> 4, lpc = lane & 15;
+    const int unit = blockIdx.x % p.units, part = blockIdx.x / p.units;
+    const int h = unit % p.H, nb = unit / p.H;
+    // this key group's blocks [b0, b1) of the unit's nblk
+    const int ngroups = G * p.split_s, gi = part * G + g;
+    const int b0 = (p.nblk * gi) / ngroups, b1 = (p.nblk * (gi + 1)) / ngroups;
+    const int my_rounds = b1 - b0;
+
+    const int64_t k_row_bytes = p.ks[2] * kElt, v_row_bytes = p.vs[2] * kElt;
+    const char* kp = (const char*)p.k + (nb * p.ks[0] + h * p.ks[1]) * kElt;
+    const char* vp = (const char*)p.v + (nb * p.vs[0] + h * p.vs[1]) * kElt;
+    uint32_t k_off[4];
+#pragma unroll
+    for (int x = 0; x < 4; x++)
+        k_off[x] = KV8 ? (uint32_t)((lane >> 3) * k_row_bytes) + ((lane & 7) << 4)
+                       : (uint32_t)(lrow * k_row_bytes) + ((lpc ^ (x * 4 + lrow)) << 4);
+    const uint32_t v_off = KV8 ? (uint32_t)((lane >> 3) * v_row_bytes) + ((lane & 7) << 4)
+                               : (uint32_t)(lrow * v_row_bytes) + ((lpc ^ (lrow << 2)) << 4);
+
+    // the fetch and the parking stores of the kernel above, for tiles of one block and two wavefronts
+    i32x4 kr[kFetch], vr[kFetch];
+    auto issue = [&](int j) {
+        if ((j + 1) * kBlk <= p.Lk) {
+#pragma unroll
+            for (int i = 0; i < kFetch; i++) {
+                const int64_t row = (int64_t)j * kBlk + (kFetch * qw + i) * kChunkRows;
+                kr[i] = __builtin_nontemporal_load((const i32x4*)(kp + row * k_row_bytes + k_off[i]));
+                vr[i] = __builtin_nontemporal_load((const i32x4*)(vp + row * v_row_bytes + v_off));
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < kFetch; i++) {
+                int64_t row = (int64_t)j * kBlk + (kFetch * qw + i) * kChunkRows + (KV8 ? lane >> 3 : lrow);
+                row = row < p.Lk ? row : p.Lk - 1;
+                const int sw_k = KV8 ? (lane & 7) << 4 : (lpc ^ (i * 4 + lrow)) << 4;
+                const int sw_v = KV8 ? (lane & 7) << 4 : (lpc ^ (lrow << 2)) << 4;
+                kr[i] = __builtin_nontemporal_load((const i32x4*)(kp + row * k_row_bytes + sw_k));
+                vr[i] = __builtin_nontemporal_load((const i32x4*)(vp + row * v_row_bytes + sw_v));
+            }
+        }
+    };
+    auto widen = [](int lo, int hi) -> i32x4 {
+        typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+        union { bf16x2 h[4]; i32x4 v; } u;
+        u.h[0] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(lo, 1.0f, false);
+        u.h[1] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(lo, 1.0f, true);
+        u.h[2] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(hi, 1.0f, false);
+        u.h[3] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(hi, 1.0f, true);
+        return u.v;
+    };
+    auto park = [&](unsigned char* tile) {
+        if constexpr (KV8) {
+#pragma unroll
+            for (int i = 0; i < 2; i++) {
+                const int row = (2 * qw + i) * 8 + (lane >> 3), pc = (2 * (lane & 7)) ^ ((lane & 7) >> 2);
+                unsigned char* krow = tile + row * 256;
+                unsigned char* vrow = tile + kTileBytes + row * 256;
+                const int swk = row & 15, swv = (row & 3) << 2;
+                *(i32x4*)(krow + ((pc ^ swk) << 4)) = widen(kr[i][0], kr[i][1]);
+                *(i32x4*)(krow + (((pc ^ 1) ^ swk) << 4)) = widen(kr[i][2], kr[i][3]);
+                *(i32x4*)(vrow + ((pc ^ swv) << 4)) = widen(vr[i][0], vr[i][1]);
+                *(i32x4*)(vrow + (((pc ^ 1) ^ swv) << 4)) = widen(vr[i][2], vr[i][3]);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; i++) {
+                *(i32x4*)(tile + (4 * qw + i) * 1024 + lane * 16) = kr[i];
+                *(i32x4*)(tile + kTileBytes + (4 * qw + i) * 1024 + lane * 16) = vr[i];
+            }
+        }
+    };
+
+    if (my_rounds > 0) issue(b0);
+
+    const int qi = qw * 32 + col;                       // this lane's query row
+    const float cu = KV8 && p.k_scale ? p.c * p.k_scale[unit] : p.c;
+    uint64_t* const my_mask = lds_mask + wave * (32 * 4);
+    {
+        const uint64_t* mrow = p.mask + (p.mask_per_batch ? (int64_t)nb * p.mask_rows * p.mask_words : 0);
+#pragma unroll
+        for (int w = 0; w < 2; w++) {
+            const int ww = 2 * hh + w;
+            my_mask[col * 4 + ww] = (qi < p.Tq && ww < p.mask_words) ? mrow[(int64_t)(qi % p.mask_rows) * p.mask_words + ww] : 0ull;
+        }
+    }
+    bf16x8 qf[8];
+    {
+        const __bf16* qp = p.q + nb * p.qs[0] + h * p.qs[1];
+#pragma unroll
+        for (int ks = 0; ks < 8; ks++) {
+            bf16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
+            if (qi < p.Tq) z = *(const bf16x8*)(qp + qi * p.qs[2] + 16 * ks + 8 * hh);
+            qf[ks] = z;
+        }
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);                 // vmcnt(0): queries, mask words and the first tile are here
+
+    const uint32_t ka0 = col * 256 + ((hh ^ (col & 15)) << 4);
+    const int vq = (lane & 15) >> 2;
+    const uint32_t va0 = (4 * hh + vq) * 256 + ((2 * ((lane >> 4) & 1) + ((lane & 3) >> 1)) << 4) + (lane & 1) * 8;
+    const uint32_t vsw = (uint32_t)vq << 2;
+
+    f32x16 o[4];
+    float m_ref = kNegBig, l_run = 0.f;
+#pragma unroll
+    for (int dt = 0; dt < 4; dt++)
+#pragma unroll
+        for (int r = 0; r < 16; r++) o[dt][r] = 0.f;
+
+    // Every wavefront passes the same number of barriers: a key group with fewer blocks than split_rounds sits the
+    // last rounds out.  Tile `buf` of a group was last read two rounds ago, which both of its wavefronts had finished
+    // before the previous barrier.
+    for (int r = 0; r < p.split_rounds; r++) {
+        unsigned char* tile = lds_tile + (g * 2 + (r & 1)) * (2 * kTileBytes);
+        if (r < my_rounds) {
+            park(tile);
+            if (r + 1 < my_rounds) issue(b0 + r + 1);
+        }
+        __syncthreads();
+        if (r < my_rounds)
+            attn_block<KV8>(tile, tile + kTileBytes, ka0, va0, vsw, hh, qf, o, m_ref, l_run, cu, (b0 + r) * kBlk, p.P, p.Tk,
+                            &my_mask[col * 4]);
+    }
+    l_run += wave_xor32(l_run);                         // the two key halves of the wavefront hold disjoint keys
+
+    // ---- the four key groups' results -> LDS.  Row q of group g: 32 pieces of four floats, piece c at slot c ^ (q & 31)
+    __syncthreads();                                    // all tiles have been read
+    float* const lds_o = (float*)lds_tile;
+    {
+        float* row = lds_o + (g * 64 + qi) * kD;
+#pragma unroll
+        for (int dt = 0; dt < 4; dt++)
+#pragma unroll
+            for (int gq = 0; gq < 4; gq++) {
+                f32x4 w;
+#pragma unroll
+                for (int e = 0; e < 4; e++) w[e] = o[dt][4 * gq + e];
+                const int piece = dt * 8 + 2 * gq + hh;
+                *(f32x4*)(row + ((piece ^ (qi & 31)) << 2)) = w;
+            }
+        if (hh == 0) {
+            lds_ml[(g * 64 + qi) * 2 + 0] = m_ref;
+            lds_ml[(g * 64 + qi) * 2 + 1] = l_run;
+        }
+    }
+    __syncthreads();
+
+    // ---- thread t: query t / 8, pieces 4 (t % 8) .. +3 (sixteen output columns)
+    const int q = tid >> 3, pc0 = (tid & 7) * 4;
+    float acc[16];
+    float m_all = kNegBig, l_all = 0.f;
+    {
+#pragma unroll
+        for (int gg = 0; gg < G; gg++) m_all = fmaxf(m_all, lds_ml[(gg * 64 + q) * 2]);
+#pragma unroll
+        for (int i = 0; i < 16; i++) acc[i] = 0.f;
+#pragma unroll
+        for (int gg = 0; gg < G; gg++) {
+            const float w = __builtin_amdgcn_exp2f(lds_ml[(gg * 64 + q) * 2] - m_all);
+            l_all += w * lds_ml[(gg * 64 + q) * 2 + 1];
+            const float* row = lds_o + (gg * 64 + q) * kD;
+#pragma unroll
+            for (int i = 0; i < 4; i++) {
+                const f32x4 x = *(const f32x4*)(row + (((pc0 + i) ^ (q & 31)) << 2));
+#pragma unroll
+                for (int e = 0; e < 4; e++) acc[4 * i + e] += w * x[e];
+            }
+        }
+    }
+    // Partial of this workgroup: output normalised by its own sum (bf16), reference and sum (fp32).  The partials cross
+    // from one XCD to another, whose L2 caches do not see each other's plain stores until a write-back of the whole
+    // cache (what a release fence at device scope costs here: tens of microseconds when every wavefront pays it).
+    // Instead every partial is written and read with device-scope atomic accesses (relaxed, 64 bits at a time), which
+    // go through to the memory side, and the order "partials before arrival" is kept by hand: each wavefront waits
+    // until all its stores are acknowledged, the workgroup meets at a barrier, and only then thread 0 counts the
+    // arrival.  The completing workgroup issues its reads after its arrival has returned.
+    typedef unsigned long long u64;
+    {
+        const float inv = l_all > 0.f ? 1.0f / l_all : 0.f;
+        const int64_t prow = ((int64_t)unit * p.split_s + part) * 64 + q;
+        union { bf16x8 h[2]; u64 w[4]; } pk;
+#pragma unroll
+        for (int e = 0; e < 8; e++) {
+            pk.h[0][e] = (__bf16)(acc[e] * inv);
+            pk.h[1][e] = (__bf16)(acc[8 + e] * inv);
+        }
+        u64* po = (u64*)(p.ws_po + prow * kD + pc0 * 4);
+#pragma unroll
+        for (int i = 0; i < 4; i++) __hip_atomic_store(po + i, pk.w[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if ((tid & 7) == 0) {
+            union { float f[2]; u64 w; } ml;
+            ml.f[0] = m_all;
+            ml.f[1] = l_all;
+            __hip_atomic_store((u64*)(p.ws_ml + prow * 2), ml.w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);                 // vmcnt(0): this wavefront's partial stores are acknowledged
+    __syncthreads();
+    if (tid == 0) lds_last = ticket_arrive(p.tickets + unit, p.split_s) ? 1 : 0;
+    __syncthreads();
+    if (!lds_last) return;
+
+    // ---- the last workgroup of the unit: partials 0 .. split_s-1 in that order, eight at a time with all their reads
+    // in flight together (one trip to the memory side per batch)
+    float m_fin = kNegBig, l_fin = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; i++) acc[i] = 0.f;
+    const int64_t prow0 = (int64_t)unit * p.split_s * 64 + q;
+    for (int s0 = 0; s0 < p.split_s; s0 += 8) {
+        union { float f[2]; u64 w; } ml[8];
+        union { bf16x8 h[2]; u64 w[4]; } pk[8];
+#pragma unroll
+        for (int i = 0; i < 8; i++) {
+            const int sidx = s0 + i < p.split_s ? s0 + i : p.split_s - 1;        // past the end: the last one again, unused
+            const int64_t prow = prow0 + sidx * 64;
+            ml[i].w = __hip_atomic_load((const u64*)(p.ws_ml + prow * 2), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const u64* po = (const u64*)(p.ws_po + prow * kD + pc0 * 4);
+#pragma unroll
+            for (int j = 0; j < 4; j++) pk[i].w[j] = __hip_atomic_load(po + j, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        float m_new = m_fin;
+#pragma unroll
+        for (int i = 0; i < 8; i++)
+            if (s0 + i < p.split_s) m_new = fmaxf(m_new, ml[i].f[0]);
+        const float resc = __builtin_amdgcn_exp2f(m_fin - m_new);
+        m_fin = m_new;
+        l_fin *= resc;
+#pragma unroll
+        for (int e = 0; e < 16; e++) acc[e] *= resc;
+#pragma unroll
+        for (int i = 0; i < 8; i++) {
+            const float w = s0 + i < p.split_s ? __builtin_amdgcn_exp2f(ml[i].f[0] - m_fin) * ml[i].f[1] : 0.f;
+            l_fin += w;
+#pragma unroll
+            for (int e = 0; e < 8; e++) {
+                acc[e] += w * (float)pk[i].h[0][e];
+                acc[8 + e] += w * (float)pk[i].h[1][e];
+            }
+        }
+    }
+    if (q < p.Tq) {
+        const float vu = KV8 && p.v_scale ? p.v_scale[unit] : 1.0f;
+        const float inv = l_fin > 0.f ? vu / l_fin : 0.f;
+        bf16x8 w0, w1;
+#pragma unroll
+        for (int e = 0; e < 8; e++) {
+            w0[e] = (__bf16)(acc[e] * inv);
+            w1[e] = (__bf16)(acc[8 + e] * inv);
+        }
+        __bf16* op = p.out + nb * p.os[0] + h * p.os[1] + q * p.os[2] + pc0 * 4;
+        *(bf16x8*)op = w0;
+        *(bf16x8*)(op + 8) = w1;
+    }
+    if (tid == 0) __hip_atomic_store(p.tickets + unit, kTicketMagic << 8, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // Merges the partials of every tail unit that was cut between streams.  A 256-thread block takes `rows` query rows
@@ -622,7 +941,12 @@ struct Plan {
     int qt, qgroups, nblk, units, n_streams, nsplit_f32;
     int dp_rounds, tail_units, tail_streams, extra_units, merge_rows;
     bool need_merge;
+    int split_s;      // > 0: the split plan with that many workgroups per unit (then nothing above but nblk, units counts)
 };
+
+constexpr int kSplitGroups = 4;       // key groups of a split-plan workgroup
+constexpr int kSplitMaxUnits = 128;   // the split plan is for launches with at most this many units
+constexpr int kSplitMaxParts = 16;    // workgroups per unit, at most
 
 Plan make_plan(const rest_attn_desc* d) {
     Plan pl{};
@@ -637,6 +961,18 @@ Plan make_plan(const rest_attn_desc* d) {
     pl.qgroups = (d->Tq + 32 * pl.qt - 1) / (32 * pl.qt);
     pl.nblk = (Lk + 16 * pl.qt - 1) / (16 * pl.qt);
     pl.units = d->Nb * d->H * pl.qgroups;
+    // Few units of at most 64 queries (one layer of a single context): the split plan.  One workgroup of four key
+    // groups per compute unit, i.e. 256 / units workgroups per unit, every key group with at least one block.
+    if (d->num_splits == 0 && pl.qt == 2 && pl.units <= kSplitMaxUnits && d->o_stride[0] % 8 == 0 && d->o_stride[1] % 8 == 0 &&
+        d->o_stride[2] % 8 == 0) {
+        int s = 256 / pl.units;
+        if (s > kSplitMaxParts) s = kSplitMaxParts;
+        if (s > pl.nblk / kSplitGroups) s = pl.nblk / kSplitGroups;
+        if (s >= 2) {
+            pl.split_s = s;
+            return pl;
+        }
+    }
     const int64_t total = (int64_t)pl.units * pl.nblk;
     int64_t w;
     if (d->num_splits > 0) {
@@ -712,6 +1048,10 @@ bool desc_ok(const rest_attn_desc* d) {
 
 }  // namespace
 
+// workspace of the split plan: [tickets: one 64-bit word per unit, padded to 256 bytes][reference, sum: units x parts x
+// 64 rows x 2 floats][normalised partial outputs: units x parts x 64 rows x 128 bf16]
+static size_t split_ticket_bytes(int units) { return ((size_t)units * 8 + 255) / 256 * 256; }
+
 extern "C" __attribute__((visibility("default"))) size_t rest_tree_attention_workspace_bytes(const rest_attn_desc* d) {
     if (!desc_ok(d)) return 0;
     const Plan pl = make_plan(d);
@@ -719,6 +1059,7 @@ extern "C" __attribute__((visibility("default"))) size_t rest_tree_attention_wor
         if (pl.nsplit_f32 == 1) return 0;
         return (size_t)d->Nb * d->H * pl.nsplit_f32 * d->Tq * (kD + 2) * sizeof(float);
     }
+    if (pl.split_s > 0) return split_ticket_bytes(pl.units) + (size_t)pl.units * pl.split_s * 64 * (2 * sizeof(float) + kD * 2);
     if (!pl.need_merge) return 0;
     return (size_t)pl.tail_streams * 2 * (pl.qt * 32) * (kD + 2) * sizeof(float);
 }
@@ -734,6 +1075,7 @@ static rest_status enqueue_tree_attention(const void* d_q, const void* d_k, cons
     const Plan pl = make_plan(d);
     const size_t need = rest_tree_attention_workspace_bytes(d);
     if (need > workspace_bytes || (need && !d_workspace)) return REST_WORKSPACE_TOO_SMALL;
+    if (need && ((uintptr_t)d_workspace & 15)) return REST_INVALID_ARG;      // partials are moved 16 bytes at a time
 
     AttnParams p;
     p.q = (const __bf16*)d_q;
@@ -754,7 +1096,27 @@ static rest_status enqueue_tree_attention(const void* d_q, const void* d_k, cons
     p.k_scale = kv8 ? d->d_k_scale : nullptr;
     p.v_scale = kv8 ? d->d_v_scale : nullptr;
 
-    if (d->dtype == REST_BF16) {
+    p.split_s = 0;
+    p.split_rounds = 0;
+    p.ws_po = nullptr;
+    p.tickets = nullptr;
+    if (d->dtype == REST_BF16 && pl.split_s > 0) {
+        p.nsplit = 1;
+        p.qgroups = 1;
+        p.units = pl.units;
+        p.n_streams = p.dp_rounds = p.tail_units = p.tail_streams = p.extra_units = 0;
+        p.split_s = pl.split_s;
+        const int ngroups = kSplitGroups * pl.split_s;
+        p.split_rounds = (pl.nblk + ngroups - 1) / ngroups;
+        p.tickets = (unsigned long long*)d_workspace;
+        p.ws_ml = (float*)((char*)d_workspace + split_ticket_bytes(pl.units));
+        p.ws_po = (__bf16*)(p.ws_ml + (size_t)pl.units * pl.split_s * 64 * 2);
+        if (kv8)
+            hipLaunchKernelGGL((tree_attn_split_kernel<true>), dim3(pl.units * pl.split_s), dim3(512), 0, stream, p);
+        else
+            hipLaunchKernelGGL((tree_attn_split_kernel<false>), dim3(pl.units * pl.split_s), dim3(512), 0, stream, p);
+        REST_HIP_TRY(hipGetLastError());
+    } else if (d->dtype == REST_BF16) {
         p.nsplit = 1;
         p.qgroups = pl.qgroups;
         p.units = pl.units;

@@ -77,9 +77,14 @@ def test_attention_workspace_sizing_is_host_only(rest):
     assert lib.rest_tree_attention(p16, p16, p16, p16, p16, ctypes.byref(wide), None, 0, None) == rest.REST_INVALID_ARG
     # 1024 (layer, head) units over 1024 streams: every stream owns whole units, no partial results
     assert rest.rest_tree_attention_workspace_bytes(make_desc(rest)) == 0
-    # one layer: 32 units x 66 key blocks = 2112 blocks over 2112 / 4 = 528 streams, two partial slots each
+    # one layer: 32 units, the split plan with 256 / 32 = 8 workgroups per unit: 32 tickets, then per workgroup
+    # 64 rows x (reference, sum as floats + 128 bf16 outputs)
     one_layer = make_desc(rest, Nb=1)
-    assert rest.rest_tree_attention_workspace_bytes(one_layer) == 528 * 2 * 64 * (128 + 2) * 4
+    assert rest.rest_tree_attention_workspace_bytes(one_layer) == 256 + 32 * 8 * 64 * (8 + 256)
+    # few key blocks: every key group of a workgroup needs one, so 9 blocks allow two workgroups per unit; below 8, stream-K
+    assert rest.rest_tree_attention_workspace_bytes(make_desc(rest, Nb=1, P=224)) == 256 + 32 * 2 * 64 * (8 + 256)
+    short = make_desc(rest, Nb=1, P=150)
+    assert rest.rest_tree_attention_workspace_bytes(short) == (32 * 7 // 4) * 2 * 64 * (128 + 2) * 4
     forced = make_desc(rest, Nb=1, num_splits=4)
     assert rest.rest_tree_attention_workspace_bytes(forced) == 32 * 4 * 2 * 64 * 130 * 4
     # 128 queries: streams of four wavefronts on 64-key tiles: 32 units x 33 tiles over 264 streams, 128 rows per slot

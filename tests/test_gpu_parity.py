@@ -272,6 +272,47 @@ def test_tree_attention_bf16_variants():
     attention_case(5, 7, 96, 1000, seed=14, tree="chain")    # 96 rows: four-wavefront streams with an idle wavefront
 
 
+@pytest.mark.parametrize("Tq,Tk", [(7, 20), (32, 70), (20, 130), (32, 200), (31, 256), (64, 256), (100, 190)])
+def test_tree_attention_arbitrary_masks_at_every_prefix_alignment(Tq, Tk):
+    """Masks that are not trees (every bit drawn at random, rows independent of each other), few query rows against up
+    to 256 draft keys, and the prefix ending at every offset 0..31 inside a block of 32 keys: the block that holds
+    the prefix's end mixes always-visible keys with masked ones at every possible shift, and the draft keys cross the
+    64-, 128- and 192-bit word boundaries of a mask row.  Both plans (units cut between workgroups with the partials
+    combined in the kernel; streams over whole units) and the 8-bit cache."""
+    scale = 1.0 / np.sqrt(128.0)
+    words = (Tk + 63) // 64
+    for r in range(32):
+        P = 32 * (1 + (r * 7) % 9) + r                    # 8+ blocks of keys, prefix end at offset r of its block
+        seed = 7000 + Tq * 300 + Tk + r
+        bits = synth.randint(seed, np.arange(Tq * words * 64), 0, 2).reshape(Tq, words * 64).astype(np.uint64)
+        bits[:, Tk:] = 0
+        if r % 5 == 0:
+            bits[r % Tq] = 0                               # a row that sees the prefix only
+        mask = np.zeros((Tq, words), np.uint64)
+        for j in range(words * 64):
+            mask[:, j // 64] |= bits[:, j] << np.uint64(j % 64)
+        qb = synth.normal_bf16_bits(seed + 1, (1, 2, Tq, 128))
+        kb = synth.normal_bf16_bits(seed + 2, (1, 2, P + Tk, 128))
+        vb = synth.normal_bf16_bits(seed + 3, (1, 2, P + Tk, 128))
+        q, k, v = (synth.bf16_bits_to_f32(x) for x in (qb, kb, vb))
+        dq, dk, dv = (dev(x.view(np.int16)).view(torch.bfloat16) for x in (qb, kb, vb))
+        want = oracle.tree_attention(q, k, v, mask, P, scale)
+        dmask = dev(mask.view(np.int64))
+        for ns in (0, 1):
+            out = torch.full_like(dq, float("nan"))
+            rest.rest_tree_attention(dq, dk, dv, dmask, P, float(scale), out=out, num_splits=ns)
+            torch.cuda.synchronize()
+            err = np.abs(out.float().cpu().numpy() - want).max()
+            assert err <= 2e-2, (P, ns, err)
+        if r % 4 == 0:
+            k8, v8 = oracle.fp8_e4m3_encode(k), oracle.fp8_e4m3_encode(v)
+            want8 = oracle.tree_attention_fp8kv(q, k8, v8, np.ones((1, 2)), np.ones((1, 2)), mask, P, scale)
+            out = torch.full_like(dq, float("nan"))
+            rest.rest_tree_attention(dq, dev(k8), dev(v8), dmask, P, float(scale), out=out)
+            torch.cuda.synchronize()
+            assert np.abs(out.float().cpu().numpy() - want8).max() <= 2e-2, (P, "e4m3")
+
+
 @pytest.mark.parametrize("Nb,H,T,P,dtype", [(22, 50, 64, 100, "bf16"), (35, 41, 64, 36, "bf16"), (42, 50, 64, 70, "bf16"),
                                             (7, 150, 33, 300, "fp8kv"), (20, 30, 128, 300, "bf16"), (10, 30, 256, 200, "bf16"),
                                             (40, 40, 64, 50, "bf16"), (31, 50, 40, 64, "fp8kv"), (30, 28, 128, 200, "bf16"),
