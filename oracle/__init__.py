@@ -491,54 +491,73 @@ def accept(ids: np.ndarray, draft_tokens: np.ndarray, parent_idx: np.ndarray, n_
 # threshold p; REST accepts a draft token only if it equals the token sampled
 # at its position, so acceptance is the same walk as in the greedy case on
 # sampled ids.  The paper fixes temperature and top-p (Table 1 caption) but not
-# the mechanics; the reading here: probabilities = softmax(logits /
-# temperature); tokens ordered by probability, highest first, equal
-# probabilities by ascending token id; the nucleus is the shortest prefix of
-# that order whose mass is >= top_p; the draw is inverse-CDF on the
-# renormalised nucleus with a uniform number u in [0, 1) supplied by the caller.
+# the mechanics.  The reading here fixes them down to the last bit, so that an
+# integer result (a token id) has one right answer whatever the order in which
+# an implementation adds things up:
+#   * probability masses are integers.  Token i weighs
+#       w_i = floor(2^36 * E((x_i - x_max) * c)),   c = log2(e) / temperature,
+#     where E(y) = 2^y is evaluated by a fixed sequence of float64 operations
+#     (below), every one of them a single correctly rounded IEEE operation; the
+#     most probable token weighs exactly 2^36, a token below 2^-36 of it
+#     nothing.  Sums of such weights are exact (below 2^53 for up to 2^17
+#     tokens), hence independent of the order of summation;
+#   * tokens are ordered by logit, highest first (+0 and -0 are one value),
+#     equal logits by ascending token id;
+#   * the nucleus is the shortest prefix of that order whose mass C_k satisfies
+#     float64(C_k) >= float32(top_p) * float64(W), W the total mass (one
+#     float64 product);
+#   * the draw is the first token whose cumulative mass satisfies
+#     float64(C_j) > float32(u) * float64(M), M the nucleus mass, u in [0, 1)
+#     the caller's uniform number.
+# E(y) for y <= 0: n = floor(y), f = y - n in [0, 1), t = f * ln 2,
+# E = 2^n * P(t), P the Taylor polynomial of exp of degree 13 in Horner form,
+# each step one multiplication and one addition (no fused multiply-add);
+# E(0) = 1 exactly.  |E(y) / 2^y - 1| < 1e-12, far below the weights' own step.
 # ---------------------------------------------------------------------------
+SAMPLE_WEIGHT_BITS = 36
+_LOG2E = float.fromhex("0x1.71547652b82fep+0")
+_LN2 = float.fromhex("0x1.62e42fefa39efp-1")
+_EXP_TAYLOR = [float.fromhex(h) for h in (
+    "0x1.0000000000000p+0", "0x1.0000000000000p+0", "0x1.0000000000000p-1", "0x1.5555555555555p-3",
+    "0x1.5555555555555p-5", "0x1.1111111111111p-7", "0x1.6c16c16c16c17p-10", "0x1.a01a01a01a01ap-13",
+    "0x1.a01a01a01a01ap-16", "0x1.71de3a556c734p-19", "0x1.27e4fb7789f5cp-22", "0x1.ae64567f544e4p-26",
+    "0x1.1eed8eff8d898p-29", "0x1.6124613a86d09p-33")]   # 1 / k!, k = 0 .. 13
+
+
+def nucleus_weights(logits: np.ndarray, temperature: float) -> np.ndarray:
+    """Integer probability masses of one row (uint64), in units of 2^-36 of the largest probability."""
+    x = np.asarray(logits, dtype=np.float32)
+    c = np.float64(_LOG2E) / np.float64(np.float32(temperature))
+    y = (x.astype(np.float64) - np.float64(x.max())) * c
+    live = y >= -64.0                                     # below: less than 2^-64 of the largest, weight 0 (also -inf)
+    y = np.where(live, y, 0.0)
+    n = np.floor(y)
+    t = (y - n) * np.float64(_LN2)
+    poly = np.full_like(t, _EXP_TAYLOR[13])
+    for k in range(12, -1, -1):
+        poly = poly * t                                   # two separately rounded operations per step
+        poly = poly + np.float64(_EXP_TAYLOR[k])
+    w = np.floor(np.ldexp(poly, (n + SAMPLE_WEIGHT_BITS).astype(np.int32)))
+    return np.where(live, w, 0.0).astype(np.uint64)
+
+
 def nucleus_sample(logits: np.ndarray, temperature: float, top_p: float, u: float):
-    """Returns (token, margin).  margin is the distance, in probability mass, between the
-    decision thresholds (top_p for the nucleus boundary, u * nucleus mass for the draw)
-    and the nearest cumulative sum: results of two float64 implementations can differ
-    only where it is at rounding level."""
-    z = np.asarray(logits, dtype=np.float64) / float(temperature)
-    z = z - z.max()
-    p = np.exp(z)
-    p = p / p.sum()
-    order = np.lexsort((np.arange(p.size), -p))          # probability descending, token id ascending
-    cum = np.cumsum(p[order])
-    hit = np.nonzero(cum >= top_p)[0]
-    k = int(hit[0]) if hit.size else p.size - 1
+    """Returns (token, margin).  margin is the distance, as a fraction of the total mass, between the decision
+    thresholds (top_p for the nucleus boundary, u * nucleus mass for the draw) and the nearest cumulative sum (a
+    diagnostic: the result itself is exact)."""
+    x = np.asarray(logits, dtype=np.float32)
+    w = nucleus_weights(x, temperature)
+    order = np.lexsort((np.arange(x.size), -x))          # logit descending, token id ascending
+    cum = np.cumsum(w[order])                             # exact integers
+    total = cum[-1]
+    thr = np.float64(np.float32(top_p)) * np.float64(total)
+    k = int(np.nonzero(cum.astype(np.float64) >= thr)[0][0])
     mass = cum[k]
-    target = float(u) * mass
-    j = int(np.nonzero(cum > target)[0][0])
-    margin = min(np.abs(cum[:k + 1] - top_p).min(), np.abs(cum[:k + 1] - target).min())
+    target = np.float64(np.float32(u)) * np.float64(mass)
+    j = int(np.nonzero(cum.astype(np.float64) > target)[0][0])
+    c64 = cum[:k + 1].astype(np.float64)
+    margin = min(np.abs(c64 - thr).min(), np.abs(c64 - target).min()) / float(total)
     return int(order[j]), float(margin)
-
-
-def nucleus_candidates(logits: np.ndarray, temperature: float, top_p: float, u: float, tol: float = 1e-9):
-    """Every token that nucleus_sample could return if each cumulative sum were off by up to `tol`
-    (another float64 implementation differs by rounding only): the nucleus may end one element
-    earlier or later when a cumulative sum is within tol of top_p, and the draw may fall on
-    either side of a cumulative sum within tol of its target.  A set; almost always one token."""
-    z = np.asarray(logits, dtype=np.float64) / float(temperature)
-    z = z - z.max()
-    p = np.exp(z)
-    p = p / p.sum()
-    order = np.lexsort((np.arange(p.size), -p))
-    cum = np.cumsum(p[order])
-    ends = [k for k in range(p.size) if cum[k] >= top_p - tol and (k == 0 or cum[k - 1] < top_p + tol)]
-    if not ends:
-        ends = [p.size - 1]
-    out = set()
-    for k in ends:
-        target = float(u) * cum[k]
-        for j in range(k + 1):
-            below = cum[j - 1] if j else 0.0
-            if below <= target + tol and cum[j] > target - tol:
-                out.add(int(order[j]))
-    return out
 
 
 def sample_ids(logits: np.ndarray, temperature: float, top_p: float, u: np.ndarray):

@@ -76,12 +76,16 @@ EDITS = {
     "compact: reads the rows it has already overwritten": ("kv", "kv_compact", "= cache[..., P + int(accept_path[i]), :]",
                                                            "= out[..., P + int(accept_path[i]), :]"),
     "compact: rows land one place late": ("kv", "kv_compact", "out[..., P + i, :] =", "out[..., P + i + 1, :] ="),
-    "sampling: nucleus must exceed top_p": ("sampling", "nucleus_sample", "np.nonzero(cum >= top_p)", "np.nonzero(cum > top_p)"),
-    "sampling: draw at cumulative mass >= target": ("sampling", "nucleus_sample", "np.nonzero(cum > target)", "np.nonzero(cum >= target)"),
-    "sampling: logits times temperature": ("sampling", "nucleus_sample", "/ float(temperature)", "* float(temperature)"),
-    "sampling: ties by descending id": ("sampling", "nucleus_sample", "np.lexsort((np.arange(p.size), -p))",
-                                        "np.lexsort((-np.arange(p.size), -p))"),
-    "sampling: u not scaled by the nucleus mass": ("sampling", "nucleus_sample", "target = float(u) * mass", "target = float(u)"),
+    "sampling: nucleus must exceed top_p": ("sampling", "nucleus_sample", "np.nonzero(cum.astype(np.float64) >= thr)", "np.nonzero(cum.astype(np.float64) > thr)"),
+    "sampling: draw at cumulative mass >= target": ("sampling", "nucleus_sample", "np.nonzero(cum.astype(np.float64) > target)", "np.nonzero(cum.astype(np.float64) >= target)"),
+    "sampling: logits times temperature": ("sampling", "nucleus_weights", "c = np.float64(_LOG2E) / np.float64(np.float32(temperature))",
+                                           "c = np.float64(_LOG2E) * np.float64(np.float32(temperature))"),
+    "sampling: ties by descending id": ("sampling", "nucleus_sample", "np.lexsort((np.arange(x.size), -x))",
+                                        "np.lexsort((-np.arange(x.size), -x))"),
+    "sampling: u not scaled by the nucleus mass": ("sampling", "nucleus_sample", "* np.float64(mass)", "* np.float64(total)"),
+    "sampling: natural exponent taken for base two": ("sampling", "nucleus_weights", "t = (y - n) * np.float64(_LN2)", "t = (y - n)"),
+    "sampling: polynomial one term short of the constant": ("sampling", "nucleus_weights", "for k in range(12, -1, -1):", "for k in range(12, 0, -1):"),
+    "sampling: weights in units of 2^-35": ("sampling", "nucleus_weights", "(n + SAMPLE_WEIGHT_BITS).astype(np.int32)", "(n + SAMPLE_WEIGHT_BITS - 1).astype(np.int32)"),
     "mask: a node does not see itself": ("integer", "mask_from_parents", "        v = i\n", "        v = int(parent_idx[i])\n"),
     "mask: parent only, no further ancestors": ("integer", "mask_from_parents", "while v != -1:", "for _ in range(2 if v != -1 else 0):\n            if v == -1:\n                break"),
     "attention: only the first mask word read": ("attention", "tree_attention", "mask[..., j // 64]", "mask[..., 0]"),
@@ -91,9 +95,6 @@ EDITS = {
     "append: 8-bit cache, multiplied by the scale": ("fp8", "rope_append_fp8kv", "kx = rope(k_new, pos, theta) / np.asarray(",
                                                     "kx = rope(k_new, pos, theta) * np.asarray("),
     "compact: last accepted row not moved": ("kv", "kv_compact", "for i in range(int(accept_len)):", "for i in range(int(accept_len) - 1):"),
-    "sampling: candidates without the tolerance at the nucleus end": ("sampling", "nucleus_candidates",
-                                                                     "if cum[k] >= top_p - tol and (k == 0 or cum[k - 1] < top_p + tol)]",
-                                                                     "if cum[k] >= top_p and (k == 0 or cum[k - 1] < top_p)][:1]"),
     "retrieve: evenly spaced sample rounded up": ("integer", "retrieve", "pick = np.array([(i * S) // K for i in range(K)]",
                                                   "pick = np.array([min((i * S + K - 1) // K, S - 1) for i in range(K)]"),
     "random selection: draw by remainder": ("integer", "random_rows", "(_mix64(h + G * (1 + j)) * n_rows) >> 64", "_mix64(h + G * (1 + j)) % n_rows"),

@@ -1,6 +1,8 @@
-"""Pins for the oracle's nucleus sampler (CPU only): hand-computed distributions, the limits in which it must turn
-into arg-max, exact frequencies on a grid of uniforms, an independent formulation of the nucleus with exact
-rationals, and the property the paper claims for it -- decoding with drafts emits what plain sampling emits."""
+"""Pins for the oracle's nucleus sampler (CPU only): its integer probability masses against the library exponential,
+hand-computed distributions, the limits in which it must turn into arg-max, exact frequencies on a grid of uniforms,
+an independent formulation of the nucleus with exact rationals, and the property the paper claims for it -- decoding
+with drafts emits what plain sampling emits."""
+import math
 from fractions import Fraction
 
 import numpy as np
@@ -23,8 +25,10 @@ def test_hand_distribution_boundaries():
     want = {0.0: 3, 0.3: 3, 0.57: 3, 0.58: 0, 0.85: 0, 0.86: 4, 0.999: 4}
     for u, tok in want.items():
         assert oracle.nucleus_sample(lg, 1.0, 0.8, u)[0] == tok, u
-    # top_p 0.75 is reached exactly by two tokens (dyadic values are exact in float64)
-    assert {oracle.nucleus_sample(lg, 1.0, 0.75, u)[0] for u in np.linspace(0, 0.999, 50)} == {3, 0}
+    # top_p just under / over the mass 0.75 of the first two tokens (the logits are float32 roundings of log p, so the
+    # sum is 0.75 only to about 1e-7)
+    assert {oracle.nucleus_sample(lg, 1.0, 0.7499, u)[0] for u in np.linspace(0, 0.999, 50)} == {3, 0}
+    assert {oracle.nucleus_sample(lg, 1.0, 0.7501, u)[0] for u in np.linspace(0, 0.999, 50)} == {3, 0, 4}
     # top_p 1: everything; the two equal tails are ordered by token id
     assert oracle.nucleus_sample(lg, 1.0, 1.0, 0.88)[0] == 1
     assert oracle.nucleus_sample(lg, 1.0, 1.0, 0.95)[0] == 2
@@ -144,18 +148,42 @@ def test_rest_decoding_with_sampled_acceptance_equals_plain_sampling():
     assert steps < 48
 
 
-def test_candidate_sets_contain_the_sample_and_are_single_away_from_boundaries():
-    rng = np.random.default_rng(9)
-    lg = rng.standard_normal(300).astype(np.float32) * 3
-    for u in rng.random(50):
-        tok, margin = oracle.nucleus_sample(lg, 0.8, 0.9, u)
-        cands = oracle.nucleus_candidates(lg, 0.8, 0.9, u)
-        assert tok in cands
-        if margin > 1e-8:
-            assert cands == {tok}
-    # on a boundary both neighbours qualify: probabilities 1/2, 1/4, 1/4 and u = 1/2 exactly
-    lg = logits_of([0.5, 0.25, 0.25])
-    assert oracle.nucleus_candidates(lg, 1.0, 1.0, 0.5) == {0, 1}
-    assert oracle.nucleus_sample(lg, 1.0, 1.0, 0.5)[0] in (0, 1)        # float32 logits: 1/2 is not hit exactly
-    # top_p exactly on a cumulative sum: the nucleus may or may not take the next token
-    assert oracle.nucleus_candidates(lg, 1.0, 0.75, 0.99) == {1, 2}
+def test_weights_are_the_library_exponential_cut_to_integers():
+    """w_i = floor(2^36 * 2^((x_i - x_max) * log2(e) / T)) with the exponential evaluated by the oracle's fixed
+    polynomial: against math.exp it may differ by the floor's one unit plus a relative 1e-12."""
+    rng = np.random.default_rng(3)
+    for T in (1.0, 0.8, 0.7, 0.05, 5.0):
+        x = (rng.standard_normal(4000) * rng.choice([0.5, 3.0, 30.0])).astype(np.float32)
+        x[7] = -np.inf
+        x[11] = x.max()
+        w = oracle.nucleus_weights(x, T)
+        assert w.dtype == np.uint64 and int(w.max()) == 2 ** 36 and int(w[11]) == 2 ** 36 and int(w[7]) == 0
+        t32, top = float(np.float32(T)), float(x.max())
+        for i in rng.integers(0, x.size, 600):
+            if np.isfinite(x[i]):
+                ref = 2.0 ** 36 * math.exp((float(x[i]) - top) / t32)
+                assert abs(int(w[i]) - ref) <= 1.0 + 1e-12 * ref, (T, i)
+    # a token far below the top one weighs nothing; weights never grow as the logit falls by a visible step
+    x = np.array([0.0, -24.0, -25.0, -26.0, -1000.0], dtype=np.float32)
+    w = oracle.nucleus_weights(x, 1.0)
+    assert int(w[1]) == math.floor(2 ** 36 * math.exp(-24.0)) and int(w[3]) == 0 and int(w[4]) == 0
+    assert int(w[2]) == math.floor(2 ** 36 * math.exp(-25.0)) == 0
+    # halving the temperature squares the ratios: 2^-3 -> 2^-6 (the logit step is a float32 rounding of 3 ln 2, so the
+    # masses are 2^33 and 2^30 only to about 2^-24 of themselves)
+    x = np.array([0.0, -3.0 * math.log(2.0)], dtype=np.float32)
+    assert abs(int(oracle.nucleus_weights(x, 1.0)[1]) - 2 ** 33) <= 2 ** 33 * 2.0 ** -22
+    assert abs(int(oracle.nucleus_weights(x, 0.5)[1]) - 2 ** 30) <= 2 ** 30 * 2.0 ** -21
+
+
+def test_masses_add_exactly_whatever_the_order():
+    """The point of integer masses: any order of summation gives the same totals, so the decisions do not depend on
+    how an implementation groups its sums."""
+    rng = np.random.default_rng(4)
+    x = (rng.standard_normal(131072) * 2).astype(np.float32)
+    w = oracle.nucleus_weights(x, 0.8)
+    total = int(w.sum())
+    assert total < 2 ** 53
+    for _ in range(3):
+        perm = rng.permutation(w.size)
+        assert int(w[perm].reshape(512, 256).sum(axis=1).sum()) == total
+        assert float(np.float64(total)) == total                        # and the sum is a float64 exactly
