@@ -460,8 +460,15 @@ def side_measurements(rest, torch, synth, corp, index, w, q, k, v, out, tree, P,
     logits[:, :8] += 9.0
     u = torch.rand(1 + T, generator=g, device=dev)
     sid = torch.empty(1 + T, dtype=torch.int32, device=dev)
-    ms = timed(lambda: rest.rest_sample_ids(logits, u, 0.8, 0.95, out=sid), 20)
+    ws_s = torch.empty(rest.rest_sample_ids_workspace_bytes(1 + T, 128256), dtype=torch.uint8, device=dev)
+    ms = timed(lambda: rest.rest_sample_ids(logits, u, 0.8, 0.95, out=sid, workspace=ws_s), 20)
     res["sample_ids_65x32000_us"] = round(ms * 1e3, 1)
+    res["sample_ids_65x32000_GBps"] = round((1 + T) * 32000 * 4 / (ms * 1e-3) / 1e9, 1)
+    big_logits = torch.randn((1 + T, 128256), generator=g, device=dev) * 2.0
+    big_logits[:, :8] += 9.0
+    ms = timed(lambda: rest.rest_sample_ids(big_logits, u, 0.8, 0.95, out=sid, workspace=ws_s), 20)
+    res["sample_ids_65x128256_us"] = round(ms * 1e3, 1)
+    del big_logits
 
     # the step with its cache steps: retrieve -> embed + append -> attention -> accept -> compact (greedy ids)
     ctx1, len1 = d_ctx[:1], d_len[:1]

@@ -58,7 +58,9 @@ enum {
     REST_OUT_OF_MEMORY = -4,      /* hipMalloc failed (index build / handle creation only) */
     REST_HIP_ERROR = -5,          /* a HIP runtime call or kernel launch failed */
     REST_IO_ERROR = -6,           /* a file could not be opened, read or written in full */
-    REST_BAD_FILE = -7            /* not an index file, or not the index of this token stream */
+    REST_BAD_FILE = -7,           /* not an index file, or not the index of this token stream */
+    REST_BOUNDS_VIOLATION = -8    /* bounds-checked build of the library only: a kernel formed an index outside its
+                                     array (the access was redirected inside it); the call's results mean nothing */
 };
 
 /* Compile-time limits of the retrieval kernels (rest_retrieve rejects larger values). */
@@ -69,7 +71,7 @@ enum {
 #define REST_MAX_QUERY_ROWS 1024    /* query rows of one rest_tree_attention slab (grouped heads stacked) */
 
 const char* rest_status_string(rest_status s);
-/* Library version string, e.g. "rest-gfx950 0.1". */
+/* Library version string, e.g. "rest-gfx950 0.2"; the bounds-checked build says so here. */
 const char* rest_version(void);
 
 /* ------------------------------------------------------------------------
@@ -302,19 +304,32 @@ rest_status rest_accept(const int32_t* d_ids, const rest_tree* tree, int32_t B, 
  * rest_sample_ids ("Sampling strategies"): nucleus sampling of the model's token
  * at R positions (the context's last token and every draft node), so that
  * rest_accept can compare sampled tokens, not arg-max tokens, with the drafts.
- * Row r: probabilities = softmax(d_logits[r, :] / temperature); tokens ordered
- * by probability, highest first, equal probabilities by ascending token id;
- * the nucleus is the shortest prefix of that order whose mass is >= top_p;
- * d_ids[r] = the first token of the order whose cumulative mass exceeds
- * d_u[r] * (nucleus mass).  d_u[r] in [0, 1) is the caller's random number for
- * that position: tie it to the position in the sequence and decoding with
- * drafts emits exactly what one-token-at-a-time sampling emits.
- * All arithmetic is fp64 on the fp32 logits; logits are finite or -inf, at
- * least one finite per row.  d_logits [R, row_stride >= V] fp32.
- * V <= 32768 (REST_UNSUPPORTED above); temperature > 0; 0 < top_p <= 1.
+ * The paper gives temperature and top-p, not the mechanics; this definition
+ * fixes the drawn token to the last bit, whatever order an implementation adds in:
+ *  - row r, token i weighs w_i = floor(2^36 * E((x_i - x_max) * c)), an integer,
+ *    with x = d_logits[r, :], c = log2(e) / temperature formed in fp64 and
+ *    E(y) = 2^y evaluated as: n = floor(y), t = (y - n) * ln 2, E = 2^n * P(t),
+ *    P = the Taylor polynomial of exp of degree 13 in Horner form, every
+ *    multiplication and addition a separate correctly rounded fp64 operation;
+ *    tokens below 2^-64 of the largest weigh 0 (so does a logit of -inf);
+ *  - tokens are ordered by logit, highest first (+0 = -0), equal logits by
+ *    ascending token id;
+ *  - the nucleus is the shortest prefix of that order whose mass C_k satisfies
+ *    (double)C_k >= (double)top_p * (double)W, W the row's total mass;
+ *  - d_ids[r] = the first token of the order whose cumulative mass satisfies
+ *    (double)C_j > (double)d_u[r] * (double)M, M the nucleus mass.
+ * d_u[r] in [0, 1) is the caller's random number for that position: tie it to
+ * the position in the sequence and decoding with drafts emits exactly what
+ * one-token-at-a-time sampling emits.  Logits are finite or -inf, at least one
+ * finite per row; d_logits [R, row_stride >= V] fp32.  V <= 131072
+ * (REST_UNSUPPORTED above: masses are summed exactly in 53 bits); temperature > 0;
+ * 0 < top_p <= 1.  d_workspace: rest_sample_ids_workspace_bytes(R, V) bytes of
+ * device memory, 8-byte aligned, no initialisation needed.
  * ---------------------------------------------------------------------- */
+size_t rest_sample_ids_workspace_bytes(int32_t R, int32_t V);
 rest_status rest_sample_ids(const float* d_logits, int64_t row_stride, const float* d_u, int32_t R, int32_t V,
-                            float temperature, float top_p, int32_t* d_ids, void* stream);
+                            float temperature, float top_p, int32_t* d_ids, void* d_workspace, size_t workspace_bytes,
+                            void* stream);
 
 /* ------------------------------------------------------------------------
  * The steps either side of verification inside one model layer.  The paper

@@ -14,7 +14,10 @@ from dataclasses import dataclass
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "librest_gfx950.so")
+# REST_LIBRARY=checked loads the bounds-checked build of the same sources (librest_gfx950_checked.so: indices that
+# depend on data or on the launch plan are clamped into their arrays and reported, every call waits for its kernels);
+# it exists to run the test suite under, not to serve from.
+LIB_PATH = os.path.join(_HERE, "librest_gfx950_checked.so" if os.environ.get("REST_LIBRARY") == "checked" else "librest_gfx950.so")
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(
@@ -30,6 +33,7 @@ REST_OUT_OF_MEMORY = -4
 REST_HIP_ERROR = -5
 REST_IO_ERROR = -6
 REST_BAD_FILE = -7
+REST_BOUNDS_VIOLATION = -8
 REST_BF16 = 0
 REST_FP32 = 1
 REST_KV_AS_DTYPE = 0
@@ -46,7 +50,7 @@ EXPORTS = [
     "rest_index_destroy", "rest_retrieve_workspace_bytes", "rest_retrieve",
     "rest_tree_attention_workspace_bytes", "rest_tree_attention", "rest_accept",
     "rest_rope_append", "rest_kv_compact", "rest_sample_ids", "rest_index_save", "rest_index_load",
-    "rest_build_index_prefix", "rest_index_sort_depth", "rest_tree_attention_noalloc",
+    "rest_build_index_prefix", "rest_index_sort_depth", "rest_tree_attention_noalloc", "rest_sample_ids_workspace_bytes",
 ]
 
 
@@ -131,7 +135,9 @@ _lib.rest_accept.argtypes = [ctypes.c_void_p, ctypes.POINTER(rest_tree), ctypes.
                              ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
 _lib.rest_sample_ids.restype = ctypes.c_int32
 _lib.rest_sample_ids.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32,
-                                 ctypes.c_float, ctypes.c_float, ctypes.c_void_p, ctypes.c_void_p]
+                                 ctypes.c_float, ctypes.c_float, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+_lib.rest_sample_ids_workspace_bytes.restype = ctypes.c_size_t
+_lib.rest_sample_ids_workspace_bytes.argtypes = [ctypes.c_int32, ctypes.c_int32]
 _lib.rest_rope_append.restype = ctypes.c_int32
 _lib.rest_rope_append.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                   ctypes.c_void_p, ctypes.POINTER(rest_kv_desc), ctypes.c_void_p]
@@ -546,17 +552,28 @@ def rest_kv_compact(k_cache: torch.Tensor, v_cache: torch.Tensor, accept_path: t
         raise RestError(st, "rest_kv_compact")
 
 
+def rest_sample_ids_workspace_bytes(R: int, V: int) -> int:
+    return _lib.rest_sample_ids_workspace_bytes(R, V)
+
+
 def rest_sample_ids(logits: torch.Tensor, u: torch.Tensor, temperature: float, top_p: float,
-                    out: torch.Tensor | None = None) -> torch.Tensor:
+                    out: torch.Tensor | None = None, workspace: torch.Tensor | None = None) -> torch.Tensor:
     """logits [R, V] fp32 (rows may be strided), u [R] fp32 in [0, 1) (device).  Returns ids [R] int32: the nucleus
-    sample of every row.  Enqueues on the current stream."""
-    assert logits.dim() == 2 and logits.stride(1) == 1 and logits.dtype == torch.float32
+    sample of every row.  workspace: rest_sample_ids_workspace_bytes(R, V) bytes of device memory (allocated here if
+    not given).  Enqueues on the current stream."""
+    _require(logits.dim() == 2 and logits.stride(1) == 1 and logits.dtype == torch.float32, "logits must be [R, V] float32, tokens contiguous")
     R, V = logits.shape
-    assert u.numel() == R and u.is_contiguous()
+    _require(u.numel() == R and u.is_contiguous() and u.dtype == torch.float32, f"u must hold {R} contiguous float32 numbers")
     if out is None:
         out = torch.empty(R, dtype=torch.int32, device=logits.device)
+    _require(out.numel() == R and out.dtype == torch.int32 and out.is_contiguous(), f"out must hold {R} contiguous int32 ids")
+    need = rest_sample_ids_workspace_bytes(R, V)
+    if workspace is None:
+        workspace = torch.empty(max(need, 8), dtype=torch.uint8, device=logits.device)
+    _require(workspace.is_contiguous() and workspace.numel() * workspace.element_size() >= need, f"workspace smaller than {need} bytes")
     st = _lib.rest_sample_ids(_dev(logits, torch.float32), logits.stride(0) if R > 1 else V, _dev(u, torch.float32), R, V,
-                              temperature, top_p, _dev(out, torch.int32), _stream())
+                              temperature, top_p, _dev(out, torch.int32), _dev(workspace), workspace.numel() * workspace.element_size(),
+                              _stream())
     if st != REST_OK:
         raise RestError(st, "rest_sample_ids")
     return out

@@ -12,11 +12,18 @@ extern "C" __attribute__((visibility("default"))) const char* rest_status_string
         case REST_HIP_ERROR: return "HIP runtime error";
         case REST_IO_ERROR: return "file input/output error";
         case REST_BAD_FILE: return "not an index file of this token stream";
+        case REST_BOUNDS_VIOLATION: return "index out of bounds inside a kernel (bounds-checked build)";
         default: return "unknown status";
     }
 }
 
-extern "C" __attribute__((visibility("default"))) const char* rest_version(void) { return "rest-gfx950 0.1"; }
+extern "C" __attribute__((visibility("default"))) const char* rest_version(void) {
+#ifdef REST_BOUNDS_CHECK
+    return "rest-gfx950 0.2 (bounds-checked build)";
+#else
+    return "rest-gfx950 0.2";
+#endif
+}
 
 extern "C" __attribute__((visibility("default"))) rest_status rest_index_from_sa(const void* d_corpus, const void* d_sa, uint64_t n_tokens, int32_t token_bytes,
                                           int32_t sa_bytes, void* stream, rest_index** out) {

@@ -45,6 +45,11 @@ constexpr int kSubBytes = kBlk * kD * 2;    // 8 KB: K or V of one 32-key block 
 constexpr float kNegBig = -1.0e30f;
 constexpr float kLazy = 8.0f;      // log2 units the running maximum may exceed the softmax reference
 constexpr int kMaxWaves = 2048;    // wavefronts in flight: eight on each of 256 compute units
+#ifdef REST_BOUNDS_CHECK
+constexpr bool kBoundsChecked = true;    // K/V rows always go through the path that clamps them to the last key
+#else
+constexpr bool kBoundsChecked = false;
+#endif
 
 struct AttnParams {
     const __bf16* q;
@@ -298,6 +303,7 @@ __global__ __launch_bounds__(64 * NW, 2) void tree_attn_bf16_kernel(AttnParams p
                                : (uint32_t)(lrow * v_row_bytes) + ((lpc ^ (lrow << 2)) << 4);
 
     auto unit_bases = [&](int unit, const char*& kp, const char*& vp) {
+        unit = (int)REST_IDX(unit, p.units, 3);
         const int slab = unit / p.qgroups;
         const int h = slab % p.H, nb = slab / p.H;
         kp = (const char*)p.k + (nb * p.ks[0] + h * p.ks[1]) * kElt;
@@ -314,7 +320,8 @@ __global__ __launch_bounds__(64 * NW, 2) void tree_attn_bf16_kernel(AttnParams p
     constexpr int kChunkRows = KV8 ? 8 : 4;            // rows of a 1 KB chunk
     auto issue = [&]() {
         const int j = ld_j;
-        if ((j + 1) * kTileKeys <= p.Lk) {
+        (void)REST_IDX((int64_t)j * kTileKeys, p.Lk, 2);       // a tile starts at a key that exists (a plan error if not)
+        if (!kBoundsChecked && (j + 1) * kTileKeys <= p.Lk) {
 #pragma unroll
             for (int i = 0; i < kFetch; i++) {
                 const int64_t row = (int64_t)j * kTileKeys + (kFetch * wave + i) * kChunkRows;
@@ -397,6 +404,7 @@ __global__ __launch_bounds__(64 * NW, 2) void tree_attn_bf16_kernel(AttnParams p
             tail_span(tb, te);
             first_seg = (unit - p.dp_rounds * p.n_streams) * p.nblk + seg_j == tb;
         }
+        unit = (int)REST_IDX(unit, p.units, 3);
         const int qg = unit % p.qgroups, slab = unit / p.qgroups;
         const int h = slab % p.H, nb = slab / p.H;
         const int qi = qg * (32 * NW) + wave * 32 + col;        // this lane's query row
@@ -473,7 +481,8 @@ __global__ __launch_bounds__(64 * NW, 2) void tree_attn_bf16_kernel(AttnParams p
                         *(bf16x4*)(op + dt * 32 + 8 * gq + 4 * hh) = w;
                     }
             } else {
-                const int64_t row = ((int64_t)gw * 2 + (first_seg ? 0 : 1)) * (32 * NW) + wave * 32 + col;
+                const int64_t row = REST_IDX(((int64_t)gw * 2 + (first_seg ? 0 : 1)) * (32 * NW) + wave * 32 + col,
+                                             (int64_t)p.tail_streams * 2 * (32 * NW), 4);
                 float* wo = p.ws_o + row * kD;
 #pragma unroll
                 for (int dt = 0; dt < 4; dt++)
@@ -545,7 +554,7 @@ __global__ __launch_bounds__(512, 1) void tree_attn_split_kernel(AttnParams p) {
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int g = wave >> 1, qw = wave & 1;            // key group; which 32 of the 64 queries
     const int hh = lane >> 5, col = lane & 31, lrow = lane >> 4, lpc = lane & 15;
-    const int unit = blockIdx.x % p.units, part = blockIdx.x / p.units;
+    const int unit = blockIdx.x % p.units, part = (int)REST_IDX(blockIdx.x / p.units, p.split_s, 6);
     const int h = unit % p.H, nb = unit / p.H;
     // this key group's blocks [b0, b1) of the unit's nblk
     const int ngroups = G * p.split_s, gi = part * G + g;
@@ -566,7 +575,8 @@ __global__ __launch_bounds__(512, 1) void tree_attn_split_kernel(AttnParams p) {
     // the fetch and the parking stores of the kernel above, for tiles of one block and two wavefronts
     i32x4 kr[kFetch], vr[kFetch];
     auto issue = [&](int j) {
-        if ((j + 1) * kBlk <= p.Lk) {
+        (void)REST_IDX((int64_t)j * kBlk, p.Lk, 2);
+        if (!kBoundsChecked && (j + 1) * kBlk <= p.Lk) {
 #pragma unroll
             for (int i = 0; i < kFetch; i++) {
                 const int64_t row = (int64_t)j * kBlk + (kFetch * qw + i) * kChunkRows;
@@ -723,7 +733,7 @@ __global__ __launch_bounds__(512, 1) void tree_attn_split_kernel(AttnParams p) {
     typedef unsigned long long u64;
     {
         const float inv = l_all > 0.f ? 1.0f / l_all : 0.f;
-        const int64_t prow = ((int64_t)unit * p.split_s + part) * 64 + q;
+        const int64_t prow = REST_IDX(((int64_t)unit * p.split_s + part) * 64 + q, (int64_t)p.units * p.split_s * 64, 5);
         union { bf16x8 h[2]; u64 w[4]; } pk;
 #pragma unroll
         for (int e = 0; e < 8; e++) {
@@ -1163,6 +1173,7 @@ static rest_status enqueue_tree_attention(const void* d_q, const void* d_k, cons
             REST_HIP_TRY(hipGetLastError());
         }
     }
+    REST_BOUNDS_EPILOGUE(stream);
     return REST_OK;
 }
 

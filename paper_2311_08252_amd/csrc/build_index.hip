@@ -46,7 +46,7 @@ __global__ void init_rank_kernel(const TokT* corpus, uint64_t n, uint32_t* rank,
 __global__ void make_keys_kernel(const uint32_t* rank, uint64_t n, uint64_t h, const uint32_t* list, uint64_t m,
                                  uint64_t* key, uint32_t* val) {
     for (uint64_t j = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; j < m; j += (uint64_t)gridDim.x * blockDim.x) {
-        const uint64_t i = list ? (uint64_t)list[j] : j;
+        const uint64_t i = REST_IDX(list ? (uint64_t)list[j] : j, n, 8);      // a listed suffix is a position of the stream
         const uint32_t second = i + h < n ? rank[i + h] : 0u;
         key[j] = ((uint64_t)rank[i] << 32) | second;
         val[j] = (uint32_t)i;
@@ -265,7 +265,7 @@ __global__ __launch_bounds__(kSortThreads) void radix_scatter_kernel(const uint6
         for (uint32_t pp = tid; pp < count; pp += kSortThreads) {
             const uint64_t kk = skey[pp];
             const uint32_t d = (uint32_t)(kk >> shift) & 255u;
-            const uint32_t dst = base[d] + (pp - dstart[d]);
+            const uint32_t dst = (uint32_t)REST_IDX(base[d] + (pp - dstart[d]), n, 9);      // scattered inside the sorted array
             key_out[dst] = kk;
             val_out[dst] = sval[pp];
         }
@@ -305,11 +305,11 @@ __global__ __launch_bounds__(256) void marks_kernel(const uint64_t* key, uint64_
 // inside the group.  In the last round of a depth-limited build every suffix gets its own place instead (offset of j
 // itself): equal keys then stay in the order they have, which is ascending position.
 __global__ void assign_rank_kernel(const uint64_t* key, const uint32_t* val, const uint32_t* run_start, const uint32_t* grp_start,
-                                   uint64_t m, int first_round, int spread, uint32_t* rank) {
+                                   uint64_t m, int first_round, int spread, uint32_t* rank, uint64_t n) {
     for (uint64_t j = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; j < m; j += (uint64_t)gridDim.x * blockDim.x) {
         const uint32_t base = first_round ? 1u : (uint32_t)(key[j] >> 32);
         const uint32_t at = spread ? (uint32_t)j : run_start[j];
-        rank[val[j]] = base + (at - grp_start[j]);
+        rank[REST_IDX(val[j], n, 10)] = base + (at - grp_start[j]);
     }
 }
 
@@ -335,7 +335,7 @@ __global__ __launch_bounds__(256) void unsettled_kernel(const uint32_t* run_star
 __global__ void compact_kernel(const uint32_t* val, const uint32_t* run_start, const uint32_t* pos, uint64_t m, uint32_t* list) {
     for (uint64_t j = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; j < m; j += (uint64_t)gridDim.x * blockDim.x) {
         const bool alone = run_start[j] == (uint32_t)j && (j + 1 == m || run_start[j + 1] == (uint32_t)(j + 1));
-        if (!alone) list[pos[j]] = val[j];
+        if (!alone) list[REST_IDX(pos[j], m, 11)] = val[j];
     }
 }
 
@@ -344,6 +344,7 @@ template <typename SaT>
 __global__ void invert_kernel(const uint32_t* rank, uint64_t n, SaT* sa) {
     for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (uint64_t)gridDim.x * blockDim.x) {
         const uint32_t r = rank[i];
+        (void)REST_IDX((uint64_t)r - 1u, n, 12);           // final ranks are 1 .. n (a rank outside is skipped, and noted)
         if (r >= 1u && (uint64_t)r <= n) sa[r - 1u] = (SaT)i;
     }
 }
@@ -487,7 +488,7 @@ extern "C" __attribute__((visibility("default"))) rest_status rest_build_index_p
         const bool limit = depth > 0 && 2 * h >= (uint64_t)depth;
         const bool spread = runs < m && (limit || h >= n);
         hipLaunchKernelGGL(assign_rank_kernel, dim3(gs), dim3(256), 0, st, s.key[cur], s.val[cur], run, grp, m, first_round ? 1 : 0,
-                           spread ? 1 : 0, s.rank);
+                           spread ? 1 : 0, s.rank, n);
         REST_HIP_TRY(hipGetLastError());
         if (runs == m) break;                               // every suffix distinct: the suffix array
         if (spread) { sorted_by = limit ? (int32_t)(2 * h) : 0; break; }
@@ -512,6 +513,7 @@ extern "C" __attribute__((visibility("default"))) rest_status rest_build_index_p
     else hipLaunchKernelGGL(invert_kernel<int64_t>, dim3(gn), dim3(256), 0, st, s.rank, n, (int64_t*)s.sa);
     REST_HIP_TRY(hipGetLastError());
     REST_HIP_TRY(hipStreamSynchronize(st));
+    REST_BOUNDS_EPILOGUE(st);
 
     rest_index* idx = nullptr;
     rest_status rs = rest_index_from_sa(d_corpus, s.sa, n, token_bytes, sa_bytes, stream_, &idx);

@@ -67,9 +67,10 @@ __device__ inline int32_t load_tok(const void* corpus, uint64_t n, uint64_t pos)
     return pos < n ? (int32_t)((const TokT*)corpus)[pos] : -1;
 }
 
+// entry `rank` of the suffix array of n entries; the entry itself is a position in the stream, i.e. below n
 template <typename SaT>
-__device__ inline uint32_t load_sa(const void* sa, uint32_t rank) {
-    return (uint32_t)((const SaT*)sa)[rank];
+__device__ inline uint32_t load_sa(const void* sa, uint64_t n, uint32_t rank) {
+    return (uint32_t)REST_IDX(((const SaT*)sa)[REST_IDX(rank, n, 0)], n, 1);
 }
 
 // tokens pos .. pos+3 of the stream with one read (element-wise, -1 past the end, for the last three positions)
@@ -186,8 +187,8 @@ __device__ void wave_search(const RetrieveParams& p, const int32_t* lds_tab, con
         if (go1) r1 = lo.probe(lane, real1);
         if (go2) r2 = hi.probe(lane, real2);
         uint32_t pos1 = 0, pos2 = 0;
-        if (real1) pos1 = load_sa<SaT>(p.sa, r1);
-        if (real2) pos2 = load_sa<SaT>(p.sa, r2);
+        if (real1) pos1 = load_sa<SaT>(p.sa, p.n_tokens, r1);
+        if (real2) pos2 = load_sa<SaT>(p.sa, p.n_tokens, r2);
         int c1, c2;
         cmp_suffix2<TokT>(p.corpus, p.n_tokens, pos1, real1, pos2, real2, q, n, c1, c2);
         if (__ballot((real1 && c1 == 0) || (real2 && c2 == 0)) && lane == 0) atomicMin(best, wave);
@@ -383,7 +384,7 @@ __global__ __launch_bounds__(kThreads) void retrieve_kernel(RetrieveParams p) {
         int32_t tok[REST_MAX_CONT_LEN];
         int len = 0;
         if (r < R) {
-            const uint32_t start = load_sa<SaT>(p.sa, kept_entry(r));
+            const uint32_t start = load_sa<SaT>(p.sa, p.n_tokens, kept_entry(r));
             rowpos[r] = start;
             const uint64_t pos = (uint64_t)start + n_star;
             const uint64_t left = p.n_tokens > pos ? p.n_tokens - pos : 0;
@@ -405,7 +406,7 @@ __global__ __launch_bounds__(kThreads) void retrieve_kernel(RetrieveParams p) {
         bool run = true;
         uint64_t ppos = 0;
         if (lane == 0 && r > 0 && r < R) {
-            ppos = (uint64_t)load_sa<SaT>(p.sa, kept_entry(r - 1)) + n_star;
+            ppos = (uint64_t)load_sa<SaT>(p.sa, p.n_tokens, kept_entry(r - 1)) + n_star;
             const uint64_t left = p.n_tokens > ppos ? p.n_tokens - ppos : 0;
             plen = left < (uint64_t)m ? (int)left : m;
         }
@@ -681,7 +682,7 @@ __global__ void top_table_kernel(const void* corpus, const void* sa, uint64_t n,
     int32_t v = 0;
     if (k < top_count) {
         const uint32_t rank = (uint32_t)rest_top_rank(n, top_count, k);
-        v = j < 0 ? (int32_t)rank : load_tok<TokT>(corpus, n, (uint64_t)load_sa<SaT>(sa, rank) + j);
+        v = j < 0 ? (int32_t)rank : load_tok<TokT>(corpus, n, (uint64_t)load_sa<SaT>(sa, n, rank) + j);
     }
     tab[i] = v;
 }
@@ -717,6 +718,7 @@ rest_status launch(const RetrieveParams& p, int B, size_t lds_bytes, hipStream_t
     }
     hipLaunchKernelGGL(kern, dim3(B), dim3(kThreads), lds_bytes, stream, p);
     REST_HIP_TRY(hipGetLastError());
+    REST_BOUNDS_EPILOGUE(stream);
     return REST_OK;
 }
 
@@ -744,6 +746,7 @@ rest_status rest_internal_make_top_table(rest_index* idx, hipStream_t stream) {
         REST_HIP_TRY(hipGetLastError());
     }
     REST_HIP_TRY(hipStreamSynchronize(stream));
+    REST_BOUNDS_EPILOGUE(stream);
     return REST_OK;
 }
 

@@ -2,247 +2,478 @@
 // "Sampling strategies"; temperature and top-p as in the caption of the main speed table).  REST accepts a draft
 // token only if it equals the token sampled at its position, so the ids written here feed rest_accept unchanged.
 //
-// Definition (the paper fixes the parameters, not the mechanics): probabilities = softmax(logits / temperature);
-// tokens ordered by probability, highest first, equal probabilities by ascending token id; the nucleus is the
-// shortest prefix of that order whose mass reaches top_p; the draw is the first token whose cumulative mass
-// exceeds u times the nucleus mass, u in [0, 1) given by the caller.
+// Definition (the paper fixes the parameters, not the mechanics; this one fixes the result to the last bit):
+//  * probability masses are integers: token i weighs w_i = floor(2^36 * E((x_i - x_max) * c)), c = log2(e) /
+//    temperature, with E(y) = 2^y evaluated by a fixed sequence of correctly rounded fp64 operations (weight_of
+//    below); sums of weights are exact, so they do not depend on the order of summation;
+//  * tokens are ordered by logit, highest first (+0 and -0 are one value), equal logits by ascending token id;
+//  * the nucleus is the shortest prefix of that order whose mass C_k satisfies double(C_k) >= double(top_p) * double(W),
+//    W the row's total mass; the draw is the first token whose cumulative mass satisfies double(C_j) > double(u) *
+//    double(M), M the nucleus mass, u in [0, 1) given by the caller.
 //
-// One 512-thread workgroup per position; a thread keeps its 64 logits (as order-preserving 32-bit keys) and their
-// exponentials (fp64) in registers.  Nothing is sorted: "the place in the sorted order where the cumulative mass
-// crosses a threshold" is found by descending the key four bits at a time.  At each level every thread adds its
-// matching elements into 16 private fp64 slots in LDS (no atomics, no conflicts), each bucket is summed over the
-// threads by one wavefront in a fixed order, and every thread walks the 16 bucket masses from the top.  Eight levels pin the key;
-// equal keys are then resolved arithmetically (their masses are equal) and by ascending token id through ballots.
-// All sums have a fixed order, so results repeat bit for bit from run to run.
-#include <mutex>
-
+// Nothing is sorted.  "The place in the order where the cumulative mass crosses a threshold" is found by descending
+// the order-preserving 32-bit key of the logit: 11 bits, 11 bits, 10 bits.  The first level's histogram of masses is
+// built by all workgroups of a row together (each adds its slice of the row into LDS, then its non-empty buckets into
+// the row's histogram in memory; integer adds, any order); the workgroup that arrives last at the row's ticket does
+// the rest alone: crossing bucket of level one, then two passes over the row for the lower levels (only the few
+// elements of the chosen bucket are weighed again), the rank among equal logits by integer arithmetic, the same
+// for the draw, and one pass to find the token of that rank.  No workgroup waits for another.
 #include "common.h"
 
 namespace {
 
-constexpr int kThreads = 512;            // 8 wavefronts: 256 VGPRs each, room for 64 keys and 64 fp64 masses
-constexpr int kPer = 64;                 // elements per thread: V <= 32768
+typedef unsigned long long u64;
+
+constexpr int kThreads = 1024;
 constexpr int kWaves = kThreads / 64;
+constexpr int kMaxSlices = 16;             // workgroups that share a row in the histogram phase, at most
+constexpr int kBatch = 16;                 // reads a thread has in flight when it walks over a row
+constexpr int kCap = 1024;                 // tokens of one level-one cell that the list in LDS holds: one per thread
+constexpr int kMaxVocab = 1 << 17;         // sums of up to 2^17 weights of at most 2^36 stay below 2^53
+constexpr int kWeightBits = 36;
+constexpr int kL1 = 2048, kL2 = 2048, kL3 = 1024;     // buckets per level: key bits 31..21, 20..10, 9..0
+constexpr int kRowWords = kL1 + 32;        // per row in the workspace: the level-one histogram, then 32 words: slice
+                                           // maxima (floats, two to a word, up to kMaxSlices) and the ticket
+
+// A row is cut into slices of slice_len tokens, one workgroup each: as many as keep all workgroups of the launch on
+// the chip at once (256 compute units, one workgroup of 1024 threads each), at least 2048 tokens long.
+struct Slicing { int slices, slice_len; };
+inline Slicing slicing_of(int R, int V) {
+    int s = 256 / (R > 0 ? R : 1);
+    if (s > kMaxSlices) s = kMaxSlices;
+    if (s > (V + 2047) / 2048) s = (V + 2047) / 2048;
+    if (s < 1) s = 1;
+    Slicing out;
+    out.slice_len = ((V + s - 1) / s + 63) / 64 * 64;
+    out.slices = (V + out.slice_len - 1) / out.slice_len;
+    return out;
+}
 
 __device__ inline uint32_t key_of(float x) {
     if (x == 0.f) x = 0.f;               // -0 and +0 are the same logit
     const uint32_t b = __builtin_bit_cast(uint32_t, x);
     return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
 }
-__device__ inline float float_of(uint32_t k) {
-    const uint32_t b = (k & 0x80000000u) ? (k & 0x7fffffffu) : ~k;
-    return __builtin_bit_cast(float, b);
+
+__device__ inline float logit_of_key(uint32_t k) {
+    return __builtin_bit_cast(float, (k & 0x80000000u) ? (k & 0x7fffffffu) : ~k);
 }
 
-struct Crossing {
-    uint32_t key;       // key of the element at which the cumulative mass crosses the target
-    double above;       // mass of all elements with a larger key
-    long long rank;     // 1-based position of the crossing element among those with this key
-    long long ties;     // number of elements with this key
-    double each;        // mass of one of them
-    bool found;
+// Level one of the search: 2048 cells, linear in how far a logit lies below the row's largest one (cell 0 holds the
+// largest), scaled so that cell 2047 starts where the weights have long been zero.  Any function that never grows
+// with the logit would do -- the cells only have to respect the order --; a linear one keeps the cell around the
+// nucleus boundary small (tens of tokens of a 32000-token row), which is what the second stage costs by.
+__device__ inline int cell_of(float x, float top, float scale) {
+    const float d = (top - x) * scale;        // >= 0; +inf for a logit of -inf
+    return d < 2047.f ? (int)d : 2047;
+}
+
+// w = floor(2^36 * E((x - top) * c)): n = floor(y), f = y - n, t = f * ln 2, E = 2^n * P(t) with P the Taylor polynomial
+// of exp of degree 13 in Horner form; every step is one multiplication and one addition, each correctly rounded (no
+// fused multiply-add), so the value is the same on every machine that computes in IEEE fp64.
+__device__ inline u64 weight_of(float x, float top, double c) {
+#pragma clang fp contract(off)
+    const double y = ((double)x - (double)top) * c;
+    if (!(y >= -64.0)) return 0ull;        // below 2^-64 of the largest (also -inf): nothing
+    const double n = floor(y);
+    const double t = (y - n) * 0x1.62e42fefa39efp-1;
+    constexpr double k[14] = {0x1.0000000000000p+0,  0x1.0000000000000p+0,  0x1.0000000000000p-1,  0x1.5555555555555p-3,
+                              0x1.5555555555555p-5,  0x1.1111111111111p-7,  0x1.6c16c16c16c17p-10, 0x1.a01a01a01a01ap-13,
+                              0x1.a01a01a01a01ap-16, 0x1.71de3a556c734p-19, 0x1.27e4fb7789f5cp-22, 0x1.ae64567f544e4p-26,
+                              0x1.1eed8eff8d898p-29, 0x1.6124613a86d09p-33};      // 1 / k!
+    double p = k[13];
+#pragma unroll
+    for (int i = 12; i >= 0; i--) {
+        p = p * t;
+        p = p + k[i];
+    }
+    return (u64)floor(ldexp(p, (int)n + kWeightBits));
+}
+
+// Calls fn(index, logit) for every token in [begin, end) of row g, the workgroup's threads side by side.  A thread's
+// reads come in batches that are all issued before the first is used: a walk is bound by the latency of a read
+// (the row sits in the L2 cache by then), so the number of reads in flight sets its time.
+template <typename Fn>
+__device__ inline void for_each_token(const float* g, int begin, int end, Fn fn) {
+    for (int base = begin; base < end; base += kThreads * kBatch) {
+        float xs[kBatch];
+#pragma unroll
+        for (int j = 0; j < kBatch; j++) {
+            const int i = base + j * kThreads + (int)threadIdx.x;
+            xs[j] = i < end ? g[i] : 0.f;
+        }
+#pragma unroll
+        for (int j = 0; j < kBatch; j++) {
+            const int i = base + j * kThreads + (int)threadIdx.x;
+            if (i < end) fn(i, xs[j]);
+        }
+    }
+}
+
+__device__ inline u64 shfl_up_u64(u64 v, int d) {
+    const uint32_t lo = __shfl_up((uint32_t)v, d, 64), hi = __shfl_up((uint32_t)(v >> 32), d, 64);
+    return ((u64)hi << 32) | lo;
+}
+
+// exclusive prefix sum over the workgroup's threads in thread order; `total` = sum over all threads
+__device__ __noinline__ u64 block_exclusive_scan(u64 v, u64* wave_sums /* LDS, kWaves + 1 */, u64& total) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    u64 incl = v;
+    for (int off = 1; off < 64; off <<= 1) {
+        const u64 y = shfl_up_u64(incl, off);
+        if (lane >= off) incl += y;
+    }
+    __syncthreads();                       // the previous use of wave_sums is over
+    if (lane == 63) wave_sums[wave] = incl;
+    __syncthreads();
+    u64 before = 0, all = 0;
+    for (int w = 0; w < kWaves; w++) {
+        if (w < wave) before += wave_sums[w];
+        all += wave_sums[w];
+    }
+    total = all;
+    return before + incl - v;
+}
+
+struct Found {
+    int bucket;      // first bucket (walking from the highest down) at which the cumulative mass meets the condition
+    u64 above;       // mass of everything before that bucket, `base` included
 };
 
-__global__ __launch_bounds__(kThreads) void sample_kernel(const float* logits, int64_t stride, const float* u, int V,
-                                                          double temperature, double top_p, int32_t* ids) {
-    extern __shared__ double acc[];                    // [16][kThreads]
-    __shared__ double level_mass[8][16];   // bucket masses of the first descent, per level
-    __shared__ double scratch_mass[16];
-    __shared__ uint32_t level_prefix[8];
-    __shared__ float red_f[kWaves];
-    __shared__ int red_i[kWaves];
-    __shared__ int row_cnt[kPer][kWaves];
-    __shared__ int pick[3];
-    if (threadIdx.x == 0) { pick[0] = 0; pick[1] = 0; pick[2] = 1; }
-    const int row = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const float* g = logits + (int64_t)row * stride;
+// The buckets of `hist` (LDS, nb of them) are walked in the order of falling logits -- from the highest bucket down
+// (descending) or from bucket 0 up -- starting at cumulative mass `base`; the crossing is the first bucket whose
+// inclusive cumulative mass C has double(C) >= thr (strict: > thr).  Every thread returns the same answer; bucket =
+// -1 if no bucket meets the condition (the callers never ask for that).
+__device__ __noinline__ Found find_crossing(const u64* hist, int nb, bool descending, u64 base, double thr, bool strict,
+                                      u64* wave_sums, int* out_bucket, u64* out_above) {
+    const int per = nb / kThreads, tid = threadIdx.x;
+    // this thread's buckets, in walking order: first, first + step, ...
+    const int first = descending ? nb - 1 - tid * per : tid * per, step = descending ? -1 : 1;
+    u64 mine = 0;
+    for (int i = 0; i < per; i++) mine += hist[first + i * step];
+    u64 total;
+    u64 cum = base + block_exclusive_scan(mine, wave_sums, total);
+    auto met = [&](u64 c) { return strict ? (double)c > thr : (double)c >= thr; };
+    if (tid == 0) *out_bucket = -1;
+    __syncthreads();
+    if (!met(cum) && met(cum + mine)) {    // the crossing lies in this thread's buckets: exactly one thread gets here
+        for (int i = 0; i < per; i++) {
+            const u64 next = cum + hist[first + i * step];
+            if (met(next)) {
+                *out_bucket = first + i * step;
+                *out_above = cum;
+                break;
+            }
+            cum = next;
+        }
+    }
+    __syncthreads();
+    Found f;
+    f.bucket = *out_bucket;
+    f.above = *out_above;
+    return f;
+}
 
-    uint32_t key[kPer];
-    double e[kPer];
+// smallest r in [1, ties] with met(above + r * each); the caller knows that r = ties meets it
+__device__ inline u64 rank_among_equals(u64 above, u64 each, u64 ties, double thr, bool strict) {
+    auto met = [&](u64 r) { const u64 c = above + r * each; return strict ? (double)c > thr : (double)c >= thr; };
+    const double gap = thr - (double)above;
+    u64 r = 1;
+    if (gap > 0.0) {
+        const double q = gap / (double)each;
+        r = q >= (double)ties ? ties : (u64)q;
+    }
+    r = r < 1 ? 1 : (r > ties ? ties : r);
+    while (r > 1 && met(r - 1)) r--;
+    while (r < ties && !met(r)) r++;
+    return r;
+}
+
+// Masses of the tokens of cell `cell` by a field of their keys (nb buckets from bit `shift`), among the tokens whose key
+// bits from want_shift up equal `want` (want_shift 32: all of them), straight from the row: the path for a cell
+// with more tokens than the list in LDS holds (thousands of equal or nearly equal logits).  Every token is weighed
+// again here; kept out of line so that the usual path does not carry its code.
+__device__ __noinline__ void fill_from_row(u64* hist, int nb, int shift, uint32_t want, int want_shift, const float* g, int V,
+                                           int cell, float top, float scale, double c) {
+    for (int i = threadIdx.x; i < V; i += kThreads) {
+        const float x = g[i];
+        const uint32_t k = key_of(x);
+        if (cell_of(x, top, scale) == cell && (want_shift >= 32 || (k >> want_shift) == want)) {
+            const u64 wt = weight_of(x, top, c);
+            if (wt) atomicAdd(&hist[(k >> shift) & (uint32_t)(nb - 1)], wt);
+        }
+    }
+}
+
+struct SampleParams {
+    const float* logits;
+    int64_t stride;
+    const float* u;
+    int32_t* ids;
+    u64* ws;              // [R][kRowWords]
+    int32_t R, V, slices, slice_len;
+    double c;             // log2(e) / temperature
+    float scale;          // cells per unit of logit: c * 2047 / 64.5
+    double top_p;
+};
+
+// Phase 0: slice maxima, and the row's histogram and ticket put to zero (the workspace needs no initialisation).
+__global__ __launch_bounds__(kThreads) void sample_prepare_kernel(SampleParams p) {
+    __shared__ float red[kWaves];
+    const int row = blockIdx.x / p.slices, slice = blockIdx.x % p.slices, tid = threadIdx.x;
+    const float* g = p.logits + (int64_t)row * p.stride;
+    u64* w = p.ws + (int64_t)row * kRowWords;
     float mx = -INFINITY;
-#pragma unroll
-    for (int i = 0; i < kPer; i++) {
-        const int j = i * kThreads + tid;
-        const float x = j < V ? g[j] : -INFINITY;
-        key[i] = j < V ? key_of(x) : 0u;       // key 0 (a NaN pattern) marks padding: mass 0, never a crossing key
-        mx = fmaxf(mx, x);
-    }
+    for_each_token(g, slice * p.slice_len, min(p.V, (slice + 1) * p.slice_len), [&](int, float x) { mx = fmaxf(mx, x); });
     for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
-    if (lane == 0) red_f[wave] = mx;
+    if ((tid & 63) == 0) red[tid >> 6] = mx;
+    // this workgroup's share of the histogram's buckets
+    const int share = (kL1 + p.slices - 1) / p.slices;
+    for (int b = slice * share + tid; b < min(kL1, (slice + 1) * share); b += kThreads) w[b] = 0ull;
     __syncthreads();
-    for (int w = 0; w < kWaves; w++) mx = fmaxf(mx, red_f[w]);
-    const double zmax = (double)mx / temperature;
+    if (tid == 0) {
+        for (int i = 1; i < kWaves; i++) mx = fmaxf(mx, red[i]);
+        ((float*)(w + kL1))[slice] = mx;
+        if (slice == 0) w[kL1 + 31] = 0ull;                   // the ticket
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void sample_select_kernel(SampleParams p) {
+    __shared__ u64 h1[kL1];                    // masses per cell
+    __shared__ u64 h2[kL2];                    // (large cells only) masses by key bits
+    __shared__ u64 h3[kL3];
+    __shared__ int cnt[kMaxVocab / 64];        // (large cells only) per group of 64 tokens: matches, then their prefix sum
+    __shared__ uint32_t list_k[kCap];          // the tokens of one cell, in no particular order: key, index, weight
+    __shared__ int list_i[kCap];
+    __shared__ u64 list_w[kCap];
+    __shared__ u64 wave_sums[kWaves + 1];
+    __shared__ int s_bucket;
+    __shared__ u64 s_above;
+    __shared__ int s_last;
+    __shared__ int s_n;                        // tokens in the cell
+    __shared__ int s_found;                    // index of the crossing token, -1: none
+    __shared__ u64 s_mass;                     // cumulative mass up to and including it
+    const int row = blockIdx.x / p.slices, slice = blockIdx.x % p.slices, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const float* g = p.logits + (int64_t)row * p.stride;
+    u64* w = p.ws + (int64_t)row * kRowWords;
+
+    float top = -INFINITY;
+    {
+        float tops[kMaxSlices];                           // all reads in flight together
 #pragma unroll
-    for (int i = 0; i < kPer; i++) {
-        const int j = i * kThreads + tid;
-        e[i] = j < V ? exp((double)float_of(key[i]) / temperature - zmax) : 0.0;
+        for (int sidx = 0; sidx < kMaxSlices; sidx++) tops[sidx] = sidx < p.slices ? ((const float*)(w + kL1))[sidx] : -INFINITY;
+#pragma unroll
+        for (int sidx = 0; sidx < kMaxSlices; sidx++) top = fmaxf(top, tops[sidx]);
     }
 
-    // descends the key to the element where the cumulative mass (largest key first) first reaches (strict: exceeds)
-    // `target`.  A recording descent keeps the bucket masses of its levels (1 KB); a later descent reuses them for as
-    // long as it follows the same prefix -- usually through the first levels (sign and exponent bits), which are the
-    // expensive ones because nearly every element takes part in them.
-    int levels_kept = 0;                           // same value in every thread
-    auto select = [&](double target, bool strict, bool record) -> Crossing {
-        Crossing c{};
-        uint32_t prefix = 0;
-        double cum = 0.0;
-        c.found = true;
-        bool follow = true;
-        for (int lvl = 0; lvl < 8; lvl++) {
-            const double* masses = &level_mass[lvl][0];
-            follow = follow && lvl < levels_kept && level_prefix[lvl] == prefix;
-            if (!follow) {
-#pragma unroll
-                for (int d = 0; d < 16; d++) acc[d * kThreads + tid] = 0.0;
-                const int sh = 28 - 4 * lvl;
-#pragma unroll
-                for (int i = 0; i < kPer; i++) {
-                    const bool match = lvl == 0 || (key[i] >> (sh + 4)) == prefix;
-                    // a private slot: the atomic is only a read-modify-write the wavefront need not wait for
-                    if (match)
-                        __hip_atomic_fetch_add(&acc[((key[i] >> sh) & 15u) * kThreads + tid], e[i], __ATOMIC_RELAXED,
-                                               __HIP_MEMORY_SCOPE_WORKGROUP);
-                }
-                __syncthreads();
-                double* dst = record ? &level_mass[lvl][0] : &scratch_mass[0];
-                for (int b = wave; b < 16; b += kWaves) {
-                    double s = 0.0;
-#pragma unroll
-                    for (int t = 0; t < kThreads / 64; t++) s += acc[b * kThreads + lane + 64 * t];
-                    for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
-                    if (lane == 0) dst[b] = s;
-                }
-                if (record) {
-                    if (tid == 0) level_prefix[lvl] = prefix;
-                    levels_kept = lvl + 1;          // deeper kept levels belonged to another prefix
-                }
-                __syncthreads();
-                masses = dst;
-            }
-            int d = 15;
-            for (; d >= 0; d--) {
-                const double next = cum + masses[d];
-                if (strict ? next > target : next >= target) break;
-                cum = next;
-            }
-            if (d < 0) {            // rounding left the total just under the target
-                c.found = false;
-                c.above = cum;
-                return c;
-            }
-            prefix = (prefix << 4) | (uint32_t)d;
-        }
-        c.key = prefix;
-        c.above = cum;
-        // elements with this key: how many, and which of them is the crossing one
-        int n = 0;
-#pragma unroll
-        for (int i = 0; i < kPer; i++) n += __popcll(__ballot(key[i] == prefix));
-        if (lane == 0) red_i[wave] = n;
+    // ---- all workgroups: masses of this slice per cell, into LDS, then the non-empty cells into the row's histogram
+    // in memory
+    for (int b = tid; b < kL1; b += kThreads) h1[b] = 0ull;
+    __syncthreads();
+    for_each_token(g, slice * p.slice_len, min(p.V, (slice + 1) * p.slice_len), [&](int, float x) {
+        const u64 wt = weight_of(x, top, p.c);
+        if (wt) atomicAdd(&h1[cell_of(x, top, p.scale)], wt);
+    });
+    __syncthreads();
+    for (int b = tid; b < kL1; b += kThreads) {
+        const u64 v = h1[b];
+        if (v) (void)__hip_atomic_fetch_add(w + b, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    // The adds above are device-scope atomics (performed where every compute unit sees them); each wavefront waits
+    // until its own have been acknowledged, the workgroup meets, and only then its arrival is counted: whoever counts
+    // the last arrival finds every slice's masses in the histogram.
+    __builtin_amdgcn_s_waitcnt(0x0F70);                 // vmcnt(0)
+    __syncthreads();
+    if (tid == 0) {
+        const u64 old = __hip_atomic_fetch_add(w + kL1 + 31, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        s_last = old + 1 == (u64)p.slices ? 1 : 0;
+    }
+    __syncthreads();
+    if (!s_last) return;
+
+    // ---- the row's last workgroup
+    u64 part = 0;
+    for (int b = tid; b < kL1; b += kThreads) {
+        const u64 v = __hip_atomic_load(w + b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        h1[b] = v;
+        part += v;
+    }
+    u64 total;
+    (void)block_exclusive_scan(part, wave_sums, total);
+    __syncthreads();
+
+    // Two descents by the same code, first the nucleus (the shortest prefix with mass >= top_p * total), then the draw
+    // (the first token with cumulative mass > u * nucleus mass).  A descent finds the cell in which the cumulative
+    // mass (highest logit first) meets the threshold, gathers that cell's tokens -- tens of them, as a rule -- into a
+    // list in LDS, weighs them, and lets every listed token add up the mass of the listed tokens that come before it
+    // in the order (higher logit, or equal logit and smaller index): the crossing token is the one whose own weight
+    // carries the cumulative mass over the threshold.  A cell with more tokens than the list holds (thousands of
+    // equal or nearly equal logits) is searched in the row itself instead, by the key's bits.
+    double thr = p.top_p * (double)total;
+    bool strict = false;
+    int token = 0;
+    for (int pass = 0; pass < 2; pass++) {
+        auto met = [&](u64 cm) { return strict ? (double)cm > thr : (double)cm >= thr; };
+        const Found f1 = find_crossing(h1, kL1, false, 0ull, thr, strict, wave_sums, &s_bucket, &s_above);
+        if (f1.bucket < 0) break;                         // cannot happen: the thresholds used here are always met
+        const int cell = f1.bucket;
+        if (tid == 0) { s_n = 0; s_found = -1; }
         __syncthreads();
-        long long ties = 0;
-        for (int w = 0; w < kWaves; w++) ties += red_i[w];
-        __syncthreads();
-        c.ties = ties;
-        c.each = exp((double)float_of(prefix) / temperature - zmax);
-        long long r = 1;
-        if (c.each > 0.0) {
-            const double q = (target - cum) / c.each;
-            r = strict ? (long long)floor(q) + 1 : (long long)ceil(q);
-        }
-        r = r < 1 ? 1 : (r > ties ? ties : r);
-        auto reached = [&](long long k) { const double m = cum + (double)k * c.each; return strict ? m > target : m >= target; };
-        while (r > 1 && reached(r - 1)) r--;
-        while (r < ties && !reached(r)) r++;
-        c.rank = r;
-        return c;
-    };
-
-    // the nucleus and its mass.  The total is the sum of the level-0 bucket masses in the order of a descent's walk,
-    // so the first descent is run with an unreachable target and stops after that level.
-    const double total = select(INFINITY, false, true).above;
-    // the nucleus descent reuses level 0 and records its own deeper levels; the draw follows it while it can
-    const Crossing nuc = select(top_p * total, false, true);
-    const double mass = nuc.found ? nuc.above + (double)nuc.rank * nuc.each : nuc.above;
-    Crossing hit = select((double)u[row] * mass, true, false);
-    if (!hit.found) hit = nuc;                         // cannot happen for u < 1 except through rounding
-    if (!hit.found) {                                  // nor this: the total is positive
-        if (tid == 0) ids[row] = 0;
-        return;
-    }
-
-    // token id = the hit.rank-th smallest index among the elements with key hit.key; index = i * kThreads + tid
+        for (int base = 0; base < p.V; base += kThreads * kBatch) {
+            float xs[kBatch];
 #pragma unroll
-    for (int i = 0; i < kPer; i++) {
-        const uint64_t b = __ballot(key[i] == hit.key);
-        if (lane == 0) row_cnt[i][wave] = __popcll(b);
-    }
-    __syncthreads();
-    if (wave == 0) {
-        // kPer * kWaves = 512 counts in index order (i major, wavefront minor), 8 per lane
-        static_assert(kPer * kWaves == 512, "eight counts per lane");
-        const int* flat = &row_cnt[0][0];
-        int mine = 0;
-        for (int t = 0; t < 8; t++) mine += flat[lane * 8 + t];
-        int incl = mine;
-        for (int off = 1; off < 64; off <<= 1) {
-            const int y = __shfl_up(incl, off, 64);
-            if (lane >= off) incl += y;
-        }
-        const int before = incl - mine;
-        const long long want = hit.rank;
-        if ((long long)before < want && want <= (long long)incl) {
-            int run = before;
-            for (int t = 0; t < 8; t++) {
-                const int c = flat[lane * 8 + t];
-                if ((long long)(run + c) >= want) {
-                    pick[0] = (lane * 8 + t) / kWaves;        // i
-                    pick[1] = (lane * 8 + t) % kWaves;        // wavefront
-                    pick[2] = (int)(want - run);               // 1-based among that ballot's set bits
-                    break;
+            for (int j = 0; j < kBatch; j++) {
+                const int i = base + j * kThreads + tid;
+                xs[j] = i < p.V ? g[i] : 0.f;
+            }
+#pragma unroll
+            for (int j = 0; j < kBatch; j++) {
+                const int i = base + j * kThreads + tid;
+                const bool m = i < p.V && cell_of(xs[j], top, p.scale) == cell;
+                const u64 ballot = __ballot(m);
+                if (ballot) {                              // one counter update per wavefront and step
+                    int start = 0;
+                    if (lane == 0) start = atomicAdd(&s_n, __popcll(ballot));
+                    start = __shfl(start, 0, 64);
+                    const int pos = start + __popcll(ballot & ((1ull << lane) - 1ull));
+                    if (m && pos < kCap) {
+                        list_k[pos] = key_of(xs[j]);
+                        list_i[pos] = i;
+                    }
                 }
-                run += c;
             }
         }
+        __syncthreads();
+        const int n = s_n;
+        u64 mass = 0;
+        if (n <= kCap) {
+            if (tid < n) list_w[tid] = weight_of(logit_of_key(list_k[tid]), top, p.c);
+            __syncthreads();
+            if (tid < n) {
+                const uint32_t k = list_k[tid];
+                const int i = list_i[tid];
+                u64 before = f1.above;
+                for (int f = 0; f < n; f++) {
+                    const uint32_t kf = list_k[f];
+                    if (kf > k || (kf == k && list_i[f] < i)) before += list_w[f];
+                }
+                const u64 mine = list_w[tid];
+                if (!met(before) && met(before + mine)) {
+                    s_found = i;
+                    s_mass = before + mine;
+                }
+            }
+            __syncthreads();
+            if (s_found < 0) break;                       // cannot happen
+            token = s_found;
+            mass = s_mass;
+        } else {
+            // three levels of key bits inside the cell, masses straight from the row
+            uint32_t want = 0;
+            u64 above = f1.above;
+            bool ok = true;
+            for (int level = 0; level < 3 && ok; level++) {
+                u64* hist = level < 2 ? h2 : h3;
+                const int nb = level < 2 ? kL2 : kL3, shift = level == 0 ? 21 : (level == 1 ? 10 : 0);
+                const int want_shift = level == 0 ? 32 : (level == 1 ? 21 : 10);
+                for (int b = tid; b < nb; b += kThreads) hist[b] = 0ull;
+                __syncthreads();
+                fill_from_row(hist, nb, shift, want, want_shift, g, p.V, cell, top, p.scale, p.c);
+                __syncthreads();
+                const Found f = find_crossing(hist, nb, true, above, thr, strict, wave_sums, &s_bucket, &s_above);
+                ok = f.bucket >= 0;
+                above = f.above;
+                want = level == 0 ? (uint32_t)f.bucket : (level == 1 ? (want << 11) | (uint32_t)f.bucket : (want << 10) | (uint32_t)f.bucket);
+            }
+            if (!ok) break;
+            const uint32_t key = want;
+            const u64 each = weight_of(logit_of_key(key), top, p.c);  // equal keys are equal logits, hence equal weights
+            const u64 ties = each ? h3[key & (kL3 - 1)] / each : 0ull;
+            __syncthreads();                              // h3 is read above by every thread before anyone reuses it
+            if (ties == 0) break;
+            const u64 r = rank_among_equals(above, each, ties, thr, strict);
+            mass = above + r * each;
+            if (pass == 1) {
+                // the token: the r-th smallest index among the tokens with this key.  Matches are counted per group
+                // of 64 consecutive tokens, the counts are scanned, and the match of that rank reports itself.
+                for (int j = tid; j < kMaxVocab / 64; j += kThreads) cnt[j] = 0;
+                __syncthreads();
+                for (int step = 0; step < 2; step++) {
+                    for (int i0 = wave * 64; i0 < p.V; i0 += kThreads) {
+                        const int i = i0 + lane;
+                        const bool m = i < p.V && key_of(g[i]) == key;
+                        const u64 ballot = __ballot(m);
+                        if (step == 0) {
+                            if (lane == 0) cnt[i0 >> 6] = __popcll(ballot);
+                        } else if (m && (u64)(cnt[i0 >> 6] + __popcll(ballot & ((1ull << lane) - 1ull))) + 1 == r) {
+                            s_found = i;
+                        }
+                    }
+                    __syncthreads();
+                    if (step == 0) {
+                        constexpr int kPer = (kMaxVocab / 64) / kThreads;          // 2
+                        u64 mine = 0;
+                        for (int j = 0; j < kPer; j++) mine += (u64)cnt[tid * kPer + j];
+                        u64 all;
+                        u64 run = block_exclusive_scan(mine, wave_sums, all);
+                        for (int j = 0; j < kPer; j++) {
+                            const int c = cnt[tid * kPer + j];
+                            cnt[tid * kPer + j] = (int)run;
+                            run += (u64)c;
+                        }
+                        __syncthreads();
+                    }
+                }
+                if (s_found < 0) break;                   // cannot happen
+                token = s_found;
+            }
+        }
+        if (pass == 0) {
+            thr = (double)p.u[row] * (double)mass;        // mass: the nucleus mass
+            strict = true;
+            token = 0;
+        }
     }
-    __syncthreads();
-    if (wave == pick[1]) {
-        const int i_star = pick[0];
-        bool m = false;
-#pragma unroll
-        for (int i = 0; i < kPer; i++)
-            if (i == i_star) m = key[i] == hit.key;
-        const uint64_t b = __ballot(m);
-        const int below = __popcll(b & ((1ull << lane) - 1ull));
-        if (m && below == pick[2] - 1) ids[row] = i_star * kThreads + tid;
-    }
+    // token: the draw, or 0 if a step that cannot fail did
+    if (tid == 0) p.ids[row] = token;
 }
 
 }  // namespace
 
+extern "C" __attribute__((visibility("default"))) size_t rest_sample_ids_workspace_bytes(int32_t R, int32_t V) {
+    if (R < 0 || V < 1 || V > kMaxVocab) return 0;
+    return (size_t)R * kRowWords * sizeof(u64);
+}
+
 extern "C" __attribute__((visibility("default"))) rest_status rest_sample_ids(const float* d_logits, int64_t row_stride, const float* d_u, int32_t R,
-                                       int32_t V, float temperature, float top_p, int32_t* d_ids, void* stream) {
+                                       int32_t V, float temperature, float top_p, int32_t* d_ids, void* d_workspace,
+                                       size_t workspace_bytes, void* stream) {
     if (!d_logits || !d_u || !d_ids) return REST_INVALID_ARG;
     if (R < 0 || V < 1 || row_stride < V) return REST_INVALID_ARG;
     if (!(temperature > 0.f) || !(temperature < 1e30f) || !(top_p > 0.f) || !(top_p <= 1.f)) return REST_INVALID_ARG;
-    if (V > kThreads * kPer) return REST_UNSUPPORTED;
+    if (V > kMaxVocab) return REST_UNSUPPORTED;
     if (R == 0) return REST_OK;
-    const size_t lds = (size_t)16 * kThreads * sizeof(double);
-    static bool granted[64] = {false};
-    static std::mutex granted_lock;                 // host threads may call at once
-    int dev = 0;
-    REST_HIP_TRY(hipGetDevice(&dev));
-    if (dev < 0 || dev >= 64) return REST_UNSUPPORTED;
-    {
-        std::lock_guard<std::mutex> hold(granted_lock);
-        if (!granted[dev]) {
-            REST_HIP_TRY(hipFuncSetAttribute((const void*)sample_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-            granted[dev] = true;
-        }
-    }
-    hipLaunchKernelGGL(sample_kernel, dim3(R), dim3(kThreads), lds, (hipStream_t)stream, d_logits, row_stride, d_u, V,
-                       (double)temperature, (double)top_p, d_ids);
+    const size_t need = rest_sample_ids_workspace_bytes(R, V);
+    if (!d_workspace || workspace_bytes < need) return REST_WORKSPACE_TOO_SMALL;
+    if ((uintptr_t)d_workspace & 7) return REST_INVALID_ARG;
+    const Slicing sl = slicing_of(R, V);
+    if ((int64_t)R * sl.slices > 0x7fffffff) return REST_INVALID_ARG;
+    SampleParams p;
+    p.logits = d_logits;
+    p.stride = row_stride;
+    p.u = d_u;
+    p.ids = d_ids;
+    p.ws = (u64*)d_workspace;
+    p.R = R;
+    p.V = V;
+    p.slices = sl.slices;
+    p.slice_len = sl.slice_len;
+    p.c = 0x1.71547652b82fep+0 / (double)temperature;         // log2(e) / temperature, one fp64 division
+    p.scale = (float)(p.c * (2047.0 / 64.5));
+    p.top_p = (double)top_p;
+    hipLaunchKernelGGL(sample_prepare_kernel, dim3(R * p.slices), dim3(kThreads), 0, (hipStream_t)stream, p);
+    REST_HIP_TRY(hipGetLastError());
+    hipLaunchKernelGGL(sample_select_kernel, dim3(R * p.slices), dim3(kThreads), 0, (hipStream_t)stream, p);
     REST_HIP_TRY(hipGetLastError());
     return REST_OK;
 }

@@ -28,7 +28,7 @@ def declared_functions():
 
 def test_header_functions_are_exported(rest):
     names = declared_functions()
-    assert len(names) == 19 and "rest_retrieve" in names and "rest_tree_attention" in names
+    assert len(names) == 20 and "rest_retrieve" in names and "rest_tree_attention" in names
     lib = ctypes.CDLL(LIB)
     for n in names:
         assert getattr(lib, n) is not None
@@ -123,13 +123,21 @@ def test_calls_reject_null_and_bad_arguments_before_touching_the_gpu(rest):
     assert lib.rest_retrieve(None, None, None, 1, 8, ctypes.byref(prm), ctypes.byref(tree), None, 0, None) == rest.REST_INVALID_ARG
     assert lib.rest_accept(None, ctypes.byref(tree), 1, 64, 10, None, None, None, None) == rest.REST_INVALID_ARG
     assert rest.rest_retrieve_workspace_bytes(4) == 0
-    assert lib.rest_sample_ids(None, 100, p16 := ctypes.c_void_p(16), 1, 100, 1.0, 0.9, p16, None) == rest.REST_INVALID_ARG
-    assert lib.rest_sample_ids(p16, 99, p16, 1, 100, 1.0, 0.9, p16, None) == rest.REST_INVALID_ARG        # stride < V
-    assert lib.rest_sample_ids(p16, 100, p16, 1, 100, 0.0, 0.9, p16, None) == rest.REST_INVALID_ARG       # temperature
-    assert lib.rest_sample_ids(p16, 100, p16, 1, 100, 1.0, 0.0, p16, None) == rest.REST_INVALID_ARG       # top_p
-    assert lib.rest_sample_ids(p16, 100, p16, 1, 100, 1.0, 1.5, p16, None) == rest.REST_INVALID_ARG
-    assert lib.rest_sample_ids(p16, 40000, p16, 1, 40000, 1.0, 0.9, p16, None) == rest.REST_UNSUPPORTED
-    assert lib.rest_sample_ids(p16, 100, p16, 0, 100, 1.0, 0.9, p16, None) == rest.REST_OK                # nothing to do
+    p16 = ctypes.c_void_p(16)
+    big = ctypes.c_size_t(1 << 30)
+    assert lib.rest_sample_ids(None, 100, p16, 1, 100, 1.0, 0.9, p16, p16, big, None) == rest.REST_INVALID_ARG
+    assert lib.rest_sample_ids(p16, 99, p16, 1, 100, 1.0, 0.9, p16, p16, big, None) == rest.REST_INVALID_ARG        # stride < V
+    assert lib.rest_sample_ids(p16, 100, p16, 1, 100, 0.0, 0.9, p16, p16, big, None) == rest.REST_INVALID_ARG       # temperature
+    assert lib.rest_sample_ids(p16, 100, p16, 1, 100, 1.0, 0.0, p16, p16, big, None) == rest.REST_INVALID_ARG       # top_p
+    assert lib.rest_sample_ids(p16, 100, p16, 1, 100, 1.0, 1.5, p16, p16, big, None) == rest.REST_INVALID_ARG
+    assert lib.rest_sample_ids(p16, 200000, p16, 1, 200000, 1.0, 0.9, p16, p16, big, None) == rest.REST_UNSUPPORTED
+    assert lib.rest_sample_ids(p16, 100, p16, 0, 100, 1.0, 0.9, p16, None, 0, None) == rest.REST_OK                 # nothing to do
+    need = rest.rest_sample_ids_workspace_bytes(65, 32000)
+    assert need == 65 * (2048 + 32) * 8 and rest.rest_sample_ids_workspace_bytes(65, 131072) == need
+    assert rest.rest_sample_ids_workspace_bytes(1, 131073) == 0
+    assert lib.rest_sample_ids(p16, 32000, p16, 65, 32000, 1.0, 0.9, p16, p16, need - 1, None) == rest.REST_WORKSPACE_TOO_SMALL
+    assert lib.rest_sample_ids(p16, 32000, p16, 65, 32000, 1.0, 0.9, p16, None, need, None) == rest.REST_WORKSPACE_TOO_SMALL
+    assert lib.rest_sample_ids(p16, 32000, p16, 65, 32000, 1.0, 0.9, p16, ctypes.c_void_p(20), need, None) == rest.REST_INVALID_ARG
     hh = ctypes.c_void_p()
     assert lib.rest_index_save(None, b"/tmp/x", None) == rest.REST_INVALID_ARG
     assert lib.rest_index_load(None, p16, 10, 4, None, ctypes.byref(hh)) == rest.REST_INVALID_ARG

@@ -138,9 +138,9 @@ def test_attention_random_configuration(case):
 
 @pytest.mark.parametrize("case", range(30))
 def test_sampling_random_configuration(case):
-    """rest_sample_ids against the oracle's candidate sets (the tokens a perturbation of 1e-9 of the mass could draw)."""
+    """rest_sample_ids against the oracle: equal token ids."""
     s = 9800 + case
-    V = [1, 2, 63, 64, 65, 513, 1000, 4097, 32000, 32768][draw(s, 0, 0, 10)]
+    V = [1, 2, 63, 64, 65, 513, 1000, 4097, 32000, 50257][draw(s, 0, 0, 10)]
     R = draw(s, 1, 1, 7)
     temperature = [0.1, 0.7, 0.8, 1.0, 2.5][draw(s, 2, 0, 5)]
     top_p = [0.05, 0.5, 0.8, 0.95, 1.0][draw(s, 3, 0, 5)]
@@ -162,7 +162,5 @@ def test_sampling_random_configuration(case):
     ids = rest.rest_sample_ids(big[:, :V], torch.from_numpy(u).cuda(), temperature, top_p)
     torch.cuda.synchronize()
     got = ids.cpu().numpy()
-    for r in range(R):
-        cands = oracle.nucleus_candidates(x[r], np.float32(temperature), np.float32(top_p), np.float32(u[r]))
-        assert int(got[r]) in cands, (case, r, V, temperature, top_p, kind, int(got[r]), cands)
-        assert len(cands) <= 3
+    want, _ = oracle.sample_ids(x, np.float32(temperature), np.float32(top_p), u)
+    np.testing.assert_array_equal(got, want, err_msg=str((case, V, temperature, top_p, kind)))
