@@ -136,7 +136,7 @@ struct Bracket {
 // wavefront index known to have a match: a wavefront with a larger index (a shorter suffix) stops as soon as it
 // sees a smaller one there and reports an empty range, which the caller never selects.
 template <typename TokT, typename SaT>
-__device__ void wave_search(const RetrieveParams& p, const int32_t* lds_tab, const int32_t (&q)[kKeyLen], int n,
+__device__ __forceinline__ void wave_search(const RetrieveParams& p, const int32_t* lds_tab, const int32_t (&q)[kKeyLen], int n,
                             int wave, int32_t* best, uint32_t& out_lo, uint32_t& out_hi) {
     const int lane = threadIdx.x & 63;
     const uint32_t N = (uint32_t)p.n_tokens;
@@ -252,12 +252,174 @@ __device__ inline int prev_set(const uint64_t* bm, int from) {
     return (w << 6) + 63 - __builtin_clzll(x);
 }
 
+// Phase B for at most 64 kept rows -- most contexts: a long suffix matches in a handful of places -- by ONE wavefront,
+// row r in lane r, without a barrier and without the bitmaps in LDS.  B_d, the segment starts of depth d (rows >= R
+// count as starts), is a ballot; the weight of node (d, r) is the distance to the next set bit of B_d; the boundary
+// weight comes from a 64-bin histogram (LDS atomics, `hist`), the boundary depth and the row rank inside it from
+// ballots; the breadth-first slot of a kept node is the number of kept nodes of smaller depth plus those of its own
+// depth in lower rows, so nothing is sorted; parents and mask rows follow from a walk down the lane's own root path,
+// whose node at depth d is the last set bit of B_d at or below r.  Same order and same output as the general path.
+template <int kM, typename TokT, typename SaT, typename Kept>
+__device__ __forceinline__ void small_tree(const RetrieveParams& p, const int b, const int R, const int n_star, const uint32_t lo,
+                                           const uint32_t hi, Kept kept_entry, uint32_t* hist) {
+    const int lane = threadIdx.x & 63, r = lane;
+    const int m = p.m, c = p.c;
+    int32_t* o_tok = p.out.draft_tokens + (int64_t)b * c;
+    int32_t* o_par = p.out.parent_idx + (int64_t)b * c;
+    int32_t* o_pos = p.out.pos_ids + (int64_t)b * c;
+    int32_t* o_wgt = p.out.node_weight + (int64_t)b * c;
+    uint64_t* o_mask = p.out.tree_mask + (int64_t)b * c * p.mask_words;
+
+    // ---- the rows: continuation tokens and their number
+    int32_t tok[kM];
+    int len = 0;
+#pragma unroll
+    for (int j = 0; j < kM; j++) tok[j] = -1;
+    if (r < R) {
+        const uint32_t start = load_sa<SaT>(p.sa, p.n_tokens, kept_entry(r));
+        const uint64_t pos = (uint64_t)start + n_star;
+        const uint64_t left = p.n_tokens > pos ? p.n_tokens - pos : 0;
+        len = left < (uint64_t)m ? (int)left : m;
+#pragma unroll
+        for (int g = 0; g < kM / 4; g++) {
+            int32_t a[4] = {-1, -1, -1, -1};
+            if (4 * g < m) load_tok4<TokT>(p.corpus, p.n_tokens, pos + 4 * g, a);
+#pragma unroll
+            for (int j = 0; j < 4; j++) tok[4 * g + j] = a[j];
+        }
+    }
+    // ---- tokens shared with the previous row
+    int l = 0;
+    {
+        const int plen = __shfl_up(len, 1, 64);
+        bool run = true;
+#pragma unroll
+        for (int j = 0; j < kM; j++) {
+            if (j < m) {
+                const int32_t prev = __shfl_up(tok[j], 1, 64);
+                run = run && j < len && j < plen && prev == tok[j];
+                l += run ? 1 : 0;
+            }
+        }
+        if (r == 0) l = 0;
+    }
+    // ---- weights per depth.  B_d = segment starts of depth d (a ballot: cheap enough to take again below instead
+    // of keeping all of them); weights, at most 64, are packed four to a register.
+    const uint64_t lt = (1ull << r) - 1ull;              // rows below mine
+    const uint64_t le = lt | (1ull << r);                // ... and mine
+    uint32_t wpack[kM / 4];
+#pragma unroll
+    for (int k = 0; k < kM / 4; k++) wpack[k] = 0;
+    auto weight = [&](int d) { return (int)((wpack[(d - 1) >> 2] >> (8 * ((d - 1) & 3))) & 0xffu); };   // d: a constant
+    int total = 0;
+#pragma unroll
+    for (int d = 1; d <= kM; d++) {
+        if (d <= m) {
+            const uint64_t Bd = __ballot(r >= R || l < d);
+            const bool node = r < R && l < d && d <= len;
+            const uint64_t later = Bd & ~le;
+            const int next = later ? __builtin_ctzll(later) : 64;
+            wpack[(d - 1) >> 2] |= (uint32_t)(node ? next - r : 0) << (8 * ((d - 1) & 3));
+            total += popc64(__ballot(node));
+        }
+    }
+    // ---- boundary of the top c in the order (weight down, depth up, row up)
+    const bool take_all = total <= c;
+    int w_star = 0, d_star = m + 1, need_d = 0, my_rank = 0;
+    if (!take_all) {
+        hist[lane + 1] = 0;                               // bin w = nodes of weight w, 1..64
+        asm volatile("" ::: "memory");                    // one wavefront: its LDS operations complete in order
+#pragma unroll
+        for (int d = 1; d <= kM; d++)
+            if (d <= m && weight(d)) atomicAdd(&hist[weight(d)], 1u);
+        asm volatile("" ::: "memory");
+        uint32_t x = hist[lane + 1];                      // lane i: weight i + 1 -> after the scan, nodes of weight >= i + 1
+        for (int off = 1; off < 64; off <<= 1) {
+            const uint32_t y = __shfl_down(x, off, 64);
+            if (lane + off < 64) x += y;
+        }
+        const uint64_t enough = __ballot(x >= (uint32_t)c);        // lane 0 holds total > c
+        const int top = 63 - __builtin_clzll(enough);
+        w_star = top + 1;
+        const int above = top < 63 ? (int)__shfl(x, top + 1, 64) : 0;
+        const int need_w = c - above;                     // nodes of the boundary weight to take
+        int acc = 0;
+        bool found = false;
+#pragma unroll
+        for (int d = 1; d <= kM; d++) {
+            if (d <= m) {
+                const uint64_t eq = __ballot(weight(d) == w_star);
+                const int cnt = popc64(eq);
+                if (!found && acc + cnt >= need_w) {
+                    found = true;
+                    d_star = d;
+                    need_d = need_w - acc;
+                    my_rank = popc64(eq & lt);
+                }
+                if (!found) acc += cnt;
+            }
+        }
+    }
+    // ---- depth by depth: the kept nodes (a ballot), their slots, and one step down my root path: slot, parent and
+    // mask row of its node at this depth, which I write if the node is mine
+    int T = 0;
+    {
+        uint64_t path[REST_MAX_NODES / 64] = {0, 0, 0, 0};
+        int par = -1;
+#pragma unroll
+        for (int d = 1; d <= kM; d++) {
+            if (d <= m) {
+                const int w = weight(d);
+                const bool keep = w > 0 && (take_all || w > w_star ||
+                                            (w == w_star && (d < d_star || (d == d_star && my_rank < need_d))));
+                const uint64_t Kd = __ballot(keep);
+                const uint64_t Bd = __ballot(r >= R || l < d);
+                const int first = T;                      // slot of the first kept node of this depth
+                T += popc64(Kd);
+                if (d <= len) {
+                    const int rp = 63 - __builtin_clzll(Bd & le);         // row 0 starts a segment at every depth
+                    const bool kept = (Kd >> rp) & 1ull;
+                    int slot = -1;
+                    if (!kept) {
+                        // not among the top c, and then neither is anything below it on my path
+#pragma unroll
+                        for (int k = 0; k < REST_MAX_NODES / 64; k++) path[k] = 0;
+                    } else {
+                        slot = (int)REST_IDX(first + popc64(Kd & ((1ull << rp) - 1ull)), c, 5);
+#pragma unroll
+                        for (int k = 0; k < REST_MAX_NODES / 64; k++)
+                            if (k == (slot >> 6)) path[k] |= 1ull << (slot & 63);
+                        if (rp == r) {
+                            o_tok[slot] = tok[d - 1];
+                            o_par[slot] = par;
+                            o_pos[slot] = d;
+                            o_wgt[slot] = w;
+#pragma unroll
+                            for (int k = 0; k < REST_MAX_NODES / 64; k++)
+                                if (k < p.mask_words) o_mask[(int64_t)slot * p.mask_words + k] = path[k];
+                        }
+                    }
+                    par = slot;
+                }
+            }
+        }
+    }
+    for (int i = T + lane; i < c; i += 64) {
+        o_tok[i] = -1; o_par[i] = -1; o_pos[i] = 0; o_wgt[i] = 0;
+        for (int k = 0; k < p.mask_words; k++) o_mask[(int64_t)i * p.mask_words + k] = 0;
+    }
+    if (lane == 0) {
+        p.out.n_nodes[b] = T;
+        p.out.matched_len[b] = n_star;
+        p.out.match_count[b] = (int64_t)(hi - lo);
+    }
+}
+
 template <typename TokT, typename SaT>
 __global__ __launch_bounds__(kThreads) void retrieve_kernel(RetrieveParams p) {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     __shared__ uint32_t s_lo[kWavesPerWG], s_hi[kWavesPerWG];
-    __shared__ int32_t s_sel;        // wave (= suffix length) chosen
-    __shared__ int32_t s_best;       // smallest wave index known to have a match while the searches run
+    __shared__ int32_t s_best;       // smallest wave index known to have a match: the suffix length chosen in the end
     __shared__ int32_t s_misc[16];
 
     const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -265,32 +427,42 @@ __global__ __launch_bounds__(kThreads) void retrieve_kernel(RetrieveParams p) {
     int t = p.ctx_len[b];
     t = t < 0 ? 0 : (t > p.ctx_stride ? p.ctx_stride : t);
 
-    // ---------------- phase A: the sampled-key table goes to LDS, then one search per wavefront
+    // ---------------- phase A: the sampled-key table goes to LDS, then one search per wavefront.
+    // The reads are issued in this order: the context length (above), my share of the table (into registers), and --
+    // once the length is here -- my query tokens; the table is parked in LDS while the query is still on its way, so
+    // that the search does not start with a cold read of its own.
     const int32_t* lds_tab = (const int32_t*)lds;
+    const int n = p.n_max - wave;
+    int32_t q[kKeyLen];
+    bool searching;
     {
+        constexpr int kShare = (table_words(kTopMax) / 4 + kThreads - 1) / kThreads;
         const int4* src = (const int4*)p.top_keys;
         int4* dst = (int4*)lds;
-        for (int i = tid; i < table_words(p.top_count) / 4; i += kThreads) dst[i] = src[i];
+        const int nvec = table_words(p.top_count) / 4;
+        int4 share[kShare];
+#pragma unroll
+        for (int i = 0; i < kShare; i++) {
+            share[i] = make_int4(0, 0, 0, 0);
+            if (tid + i * kThreads < nvec) share[i] = src[tid + i * kThreads];
+        }
+        searching = n >= p.n_min && n <= t;
+#pragma unroll
+        for (int j = 0; j < kKeyLen; j++) q[j] = (searching && j < n) ? s[t - n + j] : 0;
+#pragma unroll
+        for (int i = 0; i < kShare; i++)
+            if (tid + i * kThreads < nvec) dst[tid + i * kThreads] = share[i];
         if (tid == 0) s_best = kWavesPerWG;
     }
     __syncthreads();
     {
-        const int n = p.n_max - wave;
         uint32_t lo = 0, hi = 0;
-        if (n >= p.n_min && n <= t) {
-            int32_t q[kKeyLen];
-#pragma unroll
-            for (int j = 0; j < kKeyLen; j++) q[j] = j < n ? s[t - n + j] : 0;
-            wave_search<TokT, SaT>(p, lds_tab, q, n, wave, &s_best, lo, hi);
+        if (searching) wave_search<TokT, SaT>(p, lds_tab, q, n, wave, &s_best, lo, hi);
+        if (lane == 0) {
+            s_lo[wave] = lo;
+            s_hi[wave] = hi;
+            if (hi > lo) atomicMin(&s_best, wave);         // wave 0 holds the longest suffix
         }
-        if (lane == 0) { s_lo[wave] = lo; s_hi[wave] = hi; }
-    }
-    __syncthreads();
-    if (tid == 0) {
-        int sel = -1;
-        for (int w = 0; w < kWavesPerWG; w++)
-            if (s_hi[w] > s_lo[w]) { sel = w; break; }     // wave 0 holds the longest suffix
-        s_sel = sel;
     }
     __syncthreads();
 
@@ -302,7 +474,7 @@ __global__ __launch_bounds__(kThreads) void retrieve_kernel(RetrieveParams p) {
     int32_t* o_wgt = p.out.node_weight + (int64_t)b * c;
     uint64_t* o_mask = p.out.tree_mask + (int64_t)b * c * p.mask_words;
 
-    const int sel = s_sel;
+    const int sel = s_best < kWavesPerWG ? s_best : -1;
     if (sel < 0) {
         for (int i = tid; i < c; i += kThreads) { o_tok[i] = -1; o_par[i] = -1; o_pos[i] = 0; o_wgt[i] = 0; }
         for (int i = tid; i < c * p.mask_words; i += kThreads) o_mask[i] = 0;
@@ -358,6 +530,15 @@ __global__ __launch_bounds__(kThreads) void retrieve_kernel(RetrieveParams p) {
         const uint32_t i = drawn ? (uint32_t)s_pick[r] : (uint32_t)r;
         return spaced ? lo + i * step_q + (i * step_r) / (uint32_t)p.K : lo + i;
     };
+
+    if (R <= 64) {
+        // every wavefront is past the search: the key table in LDS is dead
+        if (wave == 0) {
+            if (m <= 16) small_tree<16, TokT, SaT>(p, b, R, n_star, lo, hi, kept_entry, (uint32_t*)lds);
+            else small_tree<REST_MAX_CONT_LEN, TokT, SaT>(p, b, R, n_star, lo, hi, kept_entry, (uint32_t*)lds);
+        }
+        return;
+    }
 
     // ---------------- phase B LDS (aliases the key table, which is dead now)
     uint64_t* seg = (uint64_t*)(lds + p.off_seg);        // [m][words] segment-start bits per depth

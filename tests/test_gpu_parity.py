@@ -128,6 +128,30 @@ def test_retrieve_small_corpora(n, vocab, seed, dtype):
         run_retrieve_case(corpus, ctx, lens, prm)
 
 
+@pytest.mark.parametrize("m,c", [(1, 64), (10, 3), (10, 64), (16, 256), (17, 40), (32, 256)])
+def test_retrieve_around_64_kept_rows(m, c):
+    """Up to 64 kept rows take a path of their own in the kernel (one wavefront, rows in lanes): a motif that occurs
+    1 .. 130 times, followed by continuations over two tokens (so that Trie nodes are shared and weights differ), and
+    a match cap that cuts the rows to 64 and to 63."""
+    motif = np.arange(1000, 1006, dtype=np.int32)
+    for k in (1, 2, 63, 64, 65, 130):
+        parts = []
+        for i in range(k):
+            parts.append(small_corpus(40, 50, 900 + i))
+            parts.append(motif)
+            parts.append(small_corpus(3 + (i * 7) % 30, 2, 7000 + i) + 7)
+        parts.append(small_corpus(25, 50, 999))
+        parts.append(motif)                                   # one more occurrence at the very end: a row of length 0
+        corpus = np.concatenate(parts).astype(np.int32)
+        ctx = np.zeros((2, 12), dtype=np.int32)
+        ctx[0, :6] = motif
+        ctx[1, :3] = motif[3:]
+        lens = np.array([6, 3], dtype=np.int32)
+        idx = None
+        for K in (8192, 64, 63):
+            idx = run_retrieve_case(corpus, ctx, lens, dict(n_max=16, n_min=2, max_matches=K, cont_len=m, max_nodes=c), index=idx)
+
+
 def test_retrieve_degenerate_streams():
     prm = dict(n_max=16, n_min=2, max_matches=1000, cont_len=10, max_nodes=32)
     same = np.full(500, 3, dtype=np.int32)            # every suffix length matches everywhere, rows reach the end
