@@ -395,7 +395,46 @@ def side_measurements(rest, torch, synth, corp, index, w, q, k, v, out, tree, P,
     lat = []
     for j in range(8):
         lat.append(timed(lambda: rest.rest_retrieve(index, d_ctx[j:j + 1], d_len[j:j + 1], out=one, **prm), 20))
+    # launched from Python one call at a time, the binding's host time per call (about 20 us) hides the kernel ...
+    res["retrieve_batch1_host_launched_us"] = [round(x * 1e3, 1) for x in lat]
+    # ... so the same 20 calls are also captured once into a HIP graph and replayed: the kernel plus the gap between
+    # two dependent launches, with no host time in between (the call is one kernel launch and nothing else)
+    side = torch.cuda.Stream()
+    lat = []
+    for j in range(8):
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            rest.rest_retrieve(index, d_ctx[j:j + 1], d_len[j:j + 1], out=one, **prm)
+            torch.cuda.synchronize()
+            with torch.cuda.graph(graph, stream=side):
+                for _ in range(20):
+                    rest.rest_retrieve(index, d_ctx[j:j + 1], d_len[j:j + 1], out=one, **prm)
+        torch.cuda.synchronize()
+        lat.append(timed(graph.replay, 10) / 20)
+        del graph
     res["retrieve_batch1_us"] = [round(x * 1e3, 1) for x in lat]
+    # inside a step the attention launch has swept the caches before every retrieval: two graphs, 16 x (attention,
+    # retrieval of context j) and 16 x attention alone; their difference per pair is what a retrieval adds to a step
+    both, alone = torch.cuda.CUDAGraph(), torch.cuda.CUDAGraph()
+    per_batch = tree.tree_mask.shape[0] > 1
+    amask = tree.tree_mask if per_batch else tree.tree_mask[0]
+    aws = torch.empty(max(rest.rest_tree_attention_workspace_bytes(rest.make_attn_desc(q, k, v, out, P, scale, per_batch)), 16),
+                      dtype=torch.uint8, device=dev)
+    with torch.cuda.stream(side):
+        rest.rest_tree_attention(q, k, v, amask, P, scale, out=out, workspace=aws)
+        torch.cuda.synchronize()
+        with torch.cuda.graph(both, stream=side):
+            for j in range(16):
+                rest.rest_tree_attention(q, k, v, amask, P, scale, out=out, workspace=aws)
+                rest.rest_retrieve(index, d_ctx[j:j + 1], d_len[j:j + 1], out=one, **prm)
+        with torch.cuda.graph(alone, stream=side):
+            for j in range(16):
+                rest.rest_tree_attention(q, k, v, amask, P, scale, out=out, workspace=aws)
+    torch.cuda.synchronize()
+    t_both = min(timed(both.replay, 5) for _ in range(3))
+    t_alone = min(timed(alone.replay, 5) for _ in range(3))
+    res["retrieve_inside_step_us"] = round((t_both - t_alone) * 1e3 / 16, 1)
+    del both, alone
 
     # the same datastore left in pinned host memory (what one larger than the GPU's memory would need): the kernels
     # read it in place over the host link

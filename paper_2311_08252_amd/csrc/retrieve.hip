@@ -88,24 +88,44 @@ __device__ inline void load_tok4(const void* corpus, uint64_t n, uint64_t pos, i
 }
 
 // Three-way comparison of the first n tokens of two suffixes (at pos1 for lanes with on1, at pos2 for lanes with
-// on2) with q; end of stream = -1 < every token.  Tokens are read four at a time, both suffixes' reads of a group
-// are issued together, and a suffix reads on only while it still ties.
+// on2) with q; end of stream = -1 < every token.  Tokens are read four at a time and both suffixes' reads are issued
+// together.  Most probes differ from q within the first four tokens; the few that tie there read all their remaining
+// tokens at once, so that a round costs two dependent reads, not one per group of four.
 template <typename TokT>
 __device__ inline void cmp_suffix2(const void* corpus, uint64_t ntok, uint32_t pos1, bool on1, uint32_t pos2, bool on2,
                                    const int32_t (&q)[kKeyLen], int n, int& c1, int& c2) {
     c1 = 0;
     c2 = 0;
+    auto settle = [&](int g, bool t, const int32_t (&a)[4], int& c) {
 #pragma unroll
-    for (int g = 0; g < kKeyLen / 4; g++) {
-        if (4 * g < n) {
-            const bool t1 = on1 && c1 == 0, t2 = on2 && c2 == 0;
-            int32_t a1[4] = {0, 0, 0, 0}, a2[4] = {0, 0, 0, 0};
-            if (t1) load_tok4<TokT>(corpus, ntok, (uint64_t)pos1 + 4 * g, a1);
-            if (t2) load_tok4<TokT>(corpus, ntok, (uint64_t)pos2 + 4 * g, a2);
+        for (int j = 3; j >= 0; j--)
+            if (t && 4 * g + j < n && a[j] != q[4 * g + j]) c = a[j] < q[4 * g + j] ? -1 : 1;
+    };
+    {
+        int32_t a1[4] = {0, 0, 0, 0}, a2[4] = {0, 0, 0, 0};
+        if (on1) load_tok4<TokT>(corpus, ntok, (uint64_t)pos1, a1);
+        if (on2) load_tok4<TokT>(corpus, ntok, (uint64_t)pos2, a2);
+        settle(0, on1, a1, c1);
+        settle(0, on2, a2, c2);
+    }
+    if (n > 4) {
+        const bool t1 = on1 && c1 == 0, t2 = on2 && c2 == 0;
+        int32_t a1[kKeyLen / 4][4], a2[kKeyLen / 4][4];
 #pragma unroll
-            for (int j = 3; j >= 0; j--) {
-                if (t1 && 4 * g + j < n && a1[j] != q[4 * g + j]) c1 = a1[j] < q[4 * g + j] ? -1 : 1;
-                if (t2 && 4 * g + j < n && a2[j] != q[4 * g + j]) c2 = a2[j] < q[4 * g + j] ? -1 : 1;
+        for (int g = 1; g < kKeyLen / 4; g++) {
+#pragma unroll
+            for (int j = 0; j < 4; j++) a1[g][j] = a2[g][j] = 0;
+            if (4 * g < n) {
+                if (t1) load_tok4<TokT>(corpus, ntok, (uint64_t)pos1 + 4 * g, a1[g]);
+                if (t2) load_tok4<TokT>(corpus, ntok, (uint64_t)pos2 + 4 * g, a2[g]);
+            }
+        }
+        // the first group that differs decides: later groups only speak while the earlier ones tie
+#pragma unroll
+        for (int g = 1; g < kKeyLen / 4; g++) {
+            if (4 * g < n) {
+                settle(g, t1 && c1 == 0, a1[g], c1);
+                settle(g, t2 && c2 == 0, a2[g], c2);
             }
         }
     }
@@ -145,12 +165,15 @@ __device__ __forceinline__ void wave_search(const RetrieveParams& p, const int32
     const int32_t* coarse = lds_tab;
     const uint32_t* rank = (const uint32_t*)(lds_tab + kCoarse);
     const int32_t* keys = lds_tab + kTabKeys;
-    auto cmp_word = [&](const int32_t* col, int stride) {     // token j of the key at col[j * stride]
+    // token j of the key at col[j * stride]; front to back, and only while some lane's key still ties with q: keys
+    // spread over a rank interval mostly differ from q within a few tokens
+    auto cmp_word = [&](const int32_t* col, int stride) {
         int c = 0;
 #pragma unroll
-        for (int j = kKeyLen - 1; j >= 0; j--) {
+        for (int j = 0; j < kKeyLen; j++) {
+            if (j >= n || __ballot(c == 0) == 0) break;
             const int32_t x = col[j * stride];
-            if (j < n && x != q[j]) c = x < q[j] ? -1 : 1;
+            if (c == 0 && x != q[j]) c = x < q[j] ? -1 : 1;
         }
         return c;
     };
@@ -252,45 +275,86 @@ __device__ inline int prev_set(const uint64_t* bm, int from) {
     return (w << 6) + 63 - __builtin_clzll(x);
 }
 
-// Phase B for at most 64 kept rows -- most contexts: a long suffix matches in a handful of places -- by ONE wavefront,
-// row r in lane r, without a barrier and without the bitmaps in LDS.  B_d, the segment starts of depth d (rows >= R
-// count as starts), is a ballot; the weight of node (d, r) is the distance to the next set bit of B_d; the boundary
-// weight comes from a 64-bin histogram (LDS atomics, `hist`), the boundary depth and the row rank inside it from
-// ballots; the breadth-first slot of a kept node is the number of kept nodes of smaller depth plus those of its own
-// depth in lower rows, so nothing is sorted; parents and mask rows follow from a walk down the lane's own root path,
-// whose node at depth d is the last set bit of B_d at or below r.  Same order and same output as the general path.
-template <int kM, typename TokT, typename SaT, typename Kept>
-__device__ __forceinline__ void small_tree(const RetrieveParams& p, const int b, const int R, const int n_star, const uint32_t lo,
-                                           const uint32_t hi, Kept kept_entry, uint32_t* hist) {
-    const int lane = threadIdx.x & 63, r = lane;
+// Entry of the suffix array that holds kept candidate i of the range [lo, lo + S): the first K entries, or, sampling
+// S > K occurrences evenly, entry lo + floor(i*S/K) = lo + i*(S/K) + floor(i*(S%K)/K); i and S%K are below K <= 8192,
+// so 32 bits hold the product.
+__device__ inline uint32_t kept_rank(uint32_t lo, uint32_t S, uint32_t K, bool strided, uint32_t i) {
+    if (strided && S > K) return lo + i * (S / K) + (i * (S % K)) / K;
+    return lo + i;
+}
+
+// One candidate row: the up to m tokens that follow the n_star matched ones at suffix-array entry `entry` (-1 beyond
+// the row's end), and how many there are.
+template <int kM, typename TokT, typename SaT>
+__device__ __forceinline__ void load_row(const RetrieveParams& p, const uint32_t entry, const bool on, const int n_star,
+                                         int32_t (&tok)[kM], int& len) {
+    len = 0;
+#pragma unroll
+    for (int j = 0; j < kM; j++) tok[j] = -1;
+    if (on) {
+        const uint32_t start = load_sa<SaT>(p.sa, p.n_tokens, entry);
+        const uint64_t pos = (uint64_t)start + n_star;
+        const uint64_t left = p.n_tokens > pos ? p.n_tokens - pos : 0;
+        len = left < (uint64_t)p.m ? (int)left : p.m;
+#pragma unroll
+        for (int g = 0; g < kM / 4; g++) {
+            int32_t a[4] = {-1, -1, -1, -1};
+            if (4 * g < p.m) load_tok4<TokT>(p.corpus, p.n_tokens, pos + 4 * g, a);
+#pragma unroll
+            for (int j = 0; j < 4; j++) tok[4 * g + j] = a[j];
+        }
+    }
+}
+
+// LDS of the phase B for few rows (byte offsets; the key table is dead by then)
+constexpr int kFewTokStride = REST_MAX_CONT_LEN + 1;                 // words per row: odd, so that rows fall on different banks
+constexpr int kFewTok = 0;                                           // int32 [64][kFewTokStride]
+constexpr int kFewLcp = kFewTok + 64 * kFewTokStride * 4;            // uint8 [64]
+constexpr int kFewLen = kFewLcp + 64;                                // uint8 [64]
+constexpr int kFewHist = kFewLen + 64;                               // uint32 [65], bin w = nodes of weight w
+constexpr int kFewDepth = kFewHist + 65 * 4 + 4;                     // uint32 [64]: per depth, nodes of the boundary weight
+constexpr int kFewKept = kFewDepth + 64 * 4;                         // uint32 [64]: per depth, kept nodes
+constexpr int kFewTotal = kFewKept + 64 * 4;                         // uint32 [2]
+constexpr int kFewSeg = kFewTotal + 8;                               // uint64 [REST_MAX_CONT_LEN] segment starts per depth
+constexpr int kFewKeep = kFewSeg + REST_MAX_CONT_LEN * 8;            // uint64 [REST_MAX_CONT_LEN] kept rows per depth
+constexpr int kFewNode = kFewKeep + REST_MAX_CONT_LEN * 8;           // uint32 [REST_MAX_NODES]: depth | row << 8 | weight << 16
+constexpr int kFewBytes = kFewNode + REST_MAX_NODES * 4;
+static_assert(kFewSeg % 8 == 0, "64-bit words are aligned");
+
+// Phase B for at most 64 kept rows -- most contexts: a long suffix matches in a handful of places.  Rows sit in
+// lanes, depths in wavefronts (wavefront w takes depths w + 1 and w + 17), so every step is a few instructions per
+// wavefront between two barriers and nothing loops over rows or depths:
+//   B_d, the segment starts of depth d (rows >= R count as starts), is a ballot; the weight of node (d, r) is the
+//   distance to the next set bit of B_d; the boundary weight comes from a 64-bin histogram, the boundary depth from
+//   per-depth counts, the row rank inside it from a ballot; the breadth-first slot of a kept node is the number of
+//   kept nodes of smaller depth plus those of its own depth in lower rows, so nothing is sorted; the parent of
+//   (d, r) is the last set bit of B_{d-1} at or below r; and node a is on the root path of node x iff
+//   depth(a) <= depth(x) and row(a) <= row(x) < row(a) + weight(a), which makes a mask word a ballot over 64 slots.
+// The rows come from the wavefront `owner` (registers tok / len, lane = row).  Same order and output as the general path.
+template <int kM>
+__device__ __forceinline__ void few_rows_tree(const RetrieveParams& p, unsigned char* lds, const int b, const int R, const int n_star,
+                                              const uint32_t match_count, const int owner, const int32_t (&tok)[kM], const int len) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, r = lane;
     const int m = p.m, c = p.c;
     int32_t* o_tok = p.out.draft_tokens + (int64_t)b * c;
     int32_t* o_par = p.out.parent_idx + (int64_t)b * c;
     int32_t* o_pos = p.out.pos_ids + (int64_t)b * c;
     int32_t* o_wgt = p.out.node_weight + (int64_t)b * c;
     uint64_t* o_mask = p.out.tree_mask + (int64_t)b * c * p.mask_words;
+    int32_t* l_tok = (int32_t*)(lds + kFewTok);
+    uint8_t* l_lcp = lds + kFewLcp;
+    uint8_t* l_len = lds + kFewLen;
+    uint32_t* l_hist = (uint32_t*)(lds + kFewHist);
+    uint32_t* l_depth = (uint32_t*)(lds + kFewDepth);
+    uint32_t* l_kept = (uint32_t*)(lds + kFewKept);
+    uint32_t* l_total = (uint32_t*)(lds + kFewTotal);
+    uint64_t* l_seg = (uint64_t*)(lds + kFewSeg);
+    uint64_t* l_keep = (uint64_t*)(lds + kFewKeep);
+    uint32_t* l_node = (uint32_t*)(lds + kFewNode);
 
-    // ---- the rows: continuation tokens and their number
-    int32_t tok[kM];
-    int len = 0;
-#pragma unroll
-    for (int j = 0; j < kM; j++) tok[j] = -1;
-    if (r < R) {
-        const uint32_t start = load_sa<SaT>(p.sa, p.n_tokens, kept_entry(r));
-        const uint64_t pos = (uint64_t)start + n_star;
-        const uint64_t left = p.n_tokens > pos ? p.n_tokens - pos : 0;
-        len = left < (uint64_t)m ? (int)left : m;
-#pragma unroll
-        for (int g = 0; g < kM / 4; g++) {
-            int32_t a[4] = {-1, -1, -1, -1};
-            if (4 * g < m) load_tok4<TokT>(p.corpus, p.n_tokens, pos + 4 * g, a);
-#pragma unroll
-            for (int j = 0; j < 4; j++) tok[4 * g + j] = a[j];
-        }
-    }
-    // ---- tokens shared with the previous row
-    int l = 0;
-    {
+    // ---- the owner parks its rows and their common prefixes with the previous row; the others clear the counters
+    if (wave == owner) {
+        int l = 0;
         const int plen = __shfl_up(len, 1, 64);
         bool run = true;
 #pragma unroll
@@ -299,119 +363,159 @@ __device__ __forceinline__ void small_tree(const RetrieveParams& p, const int b,
                 const int32_t prev = __shfl_up(tok[j], 1, 64);
                 run = run && j < len && j < plen && prev == tok[j];
                 l += run ? 1 : 0;
+                l_tok[r * kFewTokStride + j] = tok[j];
             }
         }
         if (r == 0) l = 0;
+        l_lcp[r] = (uint8_t)l;
+        l_len[r] = (uint8_t)len;
+    } else if (wave == ((owner + 1) & 15)) {
+        l_hist[lane] = 0;
+        l_depth[lane] = 0;
+        l_kept[lane] = 0;
+        if (lane < 2) { l_hist[64 + lane] = 0; l_total[lane] = 0; }
     }
-    // ---- weights per depth.  B_d = segment starts of depth d (a ballot: cheap enough to take again below instead
-    // of keeping all of them); weights, at most 64, are packed four to a register.
+    __syncthreads();
+
+    // ---- my depths: segment starts, node weights
     const uint64_t lt = (1ull << r) - 1ull;              // rows below mine
     const uint64_t le = lt | (1ull << r);                // ... and mine
-    uint32_t wpack[kM / 4];
+    const int l = l_lcp[r], rl = l_len[r];
+    int wgt[2] = {0, 0};
 #pragma unroll
-    for (int k = 0; k < kM / 4; k++) wpack[k] = 0;
-    auto weight = [&](int d) { return (int)((wpack[(d - 1) >> 2] >> (8 * ((d - 1) & 3))) & 0xffu); };   // d: a constant
-    int total = 0;
-#pragma unroll
-    for (int d = 1; d <= kM; d++) {
+    for (int h = 0; h < 2; h++) {
+        const int d = wave + 1 + 16 * h;
         if (d <= m) {
             const uint64_t Bd = __ballot(r >= R || l < d);
-            const bool node = r < R && l < d && d <= len;
+            const bool node = r < R && l < d && d <= rl;
             const uint64_t later = Bd & ~le;
             const int next = later ? __builtin_ctzll(later) : 64;
-            wpack[(d - 1) >> 2] |= (uint32_t)(node ? next - r : 0) << (8 * ((d - 1) & 3));
-            total += popc64(__ballot(node));
+            wgt[h] = node ? next - r : 0;
+            if (node) atomicAdd(&l_hist[wgt[h]], 1u);
+            const uint32_t nodes = (uint32_t)popc64(__ballot(node));
+            if (lane == 0) {
+                l_seg[d - 1] = Bd;
+                atomicAdd(&l_total[0], nodes);
+            }
         }
     }
+    __syncthreads();
+
     // ---- boundary of the top c in the order (weight down, depth up, row up)
-    const bool take_all = total <= c;
-    int w_star = 0, d_star = m + 1, need_d = 0, my_rank = 0;
-    if (!take_all) {
-        hist[lane + 1] = 0;                               // bin w = nodes of weight w, 1..64
-        asm volatile("" ::: "memory");                    // one wavefront: its LDS operations complete in order
-#pragma unroll
-        for (int d = 1; d <= kM; d++)
-            if (d <= m && weight(d)) atomicAdd(&hist[weight(d)], 1u);
-        asm volatile("" ::: "memory");
-        uint32_t x = hist[lane + 1];                      // lane i: weight i + 1 -> after the scan, nodes of weight >= i + 1
+    const bool take_all = (int)l_total[0] <= c;
+    int w_star = 0, d_star = m + 1, need_d = 0;
+    uint64_t eq[2] = {0, 0};
+    if (!take_all) {                                      // the same for every wavefront
+        uint32_t x = l_hist[lane + 1];                    // lane i: weight i + 1 -> after the scan, nodes of weight >= i + 1
         for (int off = 1; off < 64; off <<= 1) {
             const uint32_t y = __shfl_down(x, off, 64);
             if (lane + off < 64) x += y;
         }
-        const uint64_t enough = __ballot(x >= (uint32_t)c);        // lane 0 holds total > c
+        const uint64_t enough = __ballot(x >= (uint32_t)c);        // lane 0 holds the total, which is above c
         const int top = 63 - __builtin_clzll(enough);
         w_star = top + 1;
         const int above = top < 63 ? (int)__shfl(x, top + 1, 64) : 0;
         const int need_w = c - above;                     // nodes of the boundary weight to take
-        int acc = 0;
-        bool found = false;
 #pragma unroll
-        for (int d = 1; d <= kM; d++) {
+        for (int h = 0; h < 2; h++) {
+            const int d = wave + 1 + 16 * h;
             if (d <= m) {
-                const uint64_t eq = __ballot(weight(d) == w_star);
-                const int cnt = popc64(eq);
-                if (!found && acc + cnt >= need_w) {
-                    found = true;
-                    d_star = d;
-                    need_d = need_w - acc;
-                    my_rank = popc64(eq & lt);
-                }
-                if (!found) acc += cnt;
+                eq[h] = __ballot(wgt[h] == w_star);
+                if (lane == 0) l_depth[d - 1] = (uint32_t)popc64(eq[h]);
+            }
+        }
+        __syncthreads();
+        // lane i: nodes of the boundary weight at depth i + 1 -> with the scan, at depths <= i + 1
+        const uint32_t v = lane < m ? l_depth[lane] : 0;
+        uint32_t y = v;
+        for (int off = 1; off < 64; off <<= 1) {
+            const uint32_t z = __shfl_up(y, off, 64);
+            if (lane >= off) y += z;
+        }
+        const uint64_t reached = __ballot(y >= (uint32_t)need_w);  // not empty: the boundary weight has need_w nodes
+        const int at = __builtin_ctzll(reached);
+        d_star = at + 1;
+        need_d = need_w - (int)(__shfl(y, at, 64) - __shfl(v, at, 64));
+    }
+    // ---- kept nodes of my depths
+    bool keep[2] = {false, false};
+    uint64_t Kd[2] = {0, 0};
+#pragma unroll
+    for (int h = 0; h < 2; h++) {
+        const int d = wave + 1 + 16 * h;
+        if (d <= m) {
+            const int w = wgt[h];
+            keep[h] = w > 0 && (take_all || w > w_star ||
+                                (w == w_star && (d < d_star || (d == d_star && popc64(eq[h] & lt) < need_d))));
+            Kd[h] = __ballot(keep[h]);
+            if (lane == 0) {
+                l_keep[d - 1] = Kd[h];
+                l_kept[d - 1] = (uint32_t)popc64(Kd[h]);
             }
         }
     }
-    // ---- depth by depth: the kept nodes (a ballot), their slots, and one step down my root path: slot, parent and
-    // mask row of its node at this depth, which I write if the node is mine
-    int T = 0;
+    __syncthreads();
+
+    // ---- slots: lane i first holds the kept nodes of depth i + 1, then those of smaller depths
+    int T;
     {
-        uint64_t path[REST_MAX_NODES / 64] = {0, 0, 0, 0};
-        int par = -1;
+        const uint32_t v = lane < m ? l_kept[lane] : 0;
+        uint32_t y = v;
+        for (int off = 1; off < 64; off <<= 1) {
+            const uint32_t z = __shfl_up(y, off, 64);
+            if (lane >= off) y += z;
+        }
+        T = (int)__shfl(y, 63, 64);
+        const uint32_t before = y - v;
 #pragma unroll
-        for (int d = 1; d <= kM; d++) {
+        for (int h = 0; h < 2; h++) {
+            const int d = wave + 1 + 16 * h;
             if (d <= m) {
-                const int w = weight(d);
-                const bool keep = w > 0 && (take_all || w > w_star ||
-                                            (w == w_star && (d < d_star || (d == d_star && my_rank < need_d))));
-                const uint64_t Kd = __ballot(keep);
-                const uint64_t Bd = __ballot(r >= R || l < d);
-                const int first = T;                      // slot of the first kept node of this depth
-                T += popc64(Kd);
-                if (d <= len) {
-                    const int rp = 63 - __builtin_clzll(Bd & le);         // row 0 starts a segment at every depth
-                    const bool kept = (Kd >> rp) & 1ull;
-                    int slot = -1;
-                    if (!kept) {
-                        // not among the top c, and then neither is anything below it on my path
-#pragma unroll
-                        for (int k = 0; k < REST_MAX_NODES / 64; k++) path[k] = 0;
-                    } else {
-                        slot = (int)REST_IDX(first + popc64(Kd & ((1ull << rp) - 1ull)), c, 5);
-#pragma unroll
-                        for (int k = 0; k < REST_MAX_NODES / 64; k++)
-                            if (k == (slot >> 6)) path[k] |= 1ull << (slot & 63);
-                        if (rp == r) {
-                            o_tok[slot] = tok[d - 1];
-                            o_par[slot] = par;
-                            o_pos[slot] = d;
-                            o_wgt[slot] = w;
-#pragma unroll
-                            for (int k = 0; k < REST_MAX_NODES / 64; k++)
-                                if (k < p.mask_words) o_mask[(int64_t)slot * p.mask_words + k] = path[k];
-                        }
+                const int first = (int)__shfl(before, d - 1, 64);
+                const int first_up = d > 1 ? (int)__shfl(before, d - 2, 64) : 0;
+                if (keep[h]) {
+                    const int slot = (int)REST_IDX(first + popc64(Kd[h] & lt), c, 5);
+                    int par = -1;
+                    if (d > 1) {
+                        const uint64_t Bu = l_seg[d - 2], Ku = l_keep[d - 2];
+                        const int rp = 63 - __builtin_clzll(Bu & le);     // row 0 starts a segment at every depth
+                        if ((Ku >> rp) & 1ull) par = first_up + popc64(Ku & ((1ull << rp) - 1ull));
                     }
-                    par = slot;
+                    o_tok[slot] = l_tok[r * kFewTokStride + d - 1];
+                    o_par[slot] = par;
+                    o_pos[slot] = d;
+                    o_wgt[slot] = wgt[h];
+                    l_node[slot] = (uint32_t)d | ((uint32_t)r << 8) | ((uint32_t)wgt[h] << 16);
                 }
             }
         }
     }
-    for (int i = T + lane; i < c; i += 64) {
+    for (int i = T + tid; i < c; i += kThreads) {
         o_tok[i] = -1; o_par[i] = -1; o_pos[i] = 0; o_wgt[i] = 0;
         for (int k = 0; k < p.mask_words; k++) o_mask[(int64_t)i * p.mask_words + k] = 0;
     }
-    if (lane == 0) {
+    if (tid == 0) {
         p.out.n_nodes[b] = T;
         p.out.matched_len[b] = n_star;
-        p.out.match_count[b] = (int64_t)(hi - lo);
+        p.out.match_count[b] = (int64_t)match_count;
+    }
+    __syncthreads();
+
+    // ---- mask rows: lanes = the 64 slots of a word
+    for (int x = wave; x < T; x += kWavesPerWG) {
+        const uint32_t nx = l_node[x];
+        const int dx = (int)(nx & 0xffu), rx = (int)((nx >> 8) & 0xffu);
+        for (int k = 0; k < p.mask_words; k++) {
+            const int a = 64 * k + lane;
+            bool on_path = false;
+            if (a < T) {
+                const uint32_t na = l_node[a];
+                const int da = (int)(na & 0xffu), ra = (int)((na >> 8) & 0xffu), wa = (int)(na >> 16);
+                on_path = da <= dx && ra <= rx && rx < ra + wa;
+            }
+            const uint64_t word = __ballot(on_path);
+            if (lane == 0) o_mask[(int64_t)x * p.mask_words + k] = word;
+        }
     }
 }
 
@@ -455,9 +559,24 @@ __global__ __launch_bounds__(kThreads) void retrieve_kernel(RetrieveParams p) {
         if (tid == 0) s_best = kWavesPerWG;
     }
     __syncthreads();
+    // A wavefront whose range is small enough for the few-rows phase B requests its rows right away (lane = row): they
+    // are on their way while the other searches finish.
+    int32_t row_tok[16];
+    int row_len = 0;
+    bool have_rows = false;
+#pragma unroll
+    for (int j = 0; j < 16; j++) row_tok[j] = -1;
     {
         uint32_t lo = 0, hi = 0;
         if (searching) wave_search<TokT, SaT>(p, lds_tab, q, n, wave, &s_best, lo, hi);
+        {
+            const uint32_t S = hi - lo, Rw = S < (uint32_t)p.K ? S : (uint32_t)p.K;
+            if (hi > lo && p.random_seqs == 0 && p.m <= 16 && Rw <= 64) {
+                load_row<16, TokT, SaT>(p, kept_rank(lo, S, (uint32_t)p.K, p.strided != 0, (uint32_t)lane), (uint32_t)lane < Rw, n,
+                                        row_tok, row_len);
+                have_rows = true;
+            }
+        }
         if (lane == 0) {
             s_lo[wave] = lo;
             s_hi[wave] = hi;
@@ -533,9 +652,14 @@ __global__ __launch_bounds__(kThreads) void retrieve_kernel(RetrieveParams p) {
 
     if (R <= 64) {
         // every wavefront is past the search: the key table in LDS is dead
-        if (wave == 0) {
-            if (m <= 16) small_tree<16, TokT, SaT>(p, b, R, n_star, lo, hi, kept_entry, (uint32_t*)lds);
-            else small_tree<REST_MAX_CONT_LEN, TokT, SaT>(p, b, R, n_star, lo, hi, kept_entry, (uint32_t*)lds);
+        if (m <= 16) {
+            if (wave == sel && !have_rows) load_row<16, TokT, SaT>(p, kept_entry(lane), lane < R, n_star, row_tok, row_len);
+            few_rows_tree<16>(p, lds, b, R, n_star, hi - lo, sel, row_tok, row_len);
+        } else {
+            int32_t tok[REST_MAX_CONT_LEN];
+            int len;
+            load_row<REST_MAX_CONT_LEN, TokT, SaT>(p, kept_entry(lane), wave == sel && lane < R, n_star, tok, len);
+            few_rows_tree<REST_MAX_CONT_LEN>(p, lds, b, R, n_star, hi - lo, sel, tok, len);
         }
         return;
     }
@@ -984,6 +1108,7 @@ extern "C" __attribute__((visibility("default"))) rest_status rest_retrieve(cons
     size_t lds_bytes = off;
     const size_t top_bytes = (size_t)table_words(index->top_count) * 4;
     if (top_bytes > lds_bytes) lds_bytes = top_bytes;
+    if ((size_t)kFewBytes > lds_bytes) lds_bytes = kFewBytes;
     if (lds_bytes > 150 * 1024) return REST_UNSUPPORTED;
 
     hipStream_t stream = (hipStream_t)stream_;
