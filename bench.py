@@ -44,7 +44,7 @@ def main() -> int:
                          "synthetic datastore and print the mean generated length per step")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device-to-device copy five times (reference for rocprofv3 --pmc byte counters)")
-    ap.add_argument("--attention-only", metavar="NbxHxTxP[:kv8][:gqaG][:layers]", default=None,
+    ap.add_argument("--attention-only", metavar="NbxHxTxP[:kv8|:f32][:gqaG][:layers]", default=None,
                     help="only run rest_tree_attention at that shape 3 + 10 times (for rocprofv3 runs of one kernel): Nb batch "
                          "entries x H K/V heads, T draft tokens, P cached keys; kv8 = 8-bit (E4M3) cache; gqaG = G query heads "
                          "per K/V head stacked along the row axis; layers = one launch per batch entry")
@@ -296,15 +296,20 @@ def attention_only(rest, torch, synth, np, dev, spec):
     parts = spec.split(":")
     Nb, H, T, P = (int(x) for x in parts[0].split("x"))
     kv8 = "kv8" in parts[1:]
+    f32 = "f32" in parts[1:]
     by_layer = "layers" in parts[1:]
     g_heads = max([int(x[3:]) for x in parts[1:] if x.startswith("gqa")] + [1])
     Tq = T * g_heads
     g = torch.Generator(device=dev)
     g.manual_seed(T * 100000 + P + g_heads)
-    q = torch.randn((Nb, H, Tq, 128), generator=g, device=dev).to(torch.bfloat16)
+    q = torch.randn((Nb, H, Tq, 128), generator=g, device=dev)
+    if not f32:
+        q = q.to(torch.bfloat16)
     k, v = (torch.randn((Nb, H, P + T, 128), generator=g, device=dev) for _ in range(2))
     sc = None
-    if kv8:
+    if f32:
+        pass
+    elif kv8:
         k, v = (x.to(torch.float8_e4m3fn).view(torch.uint8) for x in (k, v))
         sc = torch.full((Nb * H,), 1.0, dtype=torch.float32, device=dev)
     else:
@@ -334,8 +339,15 @@ def attention_only(rest, torch, synth, np, dev, spec):
     b.record()
     torch.cuda.synchronize()
     us = a.elapsed_time(b) / 10 * 1e3
-    alg = Nb * H * (2 * (P + T) * 128 * (1 if kv8 else 2) + 2 * Tq * 128 * 2) + T * ((T + 63) // 64) * 8
+    esz = 4 if f32 else 2
+    alg = Nb * H * (2 * (P + T) * 128 * (1 if kv8 else esz) + 2 * Tq * 128 * esz) + T * ((T + 63) // 64) * 8
     flops = Nb * H * 4.0 * Tq * (P + T) * 128
+    if f32:
+        nw = 1 if Tq <= 32 else 2 if Tq <= 64 else 4 if Tq <= 128 else 8
+        return {"attention_only": spec, "kernel": f"tree_attn_f32_tiled_kernel<{nw}>", "launches_per_run": len(views),
+                "us_per_run": round(us, 1), "algorithmic_bytes_per_run": alg, "GB/s": round(alg / us / 1e3, 1),
+                "frac_of_8TB/s": round(alg / us / 1e3 / HBM_PEAK_GBS, 3), "TFLOP/s": round(flops / us / 1e6, 1),
+                "frac_of_157.3_TFLOP/s_fp32_matrix_peak": round(flops / us / 1e6 / 157.3, 3)}
     return {"attention_only": spec, "kernel": attention_kernel_name((H if by_layer else Nb * H) * ((Tq + 255) // 256), min(Tq, 256), kv8),
             "launches_per_run": len(views), "us_per_run": round(us, 1), "algorithmic_bytes_per_run": alg,
             "GB/s": round(alg / us / 1e3, 1), "frac_of_8TB/s": round(alg / us / 1e3 / HBM_PEAK_GBS, 3),

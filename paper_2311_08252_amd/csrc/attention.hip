@@ -860,81 +860,205 @@ __global__ __launch_bounds__(256) void tree_attn_streamk_merge_kernel(AttnParams
 }
 
 // ---------------------------------------------------------------------------------------------------------
-// fp32 path: plain fp32 arithmetic, one 128-thread block per (batch, head, query), one KV split per
-// blockIdx.y.  Exists for accuracy checks with fp32 inputs; not a throughput path.
-__global__ __launch_bounds__(128) void tree_attn_f32_kernel(const float* q, const float* k, const float* v,
-                                                            const uint64_t* mask, float* out, float* ws_o, float* ws_ml,
-                                                            AttnParams p) {
-    __shared__ float qs[kD];
-    __shared__ float prob[128];
-    __shared__ float red[128];
-    const int64_t rowid = blockIdx.x;
-    const int qi = (int)(rowid % p.Tq);
-    const int64_t slab = rowid / p.Tq;
+// fp32 path: one workgroup of NW wavefronts per (batch, head, 32 NW queries) and key split; wavefront w owns
+// queries [32w, 32w + 32) of the group, all share one 32-key K/V tile in LDS, so every K/V element is read once per
+// group.  S^T = K Q^T and O^T += V^T P^T run on v_mfma_f32_32x32x2_f32 with keys (then head dimensions) on the row
+// axis, as in the bf16 kernels: a lane holds the scores of ONE query, and P is used where it was produced.  The
+// instruction contracts two k-values at a time, lanes 0-31 giving one and lanes 32-63 the other; which two is free
+// as long as both operands agree: for K Q^T lane half h contributes dimensions 8j + 4h + i (one 16-byte LDS read
+// per four instructions), for V^T P^T it contributes key 8a + 4h + b, the row of S it already holds.
+// K rows are padded to 132 words in LDS so that the 32 lanes of a half, which read the same columns of 32 different
+// rows, fall on different banks.  Rows are 16-byte aligned (the host checks pointers and strides).
+constexpr int kF32KStride = kD + 4;
+template <int NW>
+__global__ __launch_bounds__(64 * NW) void tree_attn_f32_tiled_kernel(const float* q, const float* k, const float* v,
+                                                                      const uint64_t* mask, float* out, float* ws_o, float* ws_ml,
+                                                                      AttnParams p) {
+    __shared__ __attribute__((aligned(16))) float ldsK[kBlk * kF32KStride];
+    __shared__ __attribute__((aligned(16))) float ldsV[kBlk * kD];
+    constexpr int kThreadsWG = 64 * NW;
+    constexpr int kChunks = 2 * kBlk * (kD / 4) / kThreadsWG;      // 16-byte pieces of a K/V tile per thread
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, col = lane & 31, hh = lane >> 5;
+    const int qg = blockIdx.x % p.qgroups;
+    const int64_t slab = blockIdx.x / p.qgroups;
     const int h = (int)(slab % p.H);
     const int64_t nb = slab / p.H;
     const int split = blockIdx.y;
-    const int tid = threadIdx.x;
-    const float* qp = q + nb * p.qs[0] + h * p.qs[1] + qi * p.qs[2];
+    const int qi = (qg * NW + wave) * 32 + col;
+    const bool q_on = qi < p.Tq;
     const float* kp = k + nb * p.ks[0] + h * p.ks[1];
     const float* vp = v + nb * p.vs[0] + h * p.vs[1];
-    const uint64_t* mrow = mask + (p.mask_per_batch ? nb * p.mask_rows * p.mask_words : 0) + (int64_t)(qi % p.mask_rows) * p.mask_words;
-    qs[tid] = qp[tid];
-    __syncthreads();
-    const int chunk = (p.Lk + p.nsplit - 1) / p.nsplit;
-    const int k0 = split * chunk, k1 = min(p.Lk, k0 + chunk);
-    float m = kNegBig, l = 0.f, acc = 0.f;
-    for (int base = k0; base < k1; base += 128) {
-        const int key = base + tid;
-        float sc = -INFINITY;
-        if (key < k1) {
-            const int t = key - p.P;
-            bool vis = t < 0 || ((mrow[t >> 6] >> (t & 63)) & 1ull);
-            if (vis) {
-                float dot = 0.f;
-                const float* kr = kp + key * p.ks[2];
-                for (int d = 0; d < kD; d++) dot = __builtin_fmaf(qs[d], kr[d], dot);
-                sc = dot;
+
+    // my query's dimensions 8j + 4hh .. + 3, j = 0..15, and its mask row
+    f32x4 qf[kD / 8];
+    uint64_t mw[REST_MAX_NODES / 64] = {0, 0, 0, 0};
+    {
+        const float* qp = q + nb * p.qs[0] + h * p.qs[1] + (int64_t)(q_on ? qi : 0) * p.qs[2];
+#pragma unroll
+        for (int j = 0; j < kD / 8; j++) {
+            qf[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+            if (q_on) qf[j] = *(const f32x4*)(qp + 8 * j + 4 * hh);
+        }
+        if (q_on && p.Tk > 0) {
+            const uint64_t* mrow = mask + (p.mask_per_batch ? nb * p.mask_rows * p.mask_words : 0) + (int64_t)(qi % p.mask_rows) * p.mask_words;
+#pragma unroll
+            for (int w = 0; w < REST_MAX_NODES / 64; w++)
+                if (w < p.mask_words) mw[w] = mrow[w];
+        }
+    }
+    // blocks of this split
+    const int nblk = (p.Lk + kBlk - 1) / kBlk;
+    const int per = (nblk + p.nsplit - 1) / p.nsplit;
+    const int b0 = split * per, b1 = min(nblk, b0 + per);
+
+    // piece i of a thread: row = (tid + i * threads) / 32 of K (pieces below 1024) or V, 16-byte column (..) % 32
+    f32x4 stage[kChunks];
+    auto fetch = [&](int jb) {
+#pragma unroll
+        for (int i = 0; i < kChunks; i++) {
+            const int cidx = tid + i * kThreadsWG;
+            const bool is_v = cidx >= kBlk * (kD / 4);
+            const int row = (cidx % (kBlk * (kD / 4))) / (kD / 4), ch = cidx % (kD / 4);
+            const int key = jb * kBlk + row;
+            stage[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+            if (key < p.Lk) {
+                const float* src = is_v ? vp + (int64_t)REST_IDX(key, p.Lk, 6) * p.vs[2] : kp + (int64_t)REST_IDX(key, p.Lk, 6) * p.ks[2];
+                stage[i] = *(const f32x4*)(src + 4 * ch);
             }
         }
-        red[tid] = sc;
-        __syncthreads();
-        for (int st = 64; st > 0; st >>= 1) {
-            if (tid < st) red[tid] = fmaxf(red[tid], red[tid + st]);
-            __syncthreads();
+    };
+    auto park = [&]() {
+#pragma unroll
+        for (int i = 0; i < kChunks; i++) {
+            const int cidx = tid + i * kThreadsWG;
+            const bool is_v = cidx >= kBlk * (kD / 4);
+            const int row = (cidx % (kBlk * (kD / 4))) / (kD / 4), ch = cidx % (kD / 4);
+            if (is_v) *(f32x4*)(ldsV + row * kD + 4 * ch) = stage[i];
+            else *(f32x4*)(ldsK + row * kF32KStride + 4 * ch) = stage[i];
         }
-        const float m_new = fmaxf(m, red[0]);
+    };
+
+    f32x16 o[4];
+    float m_ref = kNegBig, l_run = 0.f;           // m_ref in log2 units (score * c)
+#pragma unroll
+    for (int dt = 0; dt < 4; dt++)
+#pragma unroll
+        for (int r = 0; r < 16; r++) o[dt][r] = 0.f;
+    const float cu = p.c;
+
+    if (b0 < b1) fetch(b0);
+    for (int jb = b0; jb < b1; jb++) {
+        __syncthreads();                           // everyone has left the previous tile
+        park();
         __syncthreads();
-        const float e = __builtin_amdgcn_exp2f((sc - m_new) * p.c);
-        prob[tid] = e;
-        red[tid] = e;
-        __syncthreads();
-        for (int st = 64; st > 0; st >>= 1) {
-            if (tid < st) red[tid] += red[tid + st];
-            __syncthreads();
+        if (jb + 1 < b1) fetch(jb + 1);            // on its way during the arithmetic below
+        const int key0 = jb * kBlk;
+
+        // ---- S^T[key][query] = K Q^T
+        f32x16 sc;
+#pragma unroll
+        for (int r = 0; r < 16; r++) sc[r] = 0.f;
+#pragma unroll
+        for (int j = 0; j < kD / 8; j++) {
+            const f32x4 kv = *(const f32x4*)(ldsK + col * kF32KStride + 8 * j + 4 * hh);
+#pragma unroll
+            for (int i = 0; i < 4; i++) sc = __builtin_amdgcn_mfma_f32_32x32x2f32(kv[i], qf[j][i], sc, 0, 0, 0);
         }
-        const float alpha = __builtin_amdgcn_exp2f((m - m_new) * p.c);
-        l = l * alpha + red[0];
-        acc *= alpha;
-        const int nk = min(128, k1 - base);
-        for (int jj = 0; jj < nk; jj++) acc = __builtin_fmaf(prob[jj], vp[(base + jj) * p.vs[2] + tid], acc);
-        m = m_new;
-        __syncthreads();
+        // ---- visibility: bit i of vbits <-> key key0 + i; prefix keys are visible to everyone
+        if (key0 + kBlk > p.P) {
+            const int kb = key0 - p.P;            // draft-token index of the block's first key (may be < 0)
+            const int end = p.Tk - kb;            // keys at block offset >= end are past the last key
+            const uint32_t in_range = end >= 32 ? 0xffffffffu : (end > 0 ? (1u << end) - 1u : 0u);
+            uint32_t vbits;
+            if (kb < 0) {
+                vbits = ((1u << (-kb)) - 1u) | ((uint32_t)mw[0] << (-kb));
+            } else {
+                const int w = kb >> 6, sh = kb & 63;
+                const uint64_t lo = w == 0 ? mw[0] : (w == 1 ? mw[1] : (w == 2 ? mw[2] : mw[3]));
+                const uint64_t hi = w == 0 ? mw[1] : (w == 1 ? mw[2] : (w == 2 ? mw[3] : 0ull));
+                vbits = (uint32_t)(lo >> sh);
+                if (sh > 32) vbits |= (uint32_t)(hi << (64 - sh));
+            }
+            vbits &= in_range;
+            vbits >>= 4 * hh;
+#pragma unroll
+            for (int r = 0; r < 16; r++) {
+                const bool vis = (vbits >> (8 * (r >> 2) + (r & 3))) & 1u;
+                sc[r] = vis ? sc[r] : -INFINITY;
+            }
+        }
+        // ---- softmax numerators against a lazily updated reference, per lane = per query column
+        {
+            float mx = sc[0];
+#pragma unroll
+            for (int r = 1; r < 16; r++) mx = fmaxf(mx, sc[r]);
+            mx = fmaxf(mx, wave_xor32(mx)) * cu;
+            if (__any(mx > m_ref + kLazy)) {
+                const float m_new = fmaxf(m_ref, mx);
+                const float alpha = __builtin_amdgcn_exp2f(m_ref - m_new);
+                m_ref = m_new;
+                l_run *= alpha;
+#pragma unroll
+                for (int dt = 0; dt < 4; dt++)
+#pragma unroll
+                    for (int r = 0; r < 16; r++) o[dt][r] *= alpha;
+            }
+            float sum = 0.f;
+#pragma unroll
+            for (int r = 0; r < 16; r++) {
+                sc[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[r], cu, -m_ref));
+                sum += sc[r];
+            }
+            l_run += sum;
+        }
+        // ---- O^T[d][query] += V^T P^T: lane half hh brings key 8a + 4hh + b, whose probability is its sc[4a + b]
+#pragma unroll
+        for (int a = 0; a < 4; a++)
+#pragma unroll
+            for (int bb = 0; bb < 4; bb++) {
+                const float* vrow = ldsV + (8 * a + 4 * hh + bb) * kD + col;
+#pragma unroll
+                for (int dt = 0; dt < 4; dt++)
+                    o[dt] = __builtin_amdgcn_mfma_f32_32x32x2f32(vrow[32 * dt], sc[4 * a + bb], o[dt], 0, 0, 0);
+            }
     }
+
+    // ---- o[dt][4g + e] = O[query][d = 32 dt + 8 g + 4 hh + e]; the two halves of a query hold disjoint keys' sums
+    l_run += wave_xor32(l_run);
+    if (!q_on) return;
     if (p.nsplit == 1) {
-        out[nb * p.os[0] + h * p.os[1] + qi * p.os[2] + tid] = l > 0.f ? acc / l : 0.f;
+        const float inv = l_run > 0.f ? 1.0f / l_run : 0.f;
+        float* op = out + nb * p.os[0] + h * p.os[1] + (int64_t)qi * p.os[2];
+#pragma unroll
+        for (int dt = 0; dt < 4; dt++)
+#pragma unroll
+            for (int g = 0; g < 4; g++) {
+                f32x4 w;
+#pragma unroll
+                for (int e = 0; e < 4; e++) w[e] = o[dt][4 * g + e] * inv;
+                *(f32x4*)(op + 32 * dt + 8 * g + 4 * hh) = w;
+            }
     } else {
         const int64_t row = (slab * p.nsplit + split) * p.Tq + qi;
-        ws_o[row * kD + tid] = acc;
-        if (tid == 0) {
-            ws_ml[row * 2] = m;
-            ws_ml[row * 2 + 1] = l;
+        float* wo = ws_o + row * kD;
+#pragma unroll
+        for (int dt = 0; dt < 4; dt++)
+#pragma unroll
+            for (int g = 0; g < 4; g++) {
+                f32x4 w;
+#pragma unroll
+                for (int e = 0; e < 4; e++) w[e] = o[dt][4 * g + e];
+                *(f32x4*)(wo + 32 * dt + 8 * g + 4 * hh) = w;
+            }
+        if (hh == 0) {
+            ws_ml[row * 2] = m_ref;
+            ws_ml[row * 2 + 1] = l_run;
         }
     }
 }
 
 __global__ __launch_bounds__(128) void tree_attn_f32_merge_kernel(const float* ws_o, const float* ws_ml, float* out,
-                                                                  int32_t H, int32_t Tq, int32_t nsplit, float c,
+                                                                  int32_t H, int32_t Tq, int32_t nsplit,
                                                                   int64_t os0, int64_t os1, int64_t os2) {
     const int64_t rowid = blockIdx.x;            // (slab, qi)
     const int qi = (int)(rowid % Tq);
@@ -947,7 +1071,7 @@ __global__ __launch_bounds__(128) void tree_attn_f32_merge_kernel(const float* w
     float l = 0.f, acc = 0.f;
     for (int s = 0; s < nsplit; s++) {
         const int64_t row = (slab * nsplit + s) * Tq + qi;
-        float w = __builtin_amdgcn_exp2f((ws_ml[row * 2] - m) * c);
+        const float w = __builtin_amdgcn_exp2f(ws_ml[row * 2] - m);       // references are in log2 units
         l += ws_ml[row * 2 + 1] * w;
         acc += ws_o[row * kD + d] * w;
     }
@@ -971,7 +1095,18 @@ Plan make_plan(const rest_attn_desc* d) {
     const int Lk = d->P + d->Tk;
     pl.nblk = (Lk + kBlk - 1) / kBlk;
     if (d->dtype == REST_FP32) {
-        pl.nsplit_f32 = d->num_splits > 0 ? d->num_splits : 1;
+        // groups of 32 qt queries; with few groups the keys are split so that the launch has about two workgroups per
+        // compute unit, every split with at least one block
+        pl.qt = d->Tq <= 32 ? 1 : (d->Tq <= 64 ? 2 : (d->Tq <= 128 ? 4 : 8));
+        pl.qgroups = (d->Tq + 32 * pl.qt - 1) / (32 * pl.qt);
+        pl.units = d->Nb * d->H * pl.qgroups;
+        int ns = d->num_splits;
+        if (ns <= 0) {
+            ns = (512 + pl.units - 1) / pl.units;
+            if (ns > 64) ns = 64;
+        }
+        if (ns > pl.nblk) ns = pl.nblk > 0 ? pl.nblk : 1;
+        pl.nsplit_f32 = ns;
         return pl;
     }
     // a stream of qt wavefronts covers 32 qt queries and moves tiles of 16 qt keys
@@ -1166,18 +1301,26 @@ static rest_status enqueue_tree_attention(const void* d_q, const void* d_k, cons
     } else {
         const int ns = pl.nsplit_f32;
         p.nsplit = ns;
-        p.qgroups = 1;
         p.units = 0;
         p.n_streams = 0;
         p.dp_rounds = p.tail_units = p.tail_streams = p.extra_units = 0;
         const size_t rows = (size_t)d->Nb * d->H * ns * d->Tq;
         p.ws_ml = p.ws_o ? p.ws_o + rows * kD : nullptr;
-        hipLaunchKernelGGL(tree_attn_f32_kernel, dim3(d->Nb * d->H * d->Tq, ns), dim3(128), 0, stream,
-                           (const float*)d_q, (const float*)d_k, (const float*)d_v, p.mask, (float*)d_out, p.ws_o, p.ws_ml, p);
+        p.qgroups = pl.qgroups;
+        const dim3 grid(pl.units, ns);
+        const float *fq = (const float*)d_q, *fk = (const float*)d_k, *fv = (const float*)d_v;
+        if (pl.qt == 1)
+            hipLaunchKernelGGL((tree_attn_f32_tiled_kernel<1>), grid, dim3(64), 0, stream, fq, fk, fv, p.mask, (float*)d_out, p.ws_o, p.ws_ml, p);
+        else if (pl.qt == 2)
+            hipLaunchKernelGGL((tree_attn_f32_tiled_kernel<2>), grid, dim3(128), 0, stream, fq, fk, fv, p.mask, (float*)d_out, p.ws_o, p.ws_ml, p);
+        else if (pl.qt == 4)
+            hipLaunchKernelGGL((tree_attn_f32_tiled_kernel<4>), grid, dim3(256), 0, stream, fq, fk, fv, p.mask, (float*)d_out, p.ws_o, p.ws_ml, p);
+        else
+            hipLaunchKernelGGL((tree_attn_f32_tiled_kernel<8>), grid, dim3(512), 0, stream, fq, fk, fv, p.mask, (float*)d_out, p.ws_o, p.ws_ml, p);
         REST_HIP_TRY(hipGetLastError());
         if (ns > 1) {
             hipLaunchKernelGGL(tree_attn_f32_merge_kernel, dim3(d->Nb * d->H * d->Tq), dim3(128), 0, stream,
-                               p.ws_o, p.ws_ml, (float*)d_out, d->H, d->Tq, ns, p.c, p.os[0], p.os[1], p.os[2]);
+                               p.ws_o, p.ws_ml, (float*)d_out, d->H, d->Tq, ns, p.os[0], p.os[1], p.os[2]);
             REST_HIP_TRY(hipGetLastError());
         }
     }

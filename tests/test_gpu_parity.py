@@ -400,9 +400,17 @@ def test_tree_attention_on_8bit_cache_variants():
     torch.cuda.synchronize()
 
 
-@pytest.mark.parametrize("T,P,ns", [(1, 3, 1), (64, 256, 1), (33, 200, 4), (130, 77, 2)])
+@pytest.mark.parametrize("T,P,ns", [(1, 3, 1), (64, 256, 1), (33, 200, 4), (130, 77, 2), (32, 31, 0), (64, 2048, 0), (100, 77, 0),
+                                    (130, 1000, 0), (256, 300, 3), (200, 1, 64), (20, 5000, 0), (64, 0, 0)])
 def test_tree_attention_fp32(T, P, ns):
     attention_case(2, 2, T, P, seed=40 + T, dtype="fp32", num_splits=ns)
+
+
+def test_tree_attention_fp32_variants():
+    attention_case(3, 5, 64, 515, seed=71, dtype="fp32", per_batch=True)           # a mask per batch entry
+    attention_case(1, 2, 20, 130, seed=72, dtype="fp32", Tq_extra=12)              # more query rows than draft tokens
+    attention_case(1, 3, 256, 40, seed=73, dtype="fp32", tree="chain")             # every draft token sees all before it
+    attention_case(40, 16, 16, 100, seed=74, dtype="fp32")                         # more groups than workgroups wanted: no split
 
 
 def test_tree_attention_strided_layout_and_errors():
