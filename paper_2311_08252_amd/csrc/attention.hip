@@ -742,15 +742,20 @@ __global__ __launch_bounds__(512, 1) void tree_attn_split_kernel(AttnParams p) {
     {
         const float inv = l_all > 0.f ? 1.0f / l_all : 0.f;
         const int64_t prow = REST_IDX(((int64_t)unit * p.split_s + part) * 64 + q, (int64_t)p.units * p.split_s * 64, 5);
-        union { bf16x8 h[2]; u64 w[4]; } pk;
+        union { bf16x8 h[2]; i32x4 v[2]; } pk;
 #pragma unroll
         for (int e = 0; e < 8; e++) {
             pk.h[0][e] = (__bf16)(acc[e] * inv);
             pk.h[1][e] = (__bf16)(acc[8 + e] * inv);
         }
-        u64* po = (u64*)(p.ws_po + prow * kD + pc0 * 4);
-#pragma unroll
-        for (int i = 0; i < 4; i++) __hip_atomic_store(po + i, pk.w[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        // Two 16-byte stores at device scope (sc1, what the compiler puts on a device-scope atomic store): the eight
+        // threads of a row write its 256 bytes as whole lines.  As 8-byte atomic stores the same rows cost four times
+        // their size in write traffic (WRITE_SIZE 17.0 MB per launch against 4.8 MB of partials and output).
+        __bf16* po = p.ws_po + prow * kD + pc0 * 4;
+        asm volatile("global_store_dwordx4 %0, %1, off sc1\n\tglobal_store_dwordx4 %0, %2, off offset:16 sc1"
+                     :
+                     : "v"(po), "v"(pk.v[0]), "v"(pk.v[1])
+                     : "memory");
         if ((tid & 7) == 0) {
             union { float f[2]; u64 w; } ml;
             ml.f[0] = m_all;

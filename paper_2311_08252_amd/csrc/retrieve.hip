@@ -87,6 +87,23 @@ __device__ inline void load_tok4(const void* corpus, uint64_t n, uint64_t pos, i
     }
 }
 
+// tokens pos .. pos+N-1 with one read of N tokens (N a power of two), element-wise near the end of the stream
+template <typename TokT, int N>
+__device__ inline void load_tok_group(const void* corpus, uint64_t n, uint64_t pos, int32_t (&out)[N]) {
+    if (pos + N <= n) {
+        TokT v[N];
+        __builtin_memcpy(v, (const TokT*)corpus + pos, sizeof(v));
+#pragma unroll
+        for (int j = 0; j < N; j++) out[j] = (int32_t)v[j];
+    } else {
+#pragma unroll
+        for (int j = 0; j < N; j++) out[j] = load_tok<TokT>(corpus, n, pos + j);
+    }
+}
+// tokens of a 16-byte read
+template <typename TokT>
+constexpr int kWide = 16 / (int)sizeof(TokT);
+
 // Three-way comparison of the first n tokens of two suffixes (at pos1 for lanes with on1, at pos2 for lanes with
 // on2) with q; end of stream = -1 < every token.  Tokens are read four at a time and both suffixes' reads are issued
 // together.  Most probes differ from q within the first four tokens; the few that tie there read all their remaining
@@ -296,12 +313,15 @@ __device__ __forceinline__ void load_row(const RetrieveParams& p, const uint32_t
         const uint64_t pos = (uint64_t)start + n_star;
         const uint64_t left = p.n_tokens > pos ? p.n_tokens - pos : 0;
         len = left < (uint64_t)p.m ? (int)left : p.m;
+        constexpr int G = kWide<TokT>;                 // 16 bytes a read
 #pragma unroll
-        for (int g = 0; g < kM / 4; g++) {
-            int32_t a[4] = {-1, -1, -1, -1};
-            if (4 * g < p.m) load_tok4<TokT>(p.corpus, p.n_tokens, pos + 4 * g, a);
+        for (int g = 0; g < kM / G; g++) {
+            int32_t a[G];
 #pragma unroll
-            for (int j = 0; j < 4; j++) tok[4 * g + j] = a[j];
+            for (int j = 0; j < G; j++) a[j] = -1;
+            if (G * g < p.m) load_tok_group<TokT, G>(p.corpus, p.n_tokens, pos + G * g, a);
+#pragma unroll
+            for (int j = 0; j < G; j++) tok[G * g + j] = a[j];
         }
     }
 }
@@ -694,12 +714,15 @@ __global__ __launch_bounds__(kThreads) void retrieve_kernel(RetrieveParams p) {
             const uint64_t pos = (uint64_t)start + n_star;
             const uint64_t left = p.n_tokens > pos ? p.n_tokens - pos : 0;
             len = left < (uint64_t)m ? (int)left : m;
+            constexpr int G = kWide<TokT>;             // 16 bytes a read
 #pragma unroll
-            for (int g = 0; g < REST_MAX_CONT_LEN / 4; g++) {
-                int32_t a[4] = {-1, -1, -1, -1};
-                if (4 * g < m) load_tok4<TokT>(p.corpus, p.n_tokens, pos + 4 * g, a);
+            for (int g = 0; g < REST_MAX_CONT_LEN / G; g++) {
+                int32_t a[G];
 #pragma unroll
-                for (int j = 0; j < 4; j++) tok[4 * g + j] = a[j];
+                for (int j = 0; j < G; j++) a[j] = -1;
+                if (G * g < m) load_tok_group<TokT, G>(p.corpus, p.n_tokens, pos + G * g, a);
+#pragma unroll
+                for (int j = 0; j < G; j++) tok[G * g + j] = a[j];
             }
         } else {
 #pragma unroll
