@@ -302,14 +302,13 @@ __device__ inline uint32_t kept_rank(uint32_t lo, uint32_t S, uint32_t K, bool s
 
 // One candidate row: the up to m tokens that follow the n_star matched ones at suffix-array entry `entry` (-1 beyond
 // the row's end), and how many there are.
-template <int kM, typename TokT, typename SaT>
-__device__ __forceinline__ void load_row(const RetrieveParams& p, const uint32_t entry, const bool on, const int n_star,
-                                         int32_t (&tok)[kM], int& len) {
+template <int kM, typename TokT>
+__device__ __forceinline__ void load_row_at(const RetrieveParams& p, const uint32_t start, const bool on, const int n_star,
+                                            int32_t (&tok)[kM], int& len) {
     len = 0;
 #pragma unroll
     for (int j = 0; j < kM; j++) tok[j] = -1;
     if (on) {
-        const uint32_t start = load_sa<SaT>(p.sa, p.n_tokens, entry);
         const uint64_t pos = (uint64_t)start + n_star;
         const uint64_t left = p.n_tokens > pos ? p.n_tokens - pos : 0;
         len = left < (uint64_t)p.m ? (int)left : p.m;
@@ -324,6 +323,12 @@ __device__ __forceinline__ void load_row(const RetrieveParams& p, const uint32_t
             for (int j = 0; j < G; j++) tok[G * g + j] = a[j];
         }
     }
+}
+template <int kM, typename TokT, typename SaT>
+__device__ __forceinline__ void load_row(const RetrieveParams& p, const uint32_t entry, const bool on, const int n_star,
+                                         int32_t (&tok)[kM], int& len) {
+    const uint32_t start = on ? load_sa<SaT>(p.sa, p.n_tokens, entry) : 0u;
+    load_row_at<kM, TokT>(p, start, on, n_star, tok, len);
 }
 
 // LDS of the phase B for few rows (byte offsets; the key table is dead by then)
@@ -706,43 +711,26 @@ __global__ __launch_bounds__(kThreads) void retrieve_kernel(RetrieveParams p) {
     const int row_words = (R >> 6) + 1;
     for (int base = wave * 64; base < row_words * 64; base += kThreads) {
         const int r = base + lane;
-        int32_t tok[REST_MAX_CONT_LEN];
-        int len = 0;
-        if (r < R) {
-            const uint32_t start = load_sa<SaT>(p.sa, p.n_tokens, kept_entry(r));
-            rowpos[r] = start;
-            const uint64_t pos = (uint64_t)start + n_star;
-            const uint64_t left = p.n_tokens > pos ? p.n_tokens - pos : 0;
-            len = left < (uint64_t)m ? (int)left : m;
-            constexpr int G = kWide<TokT>;             // 16 bytes a read
-#pragma unroll
-            for (int g = 0; g < REST_MAX_CONT_LEN / G; g++) {
-                int32_t a[G];
-#pragma unroll
-                for (int j = 0; j < G; j++) a[j] = -1;
-                if (G * g < m) load_tok_group<TokT, G>(p.corpus, p.n_tokens, pos + G * g, a);
-#pragma unroll
-                for (int j = 0; j < G; j++) tok[G * g + j] = a[j];
-            }
-        } else {
-#pragma unroll
-            for (int j = 0; j < REST_MAX_CONT_LEN; j++) tok[j] = -1;
-        }
-        // previous row: the neighbouring lane's registers, or a second read for lane 0
+        // my row, and for lane 0 also the row before it (every other lane finds that one in its neighbour's
+        // registers): both suffix-array entries are requested first, then both rows' tokens, 16 bytes a read
+        const bool need_prev = lane == 0 && r > 0 && r < R;
+        uint32_t start = 0, pstart = 0;
+        if (r < R) start = load_sa<SaT>(p.sa, p.n_tokens, kept_entry(r));
+        if (need_prev) pstart = load_sa<SaT>(p.sa, p.n_tokens, kept_entry(r - 1));
+        if (r < R) rowpos[r] = start;
+        int32_t tok[REST_MAX_CONT_LEN], ptok[REST_MAX_CONT_LEN];
+        int len, plen0;
+        load_row_at<REST_MAX_CONT_LEN, TokT>(p, start, r < R, n_star, tok, len);
+        load_row_at<REST_MAX_CONT_LEN, TokT>(p, pstart, need_prev, n_star, ptok, plen0);
         int plen = __shfl_up(len, 1, 64);
+        if (need_prev) plen = plen0;
         int l = 0;
         bool run = true;
-        uint64_t ppos = 0;
-        if (lane == 0 && r > 0 && r < R) {
-            ppos = (uint64_t)load_sa<SaT>(p.sa, p.n_tokens, kept_entry(r - 1)) + n_star;
-            const uint64_t left = p.n_tokens > ppos ? p.n_tokens - ppos : 0;
-            plen = left < (uint64_t)m ? (int)left : m;
-        }
 #pragma unroll
         for (int j = 0; j < REST_MAX_CONT_LEN; j++) {
             if (j < m) {
                 int32_t prev = __shfl_up(tok[j], 1, 64);
-                if (lane == 0 && r > 0 && r < R) prev = load_tok<TokT>(p.corpus, p.n_tokens, ppos + j);
+                if (need_prev) prev = ptok[j];
                 run = run && j < len && j < plen && prev == tok[j];
                 l += run ? 1 : 0;
             }
