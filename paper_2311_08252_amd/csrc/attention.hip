@@ -709,8 +709,11 @@ __global__ __launch_bounds__(512, 1) void tree_attn_split_kernel(AttnParams p) {
     }
     __syncthreads();
 
-    // ---- thread t: query t / 8, pieces 4 (t % 8) .. +3 (sixteen output columns)
-    const int q = tid >> 3, pc0 = (tid & 7) * 4;
+    // ---- thread t: query t / 8, output columns 8 (t % 8) .. +7 and 64 + 8 (t % 8) .. +7 (pieces of four columns:
+    // 2 (t % 8), the next one, and the same two 16 further on), so that the eight threads of a query write and read
+    // 128 consecutive bytes of its bf16 row with each 16-byte access
+    const int q = tid >> 3, c0 = (tid & 7) * 8, c1 = 64 + c0;
+    auto piece_of = [&](int i) { return (i < 2 ? 0 : 16) + 2 * (tid & 7) + (i & 1); };
     float acc[16];
     float m_all = kNegBig, l_all = 0.f;
     {
@@ -725,7 +728,7 @@ __global__ __launch_bounds__(512, 1) void tree_attn_split_kernel(AttnParams p) {
             const float* row = lds_o + (gg * 64 + q) * kD;
 #pragma unroll
             for (int i = 0; i < 4; i++) {
-                const f32x4 x = *(const f32x4*)(row + (((pc0 + i) ^ (q & 31)) << 2));
+                const f32x4 x = *(const f32x4*)(row + ((piece_of(i) ^ (q & 31)) << 2));
 #pragma unroll
                 for (int e = 0; e < 4; e++) acc[4 * i + e] += w * x[e];
             }
@@ -748,11 +751,11 @@ __global__ __launch_bounds__(512, 1) void tree_attn_split_kernel(AttnParams p) {
             pk.h[0][e] = (__bf16)(acc[e] * inv);
             pk.h[1][e] = (__bf16)(acc[8 + e] * inv);
         }
-        // Two 16-byte stores at device scope (sc1, what the compiler puts on a device-scope atomic store): the eight
-        // threads of a row write its 256 bytes as whole lines.  As 8-byte atomic stores the same rows cost four times
-        // their size in write traffic (WRITE_SIZE 17.0 MB per launch against 4.8 MB of partials and output).
-        __bf16* po = p.ws_po + prow * kD + pc0 * 4;
-        asm volatile("global_store_dwordx4 %0, %1, off sc1\n\tglobal_store_dwordx4 %0, %2, off offset:16 sc1"
+        // Two 16-byte stores at device scope (sc1, what the compiler puts on a device-scope atomic store); with each,
+        // the eight threads of a row write one whole 128-byte line.  As 8-byte atomic stores the same rows cost four
+        // times their size in write traffic (WRITE_SIZE 17.0 MB per launch against 4.8 MB of partials and output).
+        __bf16* po = p.ws_po + prow * kD + c0;
+        asm volatile("global_store_dwordx4 %0, %1, off sc1\n\tglobal_store_dwordx4 %0, %2, off offset:128 sc1"
                      :
                      : "v"(po), "v"(pk.v[0]), "v"(pk.v[1])
                      : "memory");
@@ -783,9 +786,10 @@ __global__ __launch_bounds__(512, 1) void tree_attn_split_kernel(AttnParams p) {
             const int sidx = s0 + i < p.split_s ? s0 + i : p.split_s - 1;        // past the end: the last one again, unused
             const int64_t prow = prow0 + sidx * 64;
             ml[i].w = __hip_atomic_load((const u64*)(p.ws_ml + prow * 2), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            const u64* po = (const u64*)(p.ws_po + prow * kD + pc0 * 4);
+            const u64* po = (const u64*)(p.ws_po + prow * kD + c0);
 #pragma unroll
-            for (int j = 0; j < 4; j++) pk[i].w[j] = __hip_atomic_load(po + j, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            for (int j = 0; j < 4; j++)          // columns c0 .. c0+7, then c1 .. c1+7 (16 eight-byte words further on)
+                pk[i].w[j] = __hip_atomic_load(po + (j & 1) + 16 * (j >> 1), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
         float m_new = m_fin;
 #pragma unroll
@@ -816,9 +820,9 @@ __global__ __launch_bounds__(512, 1) void tree_attn_split_kernel(AttnParams p) {
             w0[e] = (__bf16)(acc[e] * inv);
             w1[e] = (__bf16)(acc[8 + e] * inv);
         }
-        __bf16* op = p.out + nb * p.os[0] + h * p.os[1] + q * p.os[2] + pc0 * 4;
-        *(bf16x8*)op = w0;
-        *(bf16x8*)(op + 8) = w1;
+        __bf16* op = p.out + nb * p.os[0] + h * p.os[1] + q * p.os[2];
+        *(bf16x8*)(op + c0) = w0;
+        *(bf16x8*)(op + c1) = w1;
     }
     if (tid == 0) __hip_atomic_store(p.tickets + unit, kTicketMagic << 8, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
