@@ -284,14 +284,6 @@ __device__ inline int bit_weight(const Item& it, int wi, int b) {
     return later ? __builtin_ctzll(later) - b : it.after - (wi * 64 + b);
 }
 
-// position of the highest set bit at or before `from` (bit 0 is always set)
-__device__ inline int prev_set(const uint64_t* bm, int from) {
-    int w = from >> 6;
-    uint64_t x = bm[w] & (~0ull >> (63 - (from & 63)));
-    while (x == 0) x = bm[--w];
-    return (w << 6) + 63 - __builtin_clzll(x);
-}
-
 // Entry of the suffix array that holds kept candidate i of the range [lo, lo + S): the first K entries, or, sampling
 // S > K occurrences evenly, entry lo + floor(i*S/K) = lo + i*(S/K) + floor(i*(S%K)/K); i and S%K are below K <= 8192,
 // so 32 bits hold the product.
@@ -699,7 +691,6 @@ __global__ __launch_bounds__(kThreads) void retrieve_kernel(RetrieveParams p) {
     uint32_t* sel_wgt = sel_key + REST_MAX_NODES;        // [c]
     uint32_t* srt_key = sel_wgt + REST_MAX_NODES;        // [c]
     uint32_t* srt_wgt = srt_key + REST_MAX_NODES;        // [c]
-    int32_t* srt_par = (int32_t*)(srt_wgt + REST_MAX_NODES);  // [c]
     uint32_t* rowpos = (uint32_t*)(lds + p.off_pos);     // [K] suffix-array entry of each kept row
     int32_t* after = (int32_t*)(lds + p.off_after);      // [m][words] first set bit of seg[d] in any word after this one
     uint64_t* shortbm = (uint64_t*)(lds + p.off_short);  // [words] rows cut short by the end of the stream
@@ -936,47 +927,53 @@ __global__ __launch_bounds__(kThreads) void retrieve_kernel(RetrieveParams p) {
     int T = s_misc[4];
     T = T > c ? c : T;
 
-    // ---- B7: breadth-first order = ascending (depth, row); rank by counting, then parents, mask, tokens
-    if (tid < T) {
-        const uint32_t k = sel_key[tid];
+    // ---- B7: breadth-first order = ascending (depth, row): rank by counting, four threads per node
+    {
+        const int x = tid >> 2, part = tid & 3;
         int rank = 0;
-        for (int j = 0; j < T; j++) rank += sel_key[j] < k ? 1 : 0;
-        srt_key[rank] = k;
-        srt_wgt[rank] = sel_wgt[tid];
+        if (x < T) {
+            const uint32_t k = sel_key[x];
+#pragma unroll 4
+            for (int j = part; j < T; j += 4) rank += sel_key[j] < k ? 1 : 0;
+        }
+        rank += __shfl_xor(rank, 1, 64);
+        rank += __shfl_xor(rank, 2, 64);
+        if (x < T && part == 0) {
+            srt_key[rank] = sel_key[x];
+            srt_wgt[rank] = sel_wgt[x];
+        }
     }
     __syncthreads();
-    if (tid < T) {
-        const uint32_t k = srt_key[tid];
-        const int d = (int)(k >> 16), r = (int)(k & 0xffff);
+    // Mask rows and parents, a wavefront per node x, lanes = the 64 slots of a mask word: node a is on the root path
+    // of x iff depth(a) <= depth(x) and row(a) <= row(x) < row(a) + weight(a) (a node's rows are consecutive), so a
+    // mask word is a ballot; slots are in (depth, row) order, so the parent is the highest slot on the path below x.
+    for (int x = wave; x < T; x += kWavesPerWG) {
+        const uint32_t kx = srt_key[x];
+        const int dx = (int)(kx >> 16), rx = (int)(kx & 0xffff);
         int par = -1;
-        if (d > 1) {
-            const int rp = prev_set(seg + (d - 2) * words, r);
-            const uint32_t pk = ((uint32_t)(d - 1) << 16) | (uint32_t)rp;
-            for (int j = 0; j < tid; j++)
-                if (srt_key[j] == pk) par = j;
-        }
-        srt_par[tid] = par;
-    }
-    __syncthreads();
-    if (tid < c) {
-        uint64_t mw[REST_MAX_NODES / 64] = {0, 0, 0, 0};
-        if (tid < T) {
-            const uint32_t k = srt_key[tid];
-            const int d = (int)(k >> 16), r = (int)(k & 0xffff);
-            const uint64_t pos = (uint64_t)rowpos[r] + n_star + (d - 1);
-            o_tok[tid] = load_tok<TokT>(p.corpus, p.n_tokens, pos);
-            o_par[tid] = srt_par[tid];
-            o_pos[tid] = d;
-            o_wgt[tid] = (int32_t)srt_wgt[tid];
-            int v = tid;
-            while (v >= 0) {
-                mw[v >> 6] |= 1ull << (v & 63);
-                v = srt_par[v];
+        for (int k = 0; k < p.mask_words; k++) {
+            const int a = 64 * k + lane;
+            bool on_path = false;
+            if (a < T) {
+                const uint32_t ka = srt_key[a];
+                const int da = (int)(ka >> 16), ra = (int)(ka & 0xffff);
+                on_path = da <= dx && ra <= rx && rx < ra + (int)srt_wgt[a];
             }
-        } else {
-            o_tok[tid] = -1; o_par[tid] = -1; o_pos[tid] = 0; o_wgt[tid] = 0;
+            const uint64_t word = __ballot(on_path);
+            const uint64_t above = (x >> 6) == k ? word & ~(1ull << (x & 63)) : word;
+            if (above) par = 64 * k + 63 - __builtin_clzll(above);
+            if (lane == 0) o_mask[(int64_t)x * p.mask_words + k] = word;
         }
-        for (int w = 0; w < p.mask_words; w++) o_mask[(int64_t)tid * p.mask_words + w] = mw[w];
+        if (lane == 0) {
+            o_tok[x] = load_tok<TokT>(p.corpus, p.n_tokens, (uint64_t)rowpos[rx] + n_star + (dx - 1));
+            o_par[x] = par;
+            o_pos[x] = dx;
+            o_wgt[x] = (int32_t)srt_wgt[x];
+        }
+    }
+    for (int i = T + tid; i < c; i += kThreads) {
+        o_tok[i] = -1; o_par[i] = -1; o_pos[i] = 0; o_wgt[i] = 0;
+        for (int w = 0; w < p.mask_words; w++) o_mask[(int64_t)i * p.mask_words + w] = 0;
     }
     if (tid == 0) {
         p.out.n_nodes[b] = T;
