@@ -880,7 +880,7 @@ __global__ __launch_bounds__(256) void tree_attn_streamk_merge_kernel(AttnParams
 // rows, fall on different banks.  Rows are 16-byte aligned (the host checks pointers and strides).
 constexpr int kF32KStride = kD + 4;
 template <int NW>
-__global__ __launch_bounds__(64 * NW) void tree_attn_f32_tiled_kernel(const float* q, const float* k, const float* v,
+__global__ __launch_bounds__(64 * NW, NW == 2 ? 2 : 1) void tree_attn_f32_tiled_kernel(const float* q, const float* k, const float* v,
                                                                       const uint64_t* mask, float* out, float* ws_o, float* ws_ml,
                                                                       AttnParams p) {
     __shared__ __attribute__((aligned(16))) float ldsK[kBlk * kF32KStride];
@@ -920,30 +920,40 @@ __global__ __launch_bounds__(64 * NW) void tree_attn_f32_tiled_kernel(const floa
     const int per = (nblk + p.nsplit - 1) / p.nsplit;
     const int b0 = split * per, b1 = min(nblk, b0 + per);
 
-    // piece i of a thread: row = (tid + i * threads) / 32 of K (pieces below 1024) or V, 16-byte column (..) % 32
+    // A thread moves the same 16-byte column `ch` of rows row0, row0 + kStep, ... of K and of V: addresses differ by a
+    // constant from piece to piece, and only the last block of a slab checks rows against the end
+    constexpr int kHalf = kChunks / 2;             // pieces of K (and of V) per thread
+    constexpr int kStep = kThreadsWG / (kD / 4);   // rows between two pieces of a thread
+    const int row0 = tid / (kD / 4), ch = tid % (kD / 4);
     f32x4 stage[kChunks];
     auto fetch = [&](int jb) {
+        const int key0 = jb * kBlk;
+        const float* kb = kp + (int64_t)(key0 + row0) * p.ks[2] + 4 * ch;
+        const float* vb = vp + (int64_t)(key0 + row0) * p.vs[2] + 4 * ch;
+        if (!kBoundsChecked && key0 + kBlk <= p.Lk) {
 #pragma unroll
-        for (int i = 0; i < kChunks; i++) {
-            const int cidx = tid + i * kThreadsWG;
-            const bool is_v = cidx >= kBlk * (kD / 4);
-            const int row = (cidx % (kBlk * (kD / 4))) / (kD / 4), ch = cidx % (kD / 4);
-            const int key = jb * kBlk + row;
-            stage[i] = f32x4{0.f, 0.f, 0.f, 0.f};
-            if (key < p.Lk) {
-                const float* src = is_v ? vp + (int64_t)REST_IDX(key, p.Lk, 6) * p.vs[2] : kp + (int64_t)REST_IDX(key, p.Lk, 6) * p.ks[2];
-                stage[i] = *(const f32x4*)(src + 4 * ch);
+            for (int i = 0; i < kHalf; i++) {
+                stage[i] = *(const f32x4*)(kb + (int64_t)(i * kStep) * p.ks[2]);
+                stage[kHalf + i] = *(const f32x4*)(vb + (int64_t)(i * kStep) * p.vs[2]);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < kHalf; i++) {
+                stage[i] = stage[kHalf + i] = f32x4{0.f, 0.f, 0.f, 0.f};     // rows past the end: zeros (V must not be garbage)
+                const int key = key0 + row0 + i * kStep;
+                if (key < p.Lk) {
+                    const int64_t kk = REST_IDX(key, p.Lk, 6);
+                    stage[i] = *(const f32x4*)(kp + kk * p.ks[2] + 4 * ch);
+                    stage[kHalf + i] = *(const f32x4*)(vp + kk * p.vs[2] + 4 * ch);
+                }
             }
         }
     };
     auto park = [&]() {
 #pragma unroll
-        for (int i = 0; i < kChunks; i++) {
-            const int cidx = tid + i * kThreadsWG;
-            const bool is_v = cidx >= kBlk * (kD / 4);
-            const int row = (cidx % (kBlk * (kD / 4))) / (kD / 4), ch = cidx % (kD / 4);
-            if (is_v) *(f32x4*)(ldsV + row * kD + 4 * ch) = stage[i];
-            else *(f32x4*)(ldsK + row * kF32KStride + 4 * ch) = stage[i];
+        for (int i = 0; i < kHalf; i++) {
+            *(f32x4*)(ldsK + (row0 + i * kStep) * kF32KStride + 4 * ch) = stage[i];
+            *(f32x4*)(ldsV + (row0 + i * kStep) * kD + 4 * ch) = stage[kHalf + i];
         }
     };
 
