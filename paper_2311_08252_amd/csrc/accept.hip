@@ -2,30 +2,46 @@
 // the tree while they equal the model's own token at that position; everything after the first
 // disagreement is rejected, so the emitted sequence equals ordinary autoregressive decoding.
 //
-// One wavefront per context.  At each step the 64 lanes scan the nodes for the child of the current node
-// whose token equals the model's token; siblings carry distinct tokens, so at most one lane group hits.
+// One wavefront per context.  The tree (parents, tokens) and the model's tokens are read once -- nodes into registers,
+// four per lane, the model's tokens into LDS --, so that a step of the walk is an LDS read and a ballot: the child of
+// the current node whose token equals the model's token (siblings carry distinct tokens, so at most one node hits;
+// the lowest index is taken).
 #include "common.h"
 
 namespace {
+
+constexpr int kPerLane = REST_MAX_NODES / 64;
 
 __global__ __launch_bounds__(64) void accept_kernel(const int32_t* ids, const int32_t* draft_tokens,
                                                     const int32_t* parent_idx, const int32_t* n_nodes, int32_t c,
                                                     int32_t path_cap, int32_t* accept_len, int32_t* accept_path,
                                                     int32_t* next_token) {
+    __shared__ int32_t s_id[REST_MAX_NODES + 1];
     const int b = blockIdx.x, lane = threadIdx.x;
     const int32_t* id = ids + (int64_t)b * (1 + c);
     const int32_t* tok = draft_tokens + (int64_t)b * c;
     const int32_t* par = parent_idx + (int64_t)b * c;
     int n = n_nodes[b];
     n = n < 0 ? 0 : (n > c ? c : n);
+    int32_t my_par[kPerLane], my_tok[kPerLane];
+#pragma unroll
+    for (int k = 0; k < kPerLane; k++) {
+        const int i = 64 * k + lane;            // node 64 k + lane
+        my_par[k] = i < n ? par[i] : -2;        // -2: never a parent
+        my_tok[k] = i < n ? tok[i] : 0;
+    }
+    for (int i = lane; i <= c; i += 64) s_id[i] = id[i];
+    __syncthreads();
     int cur = -1, len = 0;
     while (len < path_cap) {
-        const int want = id[cur + 1];
-        int hit = 0x7fffffff;
-        for (int i = lane; i < n; i += 64)
-            if (par[i] == cur && tok[i] == want) hit = min(hit, i);
-        for (int off = 32; off > 0; off >>= 1) hit = min(hit, __shfl_xor(hit, off, 64));
-        if (hit == 0x7fffffff) break;
+        const int32_t want = s_id[cur + 1];
+        int hit = -1;
+#pragma unroll
+        for (int k = kPerLane - 1; k >= 0; k--) {
+            const uint64_t m = __ballot(my_par[k] == cur && my_tok[k] == want);
+            if (m) hit = 64 * k + __builtin_ctzll(m);
+        }
+        if (hit < 0) break;
         if (lane == 0) accept_path[(int64_t)b * path_cap + len] = hit;
         cur = hit;
         len++;
@@ -33,7 +49,7 @@ __global__ __launch_bounds__(64) void accept_kernel(const int32_t* ids, const in
     for (int i = len + lane; i < path_cap; i += 64) accept_path[(int64_t)b * path_cap + i] = -1;
     if (lane == 0) {
         accept_len[b] = len;
-        next_token[b] = id[cur + 1];
+        next_token[b] = s_id[cur + 1];
     }
 }
 
