@@ -324,7 +324,10 @@ rest_status rest_accept(const int32_t* d_ids, const rest_tree* tree, int32_t B, 
  * finite per row; d_logits [R, row_stride >= V] fp32.  V <= 131072
  * (REST_UNSUPPORTED above: masses are summed exactly in 53 bits); temperature > 0;
  * 0 < top_p <= 1.  d_workspace: rest_sample_ids_workspace_bytes(R, V) bytes of
- * device memory, 8-byte aligned, no initialisation needed.
+ * device memory, 8-byte aligned, no initialisation needed (rows of at most
+ * 32768 logits are handled without touching it; it is asked for all the same).
+ * Rows that start at multiples of 16 bytes (d_logits and row_stride * 4) and
+ * hold a multiple of 4 logits are read fastest.
  * ---------------------------------------------------------------------- */
 size_t rest_sample_ids_workspace_bytes(int32_t R, int32_t V);
 rest_status rest_sample_ids(const float* d_logits, int64_t row_stride, const float* d_u, int32_t R, int32_t V,

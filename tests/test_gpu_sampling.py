@@ -1,8 +1,9 @@
 """GPU parity of rest_sample_ids against the CPU oracle: the drawn token ids must be equal.
 
 The definition of the draw carries probability masses as integers and fixes every rounding of the exponential, so
-there is one right token per row whatever order an implementation adds in (oracle: sort and cumulative sum; kernel:
-histograms of masses filled with atomic adds by several workgroups)."""
+there is one right token per row whatever order an implementation adds in (oracle: sort and cumulative sum; kernels:
+histograms of masses filled with atomic adds -- by one workgroup that holds the row in registers up to 32768 tokens,
+by several workgroups per row beyond)."""
 import numpy as np
 import pytest
 import torch
@@ -16,14 +17,15 @@ if torch.cuda.is_available():
     import paper_2311_08252_amd as rest
 
 
-def check(logits, u, temperature, top_p, stride=None):
+def check(logits, u, temperature, top_p, stride=None, first=0):
+    """first: the rows start that many floats into their allocation (rows that are not 16-byte aligned)."""
     R, V = logits.shape
-    if stride is None:
+    if stride is None and first == 0:
         d_logits = torch.from_numpy(logits).cuda()
     else:
-        big = torch.full((R, stride), 7.0, dtype=torch.float32, device="cuda")
-        big[:, :V] = torch.from_numpy(logits).cuda()
-        d_logits = big[:, :V]
+        big = torch.full((R, first + (stride or V)), 7.0, dtype=torch.float32, device="cuda")
+        big[:, first:first + V] = torch.from_numpy(logits).cuda()
+        d_logits = big[:, first:first + V]
     out = torch.full((R,), -77, dtype=torch.int32, device="cuda")
     # the workspace needs no initialisation: hand over one full of ones
     ws = torch.full((rest.rest_sample_ids_workspace_bytes(R, V),), 0xFF, dtype=torch.uint8, device="cuda")
@@ -39,7 +41,9 @@ def check(logits, u, temperature, top_p, stride=None):
     (32000, 65, 0.8, 0.95, 0),        # the paper's code-generation setting, one row per position of a 64-node tree
     (32000, 65, 0.7, 0.8, 1),         # the paper's chat setting
     (32016, 9, 1.0, 1.0, 2),          # whole distribution
-    (32768, 4, 0.8, 0.95, 3),
+    (32768, 4, 0.8, 0.95, 3),         # the longest row one workgroup keeps in registers
+    (32769, 4, 0.8, 0.95, 13),        # the shortest that is cut into slices
+    (4097, 6, 0.8, 0.95, 14),         # one token into the second group of four registers
     (131072, 3, 0.8, 0.95, 9),        # largest vocabulary the call takes: sixteen workgroups per row
     (128256, 5, 0.7, 0.9, 10),        # a current vocabulary, last slice ragged
     (8192, 7, 1.0, 0.9, 11),          # exactly one slice
@@ -78,7 +82,7 @@ def test_ties_go_by_ascending_token_id():
 
 
 def test_plateaus_larger_than_the_kernels_token_list():
-    """Thousands of exactly equal logits land in one cell of the kernel's first search level; beyond 4096 of them the
+    """Thousands of exactly equal logits land in one cell of the kernel's first search level; beyond 1024 of them the
     kernel searches the row itself instead of a list in LDS.  Flat rows, a plateau of 6000 leaders, a plateau in the
     body (the nucleus boundary or the draw falls into it), logits with few distinct values."""
     V = 20000
@@ -95,6 +99,11 @@ def test_plateaus_larger_than_the_kernels_token_list():
     assert got[0] == 0 and got[1] == int(np.floor(np.float32(0.73519) * V))    # flat rows: token floor(u V)
     for top_p, temperature in ((0.9, 0.8), (0.5, 1.3), (0.999, 0.3)):
         check(logits, rng.random(6), temperature, top_p)
+    # the same in rows of 40000 tokens, which several workgroups share
+    wide = np.concatenate([logits, np.full((6, 20000), -9.0, dtype=np.float32)], axis=1)
+    wide[1, 20000:] = 0.25
+    for top_p, temperature in ((1.0, 1.0), (0.9, 0.8)):
+        check(wide, u, temperature, top_p)
 
 
 def test_minus_infinity_logits_and_strided_rows():
@@ -103,6 +112,15 @@ def test_minus_infinity_logits_and_strided_rows():
     logits[:, rng.integers(0, 3000, 2500)] = -np.inf          # masked-out tokens
     got = check(logits, rng.random(20), 0.9, 0.9, stride=3100)
     assert np.isfinite(logits[np.arange(20), got]).all()
+
+
+@pytest.mark.parametrize("V,stride,first", [(3000, 3001, 0), (3000, 3004, 1), (32000, 32002, 3), (40000, 40001, 2)])
+def test_rows_that_are_not_16_byte_aligned(V, stride, first):
+    """Aligned rows are read as groups of four floats; these cannot be."""
+    rng = np.random.default_rng(V + stride)
+    logits = (rng.standard_normal((9, V)) * 2.0).astype(np.float32)
+    logits[:, :5] += 8.0
+    check(logits, rng.random(9), 0.8, 0.95, stride=stride, first=first)
 
 
 def test_sampled_acceptance_on_the_gpu():
