@@ -106,6 +106,24 @@ def test_plateaus_larger_than_the_kernels_token_list():
         check(wide, u, temperature, top_p)
 
 
+@pytest.mark.parametrize("size", [3, 16, 17, 32, 33, 64, 65, 128, 129, 256, 300, 512, 513, 1000, 1024, 1025, 1500])
+def test_plateau_sizes_around_the_list_phases_group_widths(size):
+    """The tokens of the crossing cell are ordered by groups of 64, 32, ... 1 threads per listed token, as many as the
+    workgroup has for that many tokens, and by the search in memory beyond 1024: a plateau of `size` equal logits holds
+    the nucleus boundary and most draws, a few leaders and a random body around it."""
+    V, R = 9000, 12
+    rng = np.random.default_rng(size)
+    logits = (rng.standard_normal((R, V)) * 0.5 - 6.0).astype(np.float32)
+    for r in range(R):
+        where = rng.permutation(V)
+        logits[r, where[:size]] = np.float32(1.0 + 0.125 * r)          # the plateau, scattered over the row
+        logits[r, where[size:size + 2]] = np.float32(3.0)              # two leaders above it
+    u = rng.random(R)
+    u[0] = 0.0
+    check(logits, u, 1.0, 0.9)
+    check(logits, rng.random(R), 0.6, 0.97)
+
+
 def test_minus_infinity_logits_and_strided_rows():
     rng = np.random.default_rng(11)
     logits = rng.standard_normal((20, 3000)).astype(np.float32)
