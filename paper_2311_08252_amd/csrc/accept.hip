@@ -21,16 +21,21 @@ __global__ __launch_bounds__(64) void accept_kernel(const int32_t* ids, const in
     const int32_t* id = ids + (int64_t)b * (1 + c);
     const int32_t* tok = draft_tokens + (int64_t)b * c;
     const int32_t* par = parent_idx + (int64_t)b * c;
+    // all reads at once: the tree's c slots are read whatever the number of nodes turns out to be (it arrives with
+    // them), and the slots beyond it are struck out afterwards
     int n = n_nodes[b];
-    n = n < 0 ? 0 : (n > c ? c : n);
     int32_t my_par[kPerLane], my_tok[kPerLane];
 #pragma unroll
     for (int k = 0; k < kPerLane; k++) {
         const int i = 64 * k + lane;            // node 64 k + lane
-        my_par[k] = i < n ? par[i] : -2;        // -2: never a parent
-        my_tok[k] = i < n ? tok[i] : 0;
+        my_par[k] = i < c ? par[i] : -2;        // -2: never a parent
+        my_tok[k] = i < c ? tok[i] : 0;
     }
     for (int i = lane; i <= c; i += 64) s_id[i] = id[i];
+    n = n < 0 ? 0 : (n > c ? c : n);
+#pragma unroll
+    for (int k = 0; k < kPerLane; k++)
+        if (64 * k + lane >= n) my_par[k] = -2;
     __syncthreads();
     int cur = -1, len = 0;
     while (len < path_cap) {
