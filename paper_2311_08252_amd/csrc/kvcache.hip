@@ -154,15 +154,14 @@ __global__ __launch_bounds__(512) void kv_compact_kernel(KvParams p) {
     const int h = blockIdx.x, nb = blockIdx.y;
     const int i = threadIdx.x >> 4, piece = threadIdx.x & 15;
     const int row = p.per_batch ? nb : 0;
+    // the path's entry is read together with the path's length, not after it (the array has path_cap entries a row)
     int n = p.path_len[row];
+    int src = i < p.path_cap ? p.path[(int64_t)row * p.path_cap + i] : -1;
     n = n < 0 ? 0 : (n > p.path_cap ? p.path_cap : n);
     // the moves end at the first entry that is not a draft row
-    int src = -1;
     bool live = i < n;
-    if (live) {
-        src = p.path[(int64_t)row * p.path_cap + i];
-        live = src >= 0 && src < p.T;
-    }
+    if (!live) src = -1;
+    live = live && src >= 0 && src < p.T;
     // a move is made only if every move before it is: the smallest offending index is agreed on through LDS
     __shared__ int first_bad;
     if (threadIdx.x == 0) first_bad = 0x7fffffff;
